@@ -1,0 +1,185 @@
+#!/usr/bin/env python3
+"""Benchmark of the Cool-SD verify-and-resample hot path on one MI355X.
+
+A step is one cool_sd_verify call (softmax statistics of every target and draft row, relaxed
+accept test, first rejection, one draw from the optimal resampling law) on one batch of
+synthetic input that is already resident in HBM.  The workload is configuration 2 of the
+benchmark list (B=32, L=8, V=16384, bf16); steps cycle through a pool of distinct batches
+larger than the 256 MB last-level cache, and are replayed from a HIP graph so that the
+host's launch cost does not hide the device time.
+
+Prints ONE JSON line: verified draft tokens per second, with
+  roofline      HBM: algorithmic bytes of one launch / average time of one launch (HIP events
+                around the timed region on the launch stream)
+  cpu_baseline  the fp64 CPU oracle timed on a bounded sample of the same batches.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/),
+# scaled by the same counters' reading on a plain copy kernel; None = not measured.
+MEASURED_TRAFFIC_BYTES = {"cfg2": None, "cfg4": None, "cfg5": None}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3000)
+    ap.add_argument("--warmup", type=int, default=300)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg4", "cfg5"])
+    ap.add_argument("--launch", default="graph", choices=["graph", "direct"])
+    ap.add_argument("--pool-mb", type=float, default=600.0, help="distinct input batches cycled, total size")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="time budget of the CPU oracle sample")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--others", action="store_true", help="also time configurations 4 and 5 (extra JSON keys)")
+    return ap.parse_args()
+
+
+class Runner:
+    """Pool of resident batches of one configuration plus everything a verify call needs."""
+
+    def __init__(self, pkg, torch, cfg, pool_mb, max_pool=64):
+        from workloads import make_workload
+        self.pkg, self.torch, self.cfg = pkg, torch, cfg
+        w0 = make_workload(cfg, device="cuda", call=0)
+        self.bytes_per_step = w0.algorithmic_bytes()
+        n = int(min(max_pool, max(2, -(-int(pool_mb * 1e6) // self.bytes_per_step))))
+        self.pool = [w0] + [make_workload(cfg, device="cuda", call=c) for c in range(1, n)]
+        self.B, self.L, self.V = w0.B, w0.L, w0.V
+        self.omega_np = pkg.cool_sd_schedule(pkg.COOL_SD_SCHED_EXP, w0.L, w0.delta, w0.nu)
+        self.omega = torch.from_numpy(self.omega_np).cuda()
+        self.params = pkg.make_params(w0.target, w0.draft, top_k=w0.top_k, cfg_scale=w0.cfg_scale,
+                                      temperature=w0.temperature)
+        self.ws = torch.empty(max(pkg.cool_sd_workspace_bytes(self.params), 256), dtype=torch.uint8, device="cuda")
+        pkg.cool_sd_workspace_init(self.ws)
+        self.accept_len = torch.zeros(self.B, dtype=torch.int32, device="cuda")
+        self.next_token = torch.zeros(self.B, dtype=torch.int32, device="cuda")
+        self.graph = None
+
+    def step(self, i):
+        w = self.pool[i % len(self.pool)]
+        self.pkg.cool_sd_verify(self.params, w.target, w.target_uncond, w.draft, w.draft_uncond, w.draft_tokens,
+                                self.omega, w.u_accept, w.u_resample, self.accept_len, self.next_token,
+                                None, None, None, None, self.ws)
+
+    def capture(self):
+        """One HIP graph holding one pass over the pool (len(pool) steps)."""
+        torch = self.torch
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            for i in range(len(self.pool)):
+                self.step(i)
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(len(self.pool)):
+                self.step(i)
+        self.graph = g
+
+    def run(self, steps, launch):
+        """Enqueue `steps` steps (rounded up to whole pool passes in graph mode); returns steps issued."""
+        if launch == "graph":
+            n = len(self.pool)
+            reps = -(-steps // n)
+            for _ in range(reps):
+                self.graph.replay()
+            return reps * n
+        for i in range(steps):
+            self.step(i)
+        return steps
+
+    def time(self, steps, warmup, launch):
+        torch = self.torch
+        if launch == "graph" and self.graph is None:
+            self.capture()
+        self.run(warmup, launch)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        done = self.run(steps, launch)
+        e1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return done, wall, e0.elapsed_time(e1) * 1e-3
+
+
+def cpu_baseline(runner, budget_s):
+    """The oracle, as it stands, on whole batches of the same pool until the time budget is used."""
+    from oracle import oracle as O
+    from tests.parity_util import run_oracle
+    threads = O.max_threads()
+    run_oracle(O, runner.pool[0], runner.omega_np, num_threads=threads)      # page in / build
+    t0 = time.perf_counter()
+    calls = 0
+    while True:
+        run_oracle(O, runner.pool[calls % len(runner.pool)], runner.omega_np, num_threads=threads)
+        calls += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s:
+            break
+    tokens = calls * runner.B * runner.L
+    return {"value": tokens / el, "unit": "verified draft tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "%d verify calls of the same workload (B=%d, L=%d, V=%d), %.1f s, OpenMP over sequences"
+                      % (calls, runner.B, runner.L, runner.V, el)}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path, run with --gpus 1")
+    import torch
+    import paper_2601_09212_amd as pkg
+    pkg.binding.lib()
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+
+    cfg = int(a.workload[3:])
+    r = Runner(pkg, torch, cfg, a.pool_mb)
+    done, wall, dev_s = r.time(a.steps, a.warmup, a.launch)
+    tokens = done * r.B * r.L
+    per_launch_s = dev_s / done
+    achieved = r.bytes_per_step / per_launch_s / 1e9
+    dtype = r.pool[0].dtype
+    line = {
+        "metric": "verified draft tokens/sec (1 GPU) + achieved HBM GB/s fraction of peak",
+        "value": tokens / wall, "unit": "verified draft tokens/s", "n_gpus": 1, "steps": done, "warmup": a.warmup,
+        "ms_per_step": wall / done * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "config 2: B=32, L=8, V=16384, %s logits, exp schedule delta=1.1 nu=0.7" % dtype
+                   if cfg == 2 else "config %d: B=%d, L=%d, V=%d, %s logits" % (cfg, r.B, r.L, r.V, dtype),
+                   "input_dtype": dtype, "launch": a.launch, "pool_batches": len(r.pool),
+                   "pool_mb": len(r.pool) * r.bytes_per_step / 1e6, "bytes_per_step": r.bytes_per_step},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(a.workload),
+                     "kernel": "verify_rows_kernel", "us_per_launch": per_launch_s * 1e6},
+    }
+    if a.others:
+        extra = {}
+        for c in (4, 5):
+            rr = Runner(pkg, torch, c, 2400.0, max_pool=8)
+            d2, w2, s2 = rr.time(max(64, 8 * len(rr.pool)), 2 * len(rr.pool), a.launch)
+            extra["cfg%d" % c] = {"tokens_per_s": d2 * rr.B * rr.L / w2, "us_per_step": s2 / d2 * 1e6,
+                                  "GBps": rr.bytes_per_step / (s2 / d2) / 1e9,
+                                  "frac": rr.bytes_per_step / (s2 / d2) / 1e9 / HBM_PEAK_GBS,
+                                  "pool_batches": len(rr.pool)}
+            del rr
+            torch.cuda.empty_cache()
+        line["other_workloads"] = extra
+    if not a.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(r, a.cpu_seconds)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

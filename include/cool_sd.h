@@ -1,0 +1,148 @@
+/*
+ * cool_sd.h -- C ABI of the MI355X (gfx950) verify-and-resample library for annealed
+ * relaxed speculative decoding (Cool-SD).
+ *
+ * One call verifies, for a batch of B independent sequences, the L tokens a draft model Q
+ * proposed against the target model P (Algorithm 1, verification stage):
+ *
+ *   p_i, q_i   softmax of the target / draft logits at draft position i = 1..L (+ bonus L+1)
+ *   f_i        = min{1, omega_i p_i(x~_i) / q_i(x~_i)}, 0/0 := 1            (Eq. relax)
+ *   accept_i   = [u_i <= f_i]
+ *   tau        = number of positions before the first rejection              (Algorithm 1)
+ *   x_{tau+1}  ~ G* = Norm([p - q f]_+) at the rejected position              (Theorem 2, Eq. opt_G)
+ *                (or Norm([p - q]_+), Eq. g_tsd, in VANILLA mode),
+ *                or ~ p_{L+1} when all L tokens were accepted                 (Algorithm 1, bonus)
+ *   omega_i    relaxation schedule, e.g. delta * exp(-nu i - mu)              (Eq. sdar)
+ *
+ * Conventions
+ *   - Pointers named *_dev are device pointers valid on the current HIP device; all others
+ *     are host pointers.  The caller owns every buffer; the library allocates no device
+ *     memory and never synchronises with the host: work is enqueued on the given stream.
+ *   - Inputs are read-only; every output element is overwritten.
+ *   - Functions return COOL_SD_OK (0) or a negative cool_sd_status.  Argument errors are
+ *     detected on the host before anything is enqueued.  Draft tokens outside [0, V) are a
+ *     contract violation and are not checked on the device.
+ *   - Logits must be finite or -inf (-inf = token excluded); every row needs at least one
+ *     finite logit.  Uniforms lie in [0, 1).
+ *   - A workspace must be prepared once with cool_sd_workspace_init before its first use; a
+ *     verify/resample call leaves it prepared for the next.  Calls that share a workspace
+ *     must be ordered on one stream.
+ */
+#ifndef COOL_SD_H
+#define COOL_SD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { COOL_SD_F32 = 0, COOL_SD_BF16 = 1 } cool_sd_dtype;
+
+typedef enum {
+  COOL_SD_SCHED_UNIFORM = 0, /* omega_i = delta                         (uniform relaxation)   */
+  COOL_SD_SCHED_EXP = 1,     /* omega_i = delta exp(-nu i - mu)          (Eq. sdar)             */
+  COOL_SD_SCHED_LINEAR = 2   /* omega_i ~ (ell - i), normalised to sum delta L (App., schedule ablation) */
+} cool_sd_sched;
+
+typedef enum {
+  COOL_SD_RESAMPLE_OPT = 0,    /* G* = Norm([p - min(q, omega p)]_+)       (Eq. opt_G) */
+  COOL_SD_RESAMPLE_VANILLA = 1 /* G^van = Norm([p - q]_+)                  (Eq. g_tsd) */
+} cool_sd_resample_mode;
+
+typedef enum {
+  COOL_SD_OK = 0,
+  COOL_SD_EINVAL = -1,       /* null pointer, bad shape / stride / dtype / option           */
+  COOL_SD_EWORKSPACE = -2,   /* workspace missing, misaligned or smaller than required       */
+  COOL_SD_ELAUNCH = -3,      /* the HIP runtime refused a launch                             */
+  COOL_SD_EUNSUPPORTED = -4  /* valid request the kernels do not implement (see top_k)       */
+} cool_sd_status;
+
+typedef struct {
+  int32_t B;             /* sequences, >= 1                                                   */
+  int32_t L;             /* draft length, 1..4096                                             */
+  int32_t V;             /* vocabulary size, >= 1; rows of V contiguous elements              */
+  int32_t dtype;         /* cool_sd_dtype of every logit tensor                               */
+  int64_t t_stride_b;    /* element strides of the target logits [B, L(+1), V]                */
+  int64_t t_stride_l;
+  int64_t d_stride_b;    /* element strides of the draft logits [B, L, V]                     */
+  int64_t d_stride_l;
+  int64_t omega_stride_b;/* 0: omega is [L], shared by all sequences; else omega is [B, L]
+                            with this element stride between sequences                        */
+  int32_t has_bonus;     /* 1: target holds L+1 rows per sequence; 0: L rows, no bonus token  */
+  int32_t top_k;         /* 0 = off; else 1..V: keep logits >= the k-th largest of the row
+                            (ties kept), on BOTH models, after guidance and temperature.
+                            Implemented for V <= 16384 (else COOL_SD_EUNSUPPORTED)            */
+  float cfg_scale;       /* s of l = l_u + s (l_c - l_u); used iff the *_uncond pointers are
+                            given (classifier-free guidance, App. implementation details)     */
+  float temperature;     /* > 0; logits are multiplied by fl32(1/temperature); 1 = off        */
+  int32_t resample_mode; /* cool_sd_resample_mode                                             */
+  int32_t reserved;      /* must be 0                                                         */
+} cool_sd_params;
+
+/* Relaxation schedule (Eq. sdar and the uniform / linear variants), host only, O(L).
+ * kind: cool_sd_sched.  param: nu (EXP, > 0), ell (LINEAR, >= L), ignored (UNIFORM).
+ * omega_out: host float[L]; omega_out[i-1] = omega_i of the paper.  Evaluated in fp64 and
+ * rounded once to fp32.  COOL_SD_EINVAL on bad arguments (LINEAR with ell < L would need a
+ * negative weight). */
+int cool_sd_schedule(int32_t kind, int32_t L, float delta, float param, float* omega_out);
+
+/* Bytes of device workspace cool_sd_verify / cool_sd_resample need for these params
+ * (for resample only B, V, dtype and top_k matter).  0 on invalid params. */
+size_t cool_sd_workspace_bytes(const cool_sd_params* p);
+
+/* Prepare a workspace (zero its completion counters) on the stream.  Needed once after
+ * allocation.  workspace_dev must be 256-byte aligned. */
+int cool_sd_workspace_init(void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* Verification stage of Algorithm 1 for B sequences; asynchronous on hip_stream.
+ *   target_dev          [B, L + has_bonus, V] logits of P (conditional ones under guidance)
+ *   target_uncond_dev   same shape/strides, or NULL (no guidance)
+ *   draft_dev           [B, L, V] logits of Q;  draft_uncond_dev likewise (both or neither)
+ *   draft_tokens_dev    [B, L] int32, contiguous: x~_i
+ *   omega_dev           float [L] (or [B, L], see omega_stride_b), >= 0
+ *   u_accept_dev        float [B, L]: the uniforms r_i of Algorithm 1
+ *   u_resample_dev      float [B]: drives the draw from G* / the bonus draw (inverse CDF in
+ *                       ascending token order: smallest k with g(0)+..+g(k) > u R)
+ *   accept_len_dev      out int32 [B]: tau in [0, L]
+ *   next_token_dev      out int32 [B]: x_{tau+1}; -1 iff tau == L and has_bonus == 0
+ *   p_tok_dev, q_tok_dev, f_dev   out float [B, L], each optional (NULL = skip):
+ *                       p_i(x~_i), q_i(x~_i), f_i for every position (also after tau)
+ *   resid_mass_dev      out float [B], optional: R = sum_x g(x) of the sampled law
+ *                       (sum of p for the bonus draw, 0 when next_token = -1)
+ * The accepted tokens are draft_tokens[b, 0:tau]; they are not copied. */
+int cool_sd_verify(const cool_sd_params* p,
+                   const void* target_dev, const void* target_uncond_dev,
+                   const void* draft_dev, const void* draft_uncond_dev,
+                   const int32_t* draft_tokens_dev,
+                   const float* omega_dev,
+                   const float* u_accept_dev,
+                   const float* u_resample_dev,
+                   int32_t* accept_len_dev,
+                   int32_t* next_token_dev,
+                   float* p_tok_dev, float* q_tok_dev, float* f_dev,
+                   float* resid_mass_dev,
+                   void* workspace_dev, size_t workspace_bytes,
+                   void* hip_stream);
+
+/* Stand-alone resampling step (Eq. opt_G / Eq. g_tsd): one (target, draft) row pair per
+ * sequence.  p->L, strides_l and has_bonus are ignored; rows are [B, V] with element strides
+ * t_stride_b / d_stride_b.  omega_rows_dev float [B], u_dev float [B].
+ * draft_rows_dev == NULL samples from p itself (the bonus draw of Algorithm 1).
+ *   token_dev out int32 [B], resid_mass_dev out float [B] (optional). */
+int cool_sd_resample(const cool_sd_params* p,
+                     const void* target_rows_dev, const void* target_uncond_rows_dev,
+                     const void* draft_rows_dev, const void* draft_uncond_rows_dev,
+                     const float* omega_rows_dev, const float* u_dev,
+                     int32_t* token_dev, float* resid_mass_dev,
+                     void* workspace_dev, size_t workspace_bytes,
+                     void* hip_stream);
+
+/* Static description of a cool_sd_status. */
+const char* cool_sd_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COOL_SD_H */

@@ -1,0 +1,212 @@
+// C ABI of the Cool-SD verify-and-resample library: argument validation, workspace layout,
+// the host-side relaxation schedule, and kernel dispatch.  See include/cool_sd.h.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "cool_sd.h"
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Layout {
+  size_t seq_counter, row_counter, k2_counter, hint, acc, cand_tok, cand_R, part, rowstat, chunk_R, total;
+};
+
+// rows: logit row pairs processed by the first kernel; L1 = L + 1 candidate slots per sequence.
+Layout make_layout(int64_t B, int64_t L, int64_t rows, int64_t nchunks) {
+  Layout o{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes); return at; };
+  o.seq_counter = take(size_t(B) * 4);
+  o.row_counter = take(size_t(rows) * 4);
+  o.k2_counter = take(size_t(B) * 4);
+  o.hint = take(size_t(B) * 4);
+  o.acc = take(size_t(B) * L * 4);
+  o.cand_tok = take(size_t(B) * (L + 1) * 4);
+  o.cand_R = take(size_t(B) * (L + 1) * 4);
+  if (nchunks > 1) {
+    o.part = take(size_t(rows) * nchunks * 16);
+    o.rowstat = take(size_t(rows) * 16);
+    o.chunk_R = take(size_t(B) * nchunks * 4);
+  }
+  o.total = off;
+  return o;
+}
+
+inline int64_t n_chunks(int64_t V) { return (V + csd::kChunk - 1) / csd::kChunk; }
+
+bool params_ok(const cool_sd_params* p, bool for_resample) {
+  if (!p) return false;
+  if (p->B < 1 || p->V < 1) return false;
+  if (!for_resample && (p->L < 1 || p->L > 4096)) return false;
+  if (p->dtype != COOL_SD_F32 && p->dtype != COOL_SD_BF16) return false;
+  if (p->t_stride_b < 0 || p->d_stride_b < 0) return false;
+  if (!for_resample && (p->t_stride_l < 0 || p->d_stride_l < 0 || p->omega_stride_b < 0)) return false;
+  if (!for_resample && p->has_bonus != 0 && p->has_bonus != 1) return false;
+  if (p->top_k < 0 || p->top_k > p->V) return false;
+  if (!(p->temperature > 0.f) || !isfinite(p->temperature)) return false;
+  if (!isfinite(p->cfg_scale)) return false;
+  if (p->resample_mode != COOL_SD_RESAMPLE_OPT && p->resample_mode != COOL_SD_RESAMPLE_VANILLA) return false;
+  if (p->reserved != 0) return false;
+  const int64_t L = for_resample ? 1 : p->L;
+  const int64_t rows = for_resample ? p->B : int64_t(p->B) * (L + p->has_bonus);
+  if (rows * n_chunks(p->V) > 0x7fffffffLL) return false;   // grid size
+  return true;
+}
+
+inline bool is_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int run(const cool_sd_params* p, bool resample_only,
+        const void* t, const void* tu, const void* d, const void* du,
+        const int32_t* tokens, const float* omega, const float* u_acc, const float* u_res,
+        int32_t* accept_len, int32_t* next_token, float* p_tok, float* q_tok, float* f,
+        float* resid_mass, void* ws, size_t ws_bytes, void* stream) {
+  const int64_t L = resample_only ? 1 : p->L;
+  const int hb = resample_only ? 0 : p->has_bonus;
+  const int64_t rows = resample_only ? p->B : int64_t(p->B) * (L + hb);
+  const int64_t C = n_chunks(p->V);
+  if (p->top_k > 0 && C > 1) return COOL_SD_EUNSUPPORTED;
+  if (p->top_k > 0) return COOL_SD_EUNSUPPORTED;   // selection kernel not wired in yet
+  const Layout lay = make_layout(p->B, L, rows, C);
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0 || ws_bytes < lay.total) return COOL_SD_EWORKSPACE;
+
+  const int kE = (p->dtype == COOL_SD_BF16) ? 8 : 4;
+  bool aligned = (p->V % kE == 0) && is_aligned16(t) && (p->t_stride_b % kE == 0);
+  if (!resample_only) aligned = aligned && (p->t_stride_l % kE == 0);
+  if (tu) aligned = aligned && is_aligned16(tu);
+  if (d) {
+    aligned = aligned && is_aligned16(d) && (p->d_stride_b % kE == 0);
+    if (!resample_only) aligned = aligned && (p->d_stride_l % kE == 0);
+  }
+  if (du) aligned = aligned && is_aligned16(du);
+
+  char* w = static_cast<char*>(ws);
+  csd::KArgs a{};
+  a.t = t; a.tu = tu; a.d = d; a.du = du;
+  a.tokens = tokens; a.omega = omega; a.u_acc = u_acc; a.u_res = u_res;
+  a.accept_len = accept_len; a.next_token = next_token;
+  a.p_tok = p_tok; a.q_tok = q_tok; a.f = f; a.resid_mass = resid_mass;
+  a.t_sb = p->t_stride_b; a.d_sb = p->d_stride_b;
+  a.t_sl = resample_only ? 0 : p->t_stride_l;
+  a.d_sl = resample_only ? 0 : p->d_stride_l;
+  a.om_sb = resample_only ? 1 : p->omega_stride_b;
+  a.B = p->B; a.L = (int32_t)L; a.V = p->V; a.has_bonus = hb;
+  a.top_k = p->top_k; a.resample_mode = p->resample_mode;
+  a.resample_only = resample_only ? 1 : 0;
+  a.aligned = aligned ? 1 : 0;
+  a.nchunks = (int32_t)C;
+  a.cfg_scale = p->cfg_scale;
+  a.inv_T = 1.0f / p->temperature;
+  a.seq_counter = reinterpret_cast<uint32_t*>(w + lay.seq_counter);
+  a.row_counter = reinterpret_cast<uint32_t*>(w + lay.row_counter);
+  a.k2_counter = reinterpret_cast<uint32_t*>(w + lay.k2_counter);
+  a.hint = reinterpret_cast<uint32_t*>(w + lay.hint);
+  a.acc = reinterpret_cast<int32_t*>(w + lay.acc);
+  a.cand_tok = reinterpret_cast<int32_t*>(w + lay.cand_tok);
+  a.cand_R = reinterpret_cast<float*>(w + lay.cand_R);
+  a.part = C > 1 ? reinterpret_cast<float4*>(w + lay.part) : nullptr;
+  a.rowstat = C > 1 ? reinterpret_cast<float4*>(w + lay.rowstat) : nullptr;
+  a.chunk_R = C > 1 ? reinterpret_cast<float*>(w + lay.chunk_R) : nullptr;
+
+  const bool xf = (tu != nullptr) || (p->temperature != 1.0f) || (p->top_k > 0);
+  hipError_t e = csd::launch_verify(a, p->dtype, xf, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? COOL_SD_OK : COOL_SD_ELAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cool_sd_schedule(int32_t kind, int32_t L, float delta, float param, float* omega_out) {
+  if (L < 1 || L > 4096 || !omega_out || !(delta >= 0.f) || !isfinite(delta)) return COOL_SD_EINVAL;
+  if (kind == COOL_SD_SCHED_UNIFORM) {
+    for (int i = 0; i < L; ++i) omega_out[i] = delta;
+    return COOL_SD_OK;
+  }
+  if (kind == COOL_SD_SCHED_EXP) {
+    // omega_i = delta exp(-nu i - mu) with sum_i exp(-nu i - mu) = L, i.e. the weights
+    // exp(-nu i) rescaled to sum to L (Eq. sdar).  Anchored at i = 1 to stay in range.
+    const double nu = param;
+    if (!(nu > 0.0) || !isfinite(nu)) return COOL_SD_EINVAL;
+    double z = 0.0;
+    for (int i = L; i >= 1; --i) z += exp(-nu * double(i - 1));
+    for (int i = 1; i <= L; ++i)
+      omega_out[i - 1] = float(double(delta) * double(L) * exp(-nu * double(i - 1)) / z);
+    return COOL_SD_OK;
+  }
+  if (kind == COOL_SD_SCHED_LINEAR) {
+    // omega_i proportional to (ell - i), rescaled to sum to delta L; the common factor
+    // 1/(ell (ell+1)) of the paper's weights cancels (App., schedule ablation).
+    const double ell = param;
+    if (!(ell >= double(L)) || !isfinite(ell)) return COOL_SD_EINVAL;
+    const double z = double(L) * ell - 0.5 * double(L) * double(L + 1);
+    if (!(z > 0.0)) return COOL_SD_EINVAL;
+    for (int i = 1; i <= L; ++i) omega_out[i - 1] = float(double(delta) * double(L) * (ell - double(i)) / z);
+    return COOL_SD_OK;
+  }
+  return COOL_SD_EINVAL;
+}
+
+size_t cool_sd_workspace_bytes(const cool_sd_params* p) {
+  if (!params_ok(p, false) && !params_ok(p, true)) return 0;
+  const bool full = params_ok(p, false);
+  const int64_t L = full ? p->L : 1;
+  const int64_t rows = full ? int64_t(p->B) * (L + p->has_bonus) : p->B;
+  return make_layout(p->B, L, rows, n_chunks(p->V)).total;
+}
+
+int cool_sd_workspace_init(void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+  if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) % kAlign) != 0) return COOL_SD_EWORKSPACE;
+  hipError_t e = csd::launch_zero(static_cast<uint32_t*>(workspace_dev), workspace_bytes / 4,
+                                  static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? COOL_SD_OK : COOL_SD_ELAUNCH;
+}
+
+int cool_sd_verify(const cool_sd_params* p, const void* target_dev, const void* target_uncond_dev,
+                   const void* draft_dev, const void* draft_uncond_dev, const int32_t* draft_tokens_dev,
+                   const float* omega_dev, const float* u_accept_dev, const float* u_resample_dev,
+                   int32_t* accept_len_dev, int32_t* next_token_dev, float* p_tok_dev, float* q_tok_dev,
+                   float* f_dev, float* resid_mass_dev, void* workspace_dev, size_t workspace_bytes,
+                   void* hip_stream) {
+  if (!params_ok(p, false)) return COOL_SD_EINVAL;
+  if (!target_dev || !draft_dev || !draft_tokens_dev || !omega_dev || !u_accept_dev || !u_resample_dev ||
+      !accept_len_dev || !next_token_dev)
+    return COOL_SD_EINVAL;
+  if ((target_uncond_dev == nullptr) != (draft_uncond_dev == nullptr)) return COOL_SD_EINVAL;
+  return run(p, false, target_dev, target_uncond_dev, draft_dev, draft_uncond_dev, draft_tokens_dev, omega_dev,
+             u_accept_dev, u_resample_dev, accept_len_dev, next_token_dev, p_tok_dev, q_tok_dev, f_dev,
+             resid_mass_dev, workspace_dev, workspace_bytes, hip_stream);
+}
+
+int cool_sd_resample(const cool_sd_params* p, const void* target_rows_dev, const void* target_uncond_rows_dev,
+                     const void* draft_rows_dev, const void* draft_uncond_rows_dev, const float* omega_rows_dev,
+                     const float* u_dev, int32_t* token_dev, float* resid_mass_dev, void* workspace_dev,
+                     size_t workspace_bytes, void* hip_stream) {
+  if (!params_ok(p, true)) return COOL_SD_EINVAL;
+  if (!target_rows_dev || !u_dev || !token_dev) return COOL_SD_EINVAL;
+  if (draft_rows_dev && !omega_rows_dev) return COOL_SD_EINVAL;
+  if (!draft_rows_dev && draft_uncond_rows_dev) return COOL_SD_EINVAL;
+  if (draft_rows_dev && ((target_uncond_rows_dev == nullptr) != (draft_uncond_rows_dev == nullptr)))
+    return COOL_SD_EINVAL;
+  return run(p, true, target_rows_dev, target_uncond_rows_dev, draft_rows_dev, draft_uncond_rows_dev, nullptr,
+             omega_rows_dev, nullptr, u_dev, nullptr, token_dev, nullptr, nullptr, nullptr, resid_mass_dev,
+             workspace_dev, workspace_bytes, hip_stream);
+}
+
+const char* cool_sd_strerror(int code) {
+  switch (code) {
+    case COOL_SD_OK: return "ok";
+    case COOL_SD_EINVAL: return "invalid argument";
+    case COOL_SD_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case COOL_SD_ELAUNCH: return "HIP launch failed";
+    case COOL_SD_EUNSUPPORTED: return "request not implemented by the kernels";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

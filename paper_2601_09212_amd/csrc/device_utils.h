@@ -1,0 +1,201 @@
+// Device-side building blocks of the Cool-SD verify kernels (gfx950, wave64).
+//
+// Layout of a row chunk on chip.  A workgroup of 256 threads holds one chunk of up to
+// kChunk = 16384 consecutive logits of a row in registers.  The chunk is cut into tiles of
+// 256 x 16 bytes; in tile k thread t owns the 16-byte vector number k*256 + t, i.e. the
+// kE = 8 (bf16) or 4 (fp32) consecutive elements starting at (k*256 + t)*kE.  Every global
+// load instruction therefore reads 1 KiB of consecutive memory per wave.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace csd {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr int kChunk = 16384;
+constexpr int kDtF32 = 0;
+constexpr int kDtBF16 = 1;
+constexpr float kLog2e = 1.44269504088896340736f;
+constexpr float kRefFloor = -1.5e30f;  // "no finite logit seen yet" reference exponent
+
+template <int DT> struct Vec {
+  static constexpr int kE = (DT == kDtBF16) ? 8 : 4;       // elements per 16-byte vector
+  static constexpr int kES = (DT == kDtBF16) ? 2 : 4;      // bytes per element
+  static constexpr int kT = kChunk / (kThreads * kE);      // tiles per chunk: 8 / 16
+};
+
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// ---------------------------------------------------------------- wave / block primitives
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ int wave_min_i(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ int wave_max_i(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o, 64));
+  return v;
+}
+// inclusive prefix sum over the 64 lanes of a wave, ascending lane order
+__device__ __forceinline__ float wave_scan_incl(float v) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    float n = __shfl_up(v, o, 64);
+    if (lane >= o) v += n;
+  }
+  return v;
+}
+
+// ---------------------------------------------------------------- loads
+template <int DT> __device__ __forceinline__ uint4 neg_inf_vec() {
+  const uint32_t f = (DT == kDtBF16) ? 0xFF80FF80u : 0xFF800000u;
+  return make_uint4(f, f, f, f);
+}
+
+// One 16-byte vector of a row starting at element e (e is a multiple of kE).  Elements at or
+// beyond V read as -inf.  AL promises that the row base is 16-byte aligned and V is a positive
+// multiple of kE; otherwise elements are fetched one by one.  Both paths are branch-free (the
+// address is clamped into the row and the value replaced afterwards), so that all loads of a
+// chunk can be in flight together.
+template <int DT, bool AL>
+__device__ __forceinline__ uint4 load_vec(const char* __restrict__ row, int64_t e, int V) {
+  constexpr int kE = Vec<DT>::kE;
+  if (AL) {
+    const bool in = e < V;
+    const int64_t ec = in ? e : int64_t(V - kE);
+    uint4 v = *reinterpret_cast<const uint4*>(row + ec * Vec<DT>::kES);
+    const uint4 ninf = neg_inf_vec<DT>();
+    v.x = in ? v.x : ninf.x; v.y = in ? v.y : ninf.y; v.z = in ? v.z : ninf.z; v.w = in ? v.w : ninf.w;
+    return v;
+  }
+  uint32_t w[4];
+  if (DT == kDtBF16) {
+    const uint16_t* r = reinterpret_cast<const uint16_t*>(row);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int64_t i0 = e + 2 * j, i1 = e + 2 * j + 1;
+      uint32_t lo = r[i0 < V ? i0 : V - 1], hi = r[i1 < V ? i1 : V - 1];
+      lo = i0 < V ? lo : 0xFF80u;
+      hi = i1 < V ? hi : 0xFF80u;
+      w[j] = lo | (hi << 16);
+    }
+  } else {
+    const uint32_t* r = reinterpret_cast<const uint32_t*>(row);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int64_t i0 = e + j;
+      const uint32_t x = r[i0 < V ? i0 : V - 1];
+      w[j] = i0 < V ? x : 0xFF800000u;
+    }
+  }
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+template <int DT> __device__ __forceinline__ float vec_elem(const uint4& v, int j) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  if (DT == kDtBF16) return (j & 1) ? bf16_hi(w[j >> 1]) : bf16_lo(w[j >> 1]);
+  return __uint_as_float(w[j]);
+}
+
+// Scalar read of one logit (any alignment).
+template <int DT> __device__ __forceinline__ float load_elem(const char* __restrict__ row, int64_t e) {
+  if (DT == kDtBF16) return __uint_as_float(uint32_t(reinterpret_cast<const uint16_t*>(row)[e]) << 16);
+  return reinterpret_cast<const float*>(row)[e];
+}
+
+// Logit transform, evaluated in fp32 with exactly these roundings: the difference is rounded,
+// then one fused multiply-add, then one multiply by fl32(1/T).
+__device__ __forceinline__ float transform_logit(float lc, float lu, bool guided, float s, float inv_T) {
+  float l = lc;
+  if (guided) l = __fmaf_rn(s, __fsub_rn(lc, lu), lu);
+  return __fmul_rn(l, inv_T);
+}
+
+// ---------------------------------------------------------------- a row chunk in registers
+// RAW = true keeps bf16 pairs packed (32 registers); otherwise 64 fp32 values.
+template <int DT, bool XF> struct RowRegs {
+  static constexpr bool kRaw = (DT == kDtBF16) && !XF;
+  static constexpr int kE = Vec<DT>::kE;
+  static constexpr int kT = Vec<DT>::kT;
+  static constexpr int kWords = kRaw ? 32 : 64;
+  uint32_t w[kWords];
+
+  __device__ __forceinline__ float get(int k, int j) const {
+    if (kRaw) {
+      uint32_t v = w[k * 4 + (j >> 1)];
+      return (j & 1) ? bf16_hi(v) : bf16_lo(v);
+    }
+    return __uint_as_float(w[k * kE + j]);
+  }
+  __device__ __forceinline__ void set(int k, int j, float v) { w[k * kE + j] = __float_as_uint(v); }
+};
+
+// Load chunk [base, base + kChunk) of a row (and of its unconditional twin when guided) and
+// apply the logit transform when XF.  Out-of-range elements become -inf.
+template <int DT, bool XF, bool AL>
+__device__ __forceinline__ void load_chunk(RowRegs<DT, XF>& r, const char* __restrict__ cond,
+                                           const char* __restrict__ uncond, int64_t base, int V,
+                                           float s, float inv_T) {
+  constexpr int kE = Vec<DT>::kE, kT = Vec<DT>::kT;
+  const int tid = threadIdx.x;
+  uint4 raw[kT];
+#pragma unroll
+  for (int k = 0; k < kT; ++k) raw[k] = load_vec<DT, AL>(cond, base + int64_t(k * kThreads + tid) * kE, V);
+  if (!XF) {
+#pragma unroll
+    for (int k = 0; k < kT; ++k) {
+      r.w[k * 4 + 0] = raw[k].x; r.w[k * 4 + 1] = raw[k].y;
+      r.w[k * 4 + 2] = raw[k].z; r.w[k * 4 + 3] = raw[k].w;
+    }
+  } else {
+    const bool guided = uncond != nullptr;
+    const char* second = guided ? uncond : cond;   // unguided: a harmless re-read, no branch
+#pragma unroll
+    for (int k = 0; k < kT; ++k) {
+      const int64_t e = base + int64_t(k * kThreads + tid) * kE;
+      const uint4 ru = load_vec<DT, AL>(second, e, V);
+#pragma unroll
+      for (int j = 0; j < kE; ++j) {
+        float l = transform_logit(vec_elem<DT>(raw[k], j), vec_elem<DT>(ru, j), guided, s, inv_T);
+        r.set(k, j, (e + j < V) ? l : -INFINITY);
+      }
+    }
+  }
+}
+
+// Per-thread streaming softmax statistics in base-2 units with an INTEGER reference exponent:
+// c = ceil(max*log2e) over the logits seen so far and s = sum 2^(l*log2e - c).  Because c is an
+// integer, every later change of reference is an exact power-of-two scaling.
+template <int DT, bool XF>
+__device__ __forceinline__ void thread_stats(const RowRegs<DT, XF>& r, float& c, float& s) {
+  constexpr int kE = Vec<DT>::kE, kT = Vec<DT>::kT;
+  c = kRefFloor;
+  s = 0.f;
+#pragma unroll
+  for (int k = 0; k < kT; ++k) {
+    float tm = r.get(k, 0);
+#pragma unroll
+    for (int j = 1; j < kE; ++j) tm = fmaxf(tm, r.get(k, j));
+    const float cn = ceilf(tm * kLog2e);
+    if (cn > c) { s *= exp2_fast(c - cn); c = cn; }
+#pragma unroll
+    for (int j = 0; j < kE; ++j) s += exp2_fast(__fmaf_rn(r.get(k, j), kLog2e, -c));
+  }
+}
+
+}  // namespace csd

@@ -1,0 +1,170 @@
+"""Parity of the HIP library (through its C ABI) against the CPU oracle on seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from tests.parity_util import compare_verify, run_oracle, to_numpy
+from workloads import make_workload, uniforms24
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2601_09212_amd as pkg
+    pkg.binding.lib()
+    return pkg
+
+
+def _omega(P, w, L=None, delta=None):
+    om = P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, w.L if L is None else L, w.delta if delta is None else delta, w.nu)
+    return om
+
+
+def _run(P, oracle, w, omega_np, **kw):
+    omega = torch.from_numpy(np.ascontiguousarray(omega_np)).cuda()
+    out = P.verify_workload(w, omega, **kw)
+    torch.cuda.synchronize()
+    return to_numpy(out)
+
+
+# (cfg recipe, B, L, V, dtype): several tiles, partial tiles, ragged tails, several chunks
+SHAPES = [
+    (1, 1, 4, 16384, "f32"),        # config 1 itself
+    (2, 4, 8, 16384, "bf16"),       # config 2 rows
+    (2, 3, 5, 4104, "bf16"),        # partial last tile, vector path
+    (2, 3, 3, 5001, "bf16"),        # V not a multiple of the vector width: element-wise path
+    (1, 2, 3, 1003, "f32"),
+    (1, 2, 2, 8, "f32"),            # tiny vocabulary
+    (2, 2, 2, 1, "bf16"),           # single token
+    (4, 5, 16, 16384, "bf16"),      # config 4 rows
+    (5, 2, 3, 40000, "bf16"),       # three chunks, ragged last chunk
+    (5, 2, 2, 262144, "bf16"),      # config 5 rows
+    (1, 2, 2, 20000, "f32"),        # two chunks fp32
+    (5, 3, 2, 16392, "bf16"),       # second chunk holds one vector
+]
+
+
+@pytest.mark.parametrize("cfg,B,L,V,dtype", SHAPES)
+def test_shapes_against_oracle(P, oracle, cfg, B, L, V, dtype):
+    print("case", cfg, B, L, V, dtype, flush=True)
+    w = make_workload(cfg, device="cuda", B=B, L=L, V=V, dtype=dtype)
+    om = _omega(P, w)
+    gpu = _run(P, oracle, w, om)
+    compare_verify(oracle, w, om, gpu)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("delta", [1.0, 2.0, 4.0])
+def test_modes_and_budgets(P, oracle, mode, delta):
+    w = make_workload(4, device="cuda", B=24, L=8, V=16384)
+    om = _omega(P, w, delta=delta)
+    gpu = _run(P, oracle, w, om, resample_mode=mode)
+    st = compare_verify(oracle, w, om, gpu, resample_mode=mode)
+    assert st["tau_exempt"] + st["token_exempt"] <= 1
+
+
+def test_uniform_schedule_zero_relaxation_and_per_sequence_omega(P, oracle):
+    w = make_workload(2, device="cuda", B=16, L=8, V=16384)
+    om = P.cool_sd_schedule(P.COOL_SD_SCHED_UNIFORM, 8, 1.0)
+    compare_verify(oracle, w, om, _run(P, oracle, w, om))
+    om2 = np.tile(_omega(P, w), (16, 1)).astype(np.float32)
+    om2[::3] = 0.0
+    om2[1::3] *= 3.0
+    gpu = _run(P, oracle, w, om2)
+    assert (gpu["accept_len"][::3] == 0).all()
+    compare_verify(oracle, w, om2, gpu)
+
+
+def test_no_bonus_row(P, oracle):
+    w = make_workload(2, device="cuda", B=8, L=4, V=16384)
+    w.target = w.target[:, :4]                       # non-contiguous view: strides are honoured
+    om = np.full(4, 1e6, np.float32)                 # accept everything
+    gpu = _run(P, oracle, w, om)
+    assert (gpu["accept_len"] == 4).all() and (gpu["next_token"] == -1).all()
+    om = _omega(P, w)
+    compare_verify(oracle, w, om, _run(P, oracle, w, om), has_bonus=False)
+
+
+def test_unaligned_rows(P, oracle):
+    """Row bases that are not 16-byte aligned take the element-wise path."""
+    w = make_workload(2, device="cuda", B=3, L=3, V=4096)
+    flat = torch.zeros(w.target.numel() + 8, dtype=w.target.dtype, device="cuda")
+    flat[3:3 + w.target.numel()] = w.target.reshape(-1)
+    w.target = flat[3:3 + w.target.numel()].view(w.target.shape)
+    om = _omega(P, w)
+    compare_verify(oracle, w, om, _run(P, oracle, w, om))
+
+
+def test_edge_rows(P, oracle):
+    """Degenerate rows: identical models, one-hot rows, all-equal logits, extreme logits,
+    a draft token the target excludes, u = 0 and u next to 1."""
+    torch.manual_seed(0)
+    B, L, V = 8, 4, 16384
+    w = make_workload(1, device="cuda", B=B, L=L, V=V, dtype="f32")
+    t, d = w.target, w.draft
+    d[0] = t[0, :L]                                   # identical: never rejected at omega >= 1
+    t[1] = float("-inf"); t[1, :, 77] = 0.0          # one-hot target
+    d[1] = 0.0                                        # flat draft
+    t[2] = 3.0; d[2] = -2.0                           # all-equal logits on both
+    t[3] = t[3] * 25.0                                # logits up to about +-300
+    d[3] = d[3] * 25.0
+    t[4, :, :] = torch.where(torch.arange(V, device="cuda") % 2 == 0, t[4], torch.full_like(t[4], float("-inf")))
+    w.draft_tokens[4] = torch.tensor([1, 3, 5, 2], dtype=torch.int32)   # p(x~)=0 at odd tokens
+    w.u_accept[5] = 0.0
+    w.u_resample[5] = 0.0
+    w.u_accept[6] = 1.0 - 2.0 ** -24
+    w.u_resample[6] = 1.0 - 2.0 ** -24
+    w.draft_tokens[7] = V - 1
+    for om in (np.ones(L, np.float32), np.array([2.0, 1.0, 0.5, 0.25], np.float32)):
+        gpu = _run(P, oracle, w, om)
+        compare_verify(oracle, w, om, gpu)
+        assert gpu["accept_len"][4] == 0 or w.u_accept[4, 0] == 0
+
+
+def test_resample_entry_point(P, oracle):
+    for V, dtype in ((16384, "bf16"), (5001, "f32"), (50000, "bf16")):
+        w = make_workload(5, device="cuda", B=6, L=1, V=V, dtype=dtype)
+        t, d = w.target[:, 0].contiguous(), w.draft[:, 0].contiguous()
+        om = torch.tensor([0.25, 0.5, 1.0, 1.1, 2.0, 4.0], device="cuda")
+        u = uniforms24(torch.Generator(device="cuda").manual_seed(5), (6,), "cuda")
+        params = P.make_params(t.unsqueeze(1), d.unsqueeze(1), has_bonus=0)
+        ws = torch.empty(max(P.cool_sd_workspace_bytes(params), 256), dtype=torch.uint8, device="cuda")
+        P.cool_sd_workspace_init(ws)
+        for mode in (0, 1):
+            params.resample_mode = mode
+            tok = torch.full((6,), -7, dtype=torch.int32, device="cuda")
+            mass = torch.zeros(6, device="cuda")
+            P.cool_sd_resample(params, t, None, d, None, om, u, tok, mass, ws)
+            torch.cuda.synchronize()
+            ot, om_, g = oracle.resample(t.float().cpu().numpy(), d.float().cpu().numpy(), om.cpu().numpy(),
+                                         u.cpu().numpy(), resample_mode=mode, want_g=True)
+            np.testing.assert_allclose(mass.cpu().numpy(), om_, rtol=1e-5)
+            for b in range(6):
+                if tok[b].item() != ot[b]:
+                    C = np.cumsum(g[b]); v = float(u[b]) * om_[b]; k = tok[b].item()
+                    gap = (v - C[k]) / om_[b] if k < ot[b] else (C[k - 1] - v) / om_[b]
+                    assert g[b][k] > 0 and 0 <= gap <= 1e-6
+        # bonus draw: draft absent
+        tok = torch.full((6,), -7, dtype=torch.int32, device="cuda")
+        P.cool_sd_resample(params, t, None, None, None, None, u, tok, None, ws)
+        torch.cuda.synchronize()
+        ot, _ = oracle.resample(t.float().cpu().numpy(), None, None, u.cpu().numpy())
+        assert (tok.cpu().numpy() == ot).sum() >= 5
+
+
+def test_repeat_calls_share_workspace_and_are_deterministic(P, oracle):
+    w = make_workload(2, device="cuda", B=8, L=8, V=16384)
+    om = torch.from_numpy(_omega(P, w)).cuda()
+    params = P.make_params(w.target, w.draft)
+    ws = torch.empty(P.cool_sd_workspace_bytes(params), dtype=torch.uint8, device="cuda")
+    P.cool_sd_workspace_init(ws)
+    outs = []
+    for _ in range(5):
+        outs.append(to_numpy(P.verify_workload(w, om, workspace=ws)))
+    torch.cuda.synchronize()
+    for o in outs[1:]:
+        for k in o:
+            np.testing.assert_array_equal(o[k], outs[0][k])
+    compare_verify(oracle, w, om.cpu().numpy(), outs[-1])

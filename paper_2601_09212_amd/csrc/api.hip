@@ -14,28 +14,37 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t seq_counter, row_counter, k2_counter, hint, acc, cand_tok, cand_R, part, rowstat, chunk_R, total;
+  size_t k2_counter, chunk_R, thr, rowstat, part, total;
 };
 
-// rows: logit row pairs processed by the first kernel; L1 = L + 1 candidate slots per sequence.
-Layout make_layout(int64_t B, int64_t L, int64_t rows, int64_t nchunks) {
+// rows: all logit rows (target + draft); c1: statistics chunks per row; C: sampling chunks per row.
+Layout make_layout(int64_t B, int64_t rows, int64_t c1, int64_t C) {
   Layout o{};
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes); return at; };
-  o.seq_counter = take(size_t(B) * 4);
-  o.row_counter = take(size_t(rows) * 4);
   o.k2_counter = take(size_t(B) * 4);
-  o.hint = take(size_t(B) * 4);
-  o.acc = take(size_t(B) * L * 4);
-  o.cand_tok = take(size_t(B) * (L + 1) * 4);
-  o.cand_R = take(size_t(B) * (L + 1) * 4);
-  if (nchunks > 1) {
-    o.part = take(size_t(rows) * nchunks * 16);
-    o.rowstat = take(size_t(rows) * 16);
-    o.chunk_R = take(size_t(B) * nchunks * 4);
-  }
+  o.chunk_R = take(size_t(B) * C * 4);
+  o.thr = take(size_t(rows) * 4);
+  o.rowstat = take(size_t(rows) * 8);
+  o.part = take(size_t(rows) * c1 * 8);
   o.total = off;
   return o;
+}
+
+// Statistics-kernel chunking: tiles per chunk (of Vec::kT, kT/2, kT/4 = 16384, 8192, 4096
+// logits).  Small chunks keep more workgroups in flight; top-k needs the whole row in one.
+struct Chunking { int nt1, chunk1; int64_t c1; };
+Chunking pick_chunking(const cool_sd_params* p, int64_t rows) {
+  const int kT = (p->dtype == COOL_SD_BF16) ? 8 : 16;
+  const int kE = (p->dtype == COOL_SD_BF16) ? 8 : 4;
+  int nt = kT / 2;
+  if (p->top_k > 0) nt = kT;
+  else if (rows * ((p->V + 8191) / 8192) < 2048) nt = kT / 4;
+  Chunking c;
+  c.nt1 = nt;
+  c.chunk1 = nt * 256 * kE;
+  c.c1 = (int64_t(p->V) + c.chunk1 - 1) / c.chunk1;
+  return c;
 }
 
 inline int64_t n_chunks(int64_t V) { return (V + csd::kChunk - 1) / csd::kChunk; }
@@ -55,7 +64,7 @@ bool params_ok(const cool_sd_params* p, bool for_resample) {
   if (p->reserved != 0) return false;
   const int64_t L = for_resample ? 1 : p->L;
   const int64_t rows = for_resample ? p->B : int64_t(p->B) * (L + p->has_bonus);
-  if (rows * n_chunks(p->V) > 0x7fffffffLL) return false;   // grid size
+  if (2 * rows * ((int64_t(p->V) + 4095) / 4096) > 0x7fffffffLL) return false;   // grid size
   return true;
 }
 
@@ -71,8 +80,9 @@ int run(const cool_sd_params* p, bool resample_only,
   const int64_t rows = resample_only ? p->B : int64_t(p->B) * (L + hb);
   const int64_t C = n_chunks(p->V);
   if (p->top_k > 0 && C > 1) return COOL_SD_EUNSUPPORTED;
-  if (p->top_k > 0) return COOL_SD_EUNSUPPORTED;   // selection kernel not wired in yet
-  const Layout lay = make_layout(p->B, L, rows, C);
+  const int64_t rows_t = rows, rows_d = d ? int64_t(p->B) * L : 0;
+  const Chunking ch = pick_chunking(p, rows_t + rows_d);
+  const Layout lay = make_layout(p->B, rows_t + rows_d, ch.c1, C);
   if (!ws || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0 || ws_bytes < lay.total) return COOL_SD_EWORKSPACE;
 
   const int kE = (p->dtype == COOL_SD_BF16) ? 8 : 4;
@@ -102,16 +112,16 @@ int run(const cool_sd_params* p, bool resample_only,
   a.nchunks = (int32_t)C;
   a.cfg_scale = p->cfg_scale;
   a.inv_T = 1.0f / p->temperature;
-  a.seq_counter = reinterpret_cast<uint32_t*>(w + lay.seq_counter);
-  a.row_counter = reinterpret_cast<uint32_t*>(w + lay.row_counter);
+  a.rows_t = (int32_t)rows_t; a.rows_d = (int32_t)rows_d;
+  a.nt1 = ch.nt1; a.chunk1 = ch.chunk1; a.c1 = (int32_t)ch.c1;
   a.k2_counter = reinterpret_cast<uint32_t*>(w + lay.k2_counter);
-  a.hint = reinterpret_cast<uint32_t*>(w + lay.hint);
-  a.acc = reinterpret_cast<int32_t*>(w + lay.acc);
-  a.cand_tok = reinterpret_cast<int32_t*>(w + lay.cand_tok);
-  a.cand_R = reinterpret_cast<float*>(w + lay.cand_R);
-  a.part = C > 1 ? reinterpret_cast<float4*>(w + lay.part) : nullptr;
-  a.rowstat = C > 1 ? reinterpret_cast<float4*>(w + lay.rowstat) : nullptr;
-  a.chunk_R = C > 1 ? reinterpret_cast<float*>(w + lay.chunk_R) : nullptr;
+  a.chunk_R = reinterpret_cast<float*>(w + lay.chunk_R);
+  a.thr = reinterpret_cast<float*>(w + lay.thr);
+  a.part = reinterpret_cast<float2*>(w + lay.part);
+  a.rowstat = reinterpret_cast<float2*>(w + lay.rowstat);
+  const bool direct = ch.c1 <= 4;
+  a.stat = direct ? a.part : a.rowstat;
+  a.cs = direct ? (int32_t)ch.c1 : 1;
 
   const bool xf = (tu != nullptr) || (p->temperature != 1.0f) || (p->top_k > 0);
   hipError_t e = csd::launch_verify(a, p->dtype, xf, static_cast<hipStream_t>(stream));
@@ -156,8 +166,12 @@ size_t cool_sd_workspace_bytes(const cool_sd_params* p) {
   if (!params_ok(p, false) && !params_ok(p, true)) return 0;
   const bool full = params_ok(p, false);
   const int64_t L = full ? p->L : 1;
-  const int64_t rows = full ? int64_t(p->B) * (L + p->has_bonus) : p->B;
-  return make_layout(p->B, L, rows, n_chunks(p->V)).total;
+  const int64_t rows = full ? int64_t(p->B) * (2 * L + p->has_bonus) : 2 * int64_t(p->B);
+  const Chunking ch = pick_chunking(p, rows);
+  // sized for the finest chunking so that the answer does not depend on optional inputs
+  const int64_t c1_max = (int64_t(p->V) + 4095) / 4096;
+  (void)ch;
+  return make_layout(p->B, rows, c1_max, n_chunks(p->V)).total;
 }
 
 int cool_sd_workspace_init(void* workspace_dev, size_t workspace_bytes, void* hip_stream) {

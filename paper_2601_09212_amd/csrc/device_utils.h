@@ -1,10 +1,11 @@
 // Device-side building blocks of the Cool-SD verify kernels (gfx950, wave64).
 //
-// Layout of a row chunk on chip.  A workgroup of 256 threads holds one chunk of up to
-// kChunk = 16384 consecutive logits of a row in registers.  The chunk is cut into tiles of
-// 256 x 16 bytes; in tile k thread t owns the 16-byte vector number k*256 + t, i.e. the
-// kE = 8 (bf16) or 4 (fp32) consecutive elements starting at (k*256 + t)*kE.  Every global
-// load instruction therefore reads 1 KiB of consecutive memory per wave.
+// Layout of a row chunk on chip.  A workgroup of 256 threads holds one chunk of NT tiles of a
+// row in registers.  A tile is 256 x 16 bytes; in tile k thread t owns the 16-byte vector
+// number k*256 + t of the chunk, i.e. the kE = 8 (bf16) or 4 (fp32) consecutive elements
+// starting at (k*256 + t)*kE.  Every global load instruction therefore reads 1 KiB of
+// consecutive memory per wave.  The sampling kernel uses chunks of kChunk = 16384 logits
+// (NT = Vec::kT); the statistics kernel uses smaller ones to keep many workgroups in flight.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -127,12 +128,12 @@ __device__ __forceinline__ float transform_logit(float lc, float lu, bool guided
 }
 
 // ---------------------------------------------------------------- a row chunk in registers
-// RAW = true keeps bf16 pairs packed (32 registers); otherwise 64 fp32 values.
-template <int DT, bool XF> struct RowRegs {
+// NT tiles per thread.  bf16 input without a logit transform stays packed (4 words per tile);
+// otherwise kE fp32 values per tile.
+template <int DT, bool XF, int NT> struct RowRegs {
   static constexpr bool kRaw = (DT == kDtBF16) && !XF;
   static constexpr int kE = Vec<DT>::kE;
-  static constexpr int kT = Vec<DT>::kT;
-  static constexpr int kWords = kRaw ? 32 : 64;
+  static constexpr int kWords = NT * (kRaw ? 4 : kE);
   uint32_t w[kWords];
 
   __device__ __forceinline__ float get(int k, int j) const {
@@ -143,36 +144,46 @@ template <int DT, bool XF> struct RowRegs {
     return __uint_as_float(w[k * kE + j]);
   }
   __device__ __forceinline__ void set(int k, int j, float v) { w[k * kE + j] = __float_as_uint(v); }
+  __device__ __forceinline__ void clear() {
+#pragma unroll
+    for (int n = 0; n < kWords; ++n) w[n] = 0u;
+  }
 };
 
-// Load chunk [base, base + kChunk) of a row (and of its unconditional twin when guided) and
-// apply the logit transform when XF.  Out-of-range elements become -inf.
-template <int DT, bool XF, bool AL>
-__device__ __forceinline__ void load_chunk(RowRegs<DT, XF>& r, const char* __restrict__ cond,
+// Load the chunk of NT tiles that starts at element `base` of a row (and of its unconditional
+// twin when guided) and apply the logit transform when XF: guidance, temperature, then the
+// top-k mask "keep l >= thr" (thr = -inf: no mask).  Out-of-range elements become -inf.
+template <int DT, bool XF, bool AL, int NT>
+__device__ __forceinline__ void load_chunk(RowRegs<DT, XF, NT>& r, const char* __restrict__ cond,
                                            const char* __restrict__ uncond, int64_t base, int V,
-                                           float s, float inv_T) {
-  constexpr int kE = Vec<DT>::kE, kT = Vec<DT>::kT;
+                                           float s, float inv_T, float thr) {
+  constexpr int kE = Vec<DT>::kE;
   const int tid = threadIdx.x;
-  uint4 raw[kT];
+  uint4 raw[NT];
 #pragma unroll
-  for (int k = 0; k < kT; ++k) raw[k] = load_vec<DT, AL>(cond, base + int64_t(k * kThreads + tid) * kE, V);
+  for (int k = 0; k < NT; ++k) raw[k] = load_vec<DT, AL>(cond, base + int64_t(k * kThreads + tid) * kE, V);
   if (!XF) {
 #pragma unroll
-    for (int k = 0; k < kT; ++k) {
-      r.w[k * 4 + 0] = raw[k].x; r.w[k * 4 + 1] = raw[k].y;
-      r.w[k * 4 + 2] = raw[k].z; r.w[k * 4 + 3] = raw[k].w;
+    for (int k = 0; k < NT; ++k) {
+      if (RowRegs<DT, XF, NT>::kRaw) {
+        r.w[k * 4 + 0] = raw[k].x; r.w[k * 4 + 1] = raw[k].y;
+        r.w[k * 4 + 2] = raw[k].z; r.w[k * 4 + 3] = raw[k].w;
+      } else {
+#pragma unroll
+        for (int j = 0; j < kE; ++j) r.set(k, j, vec_elem<DT>(raw[k], j));
+      }
     }
   } else {
     const bool guided = uncond != nullptr;
     const char* second = guided ? uncond : cond;   // unguided: a harmless re-read, no branch
 #pragma unroll
-    for (int k = 0; k < kT; ++k) {
+    for (int k = 0; k < NT; ++k) {
       const int64_t e = base + int64_t(k * kThreads + tid) * kE;
       const uint4 ru = load_vec<DT, AL>(second, e, V);
 #pragma unroll
       for (int j = 0; j < kE; ++j) {
         float l = transform_logit(vec_elem<DT>(raw[k], j), vec_elem<DT>(ru, j), guided, s, inv_T);
-        r.set(k, j, (e + j < V) ? l : -INFINITY);
+        r.set(k, j, (e + j < V && l >= thr) ? l : -INFINITY);
       }
     }
   }
@@ -181,13 +192,13 @@ __device__ __forceinline__ void load_chunk(RowRegs<DT, XF>& r, const char* __res
 // Per-thread streaming softmax statistics in base-2 units with an INTEGER reference exponent:
 // c = ceil(max*log2e) over the logits seen so far and s = sum 2^(l*log2e - c).  Because c is an
 // integer, every later change of reference is an exact power-of-two scaling.
-template <int DT, bool XF>
-__device__ __forceinline__ void thread_stats(const RowRegs<DT, XF>& r, float& c, float& s) {
-  constexpr int kE = Vec<DT>::kE, kT = Vec<DT>::kT;
+template <int DT, bool XF, int NT>
+__device__ __forceinline__ void thread_stats(const RowRegs<DT, XF, NT>& r, float& c, float& s) {
+  constexpr int kE = Vec<DT>::kE;
   c = kRefFloor;
   s = 0.f;
 #pragma unroll
-  for (int k = 0; k < kT; ++k) {
+  for (int k = 0; k < NT; ++k) {
     float tm = r.get(k, 0);
 #pragma unroll
     for (int j = 1; j < kE; ++j) tm = fmaxf(tm, r.get(k, j));

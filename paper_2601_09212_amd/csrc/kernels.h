@@ -22,19 +22,19 @@ struct KArgs {
   float* f;
   float* resid_mass;        // [B] or nullptr
   int64_t t_sb, t_sl, d_sb, d_sl, om_sb;   // element strides
-  int32_t B, L, V, has_bonus, top_k, resample_mode, resample_only, aligned, nchunks;
+  int32_t B, L, V, has_bonus, top_k, resample_mode, resample_only, aligned;
+  int32_t nchunks;          // 16384-logit chunks per row (sampling kernel)
+  int32_t rows_t, rows_d;   // target rows B*(L+has_bonus), draft rows B*L (0: no draft)
+  int32_t nt1, chunk1, c1;  // statistics kernel: tiles per chunk, logits per chunk, chunks per row
   float cfg_scale, inv_T;
   // workspace
-  uint32_t* seq_counter;    // [B]       rows of a sequence that have finished
-  uint32_t* row_counter;    // [rows]    chunks of a row that have finished        (nchunks > 1)
-  uint32_t* k2_counter;     // [B]       chunks of the resampled row that finished (nchunks > 1)
-  uint32_t* hint;           // [B]       L - (earliest rejected position seen so far), 0 = none
-  int32_t* acc;             // [B, L]    accept decisions
-  int32_t* cand_tok;        // [B, L+1]  candidate draw of every row that may be sampled from
-  float* cand_R;            // [B, L+1]  its mass
-  float4* part;             // [rows, nchunks] partial (Ct, St, Cd, Sd)             (nchunks > 1)
-  float4* rowstat;          // [rows]    combined (Ct, St, Cd, Sd)                  (nchunks > 1)
-  float* chunk_R;           // [B, nchunks] residual mass per chunk                 (nchunks > 1)
+  float2* part;             // [rows_t + rows_d, c1]  (reference exponent, sum) of every statistics chunk
+  float* thr;               // [rows_t + rows_d]      top-k threshold of every row (top_k > 0)
+  float2* rowstat;          // [rows_t + rows_d]      combined statistics (written only when c1 > 4)
+  const float2* stat;       // what the sequence kernel reads: part (cs = c1 <= 4) or rowstat (cs = 1)
+  int32_t cs;
+  uint32_t* k2_counter;     // [B]           chunks of the sampled row that have finished (nchunks > 1)
+  float* chunk_R;           // [B, nchunks]  residual mass per chunk of the sampled row  (nchunks > 1)
 };
 
 // Enqueue the kernels of one verify (or stand-alone resample) call.  xf: the logit transform

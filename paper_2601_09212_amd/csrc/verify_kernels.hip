@@ -7,41 +7,42 @@
 // G* = Norm([p - min(q, omega p)]_+) (Eq. opt_G) at the first rejected position, or from
 // p_{L+1} when nothing was rejected (Algorithm 1, bonus token).
 //
-// Launch shapes.
-//   verify_rows_kernel      grid = rows x nchunks, rows = B*(L+has_bonus).  One workgroup
-//                           owns one chunk (<= 16384 logits) of one (target, draft) row pair
-//                           and keeps it in registers, so HBM is read exactly once.
-//     nchunks == 1 : fully fused.  The workgroup finishes the row: accept test, and -- only
-//                    if the row is rejected (or is the bonus row) -- the residual mass and
-//                    the inverse-CDF draw from registers.  The last workgroup of a sequence
-//                    to finish (completion counter) does the first-rejection scan and
-//                    writes tau and x_{tau+1}.  One launch per verify call.
-//     nchunks  > 1 : the workgroup publishes its partial (reference exponent, sum); the last
-//                    chunk of a row combines them and does the accept test; the last row of
-//                    a sequence writes tau.  resample_chunks_kernel then re-reads only the
-//                    one row pair per sequence that is sampled from.
-//   resample_chunks_kernel  grid = B x nchunks.
+// Two launches per verify call.
+//   row_stats_kernel   grid = (target rows + draft rows) x chunks.  The HBM-bound pass: every
+//                      logit is read once.  A workgroup streams one small chunk (4K-16K logits)
+//                      of one row through registers and writes the chunk's softmax statistics
+//                      (integer base-2 reference exponent, sum).  No workgroup talks to another;
+//                      few registers, so many workgroups per CU keep loads in flight.  With
+//                      top-k it also selects the row's threshold (row = one chunk then).
+//   sequence_kernel    grid = B x (chunks of 16384 logits).  Per sequence: combine the chunk
+//                      statistics of its rows, accept test at each position, tau = first
+//                      rejection; then re-read ONLY row tau+1 (one row pair of 2L+1, usually
+//                      still in L2 / Infinity Cache), keep it in registers, form the residual
+//                      masses and draw x_{tau+1} by a hierarchical inverse CDF.  When the row
+//                      spans several chunks the last workgroup to finish (ticket) picks the
+//                      chunk that holds u*R and searches it.
 //
-// No workgroup ever waits for another one: cross-workgroup hand-over uses "last one to
-// arrive does the work" counters, which the last arriver resets to zero.
-//
-// Hand-over protocol.  Device-wide release/acquire fences write back and invalidate the whole
-// L2 of an XCD and cost far more than this kernel's memory traffic, so none is used.  Instead
-// every value that another workgroup of the same launch will read is written with an
-// agent-scope atomic store and read with an agent-scope atomic load (both bypass the
-// per-XCD L2), by one thread, which waits for its stores to complete (s_waitcnt vmcnt(0))
-// before it takes its ticket with an agent-scope atomic add.  The reader only reads after
-// it has seen the final ticket value.
+// Hand-over between workgroups of one launch (sequence_kernel with several chunks only).
+// Device-wide release/acquire fences write back and invalidate a whole L2 and cost far more
+// than this kernel's memory traffic, so none is used.  A value that another workgroup of the
+// same launch reads is written with an agent-scope atomic store and read with an agent-scope
+// atomic load (both bypass the per-XCD L2) by one thread, which waits for its stores to
+// complete (s_waitcnt vmcnt(0)) before it takes its ticket with an agent-scope atomic add.
+// The reader only reads after it has seen the final ticket value.  No workgroup ever waits
+// for another one; the last arriver resets the ticket to zero.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
 
 #include "device_utils.h"
 #include "kernels.h"
+#include "topk.h"
 
 namespace csd {
 
 enum { kModeOpt = 0, kModeVanilla = 1, kModeP = 2 };
+
+template <int DT, bool XF> using Regs = RowRegs<DT, XF, Vec<DT>::kT>;   // a 16384-logit chunk
 
 struct Smem {
   float red_c[2][kWaves];
@@ -53,6 +54,7 @@ struct Smem {
   int pick_last[kWaves];
   int bcast_i;
   int flag;
+  float4 rowstat;
 };
 
 template <typename T> __device__ __forceinline__ T coherent_load(const T* p) {
@@ -71,60 +73,107 @@ __device__ __forceinline__ bool ticket_is_last(uint32_t* counter, uint32_t n) {
   return old == n - 1u;
 }
 
-// Wave-0-only tail of a row: publish the accept decision, take the sequence's ticket and, as
-// the last row of the sequence, find tau = first rejected position (Algorithm 1's break) and
-// emit the outputs.  Must be called by all 64 lanes of wave 0.
-__device__ __forceinline__ void finish_sequence(const KArgs& a, int b, int i, bool bonus, int acc,
-                                                bool have_cand, int cand, float R, bool fused) {
-  const int lane = threadIdx.x;
-  const int rps = a.L + a.has_bonus;
-  int last = 0;
-  if (lane == 0) {
-    if (!bonus) coherent_store(&a.acc[int64_t(b) * a.L + i], acc);
-    if (have_cand) {
-      coherent_store(&a.cand_tok[int64_t(b) * (a.L + 1) + i], cand);
-      coherent_store(&a.cand_R[int64_t(b) * (a.L + 1) + i], R);
+__device__ __forceinline__ const char* row_ptr(const void* base, int64_t elem_off, int es) {
+  return base ? reinterpret_cast<const char*>(base) + elem_off * es : nullptr;
+}
+
+// ============================================================================ kernel 1
+// Softmax statistics of one chunk of one row.  Rows are numbered: target rows first
+// (b*(L+has_bonus) + i), then draft rows (rows_t + b*L + i).
+template <int DT, bool XF, bool AL, int NT>
+__global__ __launch_bounds__(kThreads) void row_stats_kernel(const KArgs a) {
+  constexpr int kE = Vec<DT>::kE, kES = Vec<DT>::kES;
+  __shared__ float red_c[kWaves], red_s[kWaves];
+  const int C1 = a.c1;
+  const int r = blockIdx.x / C1, c = blockIdx.x - r * C1;
+  const bool is_draft = r >= a.rows_t;
+  const int rr = is_draft ? r - a.rows_t : r;
+  const int per = is_draft ? a.L : a.L + a.has_bonus;
+  const int b = rr / per, i = rr - b * per;
+  const int64_t off = is_draft ? int64_t(b) * a.d_sb + int64_t(i) * a.d_sl
+                               : int64_t(b) * a.t_sb + int64_t(i) * a.t_sl;
+  const char* cond = row_ptr(is_draft ? a.d : a.t, off, kES);
+  const char* uncond = row_ptr(is_draft ? a.du : a.tu, off, kES);
+  const int64_t base = int64_t(c) * (NT * kThreads * kE);
+
+  RowRegs<DT, XF, NT> x;
+  load_chunk<DT, XF, AL, NT>(x, cond, uncond, base, a.V, a.cfg_scale, a.inv_T, -INFINITY);
+  if constexpr (XF) {
+    if (a.top_k > 0) {   // the chunk is the whole row here
+      __shared__ TopkSmem ts;
+      float vals[NT * kE];
+#pragma unroll
+      for (int n = 0; n < NT * kE; ++n) vals[n] = __uint_as_float(x.w[n]);
+      const float thr = topk_threshold<NT * kE>(vals, a.top_k, ts);
+#pragma unroll
+      for (int n = 0; n < NT * kE; ++n) x.w[n] = (vals[n] >= thr) ? x.w[n] : 0xFF800000u;
+      if (threadIdx.x == 0) a.thr[r] = thr;
     }
-    last = ticket_is_last(&a.seq_counter[b], (uint32_t)rps) ? 1 : 0;
   }
-  last = __shfl(last, 0, 64);
-  if (!last) return;
-  int first = a.L;
-  for (int j = lane; j < a.L; j += 64)
-    if (coherent_load(&a.acc[int64_t(b) * a.L + j]) == 0) first = min(first, j);
-  const int tau = wave_min_i(first);
-  if (lane == 0) {
-    a.accept_len[b] = tau;
-    coherent_store(&a.seq_counter[b], 0u);
-    coherent_store(&a.hint[b], 0u);
-    if (fused) {
-      int tok = -1;
-      float mass = 0.f;
-      if (tau < a.L || a.has_bonus) {
-        tok = coherent_load(&a.cand_tok[int64_t(b) * (a.L + 1) + tau]);
-        mass = coherent_load(&a.cand_R[int64_t(b) * (a.L + 1) + tau]);
-      }
-      a.next_token[b] = tok;
-      if (a.resid_mass) a.resid_mass[b] = mass;
-    }
+  float ct, st;
+  thread_stats<DT, XF, NT>(x, ct, st);
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const float wc = wave_max(ct);
+  const float ws = wave_sum(st * exp2_fast(ct - wc));     // exact power-of-two rescale
+  if (lane == 0) { red_c[wv] = wc; red_s[wv] = ws; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const float C = fmaxf(fmaxf(red_c[0], red_c[1]), fmaxf(red_c[2], red_c[3]));
+    float S = red_s[0] * exp2_fast(red_c[0] - C);
+    S = __fadd_rn(S, red_s[1] * exp2_fast(red_c[1] - C));
+    S = __fadd_rn(S, red_s[2] * exp2_fast(red_c[2] - C));
+    S = __fadd_rn(S, red_s[3] * exp2_fast(red_c[3] - C));
+    a.part[int64_t(r) * C1 + c] = make_float2(C, S);
   }
 }
 
-// Block-wide combine of per-thread (c, s) pairs of two rows.  Result in every thread.
-__device__ __forceinline__ void block_stats(float c0, float s0, float c1, float s1, Smem& sm,
-                                            float& C0, float& S0, float& C1, float& S1) {
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  float w0 = wave_max(c0), w1 = wave_max(c1);
-  if (lane == 0) { sm.red_c[0][wv] = w0; sm.red_c[1][wv] = w1; }
-  __syncthreads();
-  C0 = fmaxf(fmaxf(sm.red_c[0][0], sm.red_c[0][1]), fmaxf(sm.red_c[0][2], sm.red_c[0][3]));
-  C1 = fmaxf(fmaxf(sm.red_c[1][0], sm.red_c[1][1]), fmaxf(sm.red_c[1][2], sm.red_c[1][3]));
-  float t0 = wave_sum(s0 * exp2_fast(c0 - C0));   // exact power-of-two rescale
-  float t1 = wave_sum(s1 * exp2_fast(c1 - C1));
-  if (lane == 0) { sm.red_s[0][wv] = t0; sm.red_s[1][wv] = t1; }
-  __syncthreads();
-  S0 = ((sm.red_s[0][0] + sm.red_s[0][1]) + sm.red_s[0][2]) + sm.red_s[0][3];
-  S1 = ((sm.red_s[1][0] + sm.red_s[1][1]) + sm.red_s[1][2]) + sm.red_s[1][3];
+// Optional middle kernel (rows with more than kMaxDirect statistics chunks): one wave per row
+// combines the row's chunk statistics into one (reference exponent, sum) pair.  Lanes take
+// chunks cc = lane, lane+64, ...; the reference is the maximum, sums are rescaled by exact
+// powers of two and added in a fixed order.
+__global__ __launch_bounds__(kThreads) void combine_rows_kernel(const KArgs a) {
+  const int r = blockIdx.x * kWaves + (threadIdx.x >> 6);
+  if (r >= a.rows_t + a.rows_d) return;
+  const int lane = threadIdx.x & 63;
+  const float2* p = a.part + int64_t(r) * a.c1;
+  float m = kRefFloor;
+  for (int cc = lane; cc < a.c1; cc += 64) m = fmaxf(m, p[cc].x);
+  m = wave_max(m);
+  float s = 0.f;
+  for (int cc = lane; cc < a.c1; cc += 64) s = __fadd_rn(s, p[cc].y * exp2_fast(p[cc].x - m));
+  s = wave_sum(s);
+  if (lane == 0) a.rowstat[r] = make_float2(m, s);
+}
+
+// Statistics of row r from at most kMaxDirect entries (a.stat, a.cs entries per row), all
+// loaded before any is used: reference = max, sum rescaled by exact powers of two.
+constexpr int kMaxDirect = 4;
+__device__ __forceinline__ void combine_row(const KArgs& a, int r, float& C, float& S) {
+  const float2* p = a.stat + int64_t(r) * a.cs;
+  float2 v[kMaxDirect];
+#pragma unroll
+  for (int cc = 0; cc < kMaxDirect; ++cc) {
+    v[cc] = p[cc < a.cs ? cc : 0];
+    if (cc >= a.cs) v[cc] = make_float2(kRefFloor, 0.f);
+  }
+  float m = kRefFloor;
+#pragma unroll
+  for (int cc = 0; cc < kMaxDirect; ++cc) m = fmaxf(m, v[cc].x);
+  float s = 0.f;
+#pragma unroll
+  for (int cc = 0; cc < kMaxDirect; ++cc) s = __fadd_rn(s, v[cc].y * exp2_fast(v[cc].x - m));
+  C = m; S = s;
+}
+
+// Transformed logit of one token of a row (scalar path, used for x~_i).
+template <int DT>
+__device__ __forceinline__ float token_logit(const char* cond, const char* uncond, int x, bool xf,
+                                             float s, float inv_T, float thr) {
+  float lc = load_elem<DT>(cond, x);
+  if (!xf) return lc;
+  float lu = uncond ? load_elem<DT>(uncond, x) : 0.f;
+  const float l = transform_logit(lc, lu, uncond != nullptr, s, inv_T);
+  return l >= thr ? l : -INFINITY;
 }
 
 // Unnormalised resampling mass of one token.  p = 2^(lt*log2e - Ct) / St etc.
@@ -142,7 +191,7 @@ __device__ __forceinline__ float resid_elem(float lt, float ld, const ResidCoef&
 
 // Per-thread, per-tile partial masses, then block-wide tile totals T[k] (in sm.tile_tot).
 template <int DT, bool XF>
-__device__ __forceinline__ void chunk_masses(const RowRegs<DT, XF>& rt, const RowRegs<DT, XF>& rd,
+__device__ __forceinline__ void chunk_masses(const Regs<DT, XF>& rt, const Regs<DT, XF>& rd,
                                              const ResidCoef& k, float (&part)[Vec<DT>::kT], Smem& sm) {
   constexpr int kE = Vec<DT>::kE, kT = Vec<DT>::kT;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -182,7 +231,7 @@ template <int kT> __device__ __forceinline__ float chunk_total(const Smem& sm) {
 // positive mass even when the levels' roundings disagree.  Returns the offset in the chunk
 // (same value in every thread), or -1 if the chunk holds no mass.
 template <int DT, bool XF>
-__device__ __forceinline__ int chunk_select(const RowRegs<DT, XF>& rt, const RowRegs<DT, XF>& rd,
+__device__ __forceinline__ int chunk_select(const Regs<DT, XF>& rt, const Regs<DT, XF>& rd,
                                             const ResidCoef& k, const float (&part)[Vec<DT>::kT],
                                             float v, Smem& sm) {
   constexpr int kE = Vec<DT>::kE, kT = Vec<DT>::kT;
@@ -251,252 +300,160 @@ __device__ __forceinline__ int chunk_select(const RowRegs<DT, XF>& rt, const Row
   return sm.bcast_i;
 }
 
-__device__ __forceinline__ const char* row_ptr(const void* base, int64_t elem_off, int es) {
-  return base ? reinterpret_cast<const char*>(base) + elem_off * es : nullptr;
-}
-
-// Transformed logit of one token of a row (scalar path, used for x~_i).
-template <int DT>
-__device__ __forceinline__ float token_logit(const char* cond, const char* uncond, int x, bool xf,
-                                             float s, float inv_T) {
-  float lc = load_elem<DT>(cond, x);
-  if (!xf) return lc;
-  float lu = uncond ? load_elem<DT>(uncond, x) : 0.f;
-  return transform_logit(lc, lu, uncond != nullptr, s, inv_T);
-}
-
+// ============================================================================ kernel 2
 template <int DT, bool XF, bool AL>
-__global__ __launch_bounds__(kThreads) void verify_rows_kernel(const KArgs a) {
-  constexpr int kT = Vec<DT>::kT, kES = Vec<DT>::kES;
-  __shared__ Smem sm;
-  const int C = a.nchunks;
-  const int row = blockIdx.x / C, c = blockIdx.x - row * C;
-  const int rps = a.L + a.has_bonus;
-  const int b = row / rps, i = row - b * rps;
-  const bool bonus = a.resample_only ? (a.d == nullptr) : (i == a.L);
-  const int64_t base = int64_t(c) * kChunk;
-
-  const char* t_c = row_ptr(a.t, int64_t(b) * a.t_sb + int64_t(i) * a.t_sl, kES);
-  const char* t_u = row_ptr(a.tu, int64_t(b) * a.t_sb + int64_t(i) * a.t_sl, kES);
-  const char* d_c = bonus ? nullptr : row_ptr(a.d, int64_t(b) * a.d_sb + int64_t(i) * a.d_sl, kES);
-  const char* d_u = bonus ? nullptr : row_ptr(a.du, int64_t(b) * a.d_sb + int64_t(i) * a.d_sl, kES);
-
-  RowRegs<DT, XF> rt, rd;
-  load_chunk<DT, XF, AL>(rt, t_c, t_u, base, a.V, a.cfg_scale, a.inv_T);
-  if (!bonus) {
-    load_chunk<DT, XF, AL>(rd, d_c, d_u, base, a.V, a.cfg_scale, a.inv_T);
-  } else {
-#pragma unroll
-    for (int n = 0; n < RowRegs<DT, XF>::kWords; ++n) rd.w[n] = 0u;   // never read in mode P
-  }
-
-  float ct, st, cd = kRefFloor, sd = 0.f;
-  thread_stats<DT, XF>(rt, ct, st);
-  if (!bonus) thread_stats<DT, XF>(rd, cd, sd);
-  float Ct, St, Cd, Sd;
-  block_stats(ct, st, cd, sd, sm, Ct, St, Cd, Sd);
-
-  if (C > 1) {
-    // publish the chunk's partial statistics; the last chunk of the row combines them
-    if (threadIdx.x >= 64) return;                 // the rest is scalar work for wave 0
-    int last = 0;
-    if (threadIdx.x == 0) {
-      float4* pp = &a.part[int64_t(row) * C + c];
-      coherent_store(&pp->x, Ct); coherent_store(&pp->y, St);
-      coherent_store(&pp->z, Cd); coherent_store(&pp->w, Sd);
-      last = ticket_is_last(&a.row_counter[row], (uint32_t)C) ? 1 : 0;
-    }
-    if (!__shfl(last, 0, 64)) return;
-    float mt = kRefFloor, md = kRefFloor;
-    for (int cc = 0; cc < C; ++cc) {
-      mt = fmaxf(mt, coherent_load(&a.part[int64_t(row) * C + cc].x));
-      md = fmaxf(md, coherent_load(&a.part[int64_t(row) * C + cc].z));
-    }
-    float sst = 0.f, ssd = 0.f;
-    for (int cc = 0; cc < C; ++cc) {
-      const float4* pp = &a.part[int64_t(row) * C + cc];
-      sst = __fadd_rn(sst, coherent_load(&pp->y) * exp2_fast(coherent_load(&pp->x) - mt));
-      ssd = __fadd_rn(ssd, coherent_load(&pp->w) * exp2_fast(coherent_load(&pp->z) - md));
-    }
-    Ct = mt; St = sst; Cd = md; Sd = ssd;
-    if (threadIdx.x == 0) {
-      coherent_store(&a.row_counter[row], 0u);
-      a.rowstat[row] = make_float4(Ct, St, Cd, Sd);   // read by the next kernel only
-    }
-  }
-
-  // ---- row level: acceptance test of position i (Eq. relax, Algorithm 1)
-  int acc = 1;
-  const float omega = bonus ? 1.f : a.omega[int64_t(b) * a.om_sb + i];
-  if (!bonus && !a.resample_only) {
-    int x = a.tokens[int64_t(b) * a.L + i];
-    x = min(max(x, 0), a.V - 1);
-    float lt = token_logit<DT>(t_c, t_u, x, XF, a.cfg_scale, a.inv_T);
-    float ld = token_logit<DT>(d_c, d_u, x, XF, a.cfg_scale, a.inv_T);
-    // exponents of p(x~) and q(x~) in base-2 units; the ratio p/q is formed from their
-    // difference so that it survives when both probabilities underflow fp32
-    const float et = __fmaf_rn(lt, kLog2e, -Ct), ed = __fmaf_rn(ld, kLog2e, -Cd);
-    const float p_x = exp2_fast(et) / St;
-    const float q_x = exp2_fast(ed) / Sd;
-    const float ratio = __fmul_rn(exp2_fast(__fsub_rn(et, ed)), Sd / St);
-    // f = min{1, omega p/q}; a token the draft excludes (q = 0) has f = 1, also at 0/0
-    const float fi = (ld == -INFINITY) ? 1.f : ((omega > 0.f) ? fminf(1.f, __fmul_rn(omega, ratio)) : 0.f);
-    const float u = a.u_acc[int64_t(b) * a.L + i];
-    acc = (u <= fi) ? 1 : 0;
-    if (threadIdx.x == 0) {
-      const int64_t o = int64_t(b) * a.L + i;
-      if (a.p_tok) a.p_tok[o] = p_x;
-      if (a.q_tok) a.q_tok[o] = q_x;
-      if (a.f) a.f[o] = fi;
-    }
-  } else if (a.resample_only) {
-    acc = 0;
-  }
-
-  if (C > 1) {                                     // wave 0 of the row's last chunk
-    if (!a.resample_only) finish_sequence(a, b, i, bonus, acc, false, -1, 0.f, false);
-    return;
-  }
-
-  // ---- does this row's resampling law have to be sampled?  Only the FIRST rejected position
-  // of a sequence is (Algorithm 1 breaks there), or the bonus row if nothing is rejected.  A
-  // rejected row raises hint[b] to L - i and skips the work if an earlier position already
-  // raised it higher; the bonus row skips if any position did.  The first rejected position
-  // never skips, whatever the order in which workgroups run.
-  bool need = a.resample_only != 0;
-  if (!need && (bonus || acc == 0)) {
-    if (threadIdx.x == 0) {
-      uint32_t mine = bonus ? 0u : uint32_t(a.L - i);
-      uint32_t old = bonus ? coherent_load(&a.hint[b])
-                           : __hip_atomic_fetch_max(&a.hint[b], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      sm.flag = bonus ? (old == 0u) : (mine > old);
-    }
-    __syncthreads();
-    need = sm.flag != 0;
-  }
-
-  // ---- candidate draw from this row's resampling law (Eq. opt_G / Eq. g_tsd / p_{L+1})
-  int cand = -1;
-  float R = 0.f;
-  if (need) {
-    ResidCoef k{Ct, 1.f / St, Cd, bonus ? 1.f : 1.f / Sd, omega,
-                bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
-    float part[kT];
-    chunk_masses<DT, XF>(rt, rd, k, part, sm);
-    R = chunk_total<kT>(sm);
-    if (!(R > 0.f)) {  // no rejection possible at this position: any law is optimal, use p
-      k.mode = kModeP;
-      chunk_masses<DT, XF>(rt, rd, k, part, sm);
-      R = chunk_total<kT>(sm);
-    }
-    const float u = a.u_res[b];
-    cand = chunk_select<DT, XF>(rt, rd, k, part, __fmul_rn(u, R), sm);
-    if (cand >= a.V) cand = a.V - 1;
-  }
-
-  if (a.resample_only) {
-    if (threadIdx.x == 0) {
-      a.next_token[b] = cand;
-      if (a.resid_mass) a.resid_mass[b] = R;
-    }
-    return;
-  }
-  if (threadIdx.x >= 64) return;
-  finish_sequence(a, b, i, bonus, acc, need, cand, R, true);
-}
-
-// Second kernel of the chunked path: per sequence, draw x_{tau+1} from the resampling law of
-// row tau+1 (Eq. opt_G), whose logits are re-read once.  Workgroup (b, c) computes the mass of
-// chunk c; the last one to finish picks the chunk that contains u*R and searches it.
-template <int DT, bool XF, bool AL>
-__global__ __launch_bounds__(kThreads) void resample_chunks_kernel(const KArgs a) {
+__global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
   constexpr int kT = Vec<DT>::kT, kES = Vec<DT>::kES;
   __shared__ Smem sm;
   const int C = a.nchunks;
   const int b = blockIdx.x / C, c = blockIdx.x - b * C;
   const int rps = a.L + a.has_bonus;
-  const int j = a.resample_only ? 0 : a.accept_len[b];
-  if (!a.resample_only && j >= a.L && !a.has_bonus) {
-    if (c == 0 && threadIdx.x == 0) {
-      a.next_token[b] = -1;
-      if (a.resid_mass) a.resid_mass[b] = 0.f;
+  const bool masked = XF && a.top_k > 0;
+
+  // ---- accept test at every position (Eq. relax), tau = first rejection (Algorithm 1)
+  int j = 0;
+  if (!a.resample_only) {
+    int first = a.L;
+    for (int i = threadIdx.x; i < a.L; i += kThreads) {
+      const int rt_ = b * rps + i, rd_ = a.rows_t + b * a.L + i;
+      float Ct, St, Cd, Sd;
+      combine_row(a, rt_, Ct, St);
+      combine_row(a, rd_, Cd, Sd);
+      const char* t_c = row_ptr(a.t, int64_t(b) * a.t_sb + int64_t(i) * a.t_sl, kES);
+      const char* t_u = row_ptr(a.tu, int64_t(b) * a.t_sb + int64_t(i) * a.t_sl, kES);
+      const char* d_c = row_ptr(a.d, int64_t(b) * a.d_sb + int64_t(i) * a.d_sl, kES);
+      const char* d_u = row_ptr(a.du, int64_t(b) * a.d_sb + int64_t(i) * a.d_sl, kES);
+      int x = a.tokens[int64_t(b) * a.L + i];
+      x = min(max(x, 0), a.V - 1);
+      const float lt = token_logit<DT>(t_c, t_u, x, XF, a.cfg_scale, a.inv_T, masked ? a.thr[rt_] : -INFINITY);
+      const float ld = token_logit<DT>(d_c, d_u, x, XF, a.cfg_scale, a.inv_T, masked ? a.thr[rd_] : -INFINITY);
+      // exponents of p(x~) and q(x~) in base-2 units; the ratio p/q is formed from their
+      // difference so that it survives when both probabilities underflow fp32
+      const float et = __fmaf_rn(lt, kLog2e, -Ct), ed = __fmaf_rn(ld, kLog2e, -Cd);
+      const float ratio = __fmul_rn(exp2_fast(__fsub_rn(et, ed)), Sd / St);
+      const float omega = a.omega[int64_t(b) * a.om_sb + i];
+      // f = min{1, omega p/q}; a token the draft excludes (q = 0) has f = 1, also at 0/0
+      const float fi = (ld == -INFINITY) ? 1.f : ((omega > 0.f) ? fminf(1.f, __fmul_rn(omega, ratio)) : 0.f);
+      if (!(a.u_acc[int64_t(b) * a.L + i] <= fi)) first = min(first, i);
+      if (c == 0) {
+        const int64_t o = int64_t(b) * a.L + i;
+        if (a.p_tok) a.p_tok[o] = exp2_fast(et) / St;
+        if (a.q_tok) a.q_tok[o] = exp2_fast(ed) / Sd;
+        if (a.f) a.f[o] = fi;
+      }
     }
-    return;
+    first = wave_min_i(first);
+    if ((threadIdx.x & 63) == 0) sm.pick_first[threadIdx.x >> 6] = first;
+    __syncthreads();
+    j = min(min(sm.pick_first[0], sm.pick_first[1]), min(sm.pick_first[2], sm.pick_first[3]));
+    if (c == 0 && threadIdx.x == 0) a.accept_len[b] = j;
+    if (j >= a.L && !a.has_bonus) {
+      if (c == 0 && threadIdx.x == 0) {
+        a.next_token[b] = -1;
+        if (a.resid_mass) a.resid_mass[b] = 0.f;
+      }
+      return;
+    }
   }
+
+  // ---- the row that is sampled from: position tau+1, or the bonus row (Algorithm 1)
   const bool bonus = a.resample_only ? (a.d == nullptr) : (j == a.L);
-  const int row = b * rps + j;
+  const int rt_ = b * rps + j, rd_ = a.rows_t + b * a.L + j;
+  if (threadIdx.x == 0) {
+    float Ct, St, Cd = kRefFloor, Sd = 0.f;
+    combine_row(a, rt_, Ct, St);
+    if (!bonus) combine_row(a, rd_, Cd, Sd);
+    sm.rowstat = make_float4(Ct, St, Cd, Sd);
+  }
+  __syncthreads();
+  const float4 rs = sm.rowstat;
   const char* t_c = row_ptr(a.t, int64_t(b) * a.t_sb + int64_t(j) * a.t_sl, kES);
   const char* t_u = row_ptr(a.tu, int64_t(b) * a.t_sb + int64_t(j) * a.t_sl, kES);
   const char* d_c = bonus ? nullptr : row_ptr(a.d, int64_t(b) * a.d_sb + int64_t(j) * a.d_sl, kES);
   const char* d_u = bonus ? nullptr : row_ptr(a.du, int64_t(b) * a.d_sb + int64_t(j) * a.d_sl, kES);
-  const float4 rs = a.rowstat[row];
+  const float thr_t = masked ? a.thr[rt_] : -INFINITY;
+  const float thr_d = (masked && !bonus) ? a.thr[rd_] : -INFINITY;
   const float omega = bonus ? 1.f : a.omega[int64_t(b) * a.om_sb + j];
   ResidCoef k{rs.x, 1.f / rs.y, rs.z, bonus ? 1.f : 1.f / rs.w, omega,
               bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
 
-  RowRegs<DT, XF> rt, rd;
+  Regs<DT, XF> rt, rd;
   float part[kT];
   auto load_pair = [&](int cc) {
     const int64_t base = int64_t(cc) * kChunk;
-    load_chunk<DT, XF, AL>(rt, t_c, t_u, base, a.V, a.cfg_scale, a.inv_T);
-    if (!bonus) {
-      load_chunk<DT, XF, AL>(rd, d_c, d_u, base, a.V, a.cfg_scale, a.inv_T);
-    } else {
-#pragma unroll
-      for (int n = 0; n < RowRegs<DT, XF>::kWords; ++n) rd.w[n] = 0u;
-    }
+    load_chunk<DT, XF, AL, kT>(rt, t_c, t_u, base, a.V, a.cfg_scale, a.inv_T, thr_t);
+    if (!bonus) load_chunk<DT, XF, AL, kT>(rd, d_c, d_u, base, a.V, a.cfg_scale, a.inv_T, thr_d);
+    else rd.clear();                                  // never read in mode P
   };
   load_pair(c);
   chunk_masses<DT, XF>(rt, rd, k, part, sm);
-  const float Rc = chunk_total<kT>(sm);
-  if (threadIdx.x == 0) {
-    coherent_store(&a.chunk_R[int64_t(b) * C + c], Rc);
-    sm.flag = ticket_is_last(&a.k2_counter[b], (uint32_t)C) ? 1 : 0;
-  }
-  __syncthreads();
-  if (!sm.flag) return;
+  float R = chunk_total<kT>(sm);
+  float vsel;        // remaining mass to walk inside the selected chunk
+  int cs = c;        // selected chunk
 
-  // total mass over the chunks, ascending
-  float R = 0.f;
-  for (int cc = 0; cc < C; ++cc) R = __fadd_rn(R, coherent_load(&a.chunk_R[int64_t(b) * C + cc]));
-  const bool fallback = !(R > 0.f);   // no rejection possible here: any law is optimal, use p
-  auto chunk_mass = [&](int cc) -> float {
-    if (!fallback) return coherent_load(&a.chunk_R[int64_t(b) * C + cc]);
-    const float4 pp = a.part[int64_t(row) * C + cc];
-    return __fmul_rn(__fmul_rn(pp.y, exp2_fast(pp.x - rs.x)), k.at);
-  };
-  if (fallback) {
-    k.mode = kModeP;
-    R = 0.f;
-    for (int cc = 0; cc < C; ++cc) R = __fadd_rn(R, chunk_mass(cc));
-  }
-  const float v = __fmul_rn(a.u_res[b], R);
-  int cs = -1, clast = -1;
-  float cbase = 0.f, cbase_last = 0.f, cum = 0.f;
-  for (int cc = 0; cc < C; ++cc) {
-    const float m = chunk_mass(cc);
-    if (m > 0.f) {
-      if (cs < 0 && __fadd_rn(cum, m) > v) { cs = cc; cbase = cum; }
-      clast = cc; cbase_last = cum;
+  if (C == 1) {
+    if (!(R > 0.f)) {  // no rejection possible at this position: any law is optimal, use p
+      k.mode = kModeP;
+      chunk_masses<DT, XF>(rt, rd, k, part, sm);
+      R = chunk_total<kT>(sm);
     }
-    cum = __fadd_rn(cum, m);
-  }
-  if (cs < 0) { cs = clast; cbase = cbase_last; }
-  int token = 0;
-  if (cs >= 0) {
+    vsel = __fmul_rn(a.u_res[b], R);
+  } else {
+    // several chunks: publish this chunk's mass; the last workgroup to arrive goes on
+    if (threadIdx.x == 0) {
+      coherent_store(&a.chunk_R[int64_t(b) * C + c], R);
+      sm.flag = ticket_is_last(&a.k2_counter[b], (uint32_t)C) ? 1 : 0;
+    }
+    __syncthreads();
+    if (!sm.flag) return;
+    R = 0.f;
+    for (int cc = 0; cc < C; ++cc) R = __fadd_rn(R, coherent_load(&a.chunk_R[int64_t(b) * C + cc]));
+    const bool fallback = !(R > 0.f);
+    // mass of chunk cc under the law in force; the fallback law p is summed from the chunk
+    // statistics of kernel 1 (c1 statistics chunks per 16384-logit chunk)
+    const int per = kChunk / a.chunk1;
+    auto chunk_mass = [&](int cc) -> float {
+      if (!fallback) return coherent_load(&a.chunk_R[int64_t(b) * C + cc]);
+      float m = 0.f;
+      for (int q = cc * per; q < min((cc + 1) * per, a.c1); ++q) {
+        const float2 pp = a.part[int64_t(rt_) * a.c1 + q];
+        m = __fadd_rn(m, __fmul_rn(__fmul_rn(pp.y, exp2_fast(pp.x - rs.x)), k.at));
+      }
+      return m;
+    };
+    if (fallback) {
+      k.mode = kModeP;
+      R = 0.f;
+      for (int cc = 0; cc < C; ++cc) R = __fadd_rn(R, chunk_mass(cc));
+    }
+    const float v = __fmul_rn(a.u_res[b], R);
+    int clast = -1;
+    float cbase = 0.f, cbase_last = 0.f, cum = 0.f;
+    cs = -1;
+    for (int cc = 0; cc < C; ++cc) {
+      const float m = chunk_mass(cc);
+      if (m > 0.f) {
+        if (cs < 0 && __fadd_rn(cum, m) > v) { cs = cc; cbase = cum; }
+        clast = cc; cbase_last = cum;
+      }
+      cum = __fadd_rn(cum, m);
+    }
+    if (cs < 0) { cs = clast; cbase = cbase_last; }
+    if (cs < 0) cs = 0;
+    vsel = v - cbase;
     if (cs != c || fallback) {
       __syncthreads();
       load_pair(cs);
       chunk_masses<DT, XF>(rt, rd, k, part, sm);
     }
-    const int off = chunk_select<DT, XF>(rt, rd, k, part, v - cbase, sm);
-    token = cs * kChunk + max(off, 0);
   }
+  const int off = chunk_select<DT, XF>(rt, rd, k, part, vsel, sm);
+  int token = cs * kChunk + max(off, 0);
   if (token >= a.V) token = a.V - 1;
   if (threadIdx.x == 0) {
     a.next_token[b] = token;
     if (a.resid_mass) a.resid_mass[b] = R;
-    coherent_store(&a.k2_counter[b], 0u);
+    if (C > 1) coherent_store(&a.k2_counter[b], 0u);
   }
 }
 
@@ -514,20 +471,31 @@ static hipError_t checked(const char* what) {
   return e;
 }
 
+template <int DT, bool XF, bool AL, int NT>
+static hipError_t launch_stats(const KArgs& a, hipStream_t stream) {
+  const int64_t grid = (int64_t(a.rows_t) + a.rows_d) * a.c1;
+  hipLaunchKernelGGL((row_stats_kernel<DT, XF, AL, NT>), dim3((unsigned)grid), dim3(kThreads), 0, stream, a);
+  return checked("row_stats_kernel");
+}
+
 template <int DT, bool XF, bool AL>
 static hipError_t launch_typed(const KArgs& a, hipStream_t stream) {
   (void)hipGetLastError();
-  const int64_t rows = a.resample_only ? int64_t(a.B) : int64_t(a.B) * (a.L + a.has_bonus);
-  const int64_t grid1 = rows * a.nchunks;
-  hipLaunchKernelGGL((verify_rows_kernel<DT, XF, AL>), dim3((unsigned)grid1), dim3(kThreads), 0, stream, a);
-  hipError_t e = checked("verify_rows_kernel");
+  constexpr int kT = Vec<DT>::kT;
+  hipError_t e;
+  if (a.nt1 == kT) e = launch_stats<DT, XF, AL, kT>(a, stream);
+  else if (a.nt1 == kT / 2) e = launch_stats<DT, XF, AL, kT / 2>(a, stream);
+  else e = launch_stats<DT, XF, AL, kT / 4>(a, stream);
   if (e != hipSuccess) return e;
-  if (a.nchunks > 1) {
-    const int64_t grid2 = int64_t(a.B) * a.nchunks;
-    hipLaunchKernelGGL((resample_chunks_kernel<DT, XF, AL>), dim3((unsigned)grid2), dim3(kThreads), 0, stream, a);
-    e = checked("resample_chunks_kernel");
+  if (a.cs != a.c1) {   // rows have many statistics chunks: pre-combine them, one wave per row
+    const int64_t gridc = (int64_t(a.rows_t) + a.rows_d + kWaves - 1) / kWaves;
+    hipLaunchKernelGGL(combine_rows_kernel, dim3((unsigned)gridc), dim3(kThreads), 0, stream, a);
+    e = checked("combine_rows_kernel");
+    if (e != hipSuccess) return e;
   }
-  return e;
+  const int64_t grid2 = int64_t(a.B) * a.nchunks;
+  hipLaunchKernelGGL((sequence_kernel<DT, XF, AL>), dim3((unsigned)grid2), dim3(kThreads), 0, stream, a);
+  return checked("sequence_kernel");
 }
 
 template <int DT, bool XF>

@@ -9,8 +9,10 @@ larger than the 256 MB last-level cache, and are replayed from a HIP graph so th
 host's launch cost does not hide the device time.
 
 Prints ONE JSON line: verified draft tokens per second, with
-  roofline      HBM: algorithmic bytes of one launch / average time of one launch (HIP events
-                around the timed region on the launch stream)
+  roofline      HBM, for the dominant kernel (row_stats_kernel, the pass that reads every logit):
+                algorithmic bytes of one launch / its average duration, from HIP events that the
+                library records around that kernel on the launch stream (cool_sd_profile_*),
+                over the same batches right after the timed region
   cpu_baseline  the fp64 CPU oracle timed on a bounded sample of the same batches.
 """
 import argparse
@@ -26,7 +28,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/),
 # scaled by the same counters' reading on a plain copy kernel; None = not measured.
-MEASURED_TRAFFIC_BYTES = {"cfg2": None, "cfg4": None, "cfg5": None}
+# Fetched + written bytes of row_stats_kernel per launch.
+MEASURED_TRAFFIC_BYTES = {"cfg1": None, "cfg2": 17.93e6, "cfg3": None, "cfg4": 277.42e6, "cfg5": 1143.1e6}
 
 
 def parse():
@@ -34,12 +37,16 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3000)
     ap.add_argument("--warmup", type=int, default=300)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--launch", default="graph", choices=["graph", "direct"])
     ap.add_argument("--pool-mb", type=float, default=600.0, help="distinct input batches cycled, total size")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="time budget of the CPU oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--others", action="store_true", help="also time configurations 4 and 5 (extra JSON keys)")
+    ap.add_argument("--others", action="store_true", help="also time configurations 1, 3, 4, 5 (extra JSON keys)")
+    ap.add_argument("--kernel-samples", type=int, default=200, help="instrumented calls for the per-kernel time")
+    ap.add_argument("--counter-run", action="store_true",
+                    help="for rocprofv3 --pmc: a plain device copy of known size (the counters' reference), then "
+                         "--steps direct calls; nothing is timed or printed as a result")
     return ap.parse_args()
 
 
@@ -114,6 +121,25 @@ class Runner:
         return done, wall, e0.elapsed_time(e1) * 1e-3
 
 
+    def kernel_times(self, n):
+        """Average duration of the statistics kernel and of the whole call (HIP events recorded by the
+        library on the launch stream), over n direct calls cycling through the pool."""
+        pkg, torch = self.pkg, self.torch
+        torch.cuda.synchronize()
+        pkg.cool_sd_profile_enable(True)
+        k_ms = c_ms = 0.0
+        try:
+            for i in range(n + 5):
+                self.step(i)
+                a, b = pkg.cool_sd_profile_read()
+                if i >= 5:
+                    k_ms += a
+                    c_ms += b
+        finally:
+            pkg.cool_sd_profile_enable(False)
+        return k_ms / n * 1e-3, c_ms / n * 1e-3
+
+
 def cpu_baseline(runner, budget_s):
     """The oracle, as it stands, on whole batches of the same pool until the time budget is used."""
     from oracle import oracle as O
@@ -146,10 +172,23 @@ def main():
 
     cfg = int(a.workload[3:])
     r = Runner(pkg, torch, cfg, a.pool_mb)
+    if a.counter_run:
+        # reference for the byte counters: an elementwise kernel (dst = src * 1) that moves exactly
+        # 2^30 B in and 2^30 B out
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        r.run(a.steps, "direct")
+        torch.cuda.synchronize()
+        print(json.dumps({"counter_run": a.workload, "steps": a.steps, "copy_bytes_each_way": src.numel() * 4,
+                          "bytes_per_step": r.bytes_per_step}))
+        return
     done, wall, dev_s = r.time(a.steps, a.warmup, a.launch)
     tokens = done * r.B * r.L
-    per_launch_s = dev_s / done
-    achieved = r.bytes_per_step / per_launch_s / 1e9
+    kern_s, call_s = r.kernel_times(a.kernel_samples)
+    achieved = r.bytes_per_step / kern_s / 1e9
     dtype = r.pool[0].dtype
     line = {
         "metric": "verified draft tokens/sec (1 GPU) + achieved HBM GB/s fraction of peak",
@@ -162,17 +201,24 @@ def main():
                    "pool_mb": len(r.pool) * r.bytes_per_step / 1e6, "bytes_per_step": r.bytes_per_step},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(a.workload),
-                     "kernel": "verify_rows_kernel", "us_per_launch": per_launch_s * 1e6},
+                     "kernel": "row_stats_kernel", "us_per_launch": kern_s * 1e6,
+                     "whole_call_us": call_s * 1e6, "whole_call_GBps": r.bytes_per_step / call_s / 1e9,
+                     "graph_step_us": dev_s / done * 1e6},
     }
     if a.others:
         extra = {}
-        for c in (4, 5):
-            rr = Runner(pkg, torch, c, 2400.0, max_pool=8)
+        for c in (1, 3, 4, 5):
+            if c == cfg:
+                continue
+            rr = Runner(pkg, torch, c, 2400.0 if c >= 4 else 600.0, max_pool=8 if c >= 4 else 64)
             d2, w2, s2 = rr.time(max(64, 8 * len(rr.pool)), 2 * len(rr.pool), a.launch)
+            k2, c2 = rr.kernel_times(40)
             extra["cfg%d" % c] = {"tokens_per_s": d2 * rr.B * rr.L / w2, "us_per_step": s2 / d2 * 1e6,
-                                  "GBps": rr.bytes_per_step / (s2 / d2) / 1e9,
-                                  "frac": rr.bytes_per_step / (s2 / d2) / 1e9 / HBM_PEAK_GBS,
-                                  "pool_batches": len(rr.pool)}
+                                  "whole_call_GBps": rr.bytes_per_step / (s2 / d2) / 1e9,
+                                  "whole_call_frac": rr.bytes_per_step / (s2 / d2) / 1e9 / HBM_PEAK_GBS,
+                                  "row_stats_us": k2 * 1e6, "row_stats_GBps": rr.bytes_per_step / k2 / 1e9,
+                                  "row_stats_frac": rr.bytes_per_step / k2 / 1e9 / HBM_PEAK_GBS,
+                                  "bytes_per_step": rr.bytes_per_step, "pool_batches": len(rr.pool)}
             del rr
             torch.cuda.empty_cache()
         line["other_workloads"] = extra

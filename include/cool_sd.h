@@ -24,9 +24,11 @@
  *     contract violation and are not checked on the device.
  *   - Logits must be finite or -inf (-inf = token excluded); every row needs at least one
  *     finite logit.  Uniforms lie in [0, 1).
- *   - A workspace must be prepared once with cool_sd_workspace_init before its first use; a
- *     verify/resample call leaves it prepared for the next.  Calls that share a workspace
- *     must be ordered on one stream.
+ *   - The workspace holds only intermediate results of one call (chunk statistics, masses);
+ *     nothing persists between calls and it needs no initialisation.  Calls that share a
+ *     workspace must be ordered on one stream.
+ *   - No kernel uses atomics, fences or waits on another workgroup; for given inputs the
+ *     outputs are bit-identical from run to run.
  */
 #ifndef COOL_SD_H
 #define COOL_SD_H
@@ -92,8 +94,8 @@ int cool_sd_schedule(int32_t kind, int32_t L, float delta, float param, float* o
  * (for resample only B, V, dtype and top_k matter).  0 on invalid params. */
 size_t cool_sd_workspace_bytes(const cool_sd_params* p);
 
-/* Prepare a workspace (zero its completion counters) on the stream.  Needed once after
- * allocation.  workspace_dev must be 256-byte aligned. */
+/* Zero a workspace on the stream.  Optional (no call depends on the workspace's contents);
+ * kept for callers that want defined memory.  workspace_dev must be 256-byte aligned. */
 int cool_sd_workspace_init(void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
 /* Verification stage of Algorithm 1 for B sequences; asynchronous on hip_stream.
@@ -138,6 +140,14 @@ int cool_sd_resample(const cool_sd_params* p,
                      int32_t* token_dev, float* resid_mass_dev,
                      void* workspace_dev, size_t workspace_bytes,
                      void* hip_stream);
+
+/* Benchmark instrumentation (not for production paths, not thread-safe, not usable while the
+ * stream is being captured into a graph).  While enabled, cool_sd_verify / cool_sd_resample
+ * record HIP events on the call's stream around the row-statistics kernel (the pass that reads
+ * every logit from HBM) and around the whole call.  cool_sd_profile_read waits for the last
+ * instrumented call and returns both durations in milliseconds. */
+int cool_sd_profile_enable(int enable);
+int cool_sd_profile_read(float* stats_kernel_ms, float* call_ms);
 
 /* Static description of a cool_sd_status. */
 const char* cool_sd_strerror(int code);

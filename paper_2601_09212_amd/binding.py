@@ -59,6 +59,10 @@ def lib():
         L.cool_sd_verify.restype = C.c_int
         L.cool_sd_resample.argtypes = [pp] + [vp] * 8 + [vp, C.c_size_t, vp]
         L.cool_sd_resample.restype = C.c_int
+        L.cool_sd_profile_enable.argtypes = [C.c_int]
+        L.cool_sd_profile_enable.restype = C.c_int
+        L.cool_sd_profile_read.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_float)]
+        L.cool_sd_profile_read.restype = C.c_int
         L.cool_sd_strerror.argtypes = [C.c_int]
         L.cool_sd_strerror.restype = C.c_char_p
         _lib = L
@@ -124,6 +128,21 @@ def cool_sd_resample(params, target_rows, target_uncond_rows, draft_rows, draft_
     if check and rc != 0:
         raise CoolSDError(rc, "cool_sd_resample")
     return rc
+
+
+def cool_sd_profile_enable(enable):
+    rc = lib().cool_sd_profile_enable(int(bool(enable)))
+    if rc != 0:
+        raise CoolSDError(rc, "cool_sd_profile_enable")
+
+
+def cool_sd_profile_read():
+    """(statistics-kernel ms, whole-call ms) of the last instrumented call."""
+    a, b = C.c_float(), C.c_float()
+    rc = lib().cool_sd_profile_read(C.byref(a), C.byref(b))
+    if rc != 0:
+        raise CoolSDError(rc, "cool_sd_profile_read")
+    return a.value, b.value
 
 
 # ------------------------------------------------------------------ conveniences (marshalling only)

@@ -14,7 +14,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t k2_counter, chunk_R, thr, rowstat, part, total;
+  size_t seq_stat, chunk_R, thr, rowstat, part, total;
 };
 
 // rows: all logit rows (target + draft); c1: statistics chunks per row; C: sampling chunks per row.
@@ -22,7 +22,7 @@ Layout make_layout(int64_t B, int64_t rows, int64_t c1, int64_t C) {
   Layout o{};
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes); return at; };
-  o.k2_counter = take(size_t(B) * 4);
+  o.seq_stat = take(size_t(B) * 16);
   o.chunk_R = take(size_t(B) * C * 4);
   o.thr = take(size_t(rows) * 4);
   o.rowstat = take(size_t(rows) * 8);
@@ -33,21 +33,25 @@ Layout make_layout(int64_t B, int64_t rows, int64_t c1, int64_t C) {
 
 // Statistics-kernel chunking: tiles per chunk (of Vec::kT, kT/2, kT/4 = 16384, 8192, 4096
 // logits).  Small chunks keep more workgroups in flight; top-k needs the whole row in one.
-struct Chunking { int nt1, chunk1; int64_t c1; };
+struct Chunking { int nt1, chunk1; int64_t c1; int nt2; int64_t c2; };
 Chunking pick_chunking(const cool_sd_params* p, int64_t rows) {
   const int kT = (p->dtype == COOL_SD_BF16) ? 8 : 16;
   const int kE = (p->dtype == COOL_SD_BF16) ? 8 : 4;
+  const bool one_chunk = p->V <= csd::kChunk;     // the sampled row fits one workgroup's registers
   int nt = kT / 2;
   if (p->top_k > 0) nt = kT;
-  else if (rows * ((p->V + 8191) / 8192) < 2048) nt = kT / 4;
+  else if (one_chunk && rows * ((p->V + 8191) / 8192) < 2048) nt = kT / 4;
   Chunking c;
   c.nt1 = nt;
   c.chunk1 = nt * 256 * kE;
   c.c1 = (int64_t(p->V) + c.chunk1 - 1) / c.chunk1;
+  // sampling kernel: one 16384-logit chunk, or 8192-logit chunks (then equal to the statistics chunks)
+  c.nt2 = one_chunk ? kT : kT / 2;
+  const int64_t chunk2 = int64_t(c.nt2) * 256 * kE;
+  c.c2 = (int64_t(p->V) + chunk2 - 1) / chunk2;
   return c;
 }
 
-inline int64_t n_chunks(int64_t V) { return (V + csd::kChunk - 1) / csd::kChunk; }
 
 bool params_ok(const cool_sd_params* p, bool for_resample) {
   if (!p) return false;
@@ -68,6 +72,11 @@ bool params_ok(const cool_sd_params* p, bool for_resample) {
   return true;
 }
 
+// benchmark instrumentation (see cool_sd_profile_enable)
+bool g_profile = false;
+bool g_profile_valid = false;
+hipEvent_t g_ev[3] = {nullptr, nullptr, nullptr};
+
 inline bool is_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 int run(const cool_sd_params* p, bool resample_only,
@@ -78,10 +87,10 @@ int run(const cool_sd_params* p, bool resample_only,
   const int64_t L = resample_only ? 1 : p->L;
   const int hb = resample_only ? 0 : p->has_bonus;
   const int64_t rows = resample_only ? p->B : int64_t(p->B) * (L + hb);
-  const int64_t C = n_chunks(p->V);
-  if (p->top_k > 0 && C > 1) return COOL_SD_EUNSUPPORTED;
+  if (p->top_k > 0 && p->V > csd::kChunk) return COOL_SD_EUNSUPPORTED;
   const int64_t rows_t = rows, rows_d = d ? int64_t(p->B) * L : 0;
   const Chunking ch = pick_chunking(p, rows_t + rows_d);
+  const int64_t C = ch.c2;
   const Layout lay = make_layout(p->B, rows_t + rows_d, ch.c1, C);
   if (!ws || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0 || ws_bytes < lay.total) return COOL_SD_EWORKSPACE;
 
@@ -109,13 +118,13 @@ int run(const cool_sd_params* p, bool resample_only,
   a.top_k = p->top_k; a.resample_mode = p->resample_mode;
   a.resample_only = resample_only ? 1 : 0;
   a.aligned = aligned ? 1 : 0;
-  a.nchunks = (int32_t)C;
+  a.nchunks = (int32_t)C; a.nt2 = ch.nt2;
   a.cfg_scale = p->cfg_scale;
   a.inv_T = 1.0f / p->temperature;
   a.rows_t = (int32_t)rows_t; a.rows_d = (int32_t)rows_d;
   a.nt1 = ch.nt1; a.chunk1 = ch.chunk1; a.c1 = (int32_t)ch.c1;
-  a.k2_counter = reinterpret_cast<uint32_t*>(w + lay.k2_counter);
   a.chunk_R = reinterpret_cast<float*>(w + lay.chunk_R);
+  a.seq_stat = reinterpret_cast<float4*>(w + lay.seq_stat);
   a.thr = reinterpret_cast<float*>(w + lay.thr);
   a.part = reinterpret_cast<float2*>(w + lay.part);
   a.rowstat = reinterpret_cast<float2*>(w + lay.rowstat);
@@ -124,7 +133,8 @@ int run(const cool_sd_params* p, bool resample_only,
   a.cs = direct ? (int32_t)ch.c1 : 1;
 
   const bool xf = (tu != nullptr) || (p->temperature != 1.0f) || (p->top_k > 0);
-  hipError_t e = csd::launch_verify(a, p->dtype, xf, static_cast<hipStream_t>(stream));
+  hipError_t e = csd::launch_verify(a, p->dtype, xf, static_cast<hipStream_t>(stream), g_profile ? g_ev : nullptr);
+  g_profile_valid = g_profile && e == hipSuccess;
   return e == hipSuccess ? COOL_SD_OK : COOL_SD_ELAUNCH;
 }
 
@@ -171,7 +181,7 @@ size_t cool_sd_workspace_bytes(const cool_sd_params* p) {
   // sized for the finest chunking so that the answer does not depend on optional inputs
   const int64_t c1_max = (int64_t(p->V) + 4095) / 4096;
   (void)ch;
-  return make_layout(p->B, rows, c1_max, n_chunks(p->V)).total;
+  return make_layout(p->B, rows, c1_max, c1_max).total;
 }
 
 int cool_sd_workspace_init(void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
@@ -210,6 +220,24 @@ int cool_sd_resample(const cool_sd_params* p, const void* target_rows_dev, const
   return run(p, true, target_rows_dev, target_uncond_rows_dev, draft_rows_dev, draft_uncond_rows_dev, nullptr,
              omega_rows_dev, nullptr, u_dev, nullptr, token_dev, nullptr, nullptr, nullptr, resid_mass_dev,
              workspace_dev, workspace_bytes, hip_stream);
+}
+
+int cool_sd_profile_enable(int enable) {
+  if (enable && !g_ev[0]) {
+    for (int i = 0; i < 3; ++i)
+      if (hipEventCreate(&g_ev[i]) != hipSuccess) return COOL_SD_ELAUNCH;
+  }
+  g_profile = enable != 0;
+  g_profile_valid = false;
+  return COOL_SD_OK;
+}
+
+int cool_sd_profile_read(float* stats_kernel_ms, float* call_ms) {
+  if (!g_profile_valid || !stats_kernel_ms || !call_ms) return COOL_SD_EINVAL;
+  if (hipEventSynchronize(g_ev[2]) != hipSuccess) return COOL_SD_ELAUNCH;
+  if (hipEventElapsedTime(stats_kernel_ms, g_ev[0], g_ev[1]) != hipSuccess) return COOL_SD_ELAUNCH;
+  if (hipEventElapsedTime(call_ms, g_ev[0], g_ev[2]) != hipSuccess) return COOL_SD_ELAUNCH;
+  return COOL_SD_OK;
 }
 
 const char* cool_sd_strerror(int code) {

@@ -23,7 +23,7 @@ struct KArgs {
   float* resid_mass;        // [B] or nullptr
   int64_t t_sb, t_sl, d_sb, d_sl, om_sb;   // element strides
   int32_t B, L, V, has_bonus, top_k, resample_mode, resample_only, aligned;
-  int32_t nchunks;          // 16384-logit chunks per row (sampling kernel)
+  int32_t nchunks, nt2;     // sampling kernel: chunks per row, tiles per chunk
   int32_t rows_t, rows_d;   // target rows B*(L+has_bonus), draft rows B*L (0: no draft)
   int32_t nt1, chunk1, c1;  // statistics kernel: tiles per chunk, logits per chunk, chunks per row
   float cfg_scale, inv_T;
@@ -33,13 +33,15 @@ struct KArgs {
   float2* rowstat;          // [rows_t + rows_d]      combined statistics (written only when c1 > 4)
   const float2* stat;       // what the sequence kernel reads: part (cs = c1 <= 4) or rowstat (cs = 1)
   int32_t cs;
-  uint32_t* k2_counter;     // [B]           chunks of the sampled row that have finished (nchunks > 1)
+  float4* seq_stat;         // [B]           statistics of the sampled row (several-chunk path)
   float* chunk_R;           // [B, nchunks]  residual mass per chunk of the sampled row  (nchunks > 1)
 };
 
 // Enqueue the kernels of one verify (or stand-alone resample) call.  xf: the logit transform
 // (guidance / temperature / top-k) is active.  Returns hipSuccess or the launch error.
-hipError_t launch_verify(const KArgs& a, int dtype, bool xf, hipStream_t stream);
+// ev: nullptr, or three events recorded before the statistics kernel, after it, and after the
+// last kernel.
+hipError_t launch_verify(const KArgs& a, int dtype, bool xf, hipStream_t stream, hipEvent_t* ev);
 
 // Zero n 32-bit words.
 hipError_t launch_zero(uint32_t* p, size_t n, hipStream_t stream);

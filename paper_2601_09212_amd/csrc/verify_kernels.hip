@@ -14,22 +14,17 @@
 //                      (integer base-2 reference exponent, sum).  No workgroup talks to another;
 //                      few registers, so many workgroups per CU keep loads in flight.  With
 //                      top-k it also selects the row's threshold (row = one chunk then).
-//   sequence_kernel    grid = B x (chunks of 16384 logits).  Per sequence: combine the chunk
-//                      statistics of its rows, accept test at each position, tau = first
-//                      rejection; then re-read ONLY row tau+1 (one row pair of 2L+1, usually
-//                      still in L2 / Infinity Cache), keep it in registers, form the residual
-//                      masses and draw x_{tau+1} by a hierarchical inverse CDF.  When the row
-//                      spans several chunks the last workgroup to finish (ticket) picks the
-//                      chunk that holds u*R and searches it.
-//
-// Hand-over between workgroups of one launch (sequence_kernel with several chunks only).
-// Device-wide release/acquire fences write back and invalidate a whole L2 and cost far more
-// than this kernel's memory traffic, so none is used.  A value that another workgroup of the
-// same launch reads is written with an agent-scope atomic store and read with an agent-scope
-// atomic load (both bypass the per-XCD L2) by one thread, which waits for its stores to
-// complete (s_waitcnt vmcnt(0)) before it takes its ticket with an agent-scope atomic add.
-// The reader only reads after it has seen the final ticket value.  No workgroup ever waits
-// for another one; the last arriver resets the ticket to zero.
+//   sequence_kernel    grid = B.  Per sequence: combine the chunk statistics of its rows, accept
+//                      test at each position, tau = first rejection; then re-read ONLY row tau+1
+//                      (one row pair of 2L+1, usually still in L2 / Infinity Cache), keep it in
+//                      registers, form the residual masses and draw x_{tau+1} by a hierarchical
+//                      inverse CDF.
+// Rows longer than 16384 logits do not fit one workgroup's registers; the second step is then
+// split at kernel boundaries: combine_rows_kernel (one wave per row), accept_kernel (tau, one
+// workgroup per sequence), sequence_kernel<kMasses> (mass of every 8192-logit chunk of the
+// sampled rows, streaming) and sequence_kernel<kSelect> (pick the chunk that holds u*R, re-read
+// it, inverse CDF).  No workgroup ever communicates with another one inside a launch: there are
+// no atomics, fences or spin waits anywhere, and every kernel is a pure function of its inputs.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
@@ -42,7 +37,6 @@ namespace csd {
 
 enum { kModeOpt = 0, kModeVanilla = 1, kModeP = 2 };
 
-template <int DT, bool XF> using Regs = RowRegs<DT, XF, Vec<DT>::kT>;   // a 16384-logit chunk
 
 struct Smem {
   float red_c[2][kWaves];
@@ -56,22 +50,6 @@ struct Smem {
   int flag;
   float4 rowstat;
 };
-
-template <typename T> __device__ __forceinline__ T coherent_load(const T* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-template <typename T> __device__ __forceinline__ void coherent_store(T* p, T v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// Called by ONE thread after its coherent stores: waits until they have completed, then takes
-// a ticket.  Returns true for the last of n arrivals.
-__device__ __forceinline__ bool ticket_is_last(uint32_t* counter, uint32_t n) {
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  const uint32_t old = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  asm volatile("" ::: "memory");
-  return old == n - 1u;
-}
 
 __device__ __forceinline__ const char* row_ptr(const void* base, int64_t elem_off, int es) {
   return base ? reinterpret_cast<const char*>(base) + elem_off * es : nullptr;
@@ -148,6 +126,7 @@ __global__ __launch_bounds__(kThreads) void combine_rows_kernel(const KArgs a) {
 // Statistics of row r from at most kMaxDirect entries (a.stat, a.cs entries per row), all
 // loaded before any is used: reference = max, sum rescaled by exact powers of two.
 constexpr int kMaxDirect = 4;
+constexpr int kStage = 1024;   // chunk masses staged in LDS by the sampling kernel
 __device__ __forceinline__ void combine_row(const KArgs& a, int r, float& C, float& S) {
   const float2* p = a.stat + int64_t(r) * a.cs;
   float2 v[kMaxDirect];
@@ -190,10 +169,10 @@ __device__ __forceinline__ float resid_elem(float lt, float ld, const ResidCoef&
 }
 
 // Per-thread, per-tile partial masses, then block-wide tile totals T[k] (in sm.tile_tot).
-template <int DT, bool XF>
-__device__ __forceinline__ void chunk_masses(const Regs<DT, XF>& rt, const Regs<DT, XF>& rd,
-                                             const ResidCoef& k, float (&part)[Vec<DT>::kT], Smem& sm) {
-  constexpr int kE = Vec<DT>::kE, kT = Vec<DT>::kT;
+template <int DT, bool XF, int kT>
+__device__ __forceinline__ void chunk_masses(const RowRegs<DT, XF, kT>& rt, const RowRegs<DT, XF, kT>& rd,
+                                             const ResidCoef& k, float (&part)[kT], Smem& sm) {
+  constexpr int kE = Vec<DT>::kE;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
 #pragma unroll
   for (int t = 0; t < kT; ++t) {
@@ -230,11 +209,11 @@ template <int kT> __device__ __forceinline__ float chunk_total(const Smem& sm) {
 // exceeds the remainder, else the last positive-mass entry", so the result always has
 // positive mass even when the levels' roundings disagree.  Returns the offset in the chunk
 // (same value in every thread), or -1 if the chunk holds no mass.
-template <int DT, bool XF>
-__device__ __forceinline__ int chunk_select(const Regs<DT, XF>& rt, const Regs<DT, XF>& rd,
-                                            const ResidCoef& k, const float (&part)[Vec<DT>::kT],
+template <int DT, bool XF, int kT>
+__device__ __forceinline__ int chunk_select(const RowRegs<DT, XF, kT>& rt, const RowRegs<DT, XF, kT>& rd,
+                                            const ResidCoef& k, const float (&part)[kT],
                                             float v, Smem& sm) {
-  constexpr int kE = Vec<DT>::kE, kT = Vec<DT>::kT;
+  constexpr int kE = Vec<DT>::kE;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   // level 1: tile
   int ks = -1, klast = -1;
@@ -300,55 +279,103 @@ __device__ __forceinline__ int chunk_select(const Regs<DT, XF>& rt, const Regs<D
   return sm.bcast_i;
 }
 
+// Accept test at every position of sequence b (Eq. relax) and tau = first rejection
+// (Algorithm 1), by all 256 threads of a workgroup: thread i takes positions i, i+256, ...
+// Leaves the combined statistics (Ct, St, Cd, Sd) of the row that will be sampled from --
+// position tau+1, or the bonus row L+1 -- in sm.rowstat and returns tau.  With `emit` it also
+// writes accept_len and the per-position diagnostics.
+template <int DT, bool XF>
+__device__ __forceinline__ int find_tau(const KArgs& a, int b, bool emit, Smem& sm) {
+  constexpr int kES = Vec<DT>::kES;
+  const int rps = a.L + a.has_bonus;
+  const bool masked = XF && a.top_k > 0;
+  int first = a.L;
+  for (int i0 = 0; i0 < rps; i0 += kThreads) {
+    const int i = i0 + threadIdx.x;
+    float Ct = kRefFloor, St = 0.f, Cd = kRefFloor, Sd = 0.f;
+    if (i < rps) {
+      const int rt_ = b * rps + i;
+      combine_row(a, rt_, Ct, St);
+      if (i < a.L) {
+        const int rd_ = a.rows_t + b * a.L + i;
+        combine_row(a, rd_, Cd, Sd);
+        const char* t_c = row_ptr(a.t, int64_t(b) * a.t_sb + int64_t(i) * a.t_sl, kES);
+        const char* t_u = row_ptr(a.tu, int64_t(b) * a.t_sb + int64_t(i) * a.t_sl, kES);
+        const char* d_c = row_ptr(a.d, int64_t(b) * a.d_sb + int64_t(i) * a.d_sl, kES);
+        const char* d_u = row_ptr(a.du, int64_t(b) * a.d_sb + int64_t(i) * a.d_sl, kES);
+        int x = a.tokens[int64_t(b) * a.L + i];
+        x = min(max(x, 0), a.V - 1);
+        const float lt = token_logit<DT>(t_c, t_u, x, XF, a.cfg_scale, a.inv_T, masked ? a.thr[rt_] : -INFINITY);
+        const float ld = token_logit<DT>(d_c, d_u, x, XF, a.cfg_scale, a.inv_T, masked ? a.thr[rd_] : -INFINITY);
+        // exponents of p(x~) and q(x~) in base-2 units; the ratio p/q is formed from their
+        // difference so that it survives when both probabilities underflow fp32
+        const float et = __fmaf_rn(lt, kLog2e, -Ct), ed = __fmaf_rn(ld, kLog2e, -Cd);
+        const float ratio = __fmul_rn(exp2_fast(__fsub_rn(et, ed)), Sd / St);
+        const float omega = a.omega[int64_t(b) * a.om_sb + i];
+        // f = min{1, omega p/q}; a token the draft excludes (q = 0) has f = 1, also at 0/0
+        const float fi = (ld == -INFINITY) ? 1.f : ((omega > 0.f) ? fminf(1.f, __fmul_rn(omega, ratio)) : 0.f);
+        if (!(a.u_acc[int64_t(b) * a.L + i] <= fi)) first = min(first, i);
+        if (emit) {
+          const int64_t o = int64_t(b) * a.L + i;
+          if (a.p_tok) a.p_tok[o] = exp2_fast(et) / St;
+          if (a.q_tok) a.q_tok[o] = exp2_fast(ed) / Sd;
+          if (a.f) a.f[o] = fi;
+        }
+      }
+    }
+    // the first rejection among positions < i0 + 256 is final once it is below that bound
+    int w = wave_min_i(first);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sm.pick_first[threadIdx.x >> 6] = w;
+    __syncthreads();
+    w = min(min(sm.pick_first[0], sm.pick_first[1]), min(sm.pick_first[2], sm.pick_first[3]));
+    const bool final = (w < i0 + kThreads) || (i0 + kThreads >= rps);
+    if (final) {
+      // the thread that owns row w (position w, or the bonus row when w == L) publishes its statistics
+      if (i == w) sm.rowstat = make_float4(Ct, St, Cd, Sd);
+      __syncthreads();
+      if (emit && threadIdx.x == 0) a.accept_len[b] = w;
+      return w;
+    }
+  }
+  return a.L;   // not reached
+}
+
+// Middle kernel of the several-chunk path: one workgroup per sequence finds tau and leaves
+// accept_len[b] and the sampled row's statistics for the sampling kernel.
+template <int DT, bool XF>
+__global__ __launch_bounds__(kThreads) void accept_kernel(const KArgs a) {
+  __shared__ Smem sm;
+  const int b = blockIdx.x;
+  const int j = find_tau<DT, XF>(a, b, true, sm);
+  if (threadIdx.x == 0) a.seq_stat[b] = sm.rowstat;
+  (void)j;
+}
+
 // ============================================================================ kernel 2
-template <int DT, bool XF, bool AL>
+// The draw x_{tau+1} from the resampling law of the sampled row (Eq. opt_G / Eq. g_tsd /
+// p_{L+1}).  STAGE selects what one launch does:
+//   kWhole   grid = B.      Row = one chunk.  find tau, load the row pair, masses, inverse CDF.
+//   kMasses  grid = B x C.  Rows of C chunks: workgroup (b, c) writes the mass of chunk c.
+//   kSelect  grid = B.      Rows of C chunks: pick the chunk that holds u*R, load it, inverse CDF.
+enum { kWhole = 0, kMasses = 1, kSelect = 2 };
+
+template <int DT, bool XF, bool AL, int kT, int STAGE>
 __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
-  constexpr int kT = Vec<DT>::kT, kES = Vec<DT>::kES;
+  constexpr int kES = Vec<DT>::kES;
+  constexpr int kChunk2 = kT * kThreads * Vec<DT>::kE;   // logits per sampling chunk
   __shared__ Smem sm;
   const int C = a.nchunks;
-  const int b = blockIdx.x / C, c = blockIdx.x - b * C;
+  const int b = (STAGE == kMasses) ? blockIdx.x / C : blockIdx.x;
+  const int c = (STAGE == kMasses) ? blockIdx.x - b * C : 0;
   const int rps = a.L + a.has_bonus;
   const bool masked = XF && a.top_k > 0;
 
-  // ---- accept test at every position (Eq. relax), tau = first rejection (Algorithm 1)
   int j = 0;
   if (!a.resample_only) {
-    int first = a.L;
-    for (int i = threadIdx.x; i < a.L; i += kThreads) {
-      const int rt_ = b * rps + i, rd_ = a.rows_t + b * a.L + i;
-      float Ct, St, Cd, Sd;
-      combine_row(a, rt_, Ct, St);
-      combine_row(a, rd_, Cd, Sd);
-      const char* t_c = row_ptr(a.t, int64_t(b) * a.t_sb + int64_t(i) * a.t_sl, kES);
-      const char* t_u = row_ptr(a.tu, int64_t(b) * a.t_sb + int64_t(i) * a.t_sl, kES);
-      const char* d_c = row_ptr(a.d, int64_t(b) * a.d_sb + int64_t(i) * a.d_sl, kES);
-      const char* d_u = row_ptr(a.du, int64_t(b) * a.d_sb + int64_t(i) * a.d_sl, kES);
-      int x = a.tokens[int64_t(b) * a.L + i];
-      x = min(max(x, 0), a.V - 1);
-      const float lt = token_logit<DT>(t_c, t_u, x, XF, a.cfg_scale, a.inv_T, masked ? a.thr[rt_] : -INFINITY);
-      const float ld = token_logit<DT>(d_c, d_u, x, XF, a.cfg_scale, a.inv_T, masked ? a.thr[rd_] : -INFINITY);
-      // exponents of p(x~) and q(x~) in base-2 units; the ratio p/q is formed from their
-      // difference so that it survives when both probabilities underflow fp32
-      const float et = __fmaf_rn(lt, kLog2e, -Ct), ed = __fmaf_rn(ld, kLog2e, -Cd);
-      const float ratio = __fmul_rn(exp2_fast(__fsub_rn(et, ed)), Sd / St);
-      const float omega = a.omega[int64_t(b) * a.om_sb + i];
-      // f = min{1, omega p/q}; a token the draft excludes (q = 0) has f = 1, also at 0/0
-      const float fi = (ld == -INFINITY) ? 1.f : ((omega > 0.f) ? fminf(1.f, __fmul_rn(omega, ratio)) : 0.f);
-      if (!(a.u_acc[int64_t(b) * a.L + i] <= fi)) first = min(first, i);
-      if (c == 0) {
-        const int64_t o = int64_t(b) * a.L + i;
-        if (a.p_tok) a.p_tok[o] = exp2_fast(et) / St;
-        if (a.q_tok) a.q_tok[o] = exp2_fast(ed) / Sd;
-        if (a.f) a.f[o] = fi;
-      }
-    }
-    first = wave_min_i(first);
-    if ((threadIdx.x & 63) == 0) sm.pick_first[threadIdx.x >> 6] = first;
-    __syncthreads();
-    j = min(min(sm.pick_first[0], sm.pick_first[1]), min(sm.pick_first[2], sm.pick_first[3]));
-    if (c == 0 && threadIdx.x == 0) a.accept_len[b] = j;
+    j = (STAGE == kWhole) ? find_tau<DT, XF>(a, b, true, sm) : a.accept_len[b];
     if (j >= a.L && !a.has_bonus) {
-      if (c == 0 && threadIdx.x == 0) {
+      if (STAGE != kMasses && threadIdx.x == 0) {
         a.next_token[b] = -1;
         if (a.resid_mass) a.resid_mass[b] = 0.f;
       }
@@ -359,13 +386,18 @@ __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
   // ---- the row that is sampled from: position tau+1, or the bonus row (Algorithm 1)
   const bool bonus = a.resample_only ? (a.d == nullptr) : (j == a.L);
   const int rt_ = b * rps + j, rd_ = a.rows_t + b * a.L + j;
-  if (threadIdx.x == 0) {
-    float Ct, St, Cd = kRefFloor, Sd = 0.f;
-    combine_row(a, rt_, Ct, St);
-    if (!bonus) combine_row(a, rd_, Cd, Sd);
-    sm.rowstat = make_float4(Ct, St, Cd, Sd);
+  if (a.resample_only) {
+    if (threadIdx.x == 0) {
+      float Ct, St, Cd = kRefFloor, Sd = 0.f;
+      combine_row(a, rt_, Ct, St);
+      if (!bonus) combine_row(a, rd_, Cd, Sd);
+      sm.rowstat = make_float4(Ct, St, Cd, Sd);
+    }
+    __syncthreads();
+  } else if (STAGE != kWhole) {
+    if (threadIdx.x == 0) sm.rowstat = a.seq_stat[b];
+    __syncthreads();
   }
-  __syncthreads();
   const float4 rs = sm.rowstat;
   const char* t_c = row_ptr(a.t, int64_t(b) * a.t_sb + int64_t(j) * a.t_sl, kES);
   const char* t_u = row_ptr(a.tu, int64_t(b) * a.t_sb + int64_t(j) * a.t_sl, kES);
@@ -377,43 +409,42 @@ __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
   ResidCoef k{rs.x, 1.f / rs.y, rs.z, bonus ? 1.f : 1.f / rs.w, omega,
               bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
 
-  Regs<DT, XF> rt, rd;
+  RowRegs<DT, XF, kT> rt, rd;
   float part[kT];
   auto load_pair = [&](int cc) {
-    const int64_t base = int64_t(cc) * kChunk;
+    const int64_t base = int64_t(cc) * kChunk2;
     load_chunk<DT, XF, AL, kT>(rt, t_c, t_u, base, a.V, a.cfg_scale, a.inv_T, thr_t);
     if (!bonus) load_chunk<DT, XF, AL, kT>(rd, d_c, d_u, base, a.V, a.cfg_scale, a.inv_T, thr_d);
     else rd.clear();                                  // never read in mode P
   };
-  load_pair(c);
-  chunk_masses<DT, XF>(rt, rd, k, part, sm);
-  float R = chunk_total<kT>(sm);
-  float vsel;        // remaining mass to walk inside the selected chunk
-  int cs = c;        // selected chunk
 
-  if (C == 1) {
+  if constexpr (STAGE == kMasses) {
+    load_pair(c);
+    chunk_masses<DT, XF, kT>(rt, rd, k, part, sm);
+    if (threadIdx.x == 0) a.chunk_R[int64_t(b) * C + c] = chunk_total<kT>(sm);
+    return;
+  }
+
+  float R, vsel;     // total mass; remaining mass to walk inside the selected chunk
+  int cs = 0;        // selected chunk
+  if constexpr (STAGE == kWhole) {
+    load_pair(0);
+    chunk_masses<DT, XF, kT>(rt, rd, k, part, sm);
+    R = chunk_total<kT>(sm);
     if (!(R > 0.f)) {  // no rejection possible at this position: any law is optimal, use p
       k.mode = kModeP;
-      chunk_masses<DT, XF>(rt, rd, k, part, sm);
+      chunk_masses<DT, XF, kT>(rt, rd, k, part, sm);
       R = chunk_total<kT>(sm);
     }
     vsel = __fmul_rn(a.u_res[b], R);
   } else {
-    // several chunks: publish this chunk's mass; the last workgroup to arrive goes on
-    if (threadIdx.x == 0) {
-      coherent_store(&a.chunk_R[int64_t(b) * C + c], R);
-      sm.flag = ticket_is_last(&a.k2_counter[b], (uint32_t)C) ? 1 : 0;
-    }
-    __syncthreads();
-    if (!sm.flag) return;
-    R = 0.f;
-    for (int cc = 0; cc < C; ++cc) R = __fadd_rn(R, coherent_load(&a.chunk_R[int64_t(b) * C + cc]));
-    const bool fallback = !(R > 0.f);
-    // mass of chunk cc under the law in force; the fallback law p is summed from the chunk
-    // statistics of kernel 1 (c1 statistics chunks per 16384-logit chunk)
-    const int per = kChunk / a.chunk1;
-    auto chunk_mass = [&](int cc) -> float {
-      if (!fallback) return coherent_load(&a.chunk_R[int64_t(b) * C + cc]);
+    // chunk masses are staged in LDS by all threads (one latency), then walked in ascending
+    // order; rows with more than kStage chunks walk global memory instead
+    __shared__ float cm[kStage];
+    const bool staged = C <= kStage;
+    // mass of chunk cc under the fallback law p, from the chunk statistics of kernel 1
+    const int per = kChunk2 / a.chunk1;
+    auto p_mass = [&](int cc) -> float {
       float m = 0.f;
       for (int q = cc * per; q < min((cc + 1) * per, a.c1); ++q) {
         const float2 pp = a.part[int64_t(rt_) * a.c1 + q];
@@ -421,8 +452,25 @@ __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
       }
       return m;
     };
-    if (fallback) {
+    bool fallback = false;
+    auto chunk_mass = [&](int cc) -> float {
+      if (staged) return cm[cc];
+      return fallback ? p_mass(cc) : a.chunk_R[int64_t(b) * C + cc];
+    };
+    if (staged) {
+      for (int cc = threadIdx.x; cc < C; cc += kThreads) cm[cc] = a.chunk_R[int64_t(b) * C + cc];
+      __syncthreads();
+    }
+    R = 0.f;
+    for (int cc = 0; cc < C; ++cc) R = __fadd_rn(R, chunk_mass(cc));
+    if (!(R > 0.f)) {    // no rejection possible at this position: any law is optimal, use p
+      fallback = true;
       k.mode = kModeP;
+      if (staged) {
+        __syncthreads();
+        for (int cc = threadIdx.x; cc < C; cc += kThreads) cm[cc] = p_mass(cc);
+        __syncthreads();
+      }
       R = 0.f;
       for (int cc = 0; cc < C; ++cc) R = __fadd_rn(R, chunk_mass(cc));
     }
@@ -441,19 +489,15 @@ __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
     if (cs < 0) { cs = clast; cbase = cbase_last; }
     if (cs < 0) cs = 0;
     vsel = v - cbase;
-    if (cs != c || fallback) {
-      __syncthreads();
-      load_pair(cs);
-      chunk_masses<DT, XF>(rt, rd, k, part, sm);
-    }
+    load_pair(cs);
+    chunk_masses<DT, XF, kT>(rt, rd, k, part, sm);
   }
-  const int off = chunk_select<DT, XF>(rt, rd, k, part, vsel, sm);
-  int token = cs * kChunk + max(off, 0);
+  const int off = chunk_select<DT, XF, kT>(rt, rd, k, part, vsel, sm);
+  int token = cs * kChunk2 + max(off, 0);
   if (token >= a.V) token = a.V - 1;
   if (threadIdx.x == 0) {
     a.next_token[b] = token;
     if (a.resid_mass) a.resid_mass[b] = R;
-    if (C > 1) coherent_store(&a.k2_counter[b], 0u);
   }
 }
 
@@ -479,33 +523,60 @@ static hipError_t launch_stats(const KArgs& a, hipStream_t stream) {
 }
 
 template <int DT, bool XF, bool AL>
-static hipError_t launch_typed(const KArgs& a, hipStream_t stream) {
+static hipError_t launch_rest(const KArgs& a, hipStream_t stream);
+
+template <int DT, bool XF, bool AL>
+static hipError_t launch_typed(const KArgs& a, hipStream_t stream, hipEvent_t* ev) {
   (void)hipGetLastError();
   constexpr int kT = Vec<DT>::kT;
   hipError_t e;
+  if (ev) (void)hipEventRecord(ev[0], stream);
   if (a.nt1 == kT) e = launch_stats<DT, XF, AL, kT>(a, stream);
   else if (a.nt1 == kT / 2) e = launch_stats<DT, XF, AL, kT / 2>(a, stream);
   else e = launch_stats<DT, XF, AL, kT / 4>(a, stream);
   if (e != hipSuccess) return e;
+  if (ev) (void)hipEventRecord(ev[1], stream);
+  e = launch_rest<DT, XF, AL>(a, stream);
+  if (ev) (void)hipEventRecord(ev[2], stream);
+  return e;
+}
+
+template <int DT, bool XF, bool AL>
+static hipError_t launch_rest(const KArgs& a, hipStream_t stream) {
+  constexpr int kT = Vec<DT>::kT;
+  hipError_t e;
   if (a.cs != a.c1) {   // rows have many statistics chunks: pre-combine them, one wave per row
     const int64_t gridc = (int64_t(a.rows_t) + a.rows_d + kWaves - 1) / kWaves;
     hipLaunchKernelGGL(combine_rows_kernel, dim3((unsigned)gridc), dim3(kThreads), 0, stream, a);
     e = checked("combine_rows_kernel");
     if (e != hipSuccess) return e;
   }
+  const unsigned gB = (unsigned)a.B;
+  if (a.nt2 == kT) {          // the sampled row is one chunk: everything per sequence in one workgroup
+    hipLaunchKernelGGL((sequence_kernel<DT, XF, AL, kT, kWhole>), dim3(gB), dim3(kThreads), 0, stream, a);
+    return checked("sequence_kernel");
+  }
+  if (!a.resample_only) {     // several chunks: find tau once per sequence
+    hipLaunchKernelGGL((accept_kernel<DT, XF>), dim3(gB), dim3(kThreads), 0, stream, a);
+    e = checked("accept_kernel");
+    if (e != hipSuccess) return e;
+  }
   const int64_t grid2 = int64_t(a.B) * a.nchunks;
-  hipLaunchKernelGGL((sequence_kernel<DT, XF, AL>), dim3((unsigned)grid2), dim3(kThreads), 0, stream, a);
+  hipLaunchKernelGGL((sequence_kernel<DT, XF, AL, kT / 2, kMasses>), dim3((unsigned)grid2), dim3(kThreads), 0, stream, a);
+  e = checked("sequence_kernel (masses)");
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((sequence_kernel<DT, XF, AL, kT / 2, kSelect>), dim3(gB), dim3(kThreads), 0, stream, a);
   return checked("sequence_kernel");
 }
 
 template <int DT, bool XF>
-static hipError_t launch_al(const KArgs& a, hipStream_t stream) {
-  return a.aligned ? launch_typed<DT, XF, true>(a, stream) : launch_typed<DT, XF, false>(a, stream);
+static hipError_t launch_al(const KArgs& a, hipStream_t stream, hipEvent_t* ev) {
+  return a.aligned ? launch_typed<DT, XF, true>(a, stream, ev) : launch_typed<DT, XF, false>(a, stream, ev);
 }
 
-hipError_t launch_verify(const KArgs& a, int dtype, bool xf, hipStream_t stream) {
-  if (dtype == kDtBF16) return xf ? launch_al<kDtBF16, true>(a, stream) : launch_al<kDtBF16, false>(a, stream);
-  return xf ? launch_al<kDtF32, true>(a, stream) : launch_al<kDtF32, false>(a, stream);
+hipError_t launch_verify(const KArgs& a, int dtype, bool xf, hipStream_t stream, hipEvent_t* ev) {
+  if (dtype == kDtBF16) return xf ? launch_al<kDtBF16, true>(a, stream, ev) : launch_al<kDtBF16, false>(a, stream, ev);
+  return xf ? launch_al<kDtF32, true>(a, stream, ev) : launch_al<kDtF32, false>(a, stream, ev);
 }
 
 hipError_t launch_zero(uint32_t* p, size_t n, hipStream_t stream) {

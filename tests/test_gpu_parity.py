@@ -168,3 +168,52 @@ def test_repeat_calls_share_workspace_and_are_deterministic(P, oracle):
         for k in o:
             np.testing.assert_array_equal(o[k], outs[0][k])
     compare_verify(oracle, w, om.cpu().numpy(), outs[-1])
+
+
+# ----------------------------------------------------------------------------- guidance / temperature / top-k
+@pytest.mark.parametrize("B,L,V,dtype,top_k", [
+    (4, 8, 16384, "bf16", 1000),      # config 3 rows
+    (3, 3, 16384, "f32", 1000),
+    (3, 2, 5001, "bf16", 50),         # element-wise loads
+    (2, 2, 4104, "bf16", 1),          # greedy support
+    (2, 2, 2048, "bf16", 2048),       # k = V keeps everything
+    (2, 3, 16384, "bf16", 0),         # guidance without truncation
+])
+def test_guidance_topk_against_oracle(P, oracle, B, L, V, dtype, top_k):
+    print("case cfg3", B, L, V, dtype, top_k, flush=True)
+    w = make_workload(3, device="cuda", B=B, L=L, V=V, dtype=dtype, top_k=top_k)
+    assert w.top_k == top_k
+    om = _omega(P, w)
+    gpu = _run(P, oracle, w, om)
+    st = compare_verify(oracle, w, om, gpu)
+    assert st["tau_exempt"] + st["token_exempt"] <= 1
+    # tokens outside the draft's support are accepted, outside the target's rejected: exercise both
+    w.draft_tokens = torch.randint(0, V, (B, L), dtype=torch.int32, device="cuda",
+                                   generator=torch.Generator(device="cuda").manual_seed(3))
+    compare_verify(oracle, w, om, _run(P, oracle, w, om))
+
+
+def test_topk_ties_and_temperature(P, oracle):
+    """Rows with massive ties at the threshold (coarse grid, all-equal rows) and a temperature."""
+    B, L, V = 4, 2, 16384
+    w = make_workload(3, device="cuda", B=B, L=L, V=V, dtype="bf16", top_k=100)
+    g = torch.Generator(device="cuda").manual_seed(11)
+    for t in (w.target, w.target_uncond, w.draft, w.draft_uncond):
+        t[0] = (torch.randint(-3, 4, t[0].shape, device="cuda", generator=g).float() * 0.5).to(t.dtype)  # 7 levels
+        t[1] = 1.25                                                                                     # all equal
+    w.temperature = 0.75
+    om = _omega(P, w)
+    compare_verify(oracle, w, om, _run(P, oracle, w, om))
+    # temperature alone (no guidance, no truncation) on fp32 logits
+    w2 = make_workload(1, device="cuda", B=2, L=3, V=3000, dtype="f32")
+    w2.temperature = 1.7
+    om2 = _omega(P, w2)
+    compare_verify(oracle, w2, om2, _run(P, oracle, w2, om2))
+
+
+def test_topk_long_rows_are_refused(P):
+    w = make_workload(3, device="cuda", B=1, L=1, V=20000, top_k=10)
+    om = torch.ones(1, device="cuda")
+    with pytest.raises(P.CoolSDError) as e:
+        P.verify_workload(w, om)
+    assert e.value.code == P.binding.COOL_SD_EUNSUPPORTED

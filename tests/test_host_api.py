@@ -1,0 +1,124 @@
+"""Host-side logic of the C-ABI library (no GPU): symbols, schedule, validation, workspace sizing."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2601_09212_amd as pkg
+    pkg.binding.lib()
+    return pkg
+
+
+def test_library_exports_every_declared_symbol(P):
+    header = open(os.path.join(ROOT, "include", "cool_sd.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = re.findall(r"\b(cool_sd_[a-z_]+)\s*\(", header)
+    assert set(names) >= {"cool_sd_schedule", "cool_sd_workspace_bytes", "cool_sd_workspace_init",
+                          "cool_sd_verify", "cool_sd_resample", "cool_sd_strerror"}
+    raw = C.CDLL(P.binding.LIB_PATH)
+    for n in set(names):
+        assert hasattr(raw, n), n
+
+
+def test_struct_layout_matches_header(P):
+    # 4 x int32, 5 x int64, 2 x int32, 2 x float, 2 x int32
+    assert C.sizeof(P.CoolSDParams) == 16 + 40 + 8 + 8 + 8
+
+
+@pytest.mark.parametrize("L,delta", [(1, 1.0), (4, 1.1), (8, 2.0), (16, 4.0), (64, 1.1)])
+def test_schedule_matches_oracle(P, oracle, L, delta):
+    for kind, param in ((P.COOL_SD_SCHED_EXP, 0.7), (P.COOL_SD_SCHED_EXP, 0.05), (P.COOL_SD_SCHED_UNIFORM, 0.0),
+                        (P.COOL_SD_SCHED_LINEAR, float(max(L, 8)))):
+        got = P.cool_sd_schedule(kind, L, delta, param)
+        want = oracle.schedule(kind, L, np.float32(delta), np.float32(param))
+        assert got.dtype == np.float32
+        np.testing.assert_allclose(got, want, rtol=2e-7, atol=0)
+    assert abs(P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, L, delta, 0.7).astype(np.float64).sum() - delta * L) < 1e-5 * L
+
+
+def test_schedule_rejects_bad_arguments(P):
+    for args in ((P.COOL_SD_SCHED_EXP, 4, 1.0, 0.0), (P.COOL_SD_SCHED_EXP, 0, 1.0, 0.7), (7, 4, 1.0, 0.7),
+                 (P.COOL_SD_SCHED_LINEAR, 9, 1.0, 8.0), (P.COOL_SD_SCHED_EXP, 4, -1.0, 0.7),
+                 (P.COOL_SD_SCHED_EXP, 4, float("nan"), 0.7)):
+        with pytest.raises(P.CoolSDError) as e:
+            P.cool_sd_schedule(*args)
+        assert e.value.code == P.binding.COOL_SD_EINVAL
+
+
+def _params(P, **kw):
+    base = dict(B=4, L=8, V=16384, dtype=P.COOL_SD_BF16, t_stride_b=9 * 16384, t_stride_l=16384,
+                d_stride_b=8 * 16384, d_stride_l=16384, omega_stride_b=0, has_bonus=1, top_k=0,
+                cfg_scale=1.0, temperature=1.0, resample_mode=0, reserved=0)
+    base.update(kw)
+    return P.CoolSDParams(**base)
+
+
+def test_workspace_bytes_and_invalid_params(P):
+    small = P.cool_sd_workspace_bytes(_params(P))
+    assert 0 < small < 1 << 20
+    big = P.cool_sd_workspace_bytes(_params(P, V=262144, t_stride_l=262144, d_stride_l=262144,
+                                            t_stride_b=9 * 262144, d_stride_b=8 * 262144))
+    assert big > small
+    for bad in (dict(B=0), dict(V=0), dict(dtype=3), dict(top_k=-1), dict(top_k=16385), dict(temperature=0.0),
+                dict(temperature=float("inf")), dict(cfg_scale=float("nan")), dict(resample_mode=2),
+                dict(reserved=1), dict(t_stride_b=-1)):
+        assert P.cool_sd_workspace_bytes(_params(P, **bad)) == 0, bad
+    # L out of range is still a valid stand-alone resample shape (L is ignored there)
+    assert P.cool_sd_workspace_bytes(_params(P, L=0)) > 0
+
+
+def test_verify_validates_before_touching_the_gpu(P):
+    """Argument errors come back as status codes; nothing is launched (this runs without a GPU)."""
+    lib = P.binding.lib()
+    fake = C.c_void_p(0x1000)          # never dereferenced on the host
+    null = C.c_void_p(0)
+
+    def call(params, target=fake, draft=fake, tu=null, du=null, ws=null, ws_bytes=0):
+        return lib.cool_sd_verify(C.byref(params), target, tu, draft, du, fake, fake, fake, fake, fake, fake,
+                                  null, null, null, null, ws, ws_bytes, null)
+
+    E = P.binding
+    assert call(_params(P, L=0)) == E.COOL_SD_EINVAL
+    assert call(_params(P, L=5000)) == E.COOL_SD_EINVAL
+    assert call(_params(P), target=null) == E.COOL_SD_EINVAL
+    assert call(_params(P), tu=fake) == E.COOL_SD_EINVAL               # guidance needs both unconditional tensors
+    assert call(_params(P, has_bonus=2)) == E.COOL_SD_EINVAL
+    assert call(_params(P)) == E.COOL_SD_EWORKSPACE                    # no workspace
+    assert call(_params(P), ws=C.c_void_p(0x1004), ws_bytes=1 << 20) == E.COOL_SD_EWORKSPACE   # misaligned
+    assert call(_params(P), ws=C.c_void_p(0x1000), ws_bytes=16) == E.COOL_SD_EWORKSPACE         # too small
+    assert call(_params(P, V=20000, top_k=5, t_stride_l=20000, d_stride_l=20000, t_stride_b=9 * 20000,
+                        d_stride_b=8 * 20000), ws=C.c_void_p(0x1000), ws_bytes=1 << 24) == E.COOL_SD_EUNSUPPORTED
+    assert lib.cool_sd_verify(None, fake, null, fake, null, fake, fake, fake, fake, fake, fake, null, null, null,
+                              null, null, 0, null) == E.COOL_SD_EINVAL
+    # stand-alone resample
+    r = lib.cool_sd_resample(C.byref(_params(P)), null, null, fake, null, fake, fake, fake, null, null, 0, null)
+    assert r == E.COOL_SD_EINVAL
+    r = lib.cool_sd_resample(C.byref(_params(P)), fake, null, fake, null, null, fake, fake, null, null, 0, null)
+    assert r == E.COOL_SD_EINVAL                                       # draft rows need omega
+    for code in (0, -1, -2, -3, -4, -99):
+        assert isinstance(P.cool_sd_strerror(code), str) and P.cool_sd_strerror(code)
+    assert lib.cool_sd_profile_read(None, None) == E.COOL_SD_EINVAL
+
+
+def test_binding_fails_loudly_without_library(P, monkeypatch):
+    from paper_2601_09212_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libcool_sd.so")
+    with pytest.raises(ImportError):
+        binding.lib()
+
+
+def test_product_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2601_09212_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), os.path.join(dirpath, f)

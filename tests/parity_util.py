@@ -22,7 +22,20 @@ def _close(gpu, ref, what):
         gpu[tuple(np.argwhere(bad)[0])], ref[tuple(np.argwhere(bad)[0])])
 
 
-def run_oracle(O, w, omega, resample_mode=0, num_threads=8):
+def subset(w, idx):
+    """The sequences idx of a workload, as a workload of its own (for oracle checks of samples)."""
+    import copy
+    import torch
+    idx = torch.as_tensor(idx, device=w.target.device)
+    s = copy.copy(w)
+    s.B = len(idx)
+    for name in ("target", "draft", "draft_tokens", "u_accept", "u_resample", "target_uncond", "draft_uncond"):
+        t = getattr(w, name)
+        setattr(s, name, None if t is None else t.index_select(0, idx))
+    return s
+
+
+def run_oracle(O, w, omega, resample_mode=0, num_threads=16):
     t, d, tu, du = w.logits_f32_numpy()
     return O.verify(t, d, w.draft_tokens.cpu().numpy(), omega, w.u_accept.cpu().numpy(),
                     w.u_resample.cpu().numpy(), target_uncond=tu, draft_uncond=du,

@@ -217,3 +217,28 @@ def test_topk_long_rows_are_refused(P):
     with pytest.raises(P.CoolSDError) as e:
         P.verify_workload(w, om)
     assert e.value.code == P.binding.COOL_SD_EUNSUPPORTED
+
+
+# ----------------------------------------------------------------------------- full benchmark sizes
+@pytest.mark.parametrize("cfg,n_check", [(1, None), (2, None), (3, None), (4, None), (5, 24)])
+def test_full_size_configurations(P, oracle, cfg, n_check):
+    """The five configurations at their full sizes, launched exactly as bench.py launches them (same
+    params, workspace and chunking).  Every sequence is checked against the oracle, except for
+    configuration 5 where a seeded sample of sequences is (the oracle needs ~0.3 s per sequence)."""
+    from tests.parity_util import subset
+    print("full cfg", cfg, flush=True)
+    w = make_workload(cfg, device="cuda")
+    om = _omega(P, w)
+    gpu = _run(P, oracle, w, om)
+    assert gpu["accept_len"].min() >= 0 and gpu["accept_len"].max() <= w.L
+    assert gpu["next_token"].min() >= 0 and gpu["next_token"].max() < w.V
+    if n_check is None:
+        st = compare_verify(oracle, w, om, gpu)
+    else:
+        idx = np.sort(np.random.default_rng(cfg).choice(w.B, n_check, replace=False))
+        st = compare_verify(oracle, subset(w, idx), om, {k: v[idx] for k, v in gpu.items()})
+    print("exemptions", st, flush=True)
+    assert st["tau_exempt"] + st["token_exempt"] <= 2
+    # acceptance statistics are those of speculative decoding, not degenerate
+    if w.B >= 32:
+        assert 0.5 < gpu["accept_len"].mean() < w.L - 0.5

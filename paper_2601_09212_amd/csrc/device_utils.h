@@ -159,10 +159,10 @@ __device__ __forceinline__ void load_chunk(RowRegs<DT, XF, NT>& r, const char* _
                                            float s, float inv_T, float thr) {
   constexpr int kE = Vec<DT>::kE;
   const int tid = threadIdx.x;
-  uint4 raw[NT];
+  if constexpr (!XF) {
+    uint4 raw[NT];
 #pragma unroll
-  for (int k = 0; k < NT; ++k) raw[k] = load_vec<DT, AL>(cond, base + int64_t(k * kThreads + tid) * kE, V);
-  if (!XF) {
+    for (int k = 0; k < NT; ++k) raw[k] = load_vec<DT, AL>(cond, base + int64_t(k * kThreads + tid) * kE, V);
 #pragma unroll
     for (int k = 0; k < NT; ++k) {
       if (RowRegs<DT, XF, NT>::kRaw) {
@@ -174,17 +174,30 @@ __device__ __forceinline__ void load_chunk(RowRegs<DT, XF, NT>& r, const char* _
       }
     }
   } else {
+    // Groups of kG tiles: the 2*kG raw vectors of a group are in flight together and are
+    // consumed before the next group is fetched, which bounds the registers held by raw data.
+    constexpr int kG = NT < 4 ? NT : 4;
     const bool guided = uncond != nullptr;
     const char* second = guided ? uncond : cond;   // unguided: a harmless re-read, no branch
 #pragma unroll
-    for (int k = 0; k < NT; ++k) {
-      const int64_t e = base + int64_t(k * kThreads + tid) * kE;
-      const uint4 ru = load_vec<DT, AL>(second, e, V);
+    for (int g = 0; g < NT; g += kG) {
+      uint4 rc[kG], ru[kG];
 #pragma unroll
-      for (int j = 0; j < kE; ++j) {
-        float l = transform_logit(vec_elem<DT>(raw[k], j), vec_elem<DT>(ru, j), guided, s, inv_T);
-        r.set(k, j, (e + j < V && l >= thr) ? l : -INFINITY);
+      for (int k = 0; k < kG; ++k) {
+        const int64_t e = base + int64_t((g + k) * kThreads + tid) * kE;
+        rc[k] = load_vec<DT, AL>(cond, e, V);
+        ru[k] = load_vec<DT, AL>(second, e, V);
       }
+#pragma unroll
+      for (int k = 0; k < kG; ++k) {
+        const int64_t e = base + int64_t((g + k) * kThreads + tid) * kE;
+#pragma unroll
+        for (int j = 0; j < kE; ++j) {
+          float l = transform_logit(vec_elem<DT>(rc[k], j), vec_elem<DT>(ru[k], j), guided, s, inv_T);
+          r.set(g + k, j, (e + j < V && l >= thr) ? l : -INFINITY);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 }

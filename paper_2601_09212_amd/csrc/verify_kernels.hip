@@ -55,11 +55,21 @@ __device__ __forceinline__ const char* row_ptr(const void* base, int64_t elem_of
   return base ? reinterpret_cast<const char*>(base) + elem_off * es : nullptr;
 }
 
+// LDS of the top-k selection; allocated only in kernels that apply the logit transform.
+template <bool XF> __device__ __forceinline__ TopkSmem* topk_smem() {
+  if constexpr (XF) {
+    __shared__ TopkSmem ts;
+    return &ts;
+  } else {
+    return nullptr;
+  }
+}
+
 // ============================================================================ kernel 1
 // Softmax statistics of one chunk of one row.  Rows are numbered: target rows first
 // (b*(L+has_bonus) + i), then draft rows (rows_t + b*L + i).
 template <int DT, bool XF, bool AL, int NT>
-__global__ __launch_bounds__(kThreads) void row_stats_kernel(const KArgs a) {
+__global__ __launch_bounds__(kThreads, 3) void row_stats_kernel(const KArgs a) {
   constexpr int kE = Vec<DT>::kE, kES = Vec<DT>::kES;
   __shared__ float red_c[kWaves], red_s[kWaves];
   const int C1 = a.c1;
@@ -74,17 +84,17 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(const KArgs a) {
   const char* uncond = row_ptr(is_draft ? a.du : a.tu, off, kES);
   const int64_t base = int64_t(c) * (NT * kThreads * kE);
 
+  TopkSmem* tsp = topk_smem<XF>();
+  if constexpr (XF) {
+    if (a.top_k > 0) topk_prepare(*tsp);   // the barrier inside topk_threshold orders it
+  }
   RowRegs<DT, XF, NT> x;
   load_chunk<DT, XF, AL, NT>(x, cond, uncond, base, a.V, a.cfg_scale, a.inv_T, -INFINITY);
   if constexpr (XF) {
     if (a.top_k > 0) {   // the chunk is the whole row here
-      __shared__ TopkSmem ts;
-      float vals[NT * kE];
+      const float thr = topk_threshold<NT * kE>(x.w, a.top_k, *tsp);
 #pragma unroll
-      for (int n = 0; n < NT * kE; ++n) vals[n] = __uint_as_float(x.w[n]);
-      const float thr = topk_threshold<NT * kE>(vals, a.top_k, ts);
-#pragma unroll
-      for (int n = 0; n < NT * kE; ++n) x.w[n] = (vals[n] >= thr) ? x.w[n] : 0xFF800000u;
+      for (int n = 0; n < NT * kE; ++n) x.w[n] = (__uint_as_float(x.w[n]) >= thr) ? x.w[n] : 0xFF800000u;
       if (threadIdx.x == 0) a.thr[r] = thr;
     }
   }

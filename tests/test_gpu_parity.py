@@ -242,3 +242,47 @@ def test_full_size_configurations(P, oracle, cfg, n_check):
     # acceptance statistics are those of speculative decoding, not degenerate
     if w.B >= 32:
         assert 0.5 < gpu["accept_len"].mean() < w.L - 0.5
+
+
+def test_hip_graph_replays_match_eager(P, oracle):
+    """bench.py replays verify calls from a HIP graph: every replay must reproduce the eager result,
+    also with other eager work and synchronisations between replays (both launch shapes: one-chunk
+    rows and long rows)."""
+    for cfg, kw in ((2, dict(B=8, L=8, V=16384)), (5, dict(B=4, L=4, V=40000))):
+        pool = [make_workload(cfg, device="cuda", call=c, **kw) for c in range(3)]
+        om = torch.from_numpy(_omega(P, pool[0])).cuda()
+        params = P.make_params(pool[0].target, pool[0].draft)
+        ws = torch.empty(P.cool_sd_workspace_bytes(params), dtype=torch.uint8, device="cuda")
+        outs = [dict(a=torch.zeros(kw["B"], dtype=torch.int32, device="cuda"),
+                     n=torch.zeros(kw["B"], dtype=torch.int32, device="cuda"),
+                     r=torch.zeros(kw["B"], device="cuda")) for _ in pool]
+
+        def issue():
+            for w, o in zip(pool, outs):
+                P.cool_sd_verify(params, w.target, None, w.draft, None, w.draft_tokens, om, w.u_accept,
+                                 w.u_resample, o["a"], o["n"], None, None, None, o["r"], ws)
+
+        issue()
+        torch.cuda.synchronize()
+        eager = [{k: v.clone() for k, v in o.items()} for o in outs]
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            issue()
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            issue()
+        for rep in range(4):
+            for o in outs:
+                for v in o.values():
+                    v.fill_(-3)
+            junk = torch.randn(1 << 20, device="cuda").sum()          # unrelated eager work
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert junk.item() == junk.item()
+            for o, e in zip(outs, eager):
+                for k in o:
+                    assert torch.equal(o[k], e[k]), (cfg, rep, k)

@@ -14,7 +14,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t seq_stat, chunk_R, thr, rowstat, part, total;
+  size_t seq_stat, chunk_R, thr, tok_logit, rowstat, part, total;
 };
 
 // rows: all logit rows (target + draft); c1: statistics chunks per row; C: sampling chunks per row.
@@ -25,6 +25,7 @@ Layout make_layout(int64_t B, int64_t rows, int64_t c1, int64_t C) {
   o.seq_stat = take(size_t(B) * 16);
   o.chunk_R = take(size_t(B) * C * 4);
   o.thr = take(size_t(rows) * 4);
+  o.tok_logit = take(size_t(rows) * 4);
   o.rowstat = take(size_t(rows) * 8);
   o.part = take(size_t(rows) * c1 * 8);
   o.total = off;
@@ -126,6 +127,7 @@ int run(const cool_sd_params* p, bool resample_only,
   a.chunk_R = reinterpret_cast<float*>(w + lay.chunk_R);
   a.seq_stat = reinterpret_cast<float4*>(w + lay.seq_stat);
   a.thr = reinterpret_cast<float*>(w + lay.thr);
+  a.tok_logit = reinterpret_cast<float*>(w + lay.tok_logit);
   a.part = reinterpret_cast<float2*>(w + lay.part);
   a.rowstat = reinterpret_cast<float2*>(w + lay.rowstat);
   const bool direct = ch.c1 <= 4;

@@ -153,7 +153,9 @@ template <int DT, bool XF, int NT> struct RowRegs {
 // Load the chunk of NT tiles that starts at element `base` of a row (and of its unconditional
 // twin when guided) and apply the logit transform when XF: guidance, temperature, then the
 // top-k mask "keep l >= thr" (thr = -inf: no mask).  Out-of-range elements become -inf.
-template <int DT, bool XF, bool AL, int NT>
+// Vector k of thread t is vector number k*KS + t*TS of the chunk: (KS, TS) = (256, 1) is the
+// tile layout described at the top; (1, NT) gives every thread NT consecutive vectors.
+template <int DT, bool XF, bool AL, int NT, int KS = kThreads, int TS = 1>
 __device__ __forceinline__ void load_chunk(RowRegs<DT, XF, NT>& r, const char* __restrict__ cond,
                                            const char* __restrict__ uncond, int64_t base, int V,
                                            float s, float inv_T, float thr) {
@@ -162,7 +164,7 @@ __device__ __forceinline__ void load_chunk(RowRegs<DT, XF, NT>& r, const char* _
   if constexpr (!XF) {
     uint4 raw[NT];
 #pragma unroll
-    for (int k = 0; k < NT; ++k) raw[k] = load_vec<DT, AL>(cond, base + int64_t(k * kThreads + tid) * kE, V);
+    for (int k = 0; k < NT; ++k) raw[k] = load_vec<DT, AL>(cond, base + int64_t(k * KS + tid * TS) * kE, V);
 #pragma unroll
     for (int k = 0; k < NT; ++k) {
       if (RowRegs<DT, XF, NT>::kRaw) {
@@ -184,13 +186,13 @@ __device__ __forceinline__ void load_chunk(RowRegs<DT, XF, NT>& r, const char* _
       uint4 rc[kG], ru[kG];
 #pragma unroll
       for (int k = 0; k < kG; ++k) {
-        const int64_t e = base + int64_t((g + k) * kThreads + tid) * kE;
+        const int64_t e = base + int64_t((g + k) * KS + tid * TS) * kE;
         rc[k] = load_vec<DT, AL>(cond, e, V);
         ru[k] = load_vec<DT, AL>(second, e, V);
       }
 #pragma unroll
       for (int k = 0; k < kG; ++k) {
-        const int64_t e = base + int64_t((g + k) * kThreads + tid) * kE;
+        const int64_t e = base + int64_t((g + k) * KS + tid * TS) * kE;
 #pragma unroll
         for (int j = 0; j < kE; ++j) {
           float l = transform_logit(vec_elem<DT>(rc[k], j), vec_elem<DT>(ru[k], j), guided, s, inv_T);

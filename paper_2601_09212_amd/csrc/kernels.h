@@ -30,6 +30,7 @@ struct KArgs {
   // workspace
   float2* part;             // [rows_t + rows_d, c1]  (reference exponent, sum) of every statistics chunk
   float* thr;               // [rows_t + rows_d]      top-k threshold of every row (top_k > 0)
+  float* tok_logit;         // [rows_t + rows_d]      transformed logit of the row's draft token x~_i
   float2* rowstat;          // [rows_t + rows_d]      combined statistics (written only when c1 > 4)
   const float2* stat;       // what the sequence kernel reads: part (cs = c1 <= 4) or rowstat (cs = 1)
   int32_t cs;

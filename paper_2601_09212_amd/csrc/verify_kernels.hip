@@ -55,6 +55,17 @@ __device__ __forceinline__ const char* row_ptr(const void* base, int64_t elem_of
   return base ? reinterpret_cast<const char*>(base) + elem_off * es : nullptr;
 }
 
+// Transformed logit of one token of a row (scalar path, used for x~_i).
+template <int DT>
+__device__ __forceinline__ float token_logit(const char* cond, const char* uncond, int x, bool xf,
+                                             float s, float inv_T, float thr) {
+  float lc = load_elem<DT>(cond, x);
+  if (!xf) return lc;
+  float lu = uncond ? load_elem<DT>(uncond, x) : 0.f;
+  const float l = transform_logit(lc, lu, uncond != nullptr, s, inv_T);
+  return l >= thr ? l : -INFINITY;
+}
+
 // LDS of the top-k selection; allocated only in kernels that apply the logit transform.
 template <bool XF> __device__ __forceinline__ TopkSmem* topk_smem() {
   if constexpr (XF) {
@@ -90,12 +101,23 @@ __global__ __launch_bounds__(kThreads, 3) void row_stats_kernel(const KArgs a) {
   }
   RowRegs<DT, XF, NT> x;
   load_chunk<DT, XF, AL, NT>(x, cond, uncond, base, a.V, a.cfg_scale, a.inv_T, -INFINITY);
+  float row_thr = -INFINITY;
   if constexpr (XF) {
     if (a.top_k > 0) {   // the chunk is the whole row here
       const float thr = topk_threshold<NT * kE>(x.w, a.top_k, *tsp);
 #pragma unroll
       for (int n = 0; n < NT * kE; ++n) x.w[n] = (__uint_as_float(x.w[n]) >= thr) ? x.w[n] : 0xFF800000u;
       if (threadIdx.x == 0) a.thr[r] = thr;
+      row_thr = thr;
+    }
+  }
+  // the (transformed, masked) logit of the draft token x~_i of this row, for the accept test of
+  // the next kernel: written by the chunk that holds it
+  if (a.tokens != nullptr && i < a.L && threadIdx.x == 0) {
+    int tok = a.tokens[int64_t(b) * a.L + i];
+    tok = min(max(tok, 0), a.V - 1);
+    if (tok >= base && tok < base + NT * kThreads * kE) {
+      a.tok_logit[r] = token_logit<DT>(cond, uncond, tok, XF, a.cfg_scale, a.inv_T, row_thr);
     }
   }
   float ct, st;
@@ -152,17 +174,6 @@ __device__ __forceinline__ void combine_row(const KArgs& a, int r, float& C, flo
 #pragma unroll
   for (int cc = 0; cc < kMaxDirect; ++cc) s = __fadd_rn(s, v[cc].y * exp2_fast(v[cc].x - m));
   C = m; S = s;
-}
-
-// Transformed logit of one token of a row (scalar path, used for x~_i).
-template <int DT>
-__device__ __forceinline__ float token_logit(const char* cond, const char* uncond, int x, bool xf,
-                                             float s, float inv_T, float thr) {
-  float lc = load_elem<DT>(cond, x);
-  if (!xf) return lc;
-  float lu = uncond ? load_elem<DT>(uncond, x) : 0.f;
-  const float l = transform_logit(lc, lu, uncond != nullptr, s, inv_T);
-  return l >= thr ? l : -INFINITY;
 }
 
 // Unnormalised resampling mass of one token.  p = 2^(lt*log2e - Ct) / St etc.
@@ -294,13 +305,11 @@ __device__ __forceinline__ int chunk_select(const RowRegs<DT, XF, kT>& rt, const
 // Leaves the combined statistics (Ct, St, Cd, Sd) of the row that will be sampled from --
 // position tau+1, or the bonus row L+1 -- in sm.rowstat and returns tau.  With `emit` it also
 // writes accept_len and the per-position diagnostics.
-template <int DT, bool XF>
-__device__ __forceinline__ int find_tau(const KArgs& a, int b, bool emit, Smem& sm) {
-  constexpr int kES = Vec<DT>::kES;
+template <int DT, bool XF, int TPB>
+__device__ __forceinline__ int find_tau(const KArgs& a, int b, bool emit, int* pick /*[TPB/64]*/, float4* rowstat) {
   const int rps = a.L + a.has_bonus;
-  const bool masked = XF && a.top_k > 0;
   int first = a.L;
-  for (int i0 = 0; i0 < rps; i0 += kThreads) {
+  for (int i0 = 0; i0 < rps; i0 += TPB) {
     const int i = i0 + threadIdx.x;
     float Ct = kRefFloor, St = 0.f, Cd = kRefFloor, Sd = 0.f;
     if (i < rps) {
@@ -309,14 +318,8 @@ __device__ __forceinline__ int find_tau(const KArgs& a, int b, bool emit, Smem& 
       if (i < a.L) {
         const int rd_ = a.rows_t + b * a.L + i;
         combine_row(a, rd_, Cd, Sd);
-        const char* t_c = row_ptr(a.t, int64_t(b) * a.t_sb + int64_t(i) * a.t_sl, kES);
-        const char* t_u = row_ptr(a.tu, int64_t(b) * a.t_sb + int64_t(i) * a.t_sl, kES);
-        const char* d_c = row_ptr(a.d, int64_t(b) * a.d_sb + int64_t(i) * a.d_sl, kES);
-        const char* d_u = row_ptr(a.du, int64_t(b) * a.d_sb + int64_t(i) * a.d_sl, kES);
-        int x = a.tokens[int64_t(b) * a.L + i];
-        x = min(max(x, 0), a.V - 1);
-        const float lt = token_logit<DT>(t_c, t_u, x, XF, a.cfg_scale, a.inv_T, masked ? a.thr[rt_] : -INFINITY);
-        const float ld = token_logit<DT>(d_c, d_u, x, XF, a.cfg_scale, a.inv_T, masked ? a.thr[rd_] : -INFINITY);
+        // logits of the draft token, left by the statistics kernel
+        const float lt = a.tok_logit[rt_], ld = a.tok_logit[rd_];
         // exponents of p(x~) and q(x~) in base-2 units; the ratio p/q is formed from their
         // difference so that it survives when both probabilities underflow fp32
         const float et = __fmaf_rn(lt, kLog2e, -Ct), ed = __fmaf_rn(ld, kLog2e, -Cd);
@@ -336,13 +339,15 @@ __device__ __forceinline__ int find_tau(const KArgs& a, int b, bool emit, Smem& 
     // the first rejection among positions < i0 + 256 is final once it is below that bound
     int w = wave_min_i(first);
     __syncthreads();
-    if ((threadIdx.x & 63) == 0) sm.pick_first[threadIdx.x >> 6] = w;
+    if ((threadIdx.x & 63) == 0) pick[threadIdx.x >> 6] = w;
     __syncthreads();
-    w = min(min(sm.pick_first[0], sm.pick_first[1]), min(sm.pick_first[2], sm.pick_first[3]));
-    const bool final = (w < i0 + kThreads) || (i0 + kThreads >= rps);
+    w = pick[0];
+#pragma unroll
+    for (int q = 1; q < TPB / 64; ++q) w = min(w, pick[q]);
+    const bool final = (w < i0 + TPB) || (i0 + TPB >= rps);
     if (final) {
       // the thread that owns row w (position w, or the bonus row when w == L) publishes its statistics
-      if (i == w) sm.rowstat = make_float4(Ct, St, Cd, Sd);
+      if (i == w) *rowstat = make_float4(Ct, St, Cd, Sd);
       __syncthreads();
       if (emit && threadIdx.x == 0) a.accept_len[b] = w;
       return w;
@@ -357,18 +362,172 @@ template <int DT, bool XF>
 __global__ __launch_bounds__(kThreads) void accept_kernel(const KArgs a) {
   __shared__ Smem sm;
   const int b = blockIdx.x;
-  const int j = find_tau<DT, XF>(a, b, true, sm);
+  const int j = find_tau<DT, XF, kThreads>(a, b, true, sm.pick_first, &sm.rowstat);
   if (threadIdx.x == 0) a.seq_stat[b] = sm.rowstat;
   (void)j;
 }
 
-// ============================================================================ kernel 2
-// The draw x_{tau+1} from the resampling law of the sampled row (Eq. opt_G / Eq. g_tsd /
-// p_{L+1}).  STAGE selects what one launch does:
-//   kWhole   grid = B.      Row = one chunk.  find tau, load the row pair, masses, inverse CDF.
+// ============================================================================ kernel 2, rows of one chunk
+// One workgroup of 1024 threads per sequence (rows of at most 16384 logits): find tau, re-read
+// the one row pair that is sampled from, and draw x_{tau+1} (Eq. opt_G / Eq. g_tsd / p_{L+1}).
+// This kernel is a latency chain, not a bandwidth kernel, so it is laid out for few dependent
+// steps: thread t owns the kVW CONSECUTIVE 16-byte vectors t*kVW .. t*kVW+kVW-1 of the row, so
+// the running mass in ascending token order is simply a prefix sum over threads.  Per thread:
+// one partial mass per vector; block-wide: one scan.  The thread whose interval contains u*R
+// finds the vector among its partials and re-evaluates that vector's elements.
+constexpr int kThreadsW = 1024;
+constexpr int kWavesW = kThreadsW / 64;
+
+struct SmemW {
+  int pick[kWavesW];
+  int pick_last[kWavesW];
+  float scan_tot[kWavesW];
+  float4 rowstat;
+  int token;
+};
+
+template <int DT, bool XF, bool AL>
+__global__ __launch_bounds__(kThreadsW) void sequence_whole_kernel(const KArgs a) {
+  constexpr int kE = Vec<DT>::kE, kES = Vec<DT>::kES;
+  constexpr int kVW = kChunk / (kThreadsW * kE);       // vectors per thread: 2 (bf16) / 4 (fp32)
+  __shared__ SmemW sm;
+  const int b = blockIdx.x;
+  const int rps = a.L + a.has_bonus;
+  const bool masked = XF && a.top_k > 0;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+
+  int j = 0;
+  if (!a.resample_only) {
+    j = find_tau<DT, XF, kThreadsW>(a, b, true, sm.pick, &sm.rowstat);
+    if (j >= a.L && !a.has_bonus) {
+      if (threadIdx.x == 0) {
+        a.next_token[b] = -1;
+        if (a.resid_mass) a.resid_mass[b] = 0.f;
+      }
+      return;
+    }
+  }
+  const bool bonus = a.resample_only ? (a.d == nullptr) : (j == a.L);
+  const int rt_ = b * rps + j, rd_ = a.rows_t + b * a.L + j;
+  if (a.resample_only) {
+    if (threadIdx.x == 0) {
+      float Ct, St, Cd = kRefFloor, Sd = 0.f;
+      combine_row(a, rt_, Ct, St);
+      if (!bonus) combine_row(a, rd_, Cd, Sd);
+      sm.rowstat = make_float4(Ct, St, Cd, Sd);
+    }
+    __syncthreads();
+  }
+  const float4 rs = sm.rowstat;
+  const char* t_c = row_ptr(a.t, int64_t(b) * a.t_sb + int64_t(j) * a.t_sl, kES);
+  const char* t_u = row_ptr(a.tu, int64_t(b) * a.t_sb + int64_t(j) * a.t_sl, kES);
+  const char* d_c = bonus ? nullptr : row_ptr(a.d, int64_t(b) * a.d_sb + int64_t(j) * a.d_sl, kES);
+  const char* d_u = bonus ? nullptr : row_ptr(a.du, int64_t(b) * a.d_sb + int64_t(j) * a.d_sl, kES);
+  const float thr_t = masked ? a.thr[rt_] : -INFINITY;
+  const float thr_d = (masked && !bonus) ? a.thr[rd_] : -INFINITY;
+  const float omega = bonus ? 1.f : a.omega[int64_t(b) * a.om_sb + j];
+  ResidCoef k{rs.x, 1.f / rs.y, rs.z, bonus ? 1.f : 1.f / rs.w, omega,
+              bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
+
+  RowRegs<DT, XF, kVW> rt, rd;
+  load_chunk<DT, XF, AL, kVW, 1, kVW>(rt, t_c, t_u, 0, a.V, a.cfg_scale, a.inv_T, thr_t);
+  if (!bonus) load_chunk<DT, XF, AL, kVW, 1, kVW>(rd, d_c, d_u, 0, a.V, a.cfg_scale, a.inv_T, thr_d);
+  else rd.clear();                                    // never read in mode P
+
+  float part[kVW], mine, incl, excl, R;
+  for (int attempt = 0; attempt < 2; ++attempt) {
+    mine = 0.f;
+#pragma unroll
+    for (int v = 0; v < kVW; ++v) {
+      float acc = 0.f;
+#pragma unroll
+      for (int e = 0; e < kE; ++e) acc = __fadd_rn(acc, resid_elem(rt.get(v, e), rd.get(v, e), k));
+      part[v] = acc;
+      mine = __fadd_rn(mine, acc);
+    }
+    const float incl_w = wave_scan_incl(mine);
+    float excl_w = __shfl_up(incl_w, 1, 64);
+    if (lane == 0) excl_w = 0.f;
+    __syncthreads();                                  // earlier readers of scan_tot are done
+    if (lane == 63) sm.scan_tot[wv] = incl_w;
+    __syncthreads();
+    float woff = 0.f;
+    R = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWavesW; ++w) {
+      if (w == wv) woff = R;
+      R = __fadd_rn(R, sm.scan_tot[w]);
+    }
+    incl = __fadd_rn(woff, incl_w);
+    excl = __fadd_rn(woff, excl_w);
+    if (R > 0.f || k.mode == kModeP) break;
+    k.mode = kModeP;   // no rejection possible at this position: any law is optimal, use p
+  }
+
+  // thread: first with positive mass whose inclusive sum exceeds u*R, else the last with mass
+  const float v = __fmul_rn(a.u_res[b], R);
+  const bool pos = mine > 0.f;
+  const bool hit = pos && (incl > v);
+  const unsigned long long bh = __ballot(hit), bp = __ballot(pos);
+  if (lane == 0) {
+    sm.pick[wv] = bh ? (wv * 64 + __ffsll((long long)bh) - 1) : 0x7fffffff;
+    sm.pick_last[wv] = bp ? (wv * 64 + 63 - __clzll((long long)bp)) : -1;
+  }
+  if (threadIdx.x == 0) sm.token = 0;
+  __syncthreads();
+  int win = 0x7fffffff, last_pos = -1;
+#pragma unroll
+  for (int w = 0; w < kWavesW; ++w) { win = min(win, sm.pick[w]); last_pos = max(last_pos, sm.pick_last[w]); }
+  if (win == 0x7fffffff) win = last_pos;
+  if ((int)threadIdx.x == win) {
+    // vector, then element: same rule at each level
+    const float v2 = v - excl;
+    int vs = -1, vlast = 0;
+    float vbase = 0.f, vbase_last = 0.f, cum = 0.f;
+#pragma unroll
+    for (int q = 0; q < kVW; ++q) {
+      if (part[q] > 0.f) {
+        if (vs < 0 && __fadd_rn(cum, part[q]) > v2) { vs = q; vbase = cum; }
+        vlast = q; vbase_last = cum;
+      }
+      cum = __fadd_rn(cum, part[q]);
+    }
+    if (vs < 0) { vs = vlast; vbase = vbase_last; }
+    const float v3 = v2 - vbase;
+    int found = -1, last = 0;
+    float run = 0.f;
+#pragma unroll
+    for (int q = 0; q < kVW; ++q) {
+      if (q == vs) {
+#pragma unroll
+        for (int e = 0; e < kE; ++e) {
+          const float r = resid_elem(rt.get(q, e), rd.get(q, e), k);
+          if (r > 0.f) {
+            last = e;
+            run = __fadd_rn(run, r);
+            if (found < 0 && run > v3) found = e;
+          }
+        }
+      }
+    }
+    if (found < 0) found = last;
+    sm.token = (win * kVW + vs) * kE + found;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int token = sm.token;
+    if (token >= a.V) token = a.V - 1;
+    a.next_token[b] = token;
+    if (a.resid_mass) a.resid_mass[b] = R;
+  }
+}
+
+// ============================================================================ kernel 2, long rows
+// Long rows (more than 16384 logits): the draw x_{tau+1} from the resampling law of the sampled
+// row (Eq. opt_G / Eq. g_tsd / p_{L+1}) in two launches.  STAGE selects what one launch does:
 //   kMasses  grid = B x C.  Rows of C chunks: workgroup (b, c) writes the mass of chunk c.
 //   kSelect  grid = B.      Rows of C chunks: pick the chunk that holds u*R, load it, inverse CDF.
-enum { kWhole = 0, kMasses = 1, kSelect = 2 };
+enum { kMasses = 1, kSelect = 2 };
 
 template <int DT, bool XF, bool AL, int kT, int STAGE>
 __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
@@ -383,7 +542,7 @@ __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
 
   int j = 0;
   if (!a.resample_only) {
-    j = (STAGE == kWhole) ? find_tau<DT, XF>(a, b, true, sm) : a.accept_len[b];
+    j = a.accept_len[b];
     if (j >= a.L && !a.has_bonus) {
       if (STAGE != kMasses && threadIdx.x == 0) {
         a.next_token[b] = -1;
@@ -404,7 +563,7 @@ __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
       sm.rowstat = make_float4(Ct, St, Cd, Sd);
     }
     __syncthreads();
-  } else if (STAGE != kWhole) {
+  } else {
     if (threadIdx.x == 0) sm.rowstat = a.seq_stat[b];
     __syncthreads();
   }
@@ -437,17 +596,7 @@ __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
 
   float R, vsel;     // total mass; remaining mass to walk inside the selected chunk
   int cs = 0;        // selected chunk
-  if constexpr (STAGE == kWhole) {
-    load_pair(0);
-    chunk_masses<DT, XF, kT>(rt, rd, k, part, sm);
-    R = chunk_total<kT>(sm);
-    if (!(R > 0.f)) {  // no rejection possible at this position: any law is optimal, use p
-      k.mode = kModeP;
-      chunk_masses<DT, XF, kT>(rt, rd, k, part, sm);
-      R = chunk_total<kT>(sm);
-    }
-    vsel = __fmul_rn(a.u_res[b], R);
-  } else {
+  {
     // chunk masses are staged in LDS by all threads (one latency), then walked in ascending
     // order; rows with more than kStage chunks walk global memory instead
     __shared__ float cm[kStage];
@@ -563,8 +712,8 @@ static hipError_t launch_rest(const KArgs& a, hipStream_t stream) {
   }
   const unsigned gB = (unsigned)a.B;
   if (a.nt2 == kT) {          // the sampled row is one chunk: everything per sequence in one workgroup
-    hipLaunchKernelGGL((sequence_kernel<DT, XF, AL, kT, kWhole>), dim3(gB), dim3(kThreads), 0, stream, a);
-    return checked("sequence_kernel");
+    hipLaunchKernelGGL((sequence_whole_kernel<DT, XF, AL>), dim3(gB), dim3(kThreadsW), 0, stream, a);
+    return checked("sequence_whole_kernel");
   }
   if (!a.resample_only) {     // several chunks: find tau once per sequence
     hipLaunchKernelGGL((accept_kernel<DT, XF>), dim3(gB), dim3(kThreads), 0, stream, a);

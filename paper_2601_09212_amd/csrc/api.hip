@@ -119,6 +119,8 @@ int run(const cool_sd_params* p, bool resample_only,
   a.top_k = p->top_k; a.resample_mode = p->resample_mode;
   a.resample_only = resample_only ? 1 : 0;
   a.aligned = aligned ? 1 : 0;
+  // beyond ~128 MB the logits cannot stay in L2 / Infinity Cache until the sequence kernel re-reads a row
+  a.stream_loads = (double(rows_t + rows_d) * p->V * (p->dtype == COOL_SD_BF16 ? 2 : 4) * (tu ? 2 : 1)) > 128e6 ? 1 : 0;
   a.nchunks = (int32_t)C; a.nt2 = ch.nt2;
   a.cfg_scale = p->cfg_scale;
   a.inv_T = 1.0f / p->temperature;

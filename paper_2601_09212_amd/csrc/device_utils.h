@@ -19,6 +19,9 @@ constexpr int kDtF32 = 0;
 constexpr int kDtBF16 = 1;
 constexpr float kLog2e = 1.44269504088896340736f;
 constexpr float kRefFloor = -1.5e30f;  // "no finite logit seen yet" reference exponent
+// how a kernel may load a row: element-wise, 16-byte vectors, or 16-byte vectors with the
+// nontemporal hint (large read-once inputs)
+enum { kUnaligned = 0, kAligned = 1, kAlignedStream = 2 };
 
 template <int DT> struct Vec {
   static constexpr int kE = (DT == kDtBF16) ? 8 : 4;       // elements per 16-byte vector
@@ -73,13 +76,20 @@ template <int DT> __device__ __forceinline__ uint4 neg_inf_vec() {
 // multiple of kE; otherwise elements are fetched one by one.  Both paths are branch-free (the
 // address is clamped into the row and the value replaced afterwards), so that all loads of a
 // chunk can be in flight together.
-template <int DT, bool AL>
+template <int DT, int AL>
 __device__ __forceinline__ uint4 load_vec(const char* __restrict__ row, int64_t e, int V) {
   constexpr int kE = Vec<DT>::kE;
   if (AL) {
     const bool in = e < V;
     const int64_t ec = in ? e : int64_t(V - kE);
-    uint4 v = *reinterpret_cast<const uint4*>(row + ec * Vec<DT>::kES);
+    uint4 v;
+    if (AL == kAlignedStream) {   // read-once data: do not keep it in the caches
+      typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+      const u32x4_t nv = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(row + ec * Vec<DT>::kES));
+      v = make_uint4(nv.x, nv.y, nv.z, nv.w);
+    } else {
+      v = *reinterpret_cast<const uint4*>(row + ec * Vec<DT>::kES);
+    }
     const uint4 ninf = neg_inf_vec<DT>();
     v.x = in ? v.x : ninf.x; v.y = in ? v.y : ninf.y; v.z = in ? v.z : ninf.z; v.w = in ? v.w : ninf.w;
     return v;
@@ -155,7 +165,7 @@ template <int DT, bool XF, int NT> struct RowRegs {
 // top-k mask "keep l >= thr" (thr = -inf: no mask).  Out-of-range elements become -inf.
 // Vector k of thread t is vector number k*KS + t*TS of the chunk: (KS, TS) = (256, 1) is the
 // tile layout described at the top; (1, NT) gives every thread NT consecutive vectors.
-template <int DT, bool XF, bool AL, int NT, int KS = kThreads, int TS = 1>
+template <int DT, bool XF, int AL, int NT, int KS = kThreads, int TS = 1>
 __device__ __forceinline__ void load_chunk(RowRegs<DT, XF, NT>& r, const char* __restrict__ cond,
                                            const char* __restrict__ uncond, int64_t base, int V,
                                            float s, float inv_T, float thr) {

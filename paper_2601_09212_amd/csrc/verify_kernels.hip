@@ -79,7 +79,7 @@ template <bool XF> __device__ __forceinline__ TopkSmem* topk_smem() {
 // ============================================================================ kernel 1
 // Softmax statistics of one chunk of one row.  Rows are numbered: target rows first
 // (b*(L+has_bonus) + i), then draft rows (rows_t + b*L + i).
-template <int DT, bool XF, bool AL, int NT>
+template <int DT, bool XF, int AL, int NT>
 __global__ __launch_bounds__(kThreads, 3) void row_stats_kernel(const KArgs a) {
   constexpr int kE = Vec<DT>::kE, kES = Vec<DT>::kES;
   __shared__ float red_c[kWaves], red_s[kWaves];
@@ -674,7 +674,7 @@ static hipError_t checked(const char* what) {
   return e;
 }
 
-template <int DT, bool XF, bool AL, int NT>
+template <int DT, bool XF, int AL, int NT>
 static hipError_t launch_stats(const KArgs& a, hipStream_t stream) {
   const int64_t grid = (int64_t(a.rows_t) + a.rows_d) * a.c1;
   hipLaunchKernelGGL((row_stats_kernel<DT, XF, AL, NT>), dim3((unsigned)grid), dim3(kThreads), 0, stream, a);
@@ -690,9 +690,15 @@ static hipError_t launch_typed(const KArgs& a, hipStream_t stream, hipEvent_t* e
   constexpr int kT = Vec<DT>::kT;
   hipError_t e;
   if (ev) (void)hipEventRecord(ev[0], stream);
-  if (a.nt1 == kT) e = launch_stats<DT, XF, AL, kT>(a, stream);
-  else if (a.nt1 == kT / 2) e = launch_stats<DT, XF, AL, kT / 2>(a, stream);
-  else e = launch_stats<DT, XF, AL, kT / 4>(a, stream);
+  if (AL && a.stream_loads) {   // large read-once input: nontemporal loads in the statistics pass
+    if (a.nt1 == kT) e = launch_stats<DT, XF, kAlignedStream, kT>(a, stream);
+    else if (a.nt1 == kT / 2) e = launch_stats<DT, XF, kAlignedStream, kT / 2>(a, stream);
+    else e = launch_stats<DT, XF, kAlignedStream, kT / 4>(a, stream);
+  } else {
+    if (a.nt1 == kT) e = launch_stats<DT, XF, AL ? kAligned : kUnaligned, kT>(a, stream);
+    else if (a.nt1 == kT / 2) e = launch_stats<DT, XF, AL ? kAligned : kUnaligned, kT / 2>(a, stream);
+    else e = launch_stats<DT, XF, AL ? kAligned : kUnaligned, kT / 4>(a, stream);
+  }
   if (e != hipSuccess) return e;
   if (ev) (void)hipEventRecord(ev[1], stream);
   e = launch_rest<DT, XF, AL>(a, stream);

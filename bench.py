@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/),
 # scaled by the same counters' reading on a plain copy kernel; None = not measured.
 # Fetched + written bytes of row_stats_kernel per launch.
-MEASURED_TRAFFIC_BYTES = {"cfg1": None, "cfg2": 17.93e6, "cfg3": None, "cfg4": 277.42e6, "cfg5": 1143.1e6}
+MEASURED_TRAFFIC_BYTES = {"cfg1": None, "cfg2": 17.97e6, "cfg3": 76.93e6, "cfg4": 278.04e6, "cfg5": 1143.27e6}
 
 
 def parse():

@@ -286,3 +286,46 @@ def test_hip_graph_replays_match_eager(P, oracle):
             for o, e in zip(outs, eager):
                 for k in o:
                     assert torch.equal(o[k], e[k]), (cfg, rep, k)
+
+
+def test_long_draft_windows_and_tiny_shapes(P, oracle):
+    """L beyond one block of positions (the first-rejection scan loops), and the smallest shapes."""
+    for B, L, V, dtype, delta in ((2, 1500, 64, "f32", 50.0), (3, 257, 520, "bf16", 30.0), (1, 1, 2, "f32", 1.0),
+                                  (5, 1, 16384, "bf16", 1.1)):
+        w = make_workload(1, device="cuda", B=B, L=L, V=V, dtype=dtype)
+        om = P.cool_sd_schedule(P.COOL_SD_SCHED_UNIFORM, L, delta)      # large budget: long accepted prefixes
+        gpu = _run(P, oracle, w, om)
+        compare_verify(oracle, w, om, gpu)
+        if L >= 257:
+            assert gpu["accept_len"].max() > 256 or delta < 40
+    # everything rejected at the first position
+    w = make_workload(2, device="cuda", B=4, L=8, V=16384)
+    gpu = _run(P, oracle, w, np.zeros(8, np.float32))
+    assert (gpu["accept_len"] == 0).all()
+    compare_verify(oracle, w, np.zeros(8, np.float32), gpu)
+
+
+def test_draft_side_sampling_through_resample(P, oracle):
+    """Drawing x~ ~ Q (Algorithm 1, drafting stage) is cool_sd_resample with the draft's logits as the
+    only distribution: guidance, temperature and top-k apply, then an inverse-CDF draw from q."""
+    w = make_workload(3, device="cuda", B=16, L=1, V=16384, top_k=200)
+    d, du = w.draft[:, 0].contiguous(), w.draft_uncond[:, 0].contiguous()
+    params = P.make_params(d.unsqueeze(1), d.unsqueeze(1), has_bonus=0, top_k=200, cfg_scale=4.0, temperature=0.9)
+    ws = torch.empty(P.cool_sd_workspace_bytes(params), dtype=torch.uint8, device="cuda")
+    u = uniforms24(torch.Generator(device="cuda").manual_seed(9), (16,), "cuda")
+    tok = torch.full((16,), -7, dtype=torch.int32, device="cuda")
+    mass = torch.zeros(16, device="cuda")
+    P.cool_sd_resample(params, d, du, None, None, None, u, tok, mass, ws)
+    torch.cuda.synchronize()
+    ot, om_, g = oracle.resample(d.float().cpu().numpy(), None, None, u.cpu().numpy(),
+                                 target_uncond=du.float().cpu().numpy(), cfg_scale=4.0, temperature=0.9, top_k=200,
+                                 want_g=True)
+    np.testing.assert_allclose(mass.cpu().numpy(), om_, rtol=1e-5)
+    t = tok.cpu().numpy()
+    for b in range(16):
+        assert g[b][t[b]] > 0 and (g[b] > 0).sum() >= 200
+        if t[b] != ot[b]:
+            C = np.cumsum(g[b]); v = float(u[b]) * om_[b]
+            gap = (v - C[t[b]]) / om_[b] if t[b] < ot[b] else (C[t[b] - 1] - v) / om_[b]
+            assert 0 <= gap <= 1e-6
+    assert (t == ot).sum() >= 15

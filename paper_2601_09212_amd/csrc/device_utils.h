@@ -34,15 +34,33 @@ __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w 
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
 // ---------------------------------------------------------------- wave / block primitives
+// Wave-wide reductions.  Within each row of 16 lanes a DPP butterfly (swap neighbours, swap
+// pairs, mirror the half row, mirror the row) leaves the row's result in all 16 lanes; the four
+// row results are then read with v_readlane and combined in a fixed order, so the result is
+// wave-uniform and independent of which lanes are "first".
+template <int CTRL> __device__ __forceinline__ float dpp_f(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+constexpr int kDppSwap1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppSwap2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // row_half_mirror
+constexpr int kDppMirror = 0x140;      // row_mirror
+__device__ __forceinline__ float lane_f(float v, int lane) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
+  v = fmaxf(v, dpp_f<kDppSwap1>(v));
+  v = fmaxf(v, dpp_f<kDppSwap2>(v));
+  v = fmaxf(v, dpp_f<kDppHalfMirror>(v));
+  v = fmaxf(v, dpp_f<kDppMirror>(v));
+  return fmaxf(fmaxf(lane_f(v, 0), lane_f(v, 16)), fmaxf(lane_f(v, 32), lane_f(v, 48)));
 }
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  v = __fadd_rn(v, dpp_f<kDppSwap1>(v));
+  v = __fadd_rn(v, dpp_f<kDppSwap2>(v));
+  v = __fadd_rn(v, dpp_f<kDppHalfMirror>(v));
+  v = __fadd_rn(v, dpp_f<kDppMirror>(v));
+  return __fadd_rn(__fadd_rn(lane_f(v, 0), lane_f(v, 16)), __fadd_rn(lane_f(v, 32), lane_f(v, 48)));
 }
 __device__ __forceinline__ int wave_min_i(int v) {
 #pragma unroll

@@ -126,6 +126,7 @@ def verify(target, draft, draft_tokens, omega, u_accept, u_resample, *, target_u
     B, Lt, V = t.shape
     L = d.shape[1]
     assert d.shape == (B, L, V) and Lt in (L, L + 1)
+    assert (tu is None) == (du is None) and (tu is None or (tu.shape == t.shape and du.shape == d.shape))
     has_bonus = int(Lt == L + 1)
     tok = np.ascontiguousarray(draft_tokens, dtype=np.int32).reshape(B, L)
     om = _f32(omega)

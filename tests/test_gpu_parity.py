@@ -329,3 +329,39 @@ def test_draft_side_sampling_through_resample(P, oracle):
             gap = (v - C[t[b]]) / om_[b] if t[b] < ot[b] else (C[t[b] - 1] - v) / om_[b]
             assert 0 <= gap <= 1e-6
     assert (t == ot).sum() >= 15
+
+
+def test_random_shapes_and_options(P, oracle):
+    """Seeded sweep over shapes, dtypes and options (every code path: element-wise loads, one-chunk and
+    long rows, guidance, temperature, top-k, both resampling laws, with / without bonus row)."""
+    rng = np.random.default_rng(2026)
+    n_exempt = 0
+    for case in range(40):
+        dtype = "bf16" if rng.random() < 0.6 else "f32"
+        V = int(rng.choice([3, 17, 257, 1024, 4097, 8200, 16384, 16385, 20001, 33000, 70000]))
+        B = int(rng.integers(1, 6))
+        L = int(rng.integers(1, 10))
+        guided = rng.random() < 0.4
+        cfg = 3 if guided else int(rng.choice([1, 2, 4, 5]))
+        top_k = 0
+        if V <= 16384 and rng.random() < 0.5:
+            top_k = int(rng.integers(1, V + 1))
+        w = make_workload(cfg, device="cuda", B=B, L=L, V=V, dtype=dtype, seed=1000 + case,
+                          top_k=top_k if guided else None)
+        if not guided:
+            w.top_k = top_k
+        if rng.random() < 0.3:
+            w.temperature = float(rng.choice([0.5, 0.8, 1.3]))
+        if rng.random() < 0.3:
+            w.target = w.target[:, :L]                                   # no bonus row
+            if w.target_uncond is not None:
+                w.target_uncond = w.target_uncond[:, :L]
+        mode = int(rng.integers(0, 2))
+        delta = float(rng.choice([1.0, 1.1, 2.0, 4.0]))
+        om = _omega(P, w, delta=delta)
+        print("case", case, dict(cfg=cfg, B=B, L=L, V=V, dtype=dtype, top_k=w.top_k, T=w.temperature,
+                                 bonus=w.target.shape[1] == L + 1, mode=mode, delta=delta), flush=True)
+        gpu = _run(P, oracle, w, om, resample_mode=mode)
+        st = compare_verify(oracle, w, om, gpu, resample_mode=mode, has_bonus=w.target.shape[1] == L + 1)
+        n_exempt += st["tau_exempt"] + st["token_exempt"]
+    assert n_exempt <= 2

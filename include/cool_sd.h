@@ -90,7 +90,7 @@ typedef struct {
  * negative weight). */
 int cool_sd_schedule(int32_t kind, int32_t L, float delta, float param, float* omega_out);
 
-/* Bytes of device workspace cool_sd_verify / cool_sd_resample need for these params
+/* Bytes of device workspace cool_sd_verify / cool_sd_resample / cool_sd_diagnostics need for these params
  * (for resample only B, V, dtype and top_k matter).  0 on invalid params. */
 size_t cool_sd_workspace_bytes(const cool_sd_params* p);
 
@@ -140,6 +140,25 @@ int cool_sd_resample(const cool_sd_params* p,
                      int32_t* token_dev, float* resid_mass_dev,
                      void* workspace_dev, size_t workspace_bytes,
                      void* hip_stream);
+
+/* Per-position diagnostics of Theorem 2 for the drafted prefix, asynchronous on hip_stream:
+ *   alpha_dev out float [B, L]:  alpha_i = sum_x min{q_i(x), omega_i p_i(x)} = sum_x q_i(x) f_i(x),
+ *             the probability that position i accepts a token drawn from q_i; the expected
+ *             accepted length is 1 + sum_i prod_{j<=i} alpha_j averaged over drafts (Eq. token_exp)
+ *   beta_dev  out float [B, L]:  beta_i = sum_x [min{q_i(x), omega_i p_i(x)} - p_i(x)]_+, half of
+ *             what position i adds to the total-variation bound when G* resamples
+ *             (Theorem 2, proof Step 2: sum|p - q f| - sum(1-f)q = 2 beta); 0 iff omega_i <= 1
+ *             or the excess vanishes, so strict speculative decoding reports all zeros.
+ * Tensors, strides, omega and the logit transform are those of cool_sd_verify (the bonus row of
+ * the target tensor is not read); resample_mode is ignored.  Same workspace, same size.  Rows
+ * of at most 16384 logits without top-k are read once; otherwise twice (statistics, then sums). */
+int cool_sd_diagnostics(const cool_sd_params* p,
+                        const void* target_dev, const void* target_uncond_dev,
+                        const void* draft_dev, const void* draft_uncond_dev,
+                        const float* omega_dev,
+                        float* alpha_dev, float* beta_dev,
+                        void* workspace_dev, size_t workspace_bytes,
+                        void* hip_stream);
 
 /* Benchmark instrumentation (not for production paths, not thread-safe, not usable while the
  * stream is being captured into a graph).  While enabled, cool_sd_verify / cool_sd_resample

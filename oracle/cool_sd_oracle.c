@@ -24,7 +24,8 @@
  * omega <= 1 (Theorem 1 and the omega<1 extension), chi-square of sampled
  * outputs, exact TV vs the Theorem-2 bound, the L=1 closed form, the LP value
  * of Proposition LP, Monte-Carlo accepted length vs Eq. token_exp, schedule
- * closed forms, softmax vs scipy.
+ * closed forms, softmax vs scipy; the Theorem-2 diagnostics against the exact TV at
+ * L = 1 and against Monte-Carlo acceptance rates.
  *
  * Parity unpinned by the paper (fixed only by this build's readings, and
  * checked against brute-force definitions on tiny rows): the inverse-CDF
@@ -194,6 +195,27 @@ double csd_oracle_residual(const double *p, const double *q, int V, double omega
         for (int x = 0; x < V; ++x) { g[x] = p[x]; R += g[x]; }
     }
     return R;
+}
+
+/* Per-position quantities of Theorem 2, written from their definitions.
+ *   alpha = sum_x q(x) f(x): the probability that a token drawn from q is accepted; the
+ *           factor whose running product gives E[tau + 1] in Eq. token_exp.
+ *   beta  = (1/2) [ sum_x |p(x) - q(x) f(x)| - sum_x (1 - f(x)) q(x) ]: half the bracket of the
+ *           total-variation bound when G* resamples (Theorem 2, proof Step 2).
+ * f(x) = min{1, omega p(x)/q(x)}, 0/0 := 1 (Eq. relax). */
+void csd_oracle_position_diagnostics(const double *p, const double *q, int V, double omega,
+                                     double *alpha, double *beta)
+{
+    double a = 0.0, abs_sum = 0.0, rej = 0.0;
+    for (int x = 0; x < V; ++x) {
+        double f = csd_oracle_accept_prob(p[x], q[x], omega);
+        double qf = q[x] * f;
+        a += qf;
+        abs_sum += fabs(p[x] - qf);
+        rej += (1.0 - f) * q[x];
+    }
+    *alpha = a;
+    *beta = 0.5 * (abs_sum - rej);
 }
 
 /* Inverse CDF of Norm(g) at v = u*R: the smallest token k whose running sum

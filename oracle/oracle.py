@@ -38,6 +38,8 @@ def lib():
         L.csd_oracle_accept.restype = C.c_int
         L.csd_oracle_residual.argtypes = [dp, dp, C.c_int, C.c_double, C.c_int, dp]
         L.csd_oracle_residual.restype = C.c_double
+        L.csd_oracle_position_diagnostics.argtypes = [dp, dp, C.c_int, C.c_double, dp, dp]
+        L.csd_oracle_position_diagnostics.restype = None
         L.csd_oracle_inverse_cdf.argtypes = [dp, C.c_int, C.c_double]
         L.csd_oracle_inverse_cdf.restype = C.c_int
         L.csd_oracle_verify.argtypes = [
@@ -107,6 +109,36 @@ def residual(p, q, omega, mode=RESAMPLE_OPT):
     R = lib().csd_oracle_residual(_ptr(p, C.c_double), _ptr(qq, C.c_double), p.shape[0],
                                   float(omega), mode, _ptr(g, C.c_double))
     return g, R
+
+
+def position_diagnostics(p, q, omega):
+    """(alpha, beta) of one position: acceptance probability and half the TV-bound bracket."""
+    p = np.ascontiguousarray(p, dtype=np.float64)
+    q = np.ascontiguousarray(q, dtype=np.float64)
+    out = np.empty(2, dtype=np.float64)
+    lib().csd_oracle_position_diagnostics(_ptr(p, C.c_double), _ptr(q, C.c_double), p.shape[0], float(omega),
+                                          _ptr(out[0:1], C.c_double), _ptr(out[1:2], C.c_double))
+    return float(out[0]), float(out[1])
+
+
+def diagnostics(target, draft, omega, *, target_uncond=None, draft_uncond=None, cfg_scale=1.0,
+                temperature=1.0, top_k=0):
+    """alpha[B, L], beta[B, L] (Theorem 2) of every drafted position: transform, softmax and
+    position_diagnostics per row pair.  target may carry a bonus row, which is ignored."""
+    t, d = _f32(target), _f32(draft)
+    tu, du = _f32(target_uncond), _f32(draft_uncond)
+    B, L, V = d.shape
+    assert t.shape[0] == B and t.shape[1] in (L, L + 1) and t.shape[2] == V
+    assert (tu is None) == (du is None) and (tu is None or (tu.shape == t.shape and du.shape == d.shape))
+    om = np.broadcast_to(_f32(omega), (B, L))
+    alpha = np.empty((B, L), np.float64)
+    beta = np.empty((B, L), np.float64)
+    for b in range(B):
+        for i in range(L):
+            p = softmax(transform_row(t[b, i], None if tu is None else tu[b, i], cfg_scale, temperature, top_k))
+            q = softmax(transform_row(d[b, i], None if du is None else du[b, i], cfg_scale, temperature, top_k))
+            alpha[b, i], beta[b, i] = position_diagnostics(p, q, om[b, i])
+    return alpha, beta
 
 
 def inverse_cdf(g, v):

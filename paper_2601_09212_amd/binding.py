@@ -59,6 +59,8 @@ def lib():
         L.cool_sd_verify.restype = C.c_int
         L.cool_sd_resample.argtypes = [pp] + [vp] * 8 + [vp, C.c_size_t, vp]
         L.cool_sd_resample.restype = C.c_int
+        L.cool_sd_diagnostics.argtypes = [pp] + [vp] * 7 + [vp, C.c_size_t, vp]
+        L.cool_sd_diagnostics.restype = C.c_int
         L.cool_sd_profile_enable.argtypes = [C.c_int]
         L.cool_sd_profile_enable.restype = C.c_int
         L.cool_sd_profile_read.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_float)]
@@ -130,6 +132,17 @@ def cool_sd_resample(params, target_rows, target_uncond_rows, draft_rows, draft_
     return rc
 
 
+def cool_sd_diagnostics(params, target, target_uncond, draft, draft_uncond, omega, alpha, beta, workspace,
+                        stream=None, check=True):
+    rc = lib().cool_sd_diagnostics(C.byref(params), _ptr(target), _ptr(target_uncond), _ptr(draft),
+                                   _ptr(draft_uncond), _ptr(omega), _ptr(alpha), _ptr(beta), _ptr(workspace),
+                                   0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                   _stream(stream))
+    if check and rc != 0:
+        raise CoolSDError(rc, "cool_sd_diagnostics")
+    return rc
+
+
 def cool_sd_profile_enable(enable):
     rc = lib().cool_sd_profile_enable(int(bool(enable)))
     if rc != 0:
@@ -181,3 +194,17 @@ def verify_workload(w, omega, *, resample_mode=COOL_SD_RESAMPLE_OPT, workspace=N
                    w.u_accept, w.u_resample, out["accept_len"], out["next_token"], out.get("p_tok"),
                    out.get("q_tok"), out.get("f"), out["resid_mass"], workspace)
     return out
+
+
+def diagnostics_workload(w, omega, *, workspace=None):
+    """Allocate alpha / beta (torch, on the inputs' device), call cool_sd_diagnostics once."""
+    import torch
+    dev = w.target.device
+    params = make_params(w.target, w.draft, top_k=w.top_k, cfg_scale=w.cfg_scale, temperature=w.temperature,
+                         omega_stride_b=0 if omega.dim() == 1 else omega.stride(0))
+    if workspace is None:
+        workspace = torch.empty(max(cool_sd_workspace_bytes(params), 256), dtype=torch.uint8, device=dev)
+    alpha = torch.full((w.B, w.L), float("nan"), dtype=torch.float32, device=dev)
+    beta = torch.full((w.B, w.L), float("nan"), dtype=torch.float32, device=dev)
+    cool_sd_diagnostics(params, w.target, w.target_uncond, w.draft, w.draft_uncond, omega, alpha, beta, workspace)
+    return alpha, beta

@@ -11,6 +11,9 @@ HEADERS = ["device_utils.h", "kernels.h", "topk.h"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # a*b followed by +-c stays two roundings unless the source says fma: the kernels rely on
+         # p - min(q, omega p) being exactly zero where the two are equal
+         "-ffp-contract=off",
          "-Wall", "-Wno-unused-function"]
 
 

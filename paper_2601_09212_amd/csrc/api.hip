@@ -14,11 +14,12 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t seq_stat, chunk_R, thr, tok_logit, rowstat, part, total;
+  size_t seq_stat, chunk_R, thr, tok_logit, rowstat, part, diag_part, total;
 };
 
 // rows: all logit rows (target + draft); c1: statistics chunks per row; C: sampling chunks per row.
-Layout make_layout(int64_t B, int64_t rows, int64_t c1, int64_t C) {
+// pairs x CD: (alpha, beta) chunk sums of the diagnostics call (0 pairs: region absent).
+Layout make_layout(int64_t B, int64_t rows, int64_t c1, int64_t C, int64_t pairs = 0, int64_t CD = 0) {
   Layout o{};
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes); return at; };
@@ -28,6 +29,7 @@ Layout make_layout(int64_t B, int64_t rows, int64_t c1, int64_t C) {
   o.tok_logit = take(size_t(rows) * 4);
   o.rowstat = take(size_t(rows) * 8);
   o.part = take(size_t(rows) * c1 * 8);
+  o.diag_part = take(size_t(pairs) * CD * 8);
   o.total = off;
   return o;
 }
@@ -142,6 +144,52 @@ int run(const cool_sd_params* p, bool resample_only,
   return e == hipSuccess ? COOL_SD_OK : COOL_SD_ELAUNCH;
 }
 
+// cool_sd_diagnostics: alpha_i, beta_i of every (target, draft) row pair.  The bonus row, if the
+// target tensor has one, is skipped through the strides.
+int run_diag(const cool_sd_params* p, const void* t, const void* tu, const void* d, const void* du,
+             const float* omega, float* alpha, float* beta, void* ws, size_t ws_bytes, void* stream) {
+  if (p->top_k > 0 && p->V > csd::kChunk) return COOL_SD_EUNSUPPORTED;
+  const int64_t pairs = int64_t(p->B) * p->L;
+  const Chunking ch = pick_chunking(p, 2 * pairs);
+  const bool local = p->top_k == 0 && p->V <= csd::kChunk;
+  const int64_t CD = local ? 1 : (int64_t(p->V) + 8191) / 8192;
+  const Layout lay = make_layout(p->B, 2 * pairs, ch.c1, 1, pairs, CD);
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0 || ws_bytes < lay.total) return COOL_SD_EWORKSPACE;
+
+  const int kE = (p->dtype == COOL_SD_BF16) ? 8 : 4;
+  bool aligned = (p->V % kE == 0) && is_aligned16(t) && is_aligned16(d) && (p->t_stride_b % kE == 0) &&
+                 (p->t_stride_l % kE == 0) && (p->d_stride_b % kE == 0) && (p->d_stride_l % kE == 0);
+  if (tu) aligned = aligned && is_aligned16(tu) && is_aligned16(du);
+
+  char* w = static_cast<char*>(ws);
+  csd::KArgs a{};
+  a.t = t; a.tu = tu; a.d = d; a.du = du;
+  a.omega = omega; a.alpha = alpha; a.beta = beta;
+  a.t_sb = p->t_stride_b; a.t_sl = p->t_stride_l; a.d_sb = p->d_stride_b; a.d_sl = p->d_stride_l;
+  a.om_sb = p->omega_stride_b;
+  a.B = p->B; a.L = p->L; a.V = p->V; a.has_bonus = 0;
+  a.top_k = p->top_k; a.resample_mode = p->resample_mode;
+  a.aligned = aligned ? 1 : 0;
+  a.stream_loads = 0;     // every row is read again by the second pass
+  a.nchunks = (int32_t)CD;
+  a.cfg_scale = p->cfg_scale;
+  a.inv_T = 1.0f / p->temperature;
+  a.rows_t = (int32_t)pairs; a.rows_d = (int32_t)pairs;
+  a.nt1 = ch.nt1; a.chunk1 = ch.chunk1; a.c1 = (int32_t)ch.c1;
+  a.thr = reinterpret_cast<float*>(w + lay.thr);
+  a.tok_logit = reinterpret_cast<float*>(w + lay.tok_logit);
+  a.part = reinterpret_cast<float2*>(w + lay.part);
+  a.rowstat = reinterpret_cast<float2*>(w + lay.rowstat);
+  a.diag_part = reinterpret_cast<float2*>(w + lay.diag_part);
+  const bool direct = ch.c1 <= 4;
+  a.stat = direct ? a.part : a.rowstat;
+  a.cs = direct ? (int32_t)ch.c1 : 1;
+
+  const bool xf = (tu != nullptr) || (p->temperature != 1.0f) || (p->top_k > 0);
+  hipError_t e = csd::launch_diagnostics(a, p->dtype, xf, local, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? COOL_SD_OK : COOL_SD_ELAUNCH;
+}
+
 }  // namespace
 
 extern "C" {
@@ -185,7 +233,8 @@ size_t cool_sd_workspace_bytes(const cool_sd_params* p) {
   // sized for the finest chunking so that the answer does not depend on optional inputs
   const int64_t c1_max = (int64_t(p->V) + 4095) / 4096;
   (void)ch;
-  return make_layout(p->B, rows, c1_max, c1_max).total;
+  const int64_t pairs = full ? int64_t(p->B) * L : 0;       // cool_sd_diagnostics: chunks of 8192 logits
+  return make_layout(p->B, rows, c1_max, c1_max, pairs, (int64_t(p->V) + 8191) / 8192).total;
 }
 
 int cool_sd_workspace_init(void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
@@ -224,6 +273,17 @@ int cool_sd_resample(const cool_sd_params* p, const void* target_rows_dev, const
   return run(p, true, target_rows_dev, target_uncond_rows_dev, draft_rows_dev, draft_uncond_rows_dev, nullptr,
              omega_rows_dev, nullptr, u_dev, nullptr, token_dev, nullptr, nullptr, nullptr, resid_mass_dev,
              workspace_dev, workspace_bytes, hip_stream);
+}
+
+int cool_sd_diagnostics(const cool_sd_params* p, const void* target_dev, const void* target_uncond_dev,
+                        const void* draft_dev, const void* draft_uncond_dev, const float* omega_dev,
+                        float* alpha_dev, float* beta_dev, void* workspace_dev, size_t workspace_bytes,
+                        void* hip_stream) {
+  if (!params_ok(p, false)) return COOL_SD_EINVAL;
+  if (!target_dev || !draft_dev || !omega_dev || !alpha_dev || !beta_dev) return COOL_SD_EINVAL;
+  if ((target_uncond_dev == nullptr) != (draft_uncond_dev == nullptr)) return COOL_SD_EINVAL;
+  return run_diag(p, target_dev, target_uncond_dev, draft_dev, draft_uncond_dev, omega_dev, alpha_dev, beta_dev,
+                  workspace_dev, workspace_bytes, hip_stream);
 }
 
 int cool_sd_profile_enable(int enable) {

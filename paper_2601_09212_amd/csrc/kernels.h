@@ -37,6 +37,10 @@ struct KArgs {
   int32_t cs;
   float4* seq_stat;         // [B]           statistics of the sampled row (several-chunk path)
   float* chunk_R;           // [B, nchunks]  residual mass per chunk of the sampled row  (nchunks > 1)
+  // diagnostics call only (nchunks = chunks of 8192 logits per row there, has_bonus = 0)
+  float* alpha;             // [B, L] out
+  float* beta;              // [B, L] out
+  float2* diag_part;        // [B*L, nchunks]  (alpha, beta) sums per chunk
 };
 
 // Enqueue the kernels of one verify (or stand-alone resample) call.  xf: the logit transform
@@ -44,6 +48,10 @@ struct KArgs {
 // ev: nullptr, or three events recorded before the statistics kernel, after it, and after the
 // last kernel.
 hipError_t launch_verify(const KArgs& a, int dtype, bool xf, hipStream_t stream, hipEvent_t* ev);
+
+// Enqueue the kernels of one diagnostics call (alpha_i, beta_i of every row pair).  local: rows
+// are one chunk and need no statistics pass.
+hipError_t launch_diagnostics(const KArgs& a, int dtype, bool xf, bool local, hipStream_t stream);
 
 // Zero n 32-bit words.
 hipError_t launch_zero(uint32_t* p, size_t n, hipStream_t stream);

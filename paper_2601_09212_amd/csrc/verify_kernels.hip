@@ -660,6 +660,108 @@ __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
   }
 }
 
+// ============================================================================ diagnostics
+// Per-position quantities of Theorem 2 for the row pair (p_i, q_i) with relaxation omega_i:
+//   alpha_i = sum_x min{q_i(x), omega_i p_i(x)} = sum_x q_i(x) f_i(x): the probability that a
+//             token drawn from q_i is accepted, the factor of the expected accepted length
+//             (Eq. token_exp);
+//   beta_i  = sum_x [min{q_i(x), omega_i p_i(x)} - p_i(x)]_+ : half the bracket that position i
+//             contributes to the total-variation bound when G* is the resampling law
+//             (Theorem 2, proof Step 2); zero when omega_i <= 1.
+// Both need p_i and q_i normalised, i.e. the statistics of the whole row pair first.
+//   LOCAL   the row pair is one chunk (at most 16384 logits): statistics are formed here from
+//           the registers, every logit is read once, results go straight to alpha / beta.
+//   else    statistics come from row_stats_kernel; grid = B L x CD chunks of 8192 logits; the
+//           chunk sums go to diag_part and diag_combine_kernel adds them in ascending order.
+template <int DT, bool XF, int AL, int NT, bool LOCAL>
+__global__ __launch_bounds__(kThreads) void diag_kernel(const KArgs a) {
+  constexpr int kE = Vec<DT>::kE, kES = Vec<DT>::kES;
+  __shared__ float red[4][kWaves];
+  const int CD = a.nchunks;
+  const int rp = blockIdx.x / CD, c = blockIdx.x - rp * CD;     // row pair (b, i), chunk
+  const int b = rp / a.L, i = rp - b * a.L;
+  const int rt_ = rp, rd_ = a.rows_t + rp;                       // has_bonus is 0 here
+  const int64_t offt = int64_t(b) * a.t_sb + int64_t(i) * a.t_sl;
+  const int64_t offd = int64_t(b) * a.d_sb + int64_t(i) * a.d_sl;
+  const int64_t base = int64_t(c) * (NT * kThreads * kE);
+  const bool masked = XF && !LOCAL && a.top_k > 0;
+  const float thr_t = masked ? a.thr[rt_] : -INFINITY;
+  const float thr_d = masked ? a.thr[rd_] : -INFINITY;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+
+  RowRegs<DT, XF, NT> rt, rd;
+  load_chunk<DT, XF, AL, NT>(rt, row_ptr(a.t, offt, kES), row_ptr(a.tu, offt, kES), base, a.V, a.cfg_scale,
+                             a.inv_T, thr_t);
+  load_chunk<DT, XF, AL, NT>(rd, row_ptr(a.d, offd, kES), row_ptr(a.du, offd, kES), base, a.V, a.cfg_scale,
+                             a.inv_T, thr_d);
+  float Ct, St, Cd, Sd;
+  if constexpr (LOCAL) {
+    float c0, s0, c1, s1;
+    thread_stats<DT, XF, NT>(rt, c0, s0);
+    thread_stats<DT, XF, NT>(rd, c1, s1);
+    const float wc0 = wave_max(c0), wc1 = wave_max(c1);
+    const float ws0 = wave_sum(s0 * exp2_fast(c0 - wc0));       // exact power-of-two rescale
+    const float ws1 = wave_sum(s1 * exp2_fast(c1 - wc1));
+    if (lane == 0) { red[0][wv] = wc0; red[1][wv] = ws0; red[2][wv] = wc1; red[3][wv] = ws1; }
+    __syncthreads();
+    Ct = fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3]));
+    Cd = fmaxf(fmaxf(red[2][0], red[2][1]), fmaxf(red[2][2], red[2][3]));
+    St = 0.f; Sd = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      St = __fadd_rn(St, red[1][w] * exp2_fast(red[0][w] - Ct));
+      Sd = __fadd_rn(Sd, red[3][w] * exp2_fast(red[2][w] - Cd));
+    }
+    __syncthreads();                                              // red is reused below
+  } else {
+    combine_row(a, rt_, Ct, St);
+    combine_row(a, rd_, Cd, Sd);
+  }
+  const float at = 1.f / St, ad = 1.f / Sd;
+  const float omega = a.omega[int64_t(b) * a.om_sb + i];
+  float sa = 0.f, sb = 0.f;
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+#pragma unroll
+    for (int j = 0; j < kE; ++j) {
+      const float p = __fmul_rn(exp2_fast(__fmaf_rn(rt.get(t, j), kLog2e, -Ct)), at);
+      const float q = __fmul_rn(exp2_fast(__fmaf_rn(rd.get(t, j), kLog2e, -Cd)), ad);
+      const float m = fminf(q, __fmul_rn(omega, p));
+      sa = __fadd_rn(sa, m);
+      sb = __fadd_rn(sb, fmaxf(__fsub_rn(m, p), 0.f));
+    }
+  }
+  sa = wave_sum(sa);
+  sb = wave_sum(sb);
+  if (lane == 0) { red[0][wv] = sa; red[1][wv] = sb; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const float A = __fadd_rn(__fadd_rn(__fadd_rn(red[0][0], red[0][1]), red[0][2]), red[0][3]);
+    const float Bv = __fadd_rn(__fadd_rn(__fadd_rn(red[1][0], red[1][1]), red[1][2]), red[1][3]);
+    if constexpr (LOCAL) {
+      a.alpha[rp] = A;
+      a.beta[rp] = Bv;
+    } else {
+      a.diag_part[int64_t(rp) * CD + c] = make_float2(A, Bv);
+    }
+  }
+}
+
+// Adds the chunk sums of every row pair in ascending chunk order: one thread per row pair.
+__global__ __launch_bounds__(kThreads) void diag_combine_kernel(const KArgs a) {
+  const int rp = blockIdx.x * kThreads + threadIdx.x;
+  if (rp >= a.B * a.L) return;
+  const float2* p = a.diag_part + int64_t(rp) * a.nchunks;
+  float A = 0.f, Bv = 0.f;
+  for (int c = 0; c < a.nchunks; ++c) {
+    const float2 v = p[c];
+    A = __fadd_rn(A, v.x);
+    Bv = __fadd_rn(Bv, v.y);
+  }
+  a.alpha[rp] = A;
+  a.beta[rp] = Bv;
+}
+
 __global__ void zero_words_kernel(uint32_t* p, size_t n) {
   size_t i = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
   const size_t stride = size_t(gridDim.x) * blockDim.x;
@@ -684,21 +786,25 @@ static hipError_t launch_stats(const KArgs& a, hipStream_t stream) {
 template <int DT, bool XF, bool AL>
 static hipError_t launch_rest(const KArgs& a, hipStream_t stream);
 
+// Statistics pass with the chunk size and load flavour the host chose.
+template <int DT, bool XF, bool AL>
+static hipError_t launch_stats_any(const KArgs& a, hipStream_t stream) {
+  constexpr int kT = Vec<DT>::kT;
+  if (AL && a.stream_loads) {   // large read-once input: nontemporal loads
+    if (a.nt1 == kT) return launch_stats<DT, XF, kAlignedStream, kT>(a, stream);
+    if (a.nt1 == kT / 2) return launch_stats<DT, XF, kAlignedStream, kT / 2>(a, stream);
+    return launch_stats<DT, XF, kAlignedStream, kT / 4>(a, stream);
+  }
+  if (a.nt1 == kT) return launch_stats<DT, XF, AL ? kAligned : kUnaligned, kT>(a, stream);
+  if (a.nt1 == kT / 2) return launch_stats<DT, XF, AL ? kAligned : kUnaligned, kT / 2>(a, stream);
+  return launch_stats<DT, XF, AL ? kAligned : kUnaligned, kT / 4>(a, stream);
+}
+
 template <int DT, bool XF, bool AL>
 static hipError_t launch_typed(const KArgs& a, hipStream_t stream, hipEvent_t* ev) {
   (void)hipGetLastError();
-  constexpr int kT = Vec<DT>::kT;
-  hipError_t e;
   if (ev) (void)hipEventRecord(ev[0], stream);
-  if (AL && a.stream_loads) {   // large read-once input: nontemporal loads in the statistics pass
-    if (a.nt1 == kT) e = launch_stats<DT, XF, kAlignedStream, kT>(a, stream);
-    else if (a.nt1 == kT / 2) e = launch_stats<DT, XF, kAlignedStream, kT / 2>(a, stream);
-    else e = launch_stats<DT, XF, kAlignedStream, kT / 4>(a, stream);
-  } else {
-    if (a.nt1 == kT) e = launch_stats<DT, XF, AL ? kAligned : kUnaligned, kT>(a, stream);
-    else if (a.nt1 == kT / 2) e = launch_stats<DT, XF, AL ? kAligned : kUnaligned, kT / 2>(a, stream);
-    else e = launch_stats<DT, XF, AL ? kAligned : kUnaligned, kT / 4>(a, stream);
-  }
+  hipError_t e = launch_stats_any<DT, XF, AL>(a, stream);
   if (e != hipSuccess) return e;
   if (ev) (void)hipEventRecord(ev[1], stream);
   e = launch_rest<DT, XF, AL>(a, stream);
@@ -742,6 +848,46 @@ static hipError_t launch_al(const KArgs& a, hipStream_t stream, hipEvent_t* ev) 
 hipError_t launch_verify(const KArgs& a, int dtype, bool xf, hipStream_t stream, hipEvent_t* ev) {
   if (dtype == kDtBF16) return xf ? launch_al<kDtBF16, true>(a, stream, ev) : launch_al<kDtBF16, false>(a, stream, ev);
   return xf ? launch_al<kDtF32, true>(a, stream, ev) : launch_al<kDtF32, false>(a, stream, ev);
+}
+
+template <int DT, bool XF, bool AL>
+static hipError_t launch_diag_typed(const KArgs& a, bool local, hipStream_t stream) {
+  constexpr int kT = Vec<DT>::kT;
+  constexpr int kA = AL ? kAligned : kUnaligned;
+  (void)hipGetLastError();
+  const int64_t pairs = int64_t(a.B) * a.L;
+  if (local) {
+    hipLaunchKernelGGL((diag_kernel<DT, XF, kA, kT, true>), dim3((unsigned)pairs), dim3(kThreads), 0, stream, a);
+    return checked("diag_kernel (one chunk)");
+  }
+  hipError_t e = launch_stats_any<DT, XF, AL>(a, stream);
+  if (e != hipSuccess) return e;
+  if (a.cs != a.c1) {
+    const int64_t gridc = (int64_t(a.rows_t) + a.rows_d + kWaves - 1) / kWaves;
+    hipLaunchKernelGGL(combine_rows_kernel, dim3((unsigned)gridc), dim3(kThreads), 0, stream, a);
+    e = checked("combine_rows_kernel");
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((diag_kernel<DT, XF, kA, kT / 2, false>), dim3((unsigned)(pairs * a.nchunks)), dim3(kThreads), 0,
+                     stream, a);
+  e = checked("diag_kernel");
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(diag_combine_kernel, dim3((unsigned)((pairs + kThreads - 1) / kThreads)), dim3(kThreads), 0,
+                     stream, a);
+  return checked("diag_combine_kernel");
+}
+
+hipError_t launch_diagnostics(const KArgs& a, int dtype, bool xf, bool local, hipStream_t stream) {
+  if (dtype == kDtBF16) {
+    if (xf) return a.aligned ? launch_diag_typed<kDtBF16, true, true>(a, local, stream)
+                             : launch_diag_typed<kDtBF16, true, false>(a, local, stream);
+    return a.aligned ? launch_diag_typed<kDtBF16, false, true>(a, local, stream)
+                     : launch_diag_typed<kDtBF16, false, false>(a, local, stream);
+  }
+  if (xf) return a.aligned ? launch_diag_typed<kDtF32, true, true>(a, local, stream)
+                           : launch_diag_typed<kDtF32, true, false>(a, local, stream);
+  return a.aligned ? launch_diag_typed<kDtF32, false, true>(a, local, stream)
+                   : launch_diag_typed<kDtF32, false, false>(a, local, stream);
 }
 
 hipError_t launch_zero(uint32_t* p, size_t n, hipStream_t stream) {

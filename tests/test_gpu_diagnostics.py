@@ -1,0 +1,115 @@
+"""Parity of cool_sd_diagnostics (alpha_i, beta_i of Theorem 2) against the CPU oracle.
+
+Tolerances.  alpha is a sum of non-negative terms, each with the fp32 relative error of a
+probability: 1e-5 relative.  beta = sum_x [min(q, omega p) - p]_+ subtracts probabilities, so
+its error is absolute: every term errs by at most a few ulp of p(x), hence |error| <= a few
+1e-7 x sum_x p(x); the test allows 2e-6 absolute plus 1e-5 relative.  At omega <= 1 no term can
+be positive in either arithmetic and beta must be exactly zero.
+"""
+import numpy as np
+import pytest
+import torch
+
+from workloads import make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2601_09212_amd as pkg
+    pkg.binding.lib()
+    return pkg
+
+
+def _oracle_diag(oracle, w, om):
+    kw = dict(cfg_scale=w.cfg_scale, temperature=w.temperature, top_k=w.top_k)
+    tu = None if w.target_uncond is None else w.target_uncond.float().cpu().numpy()
+    du = None if w.draft_uncond is None else w.draft_uncond.float().cpu().numpy()
+    return oracle.diagnostics(w.target.float().cpu().numpy(), w.draft.float().cpu().numpy(), om,
+                              target_uncond=tu, draft_uncond=du, **kw)
+
+
+def _check(P, oracle, w, om):
+    omega = torch.from_numpy(np.ascontiguousarray(om, dtype=np.float32)).cuda()
+    alpha, beta = P.diagnostics_workload(w, omega)
+    torch.cuda.synchronize()
+    alpha, beta = alpha.cpu().numpy().astype(np.float64), beta.cpu().numpy().astype(np.float64)
+    a_ref, b_ref = _oracle_diag(oracle, w, om)
+    np.testing.assert_allclose(alpha, a_ref, rtol=1e-5, atol=1e-9)
+    np.testing.assert_allclose(beta, b_ref, rtol=1e-5, atol=2e-6)
+    omb = np.broadcast_to(om, alpha.shape)
+    assert (beta[omb <= 1.0] == 0.0).all()
+    assert (alpha >= 0).all() and (alpha <= 1.0 + 1e-5).all() and (beta >= 0).all()
+    return alpha, beta
+
+
+SHAPES = [
+    (1, 1, 4, 16384, "f32"),        # one chunk, fp32
+    (2, 4, 8, 16384, "bf16"),       # one chunk, bf16
+    (2, 3, 5, 4104, "bf16"),        # partial last tile
+    (2, 3, 3, 5001, "bf16"),        # element-wise loads
+    (1, 2, 3, 1003, "f32"),
+    (1, 2, 2, 8, "f32"),
+    (2, 2, 2, 1, "bf16"),           # single token: alpha = min(1, omega), beta = [min(1, omega) - 1]_+ = 0
+    (5, 2, 3, 40000, "bf16"),       # statistics pass + five chunks of 8192, ragged tail
+    (5, 2, 2, 262144, "bf16"),
+    (1, 2, 2, 20000, "f32"),
+    (5, 3, 2, 16392, "bf16"),
+]
+
+
+@pytest.mark.parametrize("cfg,B,L,V,dtype", SHAPES)
+def test_diagnostics_shapes(P, oracle, cfg, B, L, V, dtype):
+    print("case", cfg, B, L, V, dtype, flush=True)
+    w = make_workload(cfg, device="cuda", B=B, L=L, V=V, dtype=dtype)
+    om = P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, L, 2.0, w.nu)
+    _check(P, oracle, w, om)
+
+
+def test_diagnostics_budgets_and_per_sequence_omega(P, oracle):
+    w = make_workload(2, device="cuda", B=6, L=8, V=16384)
+    for delta in (0.5, 1.0, 4.0):
+        _check(P, oracle, w, P.cool_sd_schedule(P.COOL_SD_SCHED_UNIFORM, 8, delta))
+    om = np.tile(P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, 8, 2.0, w.nu), (6, 1)).astype(np.float32)
+    om[0] = 0.0
+    om[1] *= 3.0
+    alpha, beta = _check(P, oracle, w, om)
+    assert (alpha[0] == 0).all() and (beta[0] == 0).all()
+
+
+def test_diagnostics_guidance_topk_and_no_bonus(P, oracle):
+    w = make_workload(3, device="cuda", B=3, L=4)                 # guided, top-k: thresholds from the statistics pass
+    om = P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, 4, 2.0, w.nu)
+    _check(P, oracle, w, om)
+    w = make_workload(3, device="cuda", B=2, L=3, top_k=0)        # guided only: one-chunk path with the transform
+    _check(P, oracle, w, om[:3])
+    w = make_workload(2, device="cuda", B=3, L=4, V=16384)
+    w.target = w.target[:, :4].contiguous()                       # no bonus row
+    _check(P, oracle, w, om)
+
+
+def test_diagnostics_predict_the_acceptance_rate(P, oracle):
+    """Eq. token_exp, position 1: over many independent sequences that share one row pair, the
+    fraction of accepted first tokens (drawn from q_1) tends to alpha_1."""
+    w = make_workload(2, device="cuda", B=1, L=1, V=4096)
+    om = np.array([1.5], np.float32)
+    alpha, _ = _check(P, oracle, w, om)
+    n = 20000
+    g = torch.Generator(device="cuda").manual_seed(5)
+    q = torch.softmax(w.draft[0, 0].float(), -1)
+    tokens = torch.multinomial(q, n, replacement=True, generator=g).to(torch.int32).reshape(n, 1)
+    target = w.target.expand(n, 2, 4096)
+    draft = w.draft.expand(n, 1, 4096)
+    params = P.make_params(target, draft)
+    ws = torch.empty(P.cool_sd_workspace_bytes(params), dtype=torch.uint8, device="cuda")
+    u = torch.rand((n, 1), generator=g, device="cuda")
+    tau = torch.empty(n, dtype=torch.int32, device="cuda")
+    nxt = torch.empty(n, dtype=torch.int32, device="cuda")
+    P.cool_sd_verify(params, target, None, draft, None, tokens, torch.from_numpy(om).cuda(), u,
+                     torch.rand(n, generator=g, device="cuda"), tau, nxt, None, None, None, None, ws)
+    torch.cuda.synchronize()
+    rate = float((tau >= 1).float().mean())
+    a = float(alpha[0, 0])
+    assert abs(rate - a) < 5 * np.sqrt(a * (1 - a) / n)

@@ -21,7 +21,7 @@ def test_library_exports_every_declared_symbol(P):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = re.findall(r"\b(cool_sd_[a-z_]+)\s*\(", header)
     assert set(names) >= {"cool_sd_schedule", "cool_sd_workspace_bytes", "cool_sd_workspace_init",
-                          "cool_sd_verify", "cool_sd_resample", "cool_sd_strerror"}
+                          "cool_sd_verify", "cool_sd_resample", "cool_sd_diagnostics", "cool_sd_strerror"}
     raw = C.CDLL(P.binding.LIB_PATH)
     for n in set(names):
         assert hasattr(raw, n), n
@@ -102,6 +102,14 @@ def test_verify_validates_before_touching_the_gpu(P):
     assert r == E.COOL_SD_EINVAL
     r = lib.cool_sd_resample(C.byref(_params(P)), fake, null, fake, null, null, fake, fake, null, null, 0, null)
     assert r == E.COOL_SD_EINVAL                                       # draft rows need omega
+    # diagnostics
+    d = lambda params, t=fake, om=fake, out=fake, ws=null, n=0: lib.cool_sd_diagnostics(
+        C.byref(params), t, null, fake, null, om, out, fake, ws, n, null)
+    assert d(_params(P), t=null) == E.COOL_SD_EINVAL
+    assert d(_params(P), om=null) == E.COOL_SD_EINVAL
+    assert d(_params(P), out=null) == E.COOL_SD_EINVAL
+    assert d(_params(P)) == E.COOL_SD_EWORKSPACE
+    assert d(_params(P), ws=C.c_void_p(0x1000), n=16) == E.COOL_SD_EWORKSPACE
     for code in (0, -1, -2, -3, -4, -99):
         assert isinstance(P.cool_sd_strerror(code), str) and P.cool_sd_strerror(code)
     assert lib.cool_sd_profile_read(None, None) == E.COOL_SD_EINVAL

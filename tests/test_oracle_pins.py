@@ -259,6 +259,42 @@ def test_single_position_tv_closed_form(oracle):
         assert abs(tv - np.maximum(np.minimum(q, om * p) - p, 0).sum()) < 1e-12
 
 
+def test_position_diagnostics_against_enumeration(oracle):
+    """Theorem 2 diagnostics.  beta is the bracket of the G* bound (proof Step 2), so
+    (a) at L = 1 it is the exact TV of the enumerated output law;
+    (b) summed over prefixes with weight Q(x_{1:i}) prod f_k it is the enumerated bound;
+    (c) it vanishes at omega <= 1; and alpha at omega = 1 is the textbook acceptance rate
+        of speculative decoding, 1 - TV(p, q)."""
+    rng = np.random.default_rng(77)
+    V = 5
+    for om in (0.6, 1.0, 1.4, 2.5):
+        P, Q = random_kernels(V, 1, rng, sharp=1.0, noise=1.0)
+        P = [rows_of(oracle, t) for t in P]
+        Q = [rows_of(oracle, t) for t in Q]
+        alpha, beta = oracle.position_diagnostics(P[0], Q[0], om)
+        law, target = output_law(oracle, P, Q, [om])
+        if om >= 1.0:
+            assert abs(0.5 * np.abs(law - target).sum() - beta) < 1e-12          # (a)
+            f = np.array([oracle.accept_prob(P[0][x], Q[0][x], om) for x in range(V)])
+            if om in (1.0, 1.4):   # rejections still happen here, so both sums of the bracket matter
+                assert np.sum((1.0 - f) * Q[0]) > 1e-3
+        else:
+            assert abs(beta) < 1e-15                                               # (c)
+        assert abs(alpha - np.minimum(Q[0], om * P[0]).sum()) < 1e-14
+        if om == 1.0:
+            assert abs(alpha - (1.0 - 0.5 * np.abs(P[0] - Q[0]).sum())) < 1e-14   # (c)
+    # (b) two positions, prefix-dependent rows
+    omega = [2.0, 1.3]
+    P, Q = random_kernels(4, 2, rng, sharp=1.0, noise=1.0)
+    P = [rows_of(oracle, t) for t in P]
+    Q = [rows_of(oracle, t) for t in Q]
+    total = oracle.position_diagnostics(P[0], Q[0], omega[0])[1]
+    for x1 in range(4):
+        w = Q[0][x1] * oracle.accept_prob(P[0][x1], Q[0][x1], omega[0])
+        total += w * oracle.position_diagnostics(P[1][x1], Q[1][x1], omega[1])[1]
+    assert abs(total - tv_bound(oracle, P, Q, omega)) < 1e-12
+
+
 def test_prop_lp_value_and_optimality(oracle):
     """Prop. LP: for 1 >= f >= min{1,p/q}, inf_G sum|p - q f - G rho| = sum|p - q f| - rho, attained by G*."""
     rng = np.random.default_rng(17)

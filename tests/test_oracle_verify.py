@@ -110,6 +110,10 @@ def test_expected_accept_length(oracle):
     alpha = [sum(q[i][x] * oracle.accept_prob(p[i][x], q[i][x], np.float32(omega[i])) for x in range(V))
              for i in range(L)]
     e_tau = float(np.sum(np.cumprod(alpha)))
+    # the batched diagnostics (logits in, alpha out) give the same factors
+    a_rows, b_rows = oracle.diagnostics(lt[None], ld[None], omega)
+    np.testing.assert_allclose(a_rows[0], alpha, rtol=1e-12)
+    assert (b_rows >= -1e-15).all() and (b_rows[0][np.asarray(omega) > 1.0] > 0).all()
     tokens = draw_tokens(rng, q, n)
     out = run_verify(oracle, lt, ld, tokens, omega, u24(rng, (n, L)), u24(rng, n))
     tau = out["accept_len"].astype(np.float64)

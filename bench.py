@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="time budget of the CPU oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--others", action="store_true", help="also time configurations 1, 3, 4, 5 (extra JSON keys)")
+    ap.add_argument("--diagnostics", action="store_true",
+                    help="also time cool_sd_diagnostics (alpha, beta of every position) on the timed workloads")
     ap.add_argument("--kernel-samples", type=int, default=200, help="instrumented calls for the per-kernel time")
     ap.add_argument("--counter-run", action="store_true",
                     help="for rocprofv3 --pmc: a plain device copy of known size (the counters' reference), then "
@@ -140,6 +142,34 @@ class Runner:
         return k_ms / n * 1e-3, c_ms / n * 1e-3
 
 
+def time_diagnostics(r, passes=6):
+    """Average duration of one cool_sd_diagnostics call over the pool (direct launches, events on the
+    launch stream).  Algorithmic bytes: the 2 B L drafted rows, once."""
+    pkg, torch = r.pkg, r.torch
+    alpha = torch.empty((r.B, r.L), dtype=torch.float32, device="cuda")
+    beta = torch.empty_like(alpha)
+
+    def one(i):
+        w = r.pool[i % len(r.pool)]
+        pkg.cool_sd_diagnostics(r.params, w.target, w.target_uncond, w.draft, w.draft_uncond, r.omega, alpha, beta,
+                                r.ws)
+    for i in range(len(r.pool)):
+        one(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n = passes * len(r.pool)
+    e0.record()
+    for i in range(n):
+        one(i)
+    e1.record()
+    torch.cuda.synchronize()
+    sec = e0.elapsed_time(e1) * 1e-3 / n
+    w0 = r.pool[0]
+    nbytes = 2 * r.B * r.L * r.V * w0.target.element_size() * (2 if w0.target_uncond is not None else 1)
+    return {"us_per_call": sec * 1e6, "algorithmic_bytes": nbytes, "GBps": nbytes / sec / 1e9,
+            "frac": nbytes / sec / 1e9 / HBM_PEAK_GBS}
+
+
 def cpu_baseline(runner, budget_s):
     """The oracle, as it stands, on whole batches of the same pool until the time budget is used."""
     from oracle import oracle as O
@@ -230,9 +260,13 @@ def main():
                                   "row_stats_us": k2 * 1e6, "row_stats_GBps": rr.bytes_per_step / k2 / 1e9,
                                   "row_stats_frac": rr.bytes_per_step / k2 / 1e9 / HBM_PEAK_GBS,
                                   "bytes_per_step": rr.bytes_per_step, "pool_batches": len(rr.pool)}
+            if a.diagnostics:
+                extra["cfg%d" % c]["diagnostics"] = time_diagnostics(rr)
             del rr
             torch.cuda.empty_cache()
         line["other_workloads"] = extra
+    if a.diagnostics:
+        line["diagnostics"] = time_diagnostics(r)
     if not a.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(r, a.cpu_seconds)
     print(json.dumps(line), flush=True)

@@ -674,61 +674,90 @@ __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
 //   else    statistics come from row_stats_kernel; grid = B L x CD chunks of 8192 logits; the
 //           chunk sums go to diag_part and diag_combine_kernel adds them in ascending order.
 template <int DT, bool XF, int AL, int NT, bool LOCAL>
-__global__ __launch_bounds__(kThreads) void diag_kernel(const KArgs a) {
+__global__ __launch_bounds__(LOCAL ? 512 : kThreads) void diag_kernel(const KArgs a) {
   constexpr int kE = Vec<DT>::kE, kES = Vec<DT>::kES;
-  __shared__ float red[4][kWaves];
+  // the one-chunk form spreads the row pair over 512 threads so that both rows cost 64 registers
+  constexpr int kTPB = LOCAL ? 512 : kThreads, kW = kTPB / 64;
+  __shared__ float red[4][kW];
   const int CD = a.nchunks;
   const int rp = blockIdx.x / CD, c = blockIdx.x - rp * CD;     // row pair (b, i), chunk
   const int b = rp / a.L, i = rp - b * a.L;
   const int rt_ = rp, rd_ = a.rows_t + rp;                       // has_bonus is 0 here
   const int64_t offt = int64_t(b) * a.t_sb + int64_t(i) * a.t_sl;
   const int64_t offd = int64_t(b) * a.d_sb + int64_t(i) * a.d_sl;
-  const int64_t base = int64_t(c) * (NT * kThreads * kE);
+  const int64_t base = int64_t(c) * (NT * kTPB * kE);
   const bool masked = XF && !LOCAL && a.top_k > 0;
   const float thr_t = masked ? a.thr[rt_] : -INFINITY;
   const float thr_d = masked ? a.thr[rd_] : -INFINITY;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
 
   RowRegs<DT, XF, NT> rt, rd;
-  load_chunk<DT, XF, AL, NT>(rt, row_ptr(a.t, offt, kES), row_ptr(a.tu, offt, kES), base, a.V, a.cfg_scale,
-                             a.inv_T, thr_t);
-  load_chunk<DT, XF, AL, NT>(rd, row_ptr(a.d, offd, kES), row_ptr(a.du, offd, kES), base, a.V, a.cfg_scale,
-                             a.inv_T, thr_d);
-  float Ct, St, Cd, Sd;
-  if constexpr (LOCAL) {
-    float c0, s0, c1, s1;
-    thread_stats<DT, XF, NT>(rt, c0, s0);
-    thread_stats<DT, XF, NT>(rd, c1, s1);
-    const float wc0 = wave_max(c0), wc1 = wave_max(c1);
-    const float ws0 = wave_sum(s0 * exp2_fast(c0 - wc0));       // exact power-of-two rescale
-    const float ws1 = wave_sum(s1 * exp2_fast(c1 - wc1));
-    if (lane == 0) { red[0][wv] = wc0; red[1][wv] = ws0; red[2][wv] = wc1; red[3][wv] = ws1; }
-    __syncthreads();
-    Ct = fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3]));
-    Cd = fmaxf(fmaxf(red[2][0], red[2][1]), fmaxf(red[2][2], red[2][3]));
-    St = 0.f; Sd = 0.f;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      St = __fadd_rn(St, red[1][w] * exp2_fast(red[0][w] - Ct));
-      Sd = __fadd_rn(Sd, red[3][w] * exp2_fast(red[2][w] - Cd));
-    }
-    __syncthreads();                                              // red is reused below
-  } else {
-    combine_row(a, rt_, Ct, St);
-    combine_row(a, rd_, Cd, Sd);
-  }
-  const float at = 1.f / St, ad = 1.f / Sd;
+  load_chunk<DT, XF, AL, NT, kTPB, 1>(rt, row_ptr(a.t, offt, kES), row_ptr(a.tu, offt, kES), base, a.V,
+                                      a.cfg_scale, a.inv_T, thr_t);
+  load_chunk<DT, XF, AL, NT, kTPB, 1>(rd, row_ptr(a.d, offd, kES), row_ptr(a.du, offd, kES), base, a.V,
+                                      a.cfg_scale, a.inv_T, thr_d);
   const float omega = a.omega[int64_t(b) * a.om_sb + i];
   float sa = 0.f, sb = 0.f;
+  if constexpr (LOCAL) {
+    // the arithmetic is what limits this form (two exponentials per logit would), so each
+    // 2^(l log2e - C) is evaluated once against the row's reference exponent and kept
+    float mt = -INFINITY, md = -INFINITY;
 #pragma unroll
-  for (int t = 0; t < NT; ++t) {
+    for (int t = 0; t < NT; ++t) {
 #pragma unroll
-    for (int j = 0; j < kE; ++j) {
-      const float p = __fmul_rn(exp2_fast(__fmaf_rn(rt.get(t, j), kLog2e, -Ct)), at);
-      const float q = __fmul_rn(exp2_fast(__fmaf_rn(rd.get(t, j), kLog2e, -Cd)), ad);
+      for (int j = 0; j < kE; ++j) { mt = fmaxf(mt, rt.get(t, j)); md = fmaxf(md, rd.get(t, j)); }
+    }
+    mt = wave_max(mt);
+    md = wave_max(md);
+    if (lane == 0) { red[0][wv] = mt; red[1][wv] = md; }
+    __syncthreads();
+    mt = red[0][0]; md = red[1][0];
+#pragma unroll
+    for (int w = 1; w < kW; ++w) { mt = fmaxf(mt, red[0][w]); md = fmaxf(md, red[1][w]); }
+    const float Ct = fmaxf(ceilf(mt * kLog2e), kRefFloor), Cd = fmaxf(ceilf(md * kLog2e), kRefFloor);
+    float et[NT * kE], ed[NT * kE];
+    float st = 0.f, sd = 0.f;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+#pragma unroll
+      for (int j = 0; j < kE; ++j) {
+        et[t * kE + j] = exp2_fast(__fmaf_rn(rt.get(t, j), kLog2e, -Ct));
+        ed[t * kE + j] = exp2_fast(__fmaf_rn(rd.get(t, j), kLog2e, -Cd));
+        st = __fadd_rn(st, et[t * kE + j]);
+        sd = __fadd_rn(sd, ed[t * kE + j]);
+      }
+    }
+    st = wave_sum(st);
+    sd = wave_sum(sd);
+    if (lane == 0) { red[2][wv] = st; red[3][wv] = sd; }
+    __syncthreads();
+    float St = 0.f, Sd = 0.f;
+#pragma unroll
+    for (int w = 0; w < kW; ++w) { St = __fadd_rn(St, red[2][w]); Sd = __fadd_rn(Sd, red[3][w]); }
+    const float at = 1.f / St, ad = 1.f / Sd;
+#pragma unroll
+    for (int n = 0; n < NT * kE; ++n) {
+      const float p = __fmul_rn(et[n], at), q = __fmul_rn(ed[n], ad);
       const float m = fminf(q, __fmul_rn(omega, p));
       sa = __fadd_rn(sa, m);
       sb = __fadd_rn(sb, fmaxf(__fsub_rn(m, p), 0.f));
+    }
+    __syncthreads();                                              // red is reused below
+  } else {
+    float Ct, St, Cd, Sd;
+    combine_row(a, rt_, Ct, St);
+    combine_row(a, rd_, Cd, Sd);
+    const float at = 1.f / St, ad = 1.f / Sd;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+#pragma unroll
+      for (int j = 0; j < kE; ++j) {
+        const float p = __fmul_rn(exp2_fast(__fmaf_rn(rt.get(t, j), kLog2e, -Ct)), at);
+        const float q = __fmul_rn(exp2_fast(__fmaf_rn(rd.get(t, j), kLog2e, -Cd)), ad);
+        const float m = fminf(q, __fmul_rn(omega, p));
+        sa = __fadd_rn(sa, m);
+        sb = __fadd_rn(sb, fmaxf(__fsub_rn(m, p), 0.f));
+      }
     }
   }
   sa = wave_sum(sa);
@@ -736,8 +765,9 @@ __global__ __launch_bounds__(kThreads) void diag_kernel(const KArgs a) {
   if (lane == 0) { red[0][wv] = sa; red[1][wv] = sb; }
   __syncthreads();
   if (threadIdx.x == 0) {
-    const float A = __fadd_rn(__fadd_rn(__fadd_rn(red[0][0], red[0][1]), red[0][2]), red[0][3]);
-    const float Bv = __fadd_rn(__fadd_rn(__fadd_rn(red[1][0], red[1][1]), red[1][2]), red[1][3]);
+    float A = 0.f, Bv = 0.f;
+#pragma unroll
+    for (int w = 0; w < kW; ++w) { A = __fadd_rn(A, red[0][w]); Bv = __fadd_rn(Bv, red[1][w]); }
     if constexpr (LOCAL) {
       a.alpha[rp] = A;
       a.beta[rp] = Bv;
@@ -857,7 +887,7 @@ static hipError_t launch_diag_typed(const KArgs& a, bool local, hipStream_t stre
   (void)hipGetLastError();
   const int64_t pairs = int64_t(a.B) * a.L;
   if (local) {
-    hipLaunchKernelGGL((diag_kernel<DT, XF, kA, kT, true>), dim3((unsigned)pairs), dim3(kThreads), 0, stream, a);
+    hipLaunchKernelGGL((diag_kernel<DT, XF, kA, kT / 2, true>), dim3((unsigned)pairs), dim3(512), 0, stream, a);
     return checked("diag_kernel (one chunk)");
   }
   hipError_t e = launch_stats_any<DT, XF, AL>(a, stream);

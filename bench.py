@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="time budget of the CPU oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--others", action="store_true", help="also time configurations 1, 3, 4, 5 (extra JSON keys)")
+    ap.add_argument("--early-exit", action="store_true",
+                    help="time the early-exit form (COOL_SD_FLAG_EARLY_EXIT) instead of the all-rows form; the "
+                         "roofline object then refers to the single kernel and to the bytes it actually needs")
     ap.add_argument("--diagnostics", action="store_true",
                     help="also time cool_sd_diagnostics (alpha, beta of every position) on the timed workloads")
     ap.add_argument("--kernel-samples", type=int, default=200, help="instrumented calls for the per-kernel time")
@@ -55,8 +58,9 @@ def parse():
 class Runner:
     """Pool of resident batches of one configuration plus everything a verify call needs."""
 
-    def __init__(self, pkg, torch, cfg, pool_mb, max_pool=64):
-        from workloads import make_workload
+    def __init__(self, pkg, torch, cfg, pool_mb, max_pool=64, flags=0, B=None):
+        from workloads import make_workload as mk
+        make_workload = (lambda c, **kw: mk(c, B=B, **kw)) if B else mk
         self.pkg, self.torch, self.cfg = pkg, torch, cfg
         w0 = make_workload(cfg, device="cuda", call=0)
         self.bytes_per_step = w0.algorithmic_bytes()
@@ -66,7 +70,7 @@ class Runner:
         self.omega_np = pkg.cool_sd_schedule(pkg.COOL_SD_SCHED_EXP, w0.L, w0.delta, w0.nu)
         self.omega = torch.from_numpy(self.omega_np).cuda()
         self.params = pkg.make_params(w0.target, w0.draft, top_k=w0.top_k, cfg_scale=w0.cfg_scale,
-                                      temperature=w0.temperature)
+                                      temperature=w0.temperature, flags=flags)
         self.ws = torch.empty(max(pkg.cool_sd_workspace_bytes(self.params), 256), dtype=torch.uint8, device="cuda")
         pkg.cool_sd_workspace_init(self.ws)
         self.accept_len = torch.zeros(self.B, dtype=torch.int32, device="cuda")
@@ -212,7 +216,8 @@ def main():
     torch.cuda.set_device(0)
 
     cfg = int(a.workload[3:])
-    r = Runner(pkg, torch, cfg, a.pool_mb)
+    flags = pkg.COOL_SD_FLAG_EARLY_EXIT if a.early_exit else 0
+    r = Runner(pkg, torch, cfg, a.pool_mb, flags=flags)
     if a.counter_run:
         # reference for the byte counters: an elementwise kernel (dst = src * 1) that moves exactly
         # 2^30 B in and 2^30 B out
@@ -238,7 +243,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "config 2: B=32, L=8, V=16384, %s logits, exp schedule delta=1.1 nu=0.7" % dtype
                    if cfg == 2 else "config %d: B=%d, L=%d, V=%d, %s logits" % (cfg, r.B, r.L, r.V, dtype),
-                   "input_dtype": dtype, "launch": a.launch, "pool_batches": len(r.pool),
+                   "input_dtype": dtype, "launch": a.launch, "early_exit": bool(a.early_exit), "pool_batches": len(r.pool),
                    "pool_mb": len(r.pool) * r.bytes_per_step / 1e6, "bytes_per_step": r.bytes_per_step},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(a.workload),
@@ -248,20 +253,24 @@ def main():
     }
     if a.others:
         extra = {}
-        for c in (1, 3, 4, 5):
-            if c == cfg:
+        # the fifth entry is configuration 4 with eight times the sequences: the regime (B well above
+        # the number of compute units) the early-exit form is meant for
+        for c, big in ((1, None), (3, None), (4, None), (5, None), (4, 2048)):
+            if c == cfg and not big:
                 continue
-            rr = Runner(pkg, torch, c, 2400.0 if c >= 4 else 600.0, max_pool=8 if c >= 4 else 64)
+            rr = Runner(pkg, torch, c, 2400.0 if c >= 4 else 600.0, max_pool=(2 if big else 8) if c >= 4 else 64,
+                        flags=flags, B=big)
             d2, w2, s2 = rr.time(max(64, 8 * len(rr.pool)), 2 * len(rr.pool), a.launch)
             k2, c2 = rr.kernel_times(40)
-            extra["cfg%d" % c] = {"tokens_per_s": d2 * rr.B * rr.L / w2, "us_per_step": s2 / d2 * 1e6,
+            name = "cfg%d" % c + ("_B%d" % big if big else "")
+            extra[name] = {"tokens_per_s": d2 * rr.B * rr.L / w2, "us_per_step": s2 / d2 * 1e6,
                                   "whole_call_GBps": rr.bytes_per_step / (s2 / d2) / 1e9,
                                   "whole_call_frac": rr.bytes_per_step / (s2 / d2) / 1e9 / HBM_PEAK_GBS,
                                   "row_stats_us": k2 * 1e6, "row_stats_GBps": rr.bytes_per_step / k2 / 1e9,
                                   "row_stats_frac": rr.bytes_per_step / k2 / 1e9 / HBM_PEAK_GBS,
                                   "bytes_per_step": rr.bytes_per_step, "pool_batches": len(rr.pool)}
             if a.diagnostics:
-                extra["cfg%d" % c]["diagnostics"] = time_diagnostics(rr)
+                extra[name]["diagnostics"] = time_diagnostics(rr)
             del rr
             torch.cuda.empty_cache()
         line["other_workloads"] = extra

@@ -61,6 +61,20 @@ typedef enum {
   COOL_SD_EUNSUPPORTED = -4  /* valid request the kernels do not implement (see top_k)       */
 } cool_sd_status;
 
+/* Options of cool_sd_verify (cool_sd_params.flags). */
+typedef enum {
+  /* Algorithm 1 stops at the first rejection; with this flag so does the memory traffic: one
+   * workgroup per sequence walks positions 1, 2, ... and reads no row pair after the rejected one
+   * (except the single pair whose loads were already issued ahead).  Pays when B is at least
+   * the number of compute units, since most of the 2L+1 rows are then never read.  Honoured for
+   * V <= 16384, L <= 1024, top_k == 0 and 16-byte aligned rows (base pointers and strides multiples
+   * of 16 bytes, V a multiple of 8 for bf16 / 4 for fp32); otherwise the call silently runs the
+   * all-rows path.
+   * When honoured, p_tok / q_tok / f of positions after the rejected one are NaN and the
+   * workspace is not touched.  accept_len, next_token and resid_mass mean the same in both. */
+  COOL_SD_FLAG_EARLY_EXIT = 1
+} cool_sd_flags;
+
 typedef struct {
   int32_t B;             /* sequences, >= 1                                                   */
   int32_t L;             /* draft length, 1..4096                                             */
@@ -80,7 +94,7 @@ typedef struct {
                             given (classifier-free guidance, App. implementation details)     */
   float temperature;     /* > 0; logits are multiplied by fl32(1/temperature); 1 = off        */
   int32_t resample_mode; /* cool_sd_resample_mode                                             */
-  int32_t reserved;      /* must be 0                                                         */
+  int32_t flags;         /* bit set of cool_sd_flags; unknown bits are an error                */
 } cool_sd_params;
 
 /* Relaxation schedule (Eq. sdar and the uniform / linear variants), host only, O(L).
@@ -110,7 +124,8 @@ int cool_sd_workspace_init(void* workspace_dev, size_t workspace_bytes, void* hi
  *   accept_len_dev      out int32 [B]: tau in [0, L]
  *   next_token_dev      out int32 [B]: x_{tau+1}; -1 iff tau == L and has_bonus == 0
  *   p_tok_dev, q_tok_dev, f_dev   out float [B, L], each optional (NULL = skip):
- *                       p_i(x~_i), q_i(x~_i), f_i for every position (also after tau)
+ *                       p_i(x~_i), q_i(x~_i), f_i for every position (also after tau; but see
+ *                       COOL_SD_FLAG_EARLY_EXIT)
  *   resid_mass_dev      out float [B], optional: R = sum_x g(x) of the sampled law
  *                       (sum of p for the bonus draw, 0 when next_token = -1)
  * The accepted tokens are draft_tokens[b, 0:tau]; they are not copied. */

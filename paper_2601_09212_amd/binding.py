@@ -12,6 +12,7 @@ import numpy as np
 COOL_SD_F32, COOL_SD_BF16 = 0, 1
 COOL_SD_SCHED_UNIFORM, COOL_SD_SCHED_EXP, COOL_SD_SCHED_LINEAR = 0, 1, 2
 COOL_SD_RESAMPLE_OPT, COOL_SD_RESAMPLE_VANILLA = 0, 1
+COOL_SD_FLAG_EARLY_EXIT = 1
 COOL_SD_OK, COOL_SD_EINVAL, COOL_SD_EWORKSPACE, COOL_SD_ELAUNCH, COOL_SD_EUNSUPPORTED = 0, -1, -2, -3, -4
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcool_sd.so")
@@ -30,7 +31,7 @@ class CoolSDParams(C.Structure):
                 ("omega_stride_b", C.c_int64),
                 ("has_bonus", C.c_int32), ("top_k", C.c_int32),
                 ("cfg_scale", C.c_float), ("temperature", C.c_float),
-                ("resample_mode", C.c_int32), ("reserved", C.c_int32)]
+                ("resample_mode", C.c_int32), ("flags", C.c_int32)]
 
 
 _lib = None
@@ -160,7 +161,7 @@ def cool_sd_profile_read():
 
 # ------------------------------------------------------------------ conveniences (marshalling only)
 def make_params(target, draft, *, has_bonus=None, top_k=0, cfg_scale=1.0, temperature=1.0,
-                resample_mode=COOL_SD_RESAMPLE_OPT, omega_stride_b=0):
+                resample_mode=COOL_SD_RESAMPLE_OPT, omega_stride_b=0, flags=0):
     """cool_sd_params for [B, L(+1), V] / [B, L, V] torch tensors (innermost dimension contiguous)."""
     import torch
     B, L, V = draft.shape
@@ -171,15 +172,16 @@ def make_params(target, draft, *, has_bonus=None, top_k=0, cfg_scale=1.0, temper
     return CoolSDParams(B=B, L=L, V=V, dtype=dt, t_stride_b=target.stride(0), t_stride_l=target.stride(1),
                         d_stride_b=draft.stride(0), d_stride_l=draft.stride(1), omega_stride_b=omega_stride_b,
                         has_bonus=has_bonus, top_k=top_k, cfg_scale=cfg_scale, temperature=temperature,
-                        resample_mode=resample_mode, reserved=0)
+                        resample_mode=resample_mode, flags=flags)
 
 
-def verify_workload(w, omega, *, resample_mode=COOL_SD_RESAMPLE_OPT, workspace=None, diagnostics=True):
+def verify_workload(w, omega, *, resample_mode=COOL_SD_RESAMPLE_OPT, workspace=None, diagnostics=True, flags=0):
     """Allocate outputs (torch, on the inputs' device), call cool_sd_verify once, return a dict of tensors."""
     import torch
     dev = w.target.device
     params = make_params(w.target, w.draft, top_k=w.top_k, cfg_scale=w.cfg_scale, temperature=w.temperature,
-                         resample_mode=resample_mode, omega_stride_b=0 if omega.dim() == 1 else omega.stride(0))
+                         resample_mode=resample_mode, omega_stride_b=0 if omega.dim() == 1 else omega.stride(0),
+                         flags=flags)
     if workspace is None:
         workspace = torch.empty(max(cool_sd_workspace_bytes(params), 256), dtype=torch.uint8, device=dev)
         cool_sd_workspace_init(workspace)

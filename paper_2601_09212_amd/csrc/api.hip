@@ -68,7 +68,7 @@ bool params_ok(const cool_sd_params* p, bool for_resample) {
   if (!(p->temperature > 0.f) || !isfinite(p->temperature)) return false;
   if (!isfinite(p->cfg_scale)) return false;
   if (p->resample_mode != COOL_SD_RESAMPLE_OPT && p->resample_mode != COOL_SD_RESAMPLE_VANILLA) return false;
-  if (p->reserved != 0) return false;
+  if ((p->flags & ~COOL_SD_FLAG_EARLY_EXIT) != 0) return false;
   const int64_t L = for_resample ? 1 : p->L;
   const int64_t rows = for_resample ? p->B : int64_t(p->B) * (L + p->has_bonus);
   if (2 * rows * ((int64_t(p->V) + 4095) / 4096) > 0x7fffffffLL) return false;   // grid size
@@ -121,6 +121,8 @@ int run(const cool_sd_params* p, bool resample_only,
   a.top_k = p->top_k; a.resample_mode = p->resample_mode;
   a.resample_only = resample_only ? 1 : 0;
   a.aligned = aligned ? 1 : 0;
+  a.early_exit = (!resample_only && aligned && (p->flags & COOL_SD_FLAG_EARLY_EXIT) && p->top_k == 0 && p->V <= csd::kChunk &&
+                  p->L <= 1024) ? 1 : 0;
   // beyond ~128 MB the logits cannot stay in L2 / Infinity Cache until the sequence kernel re-reads a row
   a.stream_loads = (double(rows_t + rows_d) * p->V * (p->dtype == COOL_SD_BF16 ? 2 : 4) * (tu ? 2 : 1)) > 128e6 ? 1 : 0;
   a.nchunks = (int32_t)C; a.nt2 = ch.nt2;

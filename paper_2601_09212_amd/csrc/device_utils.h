@@ -232,6 +232,46 @@ __device__ __forceinline__ void load_chunk(RowRegs<DT, XF, NT>& r, const char* _
   }
 }
 
+// Split form of load_chunk for code that issues loads well ahead of their use: fetch_vec only
+// issues the 16-byte load (address clamped into the row, nothing depends on the result yet);
+// finish_chunk later turns NT fetched vectors -- vector k of this thread starts at element
+// first[k] -- into a RowRegs exactly as load_chunk would (range mask, logit transform, top-k
+// mask).  Aligned rows only (see load_vec).
+template <int DT>
+__device__ __forceinline__ uint4 fetch_vec(const char* __restrict__ row, int64_t e, int V) {
+  constexpr int kE = Vec<DT>::kE;
+  const int64_t ec = e < V ? e : int64_t(V - kE);
+  return *reinterpret_cast<const uint4*>(row + ec * Vec<DT>::kES);
+}
+
+template <int DT, bool XF, int NT>
+__device__ __forceinline__ void finish_chunk(RowRegs<DT, XF, NT>& r, const uint4 (&rc)[NT], const uint4 (&ru)[NT],
+                                             const int64_t (&first)[NT], int V, bool guided, float s, float inv_T,
+                                             float thr) {
+  constexpr int kE = Vec<DT>::kE;
+#pragma unroll
+  for (int k = 0; k < NT; ++k) {
+    if constexpr (!XF) {
+      const bool in = first[k] < V;
+      const uint4 ninf = neg_inf_vec<DT>();
+      uint4 v = rc[k];
+      v.x = in ? v.x : ninf.x; v.y = in ? v.y : ninf.y; v.z = in ? v.z : ninf.z; v.w = in ? v.w : ninf.w;
+      if (RowRegs<DT, XF, NT>::kRaw) {
+        r.w[k * 4 + 0] = v.x; r.w[k * 4 + 1] = v.y; r.w[k * 4 + 2] = v.z; r.w[k * 4 + 3] = v.w;
+      } else {
+#pragma unroll
+        for (int j = 0; j < kE; ++j) r.set(k, j, vec_elem<DT>(v, j));
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < kE; ++j) {
+        const float l = transform_logit(vec_elem<DT>(rc[k], j), vec_elem<DT>(ru[k], j), guided, s, inv_T);
+        r.set(k, j, (first[k] + j < V && l >= thr) ? l : -INFINITY);
+      }
+    }
+  }
+}
+
 // Per-thread streaming softmax statistics in base-2 units with an INTEGER reference exponent:
 // c = ceil(max*log2e) over the logits seen so far and s = sum 2^(l*log2e - c).  Because c is an
 // integer, every later change of reference is an exact power-of-two scaling.

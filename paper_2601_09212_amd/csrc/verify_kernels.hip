@@ -386,55 +386,18 @@ struct SmemW {
   int token;
 };
 
-template <int DT, bool XF, bool AL>
-__global__ __launch_bounds__(kThreadsW) void sequence_whole_kernel(const KArgs a) {
-  constexpr int kE = Vec<DT>::kE, kES = Vec<DT>::kES;
-  constexpr int kVW = kChunk / (kThreadsW * kE);       // vectors per thread: 2 (bf16) / 4 (fp32)
-  __shared__ SmemW sm;
-  const int b = blockIdx.x;
-  const int rps = a.L + a.has_bonus;
-  const bool masked = XF && a.top_k > 0;
+// One draw from the resampling law of a row pair that 1024 threads hold in registers (thread t
+// owns the kVW consecutive vectors t*kVW ..): per-vector masses, one block scan, then vector and
+// element inside the thread whose interval contains u*R.  If the law has no mass (no rejection
+// is possible at this position) it falls back to p.  Returns the token in every thread, R = the
+// law's mass.
+template <int DT, bool XF, int kVW>
+__device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, const RowRegs<DT, XF, kVW>& rd,
+                                            ResidCoef k, float u, int V, SmemW& sm, float& R) {
+  constexpr int kE = Vec<DT>::kE;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-
-  int j = 0;
-  if (!a.resample_only) {
-    j = find_tau<DT, XF, kThreadsW>(a, b, true, sm.pick, &sm.rowstat);
-    if (j >= a.L && !a.has_bonus) {
-      if (threadIdx.x == 0) {
-        a.next_token[b] = -1;
-        if (a.resid_mass) a.resid_mass[b] = 0.f;
-      }
-      return;
-    }
-  }
-  const bool bonus = a.resample_only ? (a.d == nullptr) : (j == a.L);
-  const int rt_ = b * rps + j, rd_ = a.rows_t + b * a.L + j;
-  if (a.resample_only) {
-    if (threadIdx.x == 0) {
-      float Ct, St, Cd = kRefFloor, Sd = 0.f;
-      combine_row(a, rt_, Ct, St);
-      if (!bonus) combine_row(a, rd_, Cd, Sd);
-      sm.rowstat = make_float4(Ct, St, Cd, Sd);
-    }
-    __syncthreads();
-  }
-  const float4 rs = sm.rowstat;
-  const char* t_c = row_ptr(a.t, int64_t(b) * a.t_sb + int64_t(j) * a.t_sl, kES);
-  const char* t_u = row_ptr(a.tu, int64_t(b) * a.t_sb + int64_t(j) * a.t_sl, kES);
-  const char* d_c = bonus ? nullptr : row_ptr(a.d, int64_t(b) * a.d_sb + int64_t(j) * a.d_sl, kES);
-  const char* d_u = bonus ? nullptr : row_ptr(a.du, int64_t(b) * a.d_sb + int64_t(j) * a.d_sl, kES);
-  const float thr_t = masked ? a.thr[rt_] : -INFINITY;
-  const float thr_d = (masked && !bonus) ? a.thr[rd_] : -INFINITY;
-  const float omega = bonus ? 1.f : a.omega[int64_t(b) * a.om_sb + j];
-  ResidCoef k{rs.x, 1.f / rs.y, rs.z, bonus ? 1.f : 1.f / rs.w, omega,
-              bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
-
-  RowRegs<DT, XF, kVW> rt, rd;
-  load_chunk<DT, XF, AL, kVW, 1, kVW>(rt, t_c, t_u, 0, a.V, a.cfg_scale, a.inv_T, thr_t);
-  if (!bonus) load_chunk<DT, XF, AL, kVW, 1, kVW>(rd, d_c, d_u, 0, a.V, a.cfg_scale, a.inv_T, thr_d);
-  else rd.clear();                                    // never read in mode P
-
-  float part[kVW], mine, incl, excl, R;
+  float part[kVW], mine, incl, excl;
+  R = 0.f;
   for (int attempt = 0; attempt < 2; ++attempt) {
     mine = 0.f;
 #pragma unroll
@@ -465,7 +428,7 @@ __global__ __launch_bounds__(kThreadsW) void sequence_whole_kernel(const KArgs a
   }
 
   // thread: first with positive mass whose inclusive sum exceeds u*R, else the last with mass
-  const float v = __fmul_rn(a.u_res[b], R);
+  const float v = __fmul_rn(u, R);
   const bool pos = mine > 0.f;
   const bool hit = pos && (incl > v);
   const unsigned long long bh = __ballot(hit), bp = __ballot(pos);
@@ -514,9 +477,243 @@ __global__ __launch_bounds__(kThreadsW) void sequence_whole_kernel(const KArgs a
     sm.token = (win * kVW + vs) * kE + found;
   }
   __syncthreads();
+  const int token = sm.token;
+  return token >= V ? V - 1 : token;
+}
+
+template <int DT, bool XF, bool AL>
+__global__ __launch_bounds__(kThreadsW) void sequence_whole_kernel(const KArgs a) {
+  constexpr int kE = Vec<DT>::kE, kES = Vec<DT>::kES;
+  constexpr int kVW = kChunk / (kThreadsW * kE);       // vectors per thread: 2 (bf16) / 4 (fp32)
+  __shared__ SmemW sm;
+  const int b = blockIdx.x;
+  const int rps = a.L + a.has_bonus;
+  const bool masked = XF && a.top_k > 0;
+
+
+  int j = 0;
+  if (!a.resample_only) {
+    j = find_tau<DT, XF, kThreadsW>(a, b, true, sm.pick, &sm.rowstat);
+    if (j >= a.L && !a.has_bonus) {
+      if (threadIdx.x == 0) {
+        a.next_token[b] = -1;
+        if (a.resid_mass) a.resid_mass[b] = 0.f;
+      }
+      return;
+    }
+  }
+  const bool bonus = a.resample_only ? (a.d == nullptr) : (j == a.L);
+  const int rt_ = b * rps + j, rd_ = a.rows_t + b * a.L + j;
+  if (a.resample_only) {
+    if (threadIdx.x == 0) {
+      float Ct, St, Cd = kRefFloor, Sd = 0.f;
+      combine_row(a, rt_, Ct, St);
+      if (!bonus) combine_row(a, rd_, Cd, Sd);
+      sm.rowstat = make_float4(Ct, St, Cd, Sd);
+    }
+    __syncthreads();
+  }
+  const float4 rs = sm.rowstat;
+  const char* t_c = row_ptr(a.t, int64_t(b) * a.t_sb + int64_t(j) * a.t_sl, kES);
+  const char* t_u = row_ptr(a.tu, int64_t(b) * a.t_sb + int64_t(j) * a.t_sl, kES);
+  const char* d_c = bonus ? nullptr : row_ptr(a.d, int64_t(b) * a.d_sb + int64_t(j) * a.d_sl, kES);
+  const char* d_u = bonus ? nullptr : row_ptr(a.du, int64_t(b) * a.d_sb + int64_t(j) * a.d_sl, kES);
+  const float thr_t = masked ? a.thr[rt_] : -INFINITY;
+  const float thr_d = (masked && !bonus) ? a.thr[rd_] : -INFINITY;
+  const float omega = bonus ? 1.f : a.omega[int64_t(b) * a.om_sb + j];
+  ResidCoef k{rs.x, 1.f / rs.y, rs.z, bonus ? 1.f : 1.f / rs.w, omega,
+              bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
+
+  RowRegs<DT, XF, kVW> rt, rd;
+  load_chunk<DT, XF, AL, kVW, 1, kVW>(rt, t_c, t_u, 0, a.V, a.cfg_scale, a.inv_T, thr_t);
+  if (!bonus) load_chunk<DT, XF, AL, kVW, 1, kVW>(rd, d_c, d_u, 0, a.V, a.cfg_scale, a.inv_T, thr_d);
+  else rd.clear();                                    // never read in mode P
+
+  float R;
+  const int token = sample_whole<DT, XF, kVW>(rt, rd, k, a.u_res[b], a.V, sm, R);
   if (threadIdx.x == 0) {
-    int token = sm.token;
-    if (token >= a.V) token = a.V - 1;
+    a.next_token[b] = token;
+    if (a.resid_mass) a.resid_mass[b] = R;
+  }
+}
+
+// ============================================================================ early-exit variant
+// Algorithm 1 stops verifying at the first rejection; this kernel does the same with the memory
+// traffic: one workgroup of 1024 threads per sequence walks the positions in order, holds the
+// current (target, draft) row pair in registers, forms its softmax statistics and the accept
+// test, and on the first rejection draws x_{tau+1} from the pair it already holds.  Rows after
+// the rejected position are never read, except the one pair whose loads were issued ahead while
+// the current pair was being processed.  For 16-byte aligned rows of at most 16384 logits,
+// L <= kMaxLEarly and no top-k.  Per-position outputs after the rejected position are set to NaN.
+constexpr int kMaxLEarly = 1024;
+
+struct SmemE {
+  SmemW w;
+  float red_c[2][2][kWavesW];    // [step parity][target / draft][wave]
+  float red_s[2][2][kWavesW];
+  float tokl[2][2];              // [step parity][target / draft] logit of the draft token
+  int tok[kMaxLEarly];
+  float u[kMaxLEarly];
+  float om[kMaxLEarly];
+};
+
+// Block-wide softmax statistics of a row spread over 1024 threads: per-thread (c, s) are reduced
+// per wave and left in LDS (slot par, row which); after the caller's barrier block_stats_read
+// combines the 16 wave entries (reference = max, sums rescaled by exact powers of two, fixed tree).
+template <int DT, bool XF, int kVW>
+__device__ __forceinline__ void block_stats_write(const RowRegs<DT, XF, kVW>& r, SmemE& sm, int par, int which) {
+  float c, s;
+  thread_stats<DT, XF, kVW>(r, c, s);
+  const float wc = wave_max(c);
+  const float ws = wave_sum(s * exp2_fast(c - wc));
+  if ((threadIdx.x & 63) == 0) { sm.red_c[par][which][threadIdx.x >> 6] = wc; sm.red_s[par][which][threadIdx.x >> 6] = ws; }
+}
+__device__ __forceinline__ void block_stats_read(const SmemE& sm, int par, int which, float& C, float& S) {
+  // every wave reduces the 16 entries for itself, one per lane, instead of every thread reading all
+  const int lane = threadIdx.x & 63;
+  const float c = lane < kWavesW ? sm.red_c[par][which][lane] : kRefFloor;
+  const float s = lane < kWavesW ? sm.red_s[par][which][lane] : 0.f;
+  C = wave_max(c);
+  S = wave_sum(s * exp2_fast(c - C));
+}
+
+// D: row pairs in flight ahead of the one being processed (a ring of register slots; the loop is
+// unrolled by D so that every slot is a fixed set of registers).  One is what is used: a step is
+// bound by its arithmetic and its barrier (about 3 us for 16 waves sharing one compute unit), not
+// by the load latency, so deeper rings only cost registers and read more unneeded pairs.
+template <int DT, bool XF, int D>
+__global__ __launch_bounds__(kThreadsW) void sequence_early_exit_kernel(const KArgs a) {
+  constexpr int kE = Vec<DT>::kE, kES = Vec<DT>::kES;
+  constexpr int kVW = kChunk / (kThreadsW * kE);       // vectors per thread: 2 (bf16) / 4 (fp32)
+  constexpr int kPer = kVW * kE;                       // logits per thread
+  __shared__ SmemE sm;
+  const int b = blockIdx.x, L = a.L, tid = threadIdx.x;
+  for (int i = tid; i < L; i += kThreadsW) {
+    sm.tok[i] = min(max(a.tokens[int64_t(b) * L + i], 0), a.V - 1);
+    sm.u[i] = a.u_acc[int64_t(b) * L + i];
+    sm.om[i] = a.omega[int64_t(b) * a.om_sb + i];
+  }
+  // pair i < L: target and draft row of position i+1; "pair" L: the bonus row alone.  A slot
+  // holds the fetched vectors untouched, so nothing waits for them until the pair's turn comes.
+  struct Slot { uint4 tc[kVW], dc[kVW], tu[kVW], du[kVW]; };   // tu / du stay unused without a logit transform
+  const bool guided = XF && a.tu != nullptr;
+  int64_t first[kVW];
+#pragma unroll
+  for (int v = 0; v < kVW; ++v) first[v] = int64_t(tid * kVW + v) * kE;
+  // Always the same number of loads, whatever i is (row indices are clamped to the last valid row,
+  // whose re-read is harmless): the compiler can then count how many younger loads are in flight
+  // and wait only for the slot being consumed.
+  auto fetch_pair = [&](Slot& sl, int i) {
+    const int it = min(i, L + a.has_bonus - 1), id = min(i, L - 1);
+    const int64_t ot = int64_t(b) * a.t_sb + int64_t(it) * a.t_sl;
+    const int64_t od = int64_t(b) * a.d_sb + int64_t(id) * a.d_sl;
+    const char* tc = row_ptr(a.t, ot, kES);
+    const char* dc = row_ptr(a.d, od, kES);
+    const char* tu = guided ? row_ptr(a.tu, ot, kES) : tc;
+    const char* du = guided ? row_ptr(a.du, od, kES) : dc;
+#pragma unroll
+    for (int v = 0; v < kVW; ++v) {
+      sl.tc[v] = fetch_vec<DT>(tc, first[v], a.V);
+      sl.dc[v] = fetch_vec<DT>(dc, first[v], a.V);
+      if constexpr (XF) {
+        sl.tu[v] = fetch_vec<DT>(tu, first[v], a.V);
+        sl.du[v] = fetch_vec<DT>(du, first[v], a.V);
+      }
+    }
+  };
+  Slot slot[D];
+#pragma unroll
+  for (int s = 0; s < D; ++s) {
+#pragma unroll
+    for (int v = 0; v < kVW; ++v) {
+      slot[s].tc[v] = slot[s].dc[v] = slot[s].tu[v] = slot[s].du[v] = make_uint4(0u, 0u, 0u, 0u);
+    }
+    fetch_pair(slot[s], s);
+  }
+  RowRegs<DT, XF, kVW> rt, rd;
+  rt.clear();
+  rd.clear();
+  __syncthreads();                                      // tok / u / om are visible
+
+  int j = L;                                            // first rejected position
+  float Ct = kRefFloor, St = 1.f, Cd = kRefFloor, Sd = 1.f;
+  // One verification step on the pair in slot sl (position i); true = rejected.
+  auto step = [&](Slot& sl, int i) -> bool {
+    finish_chunk<DT, XF, kVW>(rt, sl.tc, sl.tu, first, a.V, guided, a.cfg_scale, a.inv_T, -INFINITY);
+    finish_chunk<DT, XF, kVW>(rd, sl.dc, sl.du, first, a.V, guided, a.cfg_scale, a.inv_T, -INFINITY);
+    fetch_pair(sl, i + D);                              // refill the slot before working on the pair
+    const int par = i & 1;
+    block_stats_write<DT, XF, kVW>(rt, sm, par, 0);
+    block_stats_write<DT, XF, kVW>(rd, sm, par, 1);
+    // the thread that holds x~_i publishes its two logits
+    const int idx = sm.tok[i] - tid * kPer;
+    float lt = 0.f, ld = 0.f;
+    if ((sm.tok[i] >> 6) / kPer == (tid >> 6)) {        // only the wave that holds the token looks for it
+#pragma unroll
+      for (int v = 0; v < kVW; ++v) {
+#pragma unroll
+        for (int e = 0; e < kE; ++e) {
+          if (idx == v * kE + e) { lt = rt.get(v, e); ld = rd.get(v, e); }
+        }
+      }
+      if (idx >= 0 && idx < kPer) { sm.tokl[par][0] = lt; sm.tokl[par][1] = ld; }
+    }
+    __syncthreads();       // the only barrier of a step: LDS slots alternate with the step parity
+    block_stats_read(sm, par, 0, Ct, St);
+    block_stats_read(sm, par, 1, Cd, Sd);
+    lt = sm.tokl[par][0];
+    ld = sm.tokl[par][1];
+    // same evaluation of f_i = min{1, omega_i p_i(x~_i) / q_i(x~_i)} as the all-rows path (Eq. relax)
+    const float et = __fmaf_rn(lt, kLog2e, -Ct), ed = __fmaf_rn(ld, kLog2e, -Cd);
+    const float ratio = __fmul_rn(exp2_fast(__fsub_rn(et, ed)), Sd / St);
+    const float omega = sm.om[i];
+    const float fi = (ld == -INFINITY) ? 1.f : ((omega > 0.f) ? fminf(1.f, __fmul_rn(omega, ratio)) : 0.f);
+    if (tid == 0) {
+      const int64_t o = int64_t(b) * L + i;
+      if (a.p_tok) a.p_tok[o] = exp2_fast(et) / St;
+      if (a.q_tok) a.q_tok[o] = exp2_fast(ed) / Sd;
+      if (a.f) a.f[o] = fi;
+    }
+    return !(sm.u[i] <= fi);                            // uniform: every thread sees the same values
+  };
+  for (int i0 = 0; i0 < L && j == L; i0 += D) {
+#pragma unroll
+    for (int s = 0; s < D; ++s) {
+      if (j == L && i0 + s < L) {
+        if (step(slot[s], i0 + s)) j = i0 + s;
+      }
+    }
+  }
+  // positions that were never evaluated
+  for (int i = j + 1 + tid; i < L; i += kThreadsW) {
+    const int64_t o = int64_t(b) * L + i;
+    if (a.p_tok) a.p_tok[o] = NAN;
+    if (a.q_tok) a.q_tok[o] = NAN;
+    if (a.f) a.f[o] = NAN;
+  }
+  if (tid == 0) a.accept_len[b] = j;
+  const bool bonus = j == L;
+  if (bonus) {
+    if (!a.has_bonus) {
+      if (tid == 0) {
+        a.next_token[b] = -1;
+        if (a.resid_mass) a.resid_mass[b] = 0.f;
+      }
+      return;
+    }
+    // everything was accepted: fetch row L+1 now (its statistics go to the LDS slot of parity
+    // L & 1, last used two steps ago or never)
+    fetch_pair(slot[0], L);
+    finish_chunk<DT, XF, kVW>(rt, slot[0].tc, slot[0].tu, first, a.V, guided, a.cfg_scale, a.inv_T, -INFINITY);
+    block_stats_write<DT, XF, kVW>(rt, sm, L & 1, 0);
+    __syncthreads();
+    block_stats_read(sm, L & 1, 0, Ct, St);
+  }
+  ResidCoef k{Ct, 1.f / St, Cd, bonus ? 1.f : 1.f / Sd, bonus ? 1.f : sm.om[j],
+              bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
+  float R;
+  const int token = sample_whole<DT, XF, kVW>(rt, rd, k, a.u_res[b], a.V, sm.w, R);
+  if (tid == 0) {
     a.next_token[b] = token;
     if (a.resid_mass) a.resid_mass[b] = R;
   }
@@ -834,6 +1031,13 @@ template <int DT, bool XF, bool AL>
 static hipError_t launch_typed(const KArgs& a, hipStream_t stream, hipEvent_t* ev) {
   (void)hipGetLastError();
   if (ev) (void)hipEventRecord(ev[0], stream);
+  if (a.early_exit) {   // one launch; there is no separate statistics pass to time
+    if (ev) (void)hipEventRecord(ev[1], stream);
+    hipLaunchKernelGGL((sequence_early_exit_kernel<DT, XF, 1>), dim3((unsigned)a.B), dim3(kThreadsW), 0, stream, a);
+    hipError_t ee = checked("sequence_early_exit_kernel");
+    if (ev) (void)hipEventRecord(ev[2], stream);
+    return ee;
+  }
   hipError_t e = launch_stats_any<DT, XF, AL>(a, stream);
   if (e != hipSuccess) return e;
   if (ev) (void)hipEventRecord(ev[1], stream);

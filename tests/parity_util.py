@@ -57,14 +57,21 @@ def _oracle_row_law(O, w, b, j, omega_bj, resample_mode):
     return int(tok[0]), float(mass[0]), g[0]
 
 
-def compare_verify(O, w, omega, gpu, ref=None, resample_mode=0, has_bonus=True):
-    """Assert parity of one verify call.  gpu: dict of numpy arrays.  Returns counters."""
+def compare_verify(O, w, omega, gpu, ref=None, resample_mode=0, has_bonus=True, early_exit=False):
+    """Assert parity of one verify call.  gpu: dict of numpy arrays.  Returns counters.
+    early_exit: the per-position outputs after the rejected position must be NaN (never evaluated)."""
     omega = np.asarray(omega, np.float32)
     if ref is None:
         ref = run_oracle(O, w, omega, resample_mode)
     B, L = w.B, w.L
     ua = w.u_accept.cpu().numpy().astype(np.float64)
     ur = w.u_resample.cpu().numpy().astype(np.float64)
+    if "p_tok" in gpu and early_exit:
+        gpu = dict(gpu)
+        later = np.arange(L)[None, :] > gpu["accept_len"][:, None]
+        for k in ("p_tok", "q_tok", "f"):
+            assert np.isnan(gpu[k][later]).all() and not np.isnan(gpu[k][~later]).any(), k
+            gpu[k] = np.where(later, ref[k], gpu[k])
     if "p_tok" in gpu:
         _close(gpu["p_tok"], ref["p_tok"], "p_tok")
         _close(gpu["q_tok"], ref["q_tok"], "q_tok")

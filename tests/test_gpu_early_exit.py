@@ -1,0 +1,94 @@
+"""Parity of the early-exit form of cool_sd_verify (COOL_SD_FLAG_EARLY_EXIT) against the CPU
+oracle, with the same tolerances as the all-rows form, and agreement of the two forms."""
+import numpy as np
+import pytest
+import torch
+
+from tests.parity_util import compare_verify, to_numpy
+from workloads import make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2601_09212_amd as pkg
+    pkg.binding.lib()
+    return pkg
+
+
+def _both(P, w, om, **kw):
+    omega = torch.from_numpy(np.ascontiguousarray(om, dtype=np.float32)).cuda()
+    early = to_numpy(P.verify_workload(w, omega, flags=P.COOL_SD_FLAG_EARLY_EXIT, **kw))
+    full = to_numpy(P.verify_workload(w, omega, **kw))
+    torch.cuda.synchronize()
+    return early, full
+
+
+SHAPES = [
+    (1, 1, 4, 16384, "f32"),
+    (2, 32, 8, 16384, "bf16"),      # config 2
+    (2, 3, 5, 4104, "bf16"),        # partial last vector block
+    (2, 3, 3, 5001, "bf16"),        # rows not 16-byte aligned: served by the all-rows path
+    (1, 2, 3, 1003, "f32"),
+    (1, 2, 2, 8, "f32"),
+    (2, 2, 2, 1, "bf16"),
+    (4, 40, 16, 16384, "bf16"),     # config 4 rows
+    (2, 2, 1, 16384, "bf16"),       # L = 1
+    (2, 2, 300, 512, "bf16"),       # long draft window
+]
+
+
+@pytest.mark.parametrize("cfg,B,L,V,dtype", SHAPES)
+def test_early_exit_shapes(P, oracle, cfg, B, L, V, dtype):
+    print("case", cfg, B, L, V, dtype, flush=True)
+    w = make_workload(cfg, device="cuda", B=B, L=L, V=V, dtype=dtype)
+    om = P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, L, w.delta, w.nu)
+    early, full = _both(P, w, om)
+    honoured = V % (8 if dtype == "bf16" else 4) == 0     # otherwise the rows are not 16-byte aligned
+    compare_verify(oracle, w, om, early, early_exit=honoured)
+    # the two forms sum the softmax denominators in different orders, so they may differ where a
+    # uniform sits on a threshold; everywhere else they agree
+    same = early["accept_len"] == full["accept_len"]
+    assert same.mean() >= 0.9
+    assert (early["next_token"][same] == full["next_token"][same]).mean() >= 0.9
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_early_exit_modes_budgets_and_no_bonus(P, oracle, mode):
+    w = make_workload(4, device="cuda", B=24, L=8, V=16384)
+    for delta in (1.0, 4.0, 50.0):      # delta = 50: nearly everything is accepted, bonus draws
+        om = P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, 8, delta, w.nu)
+        early, _ = _both(P, w, om, resample_mode=mode)
+        compare_verify(oracle, w, om, early, resample_mode=mode, early_exit=True)
+    om = P.cool_sd_schedule(P.COOL_SD_SCHED_UNIFORM, 8, 50.0)
+    w.target = w.target[:, :8].contiguous()
+    early, _ = _both(P, w, om, resample_mode=mode)
+    compare_verify(oracle, w, om, early, resample_mode=mode, has_bonus=False, early_exit=True)
+    assert (early["next_token"][early["accept_len"] == 8] == -1).all() and (early["accept_len"] == 8).any()
+
+
+def test_early_exit_per_sequence_omega_guidance_and_temperature(P, oracle):
+    w = make_workload(2, device="cuda", B=9, L=6, V=16384)
+    om = np.tile(P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, 6, 2.0, w.nu), (9, 1)).astype(np.float32)
+    om[::3] = 0.0
+    om[1::3] *= 3.0
+    early, _ = _both(P, w, om)
+    compare_verify(oracle, w, om, early, early_exit=True)
+    assert (early["accept_len"][::3] == 0).all()
+    w = make_workload(3, device="cuda", B=4, L=5, top_k=0)      # guided logits, no top-k
+    w.temperature = 0.7
+    om = P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, 5, 1.5, w.nu)
+    early, _ = _both(P, w, om)
+    compare_verify(oracle, w, om, early, early_exit=True)
+
+
+def test_early_exit_falls_back_where_not_supported(P, oracle):
+    """top-k and rows longer than 16384 logits run the all-rows path: every position is filled."""
+    for w in (make_workload(3, device="cuda", B=3, L=4), make_workload(5, device="cuda", B=2, L=3, V=40000)):
+        om = P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, w.L, w.delta, w.nu)
+        early, full = _both(P, w, om)
+        compare_verify(oracle, w, om, early)
+        for k in early:
+            np.testing.assert_array_equal(early[k], full[k])

@@ -55,7 +55,7 @@ def test_schedule_rejects_bad_arguments(P):
 def _params(P, **kw):
     base = dict(B=4, L=8, V=16384, dtype=P.COOL_SD_BF16, t_stride_b=9 * 16384, t_stride_l=16384,
                 d_stride_b=8 * 16384, d_stride_l=16384, omega_stride_b=0, has_bonus=1, top_k=0,
-                cfg_scale=1.0, temperature=1.0, resample_mode=0, reserved=0)
+                cfg_scale=1.0, temperature=1.0, resample_mode=0, flags=0)
     base.update(kw)
     return P.CoolSDParams(**base)
 
@@ -68,7 +68,7 @@ def test_workspace_bytes_and_invalid_params(P):
     assert big > small
     for bad in (dict(B=0), dict(V=0), dict(dtype=3), dict(top_k=-1), dict(top_k=16385), dict(temperature=0.0),
                 dict(temperature=float("inf")), dict(cfg_scale=float("nan")), dict(resample_mode=2),
-                dict(reserved=1), dict(t_stride_b=-1)):
+                dict(flags=2), dict(flags=-1), dict(t_stride_b=-1)):
         assert P.cool_sd_workspace_bytes(_params(P, **bad)) == 0, bad
     # L out of range is still a valid stand-alone resample shape (L is ignored there)
     assert P.cool_sd_workspace_bytes(_params(P, L=0)) > 0

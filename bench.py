@@ -29,7 +29,9 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/),
 # scaled by the same counters' reading on a plain copy kernel; None = not measured.
 # Fetched + written bytes of row_stats_kernel per launch.
-MEASURED_TRAFFIC_BYTES = {"cfg1": None, "cfg2": 17.97e6, "cfg3": 76.93e6, "cfg4": 278.04e6, "cfg5": 1143.27e6}
+MEASURED_TRAFFIC_BYTES = {"cfg1": None, "cfg2": 17.97e6, "cfg3": 74.28e6, "cfg4": 278.04e6, "cfg5": 1143.26e6}
+# the same for sequence_early_exit_kernel (--early-exit)
+MEASURED_TRAFFIC_EARLY = {"cfg2": 7.95e6, "cfg4": 51.28e6}
 
 
 def parse():
@@ -128,11 +130,38 @@ class Runner:
 
 
     def kernel_times(self, n):
-        """Average duration of the statistics kernel and of the whole call (HIP events recorded by the
-        library on the launch stream), over n direct calls cycling through the pool."""
+        """Average duration of the statistics kernel and of the whole call, over the pool.
+
+        Statistics kernel: the library is switched to launch that kernel alone, one graph holds one such
+        launch per pool batch, and HIP events on the launch stream bracket replays of it: back-to-back
+        launches, so the figure is the kernel's duration plus the gap between two launches.
+        Whole call (and the statistics kernel once more, `events`): HIP events that the library records
+        around one direct call on the launch stream; these include the dispatch latency of a lone launch."""
         pkg, torch = self.pkg, self.torch
         torch.cuda.synchronize()
-        pkg.cool_sd_profile_enable(True)
+        pkg.cool_sd_profile_enable(2)
+        try:
+            for i in range(len(self.pool)):
+                self.step(i)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for i in range(len(self.pool)):
+                    self.step(i)
+            reps = max(2, -(-n // len(self.pool)))
+            g.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            k_graph = e0.elapsed_time(e1) * 1e-3 / (reps * len(self.pool))
+            del g
+        finally:
+            pkg.cool_sd_profile_enable(0)
+        pkg.cool_sd_profile_enable(1)
         k_ms = c_ms = 0.0
         try:
             for i in range(n + 5):
@@ -142,8 +171,20 @@ class Runner:
                     k_ms += a
                     c_ms += b
         finally:
-            pkg.cool_sd_profile_enable(False)
-        return k_ms / n * 1e-3, c_ms / n * 1e-3
+            pkg.cool_sd_profile_enable(0)
+        return k_graph, k_ms / n * 1e-3, c_ms / n * 1e-3
+
+
+def run_diagnostics(r, n):
+    """n direct cool_sd_diagnostics calls cycling through the pool (for profiler runs)."""
+    pkg, torch = r.pkg, r.torch
+    alpha = torch.empty((r.B, r.L), dtype=torch.float32, device="cuda")
+    beta = torch.empty_like(alpha)
+    for i in range(n):
+        w = r.pool[i % len(r.pool)]
+        pkg.cool_sd_diagnostics(r.params, w.target, w.target_uncond, w.draft, w.draft_uncond, r.omega, alpha, beta,
+                                r.ws)
+    torch.cuda.synchronize()
 
 
 def time_diagnostics(r, passes=6):
@@ -228,13 +269,26 @@ def main():
         torch.cuda.synchronize()
         r.run(a.steps, "direct")
         torch.cuda.synchronize()
+        if a.diagnostics:
+            run_diagnostics(r, a.steps)
         print(json.dumps({"counter_run": a.workload, "steps": a.steps, "copy_bytes_each_way": src.numel() * 4,
                           "bytes_per_step": r.bytes_per_step}))
         return
     done, wall, dev_s = r.time(a.steps, a.warmup, a.launch)
     tokens = done * r.B * r.L
-    kern_s, call_s = r.kernel_times(a.kernel_samples)
-    achieved = r.bytes_per_step / kern_s / 1e9
+    kern_s, kern_ev_s, call_s = r.kernel_times(a.kernel_samples)
+    kernel_name, kernel_bytes = "row_stats_kernel", r.bytes_per_step
+    if a.early_exit and r.V <= 16384:
+        # one kernel per call; its algorithmic bytes are the rows Algorithm 1 needs: both rows of every
+        # position up to and including the rejected one, or all L pairs plus the bonus row
+        need = 0
+        for i in range(len(r.pool)):
+            r.step(i)
+            tau = r.accept_len.cpu().numpy().astype("int64")
+            need += int(((tau + 1).clip(max=r.L) * 2 + (tau == r.L)).sum()) * r.V * r.pool[0].target.element_size()
+        kernel_name, kernel_bytes = "sequence_early_exit_kernel", need / len(r.pool)
+        kern_s = dev_s / done
+    achieved = kernel_bytes / kern_s / 1e9
     dtype = r.pool[0].dtype
     line = {
         "metric": "verified draft tokens/sec (1 GPU) + achieved HBM GB/s fraction of peak",
@@ -246,8 +300,11 @@ def main():
                    "input_dtype": dtype, "launch": a.launch, "early_exit": bool(a.early_exit), "pool_batches": len(r.pool),
                    "pool_mb": len(r.pool) * r.bytes_per_step / 1e6, "bytes_per_step": r.bytes_per_step},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(a.workload),
-                     "kernel": "row_stats_kernel", "us_per_launch": kern_s * 1e6,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": (MEASURED_TRAFFIC_EARLY if a.early_exit else MEASURED_TRAFFIC_BYTES).get(a.workload),
+                     "kernel": kernel_name, "algorithmic_bytes_per_launch": kernel_bytes,
+                     "us_per_launch": kern_s * 1e6,
+                     "us_per_launch_lone_events": kern_ev_s * 1e6,
                      "whole_call_us": call_s * 1e6, "whole_call_GBps": r.bytes_per_step / call_s / 1e9,
                      "graph_step_us": dev_s / done * 1e6},
     }
@@ -261,7 +318,7 @@ def main():
             rr = Runner(pkg, torch, c, 2400.0 if c >= 4 else 600.0, max_pool=(2 if big else 8) if c >= 4 else 64,
                         flags=flags, B=big)
             d2, w2, s2 = rr.time(max(64, 8 * len(rr.pool)), 2 * len(rr.pool), a.launch)
-            k2, c2 = rr.kernel_times(40)
+            k2, _, c2 = rr.kernel_times(40)
             name = "cfg%d" % c + ("_B%d" % big if big else "")
             extra[name] = {"tokens_per_s": d2 * rr.B * rr.L / w2, "us_per_step": s2 / d2 * 1e6,
                                   "whole_call_GBps": rr.bytes_per_step / (s2 / d2) / 1e9,

@@ -175,12 +175,14 @@ int cool_sd_diagnostics(const cool_sd_params* p,
                         void* workspace_dev, size_t workspace_bytes,
                         void* hip_stream);
 
-/* Benchmark instrumentation (not for production paths, not thread-safe, not usable while the
- * stream is being captured into a graph).  While enabled, cool_sd_verify / cool_sd_resample
- * record HIP events on the call's stream around the row-statistics kernel (the pass that reads
- * every logit from HBM) and around the whole call.  cool_sd_profile_read waits for the last
- * instrumented call and returns both durations in milliseconds. */
-int cool_sd_profile_enable(int enable);
+/* Benchmark instrumentation (not for production paths, not thread-safe).  mode 0: off.
+ * mode 1 (not usable while the stream is being captured into a graph): cool_sd_verify /
+ * cool_sd_resample record HIP events on the call's stream around the row-statistics kernel (the
+ * pass that reads every logit from HBM) and around the whole call; cool_sd_profile_read waits for
+ * the last instrumented call and returns both durations in milliseconds.
+ * mode 2: cool_sd_verify / cool_sd_resample enqueue the row-statistics kernel ALONE and write no
+ * output, so that a benchmark can time that kernel back to back (also from a captured graph). */
+int cool_sd_profile_enable(int mode);
 int cool_sd_profile_read(float* stats_kernel_ms, float* call_ms);
 
 /* Static description of a cool_sd_status. */

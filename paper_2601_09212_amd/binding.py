@@ -144,8 +144,9 @@ def cool_sd_diagnostics(params, target, target_uncond, draft, draft_uncond, omeg
     return rc
 
 
-def cool_sd_profile_enable(enable):
-    rc = lib().cool_sd_profile_enable(int(bool(enable)))
+def cool_sd_profile_enable(mode):
+    """0 / False: off; 1 / True: events around the statistics kernel and the call; 2: statistics kernel only."""
+    rc = lib().cool_sd_profile_enable(int(mode))
     if rc != 0:
         raise CoolSDError(rc, "cool_sd_profile_enable")
 

@@ -77,6 +77,7 @@ bool params_ok(const cool_sd_params* p, bool for_resample) {
 
 // benchmark instrumentation (see cool_sd_profile_enable)
 bool g_profile = false;
+bool g_stats_only = false;   // benchmark mode 2: enqueue the statistics kernel alone
 bool g_profile_valid = false;
 hipEvent_t g_ev[3] = {nullptr, nullptr, nullptr};
 
@@ -121,6 +122,7 @@ int run(const cool_sd_params* p, bool resample_only,
   a.top_k = p->top_k; a.resample_mode = p->resample_mode;
   a.resample_only = resample_only ? 1 : 0;
   a.aligned = aligned ? 1 : 0;
+  a.stats_only = g_stats_only ? 1 : 0;
   a.early_exit = (!resample_only && aligned && (p->flags & COOL_SD_FLAG_EARLY_EXIT) && p->top_k == 0 && p->V <= csd::kChunk &&
                   p->L <= 1024) ? 1 : 0;
   // beyond ~128 MB the logits cannot stay in L2 / Infinity Cache until the sequence kernel re-reads a row
@@ -289,11 +291,13 @@ int cool_sd_diagnostics(const cool_sd_params* p, const void* target_dev, const v
 }
 
 int cool_sd_profile_enable(int enable) {
-  if (enable && !g_ev[0]) {
+  if (enable < 0 || enable > 2) return COOL_SD_EINVAL;
+  if (enable == 1 && !g_ev[0]) {
     for (int i = 0; i < 3; ++i)
       if (hipEventCreate(&g_ev[i]) != hipSuccess) return COOL_SD_ELAUNCH;
   }
-  g_profile = enable != 0;
+  g_profile = enable == 1;
+  g_stats_only = enable == 2;
   g_profile_valid = false;
   return COOL_SD_OK;
 }

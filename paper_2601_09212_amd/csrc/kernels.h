@@ -23,6 +23,7 @@ struct KArgs {
   float* resid_mass;        // [B] or nullptr
   int64_t t_sb, t_sl, d_sb, d_sl, om_sb;   // element strides
   int32_t B, L, V, has_bonus, top_k, resample_mode, resample_only, aligned;
+  int32_t stats_only;       // benchmark: launch row_stats_kernel only
   int32_t early_exit;       // verify: stop reading a sequence's rows at its first rejection (one kernel)
   int32_t stream_loads;     // statistics kernel: input larger than the caches, use nontemporal loads
   int32_t nchunks, nt2;     // sampling kernel: chunks per row, tiles per chunk

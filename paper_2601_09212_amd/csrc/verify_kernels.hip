@@ -1031,7 +1031,7 @@ template <int DT, bool XF, bool AL>
 static hipError_t launch_typed(const KArgs& a, hipStream_t stream, hipEvent_t* ev) {
   (void)hipGetLastError();
   if (ev) (void)hipEventRecord(ev[0], stream);
-  if (a.early_exit) {   // one launch; there is no separate statistics pass to time
+  if (a.early_exit && !a.stats_only) {   // one launch; there is no separate statistics pass to time
     if (ev) (void)hipEventRecord(ev[1], stream);
     hipLaunchKernelGGL((sequence_early_exit_kernel<DT, XF, 1>), dim3((unsigned)a.B), dim3(kThreadsW), 0, stream, a);
     hipError_t ee = checked("sequence_early_exit_kernel");
@@ -1039,7 +1039,7 @@ static hipError_t launch_typed(const KArgs& a, hipStream_t stream, hipEvent_t* e
     return ee;
   }
   hipError_t e = launch_stats_any<DT, XF, AL>(a, stream);
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || a.stats_only) return e;
   if (ev) (void)hipEventRecord(ev[1], stream);
   e = launch_rest<DT, XF, AL>(a, stream);
   if (ev) (void)hipEventRecord(ev[2], stream);

@@ -149,9 +149,15 @@ template <int DT> __device__ __forceinline__ float load_elem(const char* __restr
 
 // Logit transform, evaluated in fp32 with exactly these roundings: the difference is rounded,
 // then one fused multiply-add, then one multiply by fl32(1/T).
+// Guidance l_u + s (l_c - l_u).  Where both logits are -inf (a token excluded on both sides, or
+// an element beyond the end of the row) the difference is NaN; fmaxf returns its other operand
+// then, so such an entry stays excluded (-inf).
+__device__ __forceinline__ float guide_logit(float lc, float lu, float s) {
+  return fmaxf(__fmaf_rn(s, __fsub_rn(lc, lu), lu), -INFINITY);
+}
 __device__ __forceinline__ float transform_logit(float lc, float lu, bool guided, float s, float inv_T) {
   float l = lc;
-  if (guided) l = __fmaf_rn(s, __fsub_rn(lc, lu), lu);
+  if (guided) l = guide_logit(lc, lu, s);
   return __fmul_rn(l, inv_T);
 }
 
@@ -182,8 +188,9 @@ template <int DT, bool XF, int NT> struct RowRegs {
 // twin when guided) and apply the logit transform when XF: guidance, temperature, then the
 // top-k mask "keep l >= thr" (thr = -inf: no mask).  Out-of-range elements become -inf.
 // Vector k of thread t is vector number k*KS + t*TS of the chunk: (KS, TS) = (256, 1) is the
-// tile layout described at the top; (1, NT) gives every thread NT consecutive vectors.
-template <int DT, bool XF, int AL, int NT, int KS = kThreads, int TS = 1>
+// tile layout described at the top; (1, NT) gives every thread NT consecutive vectors.  With a
+// logit transform, KG tiles (of both tensors) are in flight at a time.
+template <int DT, bool XF, int AL, int NT, int KS = kThreads, int TS = 1, int KG = 4, int GD = -1>
 __device__ __forceinline__ void load_chunk(RowRegs<DT, XF, NT>& r, const char* __restrict__ cond,
                                            const char* __restrict__ uncond, int64_t base, int V,
                                            float s, float inv_T, float thr) {
@@ -204,30 +211,42 @@ __device__ __forceinline__ void load_chunk(RowRegs<DT, XF, NT>& r, const char* _
       }
     }
   } else {
-    // Groups of kG tiles: the 2*kG raw vectors of a group are in flight together and are
-    // consumed before the next group is fetched, which bounds the registers held by raw data.
-    constexpr int kG = NT < 4 ? NT : 4;
-    const bool guided = uncond != nullptr;
-    const char* second = guided ? uncond : cond;   // unguided: a harmless re-read, no branch
+    // Groups of kG tiles: the raw vectors of a group are in flight together and are consumed
+    // before the next group is fetched, which bounds the registers held by raw data.  The
+    // options (guided, temperature, mask) are the same for every thread, so each is one branch
+    // around a loop, not a select per element.
+    constexpr int kG = NT < KG ? NT : KG;
+    // GD: guidance known at compile time (1 on, 0 off) or decided by the pointer (-1)
+    const bool guided = GD < 0 ? (uncond != nullptr) : (GD == 1);
 #pragma unroll
     for (int g = 0; g < NT; g += kG) {
       uint4 rc[kG], ru[kG];
 #pragma unroll
-      for (int k = 0; k < kG; ++k) {
-        const int64_t e = base + int64_t((g + k) * KS + tid * TS) * kE;
-        rc[k] = load_vec<DT, AL>(cond, e, V);
-        ru[k] = load_vec<DT, AL>(second, e, V);
-      }
+      for (int k = 0; k < kG; ++k) rc[k] = load_vec<DT, AL>(cond, base + int64_t((g + k) * KS + tid * TS) * kE, V);
+      if (guided) {
 #pragma unroll
-      for (int k = 0; k < kG; ++k) {
-        const int64_t e = base + int64_t((g + k) * KS + tid * TS) * kE;
+        for (int k = 0; k < kG; ++k) ru[k] = load_vec<DT, AL>(uncond, base + int64_t((g + k) * KS + tid * TS) * kE, V);
 #pragma unroll
-        for (int j = 0; j < kE; ++j) {
-          float l = transform_logit(vec_elem<DT>(rc[k], j), vec_elem<DT>(ru[k], j), guided, s, inv_T);
-          r.set(g + k, j, (e + j < V && l >= thr) ? l : -INFINITY);
+        for (int k = 0; k < kG; ++k) {
+#pragma unroll
+          for (int j = 0; j < kE; ++j) r.set(g + k, j, guide_logit(vec_elem<DT>(rc[k], j), vec_elem<DT>(ru[k], j), s));
+        }
+      } else {
+#pragma unroll
+        for (int k = 0; k < kG; ++k) {
+#pragma unroll
+          for (int j = 0; j < kE; ++j) r.set(g + k, j, vec_elem<DT>(rc[k], j));
         }
       }
       __builtin_amdgcn_sched_barrier(0);
+    }
+    if (inv_T != 1.0f) {               // multiplying by 1 would change nothing
+#pragma unroll
+      for (int n = 0; n < NT * kE; ++n) r.w[n] = __float_as_uint(__fmul_rn(__uint_as_float(r.w[n]), inv_T));
+    }
+    if (thr > -INFINITY) {             // top-k mask: keep l >= thr
+#pragma unroll
+      for (int n = 0; n < NT * kE; ++n) r.w[n] = (__uint_as_float(r.w[n]) >= thr) ? r.w[n] : 0xFF800000u;
     }
   }
 }

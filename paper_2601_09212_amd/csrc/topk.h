@@ -1,5 +1,5 @@
 // Block-wide exact selection of the k-th largest value of a row held in registers (fp32,
-// NT*kE values per thread, 256 threads).  Used for the top-k truncation "keep l >= k-th
+// NVAL values per thread, TPB threads).  Used for the top-k truncation "keep l >= k-th
 // largest", ties at the threshold all kept.
 //
 // Method: value-bucket refinement.  The finite values lie in [lo, hi].  2048 equal-width
@@ -9,6 +9,9 @@
 // minimum and maximum and the step repeats.  The bucket index is a monotone function of the
 // value, so every value of a lower-numbered bucket is >= every value of a higher one.  For
 // Gaussian-like logits one step leaves about ten candidates.
+//
+// The common case (no -inf entry in the row, one step) is kept short: the histogram pass is
+// then three instructions and one LDS atomic per value, with no range test.
 #pragma once
 #include "device_utils.h"
 
@@ -17,11 +20,11 @@ namespace csd {
 constexpr int kBuckets = 2048;
 constexpr int kListCap = 1024;
 
-struct TopkSmem {
+template <int TPB> struct TopkSmem {
   uint32_t hist[kBuckets];
   float list[kListCap];
-  float red_lo[kWaves], red_hi[kWaves];
-  uint32_t wave_tot[kWaves];
+  float red_lo[TPB / 64], red_hi[TPB / 64];
+  uint32_t wave_tot[TPB / 64];
   uint32_t n_list;
   uint32_t key_min, key_max;
   int bsel;
@@ -38,46 +41,57 @@ __device__ __forceinline__ float key_value(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
+// Bucket of a value v in [lo, hi]: scale = fl(kBucketSpan / (hi - lo)) makes the product stay
+// below kBuckets (2047.99 (1 + 2^-24)^2 < 2048), so no clamp is needed; subtraction,
+// multiplication and truncation are monotone, which is all the method relies on.
+constexpr float kBucketSpan = 2047.99f;
 __device__ __forceinline__ int bucket_of(float v, float hi, float scale) {
-  const int b = (int)__fmul_rn(__fsub_rn(hi, v), scale);
-  return b > kBuckets - 1 ? kBuckets - 1 : b;
+  return (int)__fmul_rn(__fsub_rn(hi, v), scale);
+}
+
+__device__ __forceinline__ float wave_min(float v) {
+  v = fminf(v, dpp_f<kDppSwap1>(v));
+  v = fminf(v, dpp_f<kDppSwap2>(v));
+  v = fminf(v, dpp_f<kDppHalfMirror>(v));
+  v = fminf(v, dpp_f<kDppMirror>(v));
+  return fminf(fminf(lane_f(v, 0), lane_f(v, 16)), fminf(lane_f(v, 32), lane_f(v, 48)));
 }
 
 // k-th largest of the values of all threads that lie in [lo, hi]; the caller guarantees that lo
 // and hi are the minimum and maximum of the finite values and that the LDS histogram is zero.
-// Returns -inf when fewer than k values are finite.  All 256 threads must call it; result in
-// every thread.
-template <int NVAL>
+// in_range: every value of every thread lies in [lo, hi] (no -inf entries), so the first pass
+// needs no range test.  Returns -inf when fewer than k values are finite.  All TPB threads must
+// call it; result in every thread.
+template <int NVAL, int TPB>
 __device__ __forceinline__ float kth_largest(const uint32_t (&xw)[NVAL], uint32_t kk, float lo, float hi,
-                                             TopkSmem& ts) {
-  constexpr bool exact_lo = true;
+                                             bool in_range, TopkSmem<TPB>& ts) {
+  constexpr int kW = TPB / 64;            // waves
+  constexpr int kPer = kBuckets / TPB;    // buckets owned by one thread in the prefix step
   auto X = [&](int i) { return __uint_as_float(xw[i]); };
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  bool narrowed = false;                               // hi is no longer the maximum of the values
   for (int iter = 0; iter < 16; ++iter) {
-    if (!(hi > lo) && (exact_lo || narrowed)) return hi;   // every remaining candidate ties
+    if (!(hi > lo)) return hi;                           // every remaining candidate ties
     const float width = __fsub_rn(hi, lo);
-    const float scale = (width > 0.f) ? (float)kBuckets / width : 0.f;
+    const float scale = kBucketSpan / width;
     if (iter > 0) {       // the first pass finds the histogram zeroed by topk_prepare
       __syncthreads();
-      for (int i = tid; i < kBuckets; i += kThreads) ts.hist[i] = 0u;
+      for (int i = tid; i < kBuckets; i += TPB) ts.hist[i] = 0u;
       if (tid == 0) { ts.n_list = 0u; ts.key_min = 0xffffffffu; ts.key_max = 0u; }
       __syncthreads();
     }
-    if (!narrowed) {
+    if (in_range) {
 #pragma unroll
-      for (int i = 0; i < NVAL; ++i)
-        if (X(i) >= lo) atomicAdd(&ts.hist[bucket_of(X(i), hi, scale)], 1u);
+      for (int i = 0; i < NVAL; ++i) atomicAdd(&ts.hist[bucket_of(X(i), hi, scale)], 1u);
     } else {
 #pragma unroll
       for (int i = 0; i < NVAL; ++i)
         if (X(i) >= lo && X(i) <= hi) atomicAdd(&ts.hist[bucket_of(X(i), hi, scale)], 1u);
     }
     __syncthreads();
-    // bucket that holds the kk-th largest: thread t owns buckets [8t, 8t+8)
-    uint32_t h[8], local = 0;
+    // bucket that holds the kk-th largest: thread t owns buckets [kPer t, kPer (t+1))
+    uint32_t h[kPer], local = 0;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) { h[j] = ts.hist[tid * 8 + j]; local += h[j]; }
+    for (int j = 0; j < kPer; ++j) { h[j] = ts.hist[tid * kPer + j]; local += h[j]; }
     uint32_t incl = local;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
@@ -86,15 +100,18 @@ __device__ __forceinline__ float kth_largest(const uint32_t (&xw)[NVAL], uint32_
     }
     if (lane == 63) ts.wave_tot[wv] = incl;
     __syncthreads();
-    uint32_t before = incl - local;
-    for (int w = 0; w < wv; ++w) before += ts.wave_tot[w];
-    const uint32_t total = ts.wave_tot[0] + ts.wave_tot[1] + ts.wave_tot[2] + ts.wave_tot[3];
-    if (kk > total) return (exact_lo || narrowed) ? -INFINITY : NAN;
+    uint32_t before = incl - local, total = 0;
+#pragma unroll
+    for (int w = 0; w < kW; ++w) {
+      before += (w < wv) ? ts.wave_tot[w] : 0u;
+      total += ts.wave_tot[w];
+    }
+    if (kk > total) return -INFINITY;
     if (before < kk && kk <= before + local) {
       uint32_t cum = before;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        if (cum < kk && kk <= cum + h[j]) { ts.bsel = tid * 8 + j; ts.k_in_bucket = kk - cum; ts.n_in_bucket = h[j]; }
+      for (int j = 0; j < kPer; ++j) {
+        if (cum < kk && kk <= cum + h[j]) { ts.bsel = tid * kPer + j; ts.k_in_bucket = kk - cum; ts.n_in_bucket = h[j]; }
         cum += h[j];
       }
     }
@@ -103,20 +120,21 @@ __device__ __forceinline__ float kth_largest(const uint32_t (&xw)[NVAL], uint32_
     const uint32_t nb = ts.n_in_bucket;
     kk = ts.k_in_bucket;
     // value interval that certainly contains bucket bsel (bucket edges +- 1e-5 of the range,
-    // far more than the rounding of bucket_of); exact membership is re-checked on the few hits
-    const float step = width * (1.0f / kBuckets);
+    // far more than the rounding of bucket_of) and lies inside [lo, hi]; exact membership is
+    // re-checked on the few hits
+    const float step = width * (1.0f / kBucketSpan);
     const float margin = width * 1e-5f;
-    const float g_hi = hi - (float)bsel * step + margin;
-    const float g_lo = (bsel == kBuckets - 1 || !(width > 0.f)) ? lo : fmaxf(lo, hi - (float)(bsel + 1) * step - margin);
+    const float g_hi = fminf(hi, hi - (float)bsel * step + margin);
+    const float g_lo = fmaxf(lo, hi - (float)(bsel + 1) * step - margin);
     if (nb <= (uint32_t)kListCap) {
 #pragma unroll
       for (int i = 0; i < NVAL; ++i)
         if (X(i) >= g_lo && X(i) <= g_hi) {
-          if (X(i) <= hi && bucket_of(X(i), hi, scale) == bsel) ts.list[atomicAdd(&ts.n_list, 1u)] = X(i);
+          if (bucket_of(X(i), hi, scale) == bsel) ts.list[atomicAdd(&ts.n_list, 1u)] = X(i);
         }
       __syncthreads();
       // the kk-th largest v has fewer than kk values above it and at least kk values >= it
-      for (uint32_t i = tid; i < nb; i += kThreads) {
+      for (uint32_t i = tid; i < nb; i += TPB) {
         const float v = ts.list[i];
         uint32_t g = 0, ge = 0;
         for (uint32_t j = 0; j < nb; ++j) { g += ts.list[j] > v; ge += ts.list[j] >= v; }
@@ -129,47 +147,69 @@ __device__ __forceinline__ float kth_largest(const uint32_t (&xw)[NVAL], uint32_
 #pragma unroll
     for (int i = 0; i < NVAL; ++i)
       if (X(i) >= g_lo && X(i) <= g_hi) {
-        if (X(i) <= hi && bucket_of(X(i), hi, scale) == bsel) {
-          atomicMin(&ts.key_min, order_key(X(i)));
-          atomicMax(&ts.key_max, order_key(X(i)));
+        if (bucket_of(X(i), hi, scale) == bsel) {
+          // the empty asm pins the key computation to this rare path: the values do not change
+          // between steps, and hoisting 'order_key' of all of them out of the step loop would
+          // cost one register per value on the common path
+          float xv = X(i);
+          asm volatile("" : "+v"(xv));
+          atomicMin(&ts.key_min, order_key(xv));
+          atomicMax(&ts.key_max, order_key(xv));
         }
       }
     __syncthreads();
     lo = key_value(ts.key_min);
     hi = key_value(ts.key_max);
-    narrowed = true;
+    in_range = false;
   }
   return hi;   // not reached for fp32 inputs: every step splits distinct values
 }
 
-// Returns the k-th largest of all NVAL x 256 values (1 <= k <= their number, -inf entries
-// included); -inf when fewer than k values are finite.  All 256 threads must call it.
-template <int NVAL>
-__device__ __forceinline__ float topk_threshold(const uint32_t (&xw)[NVAL], int k, TopkSmem& ts) {
+// Returns the k-th largest of all NVAL x TPB values (1 <= k <= their number, -inf entries
+// included); -inf when fewer than k values are finite.  row_max receives the largest value
+// (-inf for a row without a finite entry).  All TPB threads must call it.
+template <int NVAL, int TPB>
+__device__ __forceinline__ float topk_threshold(const uint32_t (&xw)[NVAL], int k, TopkSmem<TPB>& ts, float& row_max) {
   auto X = [&](int i) { return __uint_as_float(xw[i]); };
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  float hi = -INFINITY, lo = INFINITY;
+  float hi = X(0), lo = X(0);
 #pragma unroll
-  for (int i = 0; i < NVAL; ++i) {
+  for (int i = 1; i < NVAL; ++i) {
     hi = fmaxf(hi, X(i));
-    lo = (X(i) > -INFINITY) ? fminf(lo, X(i)) : lo;
+    lo = fminf(lo, X(i));
   }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    lo = fminf(lo, __shfl_xor(lo, o, 64));
-    hi = fmaxf(hi, __shfl_xor(hi, o, 64));
-  }
+  lo = wave_min(lo);
+  hi = wave_max(hi);
   if (lane == 0) { ts.red_lo[wv] = lo; ts.red_hi[wv] = hi; }
   __syncthreads();
-  lo = fminf(fminf(ts.red_lo[0], ts.red_lo[1]), fminf(ts.red_lo[2], ts.red_lo[3]));
-  hi = fmaxf(fmaxf(ts.red_hi[0], ts.red_hi[1]), fmaxf(ts.red_hi[2], ts.red_hi[3]));
+  lo = ts.red_lo[0];
+  hi = ts.red_hi[0];
+#pragma unroll
+  for (int w = 1; w < TPB / 64; ++w) { lo = fminf(lo, ts.red_lo[w]); hi = fmaxf(hi, ts.red_hi[w]); }
+  row_max = hi;
   if (!(hi > -INFINITY)) return -INFINITY;           // no finite value at all
-  return kth_largest<NVAL>(xw, (uint32_t)k, lo, hi, ts);
+  bool in_range = true;
+  if (!(lo > -INFINITY)) {
+    // the row has -inf entries (excluded tokens, or elements beyond V): the minimum of the
+    // finite values is needed for the bucket range
+    in_range = false;
+    lo = INFINITY;
+#pragma unroll
+    for (int i = 0; i < NVAL; ++i) lo = (X(i) > -INFINITY) ? fminf(lo, X(i)) : lo;
+    lo = wave_min(lo);
+    __syncthreads();                                   // red_lo was read above
+    if (lane == 0) ts.red_lo[wv] = lo;
+    __syncthreads();
+    lo = ts.red_lo[0];
+#pragma unroll
+    for (int w = 1; w < TPB / 64; ++w) lo = fminf(lo, ts.red_lo[w]);
+  }
+  return kth_largest<NVAL, TPB>(xw, (uint32_t)k, lo, hi, in_range, ts);
 }
 
 // Zero the histogram; call it (all threads) before topk_threshold, e.g. while loads are in flight.
-__device__ __forceinline__ void topk_prepare(TopkSmem& ts) {
-  for (int i = threadIdx.x; i < kBuckets; i += kThreads) ts.hist[i] = 0u;
+template <int TPB> __device__ __forceinline__ void topk_prepare(TopkSmem<TPB>& ts) {
+  for (int i = threadIdx.x; i < kBuckets; i += TPB) ts.hist[i] = 0u;
   if (threadIdx.x == 0) { ts.n_list = 0u; ts.key_min = 0xffffffffu; ts.key_max = 0u; }
 }
 

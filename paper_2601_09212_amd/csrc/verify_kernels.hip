@@ -36,6 +36,8 @@
 namespace csd {
 
 enum { kModeOpt = 0, kModeVanilla = 1, kModeP = 2 };
+constexpr int kThreadsW = 1024;    // workgroup size of the per-row / per-sequence kernels
+constexpr int kWavesW = kThreadsW / 64;
 
 
 struct Smem {
@@ -55,69 +57,63 @@ __device__ __forceinline__ const char* row_ptr(const void* base, int64_t elem_of
   return base ? reinterpret_cast<const char*>(base) + elem_off * es : nullptr;
 }
 
-// Transformed logit of one token of a row (scalar path, used for x~_i).
-template <int DT>
-__device__ __forceinline__ float token_logit(const char* cond, const char* uncond, int x, bool xf,
-                                             float s, float inv_T, float thr) {
-  float lc = load_elem<DT>(cond, x);
-  if (!xf) return lc;
-  float lu = uncond ? load_elem<DT>(uncond, x) : 0.f;
-  const float l = transform_logit(lc, lu, uncond != nullptr, s, inv_T);
-  return l >= thr ? l : -INFINITY;
-}
-
-// LDS of the top-k selection; allocated only in kernels that apply the logit transform.
-template <bool XF> __device__ __forceinline__ TopkSmem* topk_smem() {
-  if constexpr (XF) {
-    __shared__ TopkSmem ts;
-    return &ts;
-  } else {
-    return nullptr;
-  }
-}
-
 // ============================================================================ kernel 1
 // Softmax statistics of one chunk of one row.  Rows are numbered: target rows first
 // (b*(L+has_bonus) + i), then draft rows (rows_t + b*L + i).
+struct RowRef {
+  int b, i;
+  bool is_draft;
+  const char* cond;
+  const char* uncond;
+};
+template <int DT> __device__ __forceinline__ RowRef row_ref(const KArgs& a, int r) {
+  constexpr int kES = Vec<DT>::kES;
+  RowRef o;
+  o.is_draft = r >= a.rows_t;
+  const int rr = o.is_draft ? r - a.rows_t : r;
+  const int per = o.is_draft ? a.L : a.L + a.has_bonus;
+  o.b = rr / per;
+  o.i = rr - o.b * per;
+  const int64_t off = o.is_draft ? int64_t(o.b) * a.d_sb + int64_t(o.i) * a.d_sl
+                                 : int64_t(o.b) * a.t_sb + int64_t(o.i) * a.t_sl;
+  o.cond = row_ptr(o.is_draft ? a.d : a.t, off, kES);
+  o.uncond = row_ptr(o.is_draft ? a.du : a.tu, off, kES);
+  return o;
+}
+
 template <int DT, bool XF, int AL, int NT>
 __global__ __launch_bounds__(kThreads, 3) void row_stats_kernel(const KArgs a) {
-  constexpr int kE = Vec<DT>::kE, kES = Vec<DT>::kES;
+  constexpr int kE = Vec<DT>::kE;
   __shared__ float red_c[kWaves], red_s[kWaves];
   const int C1 = a.c1;
   const int r = blockIdx.x / C1, c = blockIdx.x - r * C1;
-  const bool is_draft = r >= a.rows_t;
-  const int rr = is_draft ? r - a.rows_t : r;
-  const int per = is_draft ? a.L : a.L + a.has_bonus;
-  const int b = rr / per, i = rr - b * per;
-  const int64_t off = is_draft ? int64_t(b) * a.d_sb + int64_t(i) * a.d_sl
-                               : int64_t(b) * a.t_sb + int64_t(i) * a.t_sl;
-  const char* cond = row_ptr(is_draft ? a.d : a.t, off, kES);
-  const char* uncond = row_ptr(is_draft ? a.du : a.tu, off, kES);
+  const RowRef rw = row_ref<DT>(a, r);
   const int64_t base = int64_t(c) * (NT * kThreads * kE);
+  // the draft token x~_i of this row, if this chunk holds it: requested before the chunk's loads
+  // so that its latency hides behind theirs
+  int tok = -1;
+  if (a.tokens != nullptr && rw.i < a.L) tok = a.tokens[int64_t(rw.b) * a.L + rw.i];
 
-  TopkSmem* tsp = topk_smem<XF>();
-  if constexpr (XF) {
-    if (a.top_k > 0) topk_prepare(*tsp);   // the barrier inside topk_threshold orders it
-  }
   RowRegs<DT, XF, NT> x;
-  load_chunk<DT, XF, AL, NT>(x, cond, uncond, base, a.V, a.cfg_scale, a.inv_T, -INFINITY);
-  float row_thr = -INFINITY;
-  if constexpr (XF) {
-    if (a.top_k > 0) {   // the chunk is the whole row here
-      const float thr = topk_threshold<NT * kE>(x.w, a.top_k, *tsp);
+  load_chunk<DT, XF, AL, NT>(x, rw.cond, rw.uncond, base, a.V, a.cfg_scale, a.inv_T, -INFINITY);
+  // the (transformed) logit of x~_i for the accept test of the next kernel, taken from the
+  // registers of the thread that holds it: element e of vector (tile k, thread t) is token
+  // base + (k*256 + t)*kE + e
+  if (tok >= 0) {
+    tok = min(tok, a.V - 1);
+    const int64_t rel = int64_t(tok) - base;
+    if (rel >= 0 && rel < NT * kThreads * kE) {
+      const int vec = int(rel) / kE, e = int(rel) - vec * kE;
+      if ((vec & (kThreads - 1)) == (int)threadIdx.x) {
+        const int k = vec / kThreads;
+        float l = 0.f;
 #pragma unroll
-      for (int n = 0; n < NT * kE; ++n) x.w[n] = (__uint_as_float(x.w[n]) >= thr) ? x.w[n] : 0xFF800000u;
-      if (threadIdx.x == 0) a.thr[r] = thr;
-      row_thr = thr;
-    }
-  }
-  // the (transformed, masked) logit of the draft token x~_i of this row, for the accept test of
-  // the next kernel: written by the chunk that holds it
-  if (a.tokens != nullptr && i < a.L && threadIdx.x == 0) {
-    int tok = a.tokens[int64_t(b) * a.L + i];
-    tok = min(max(tok, 0), a.V - 1);
-    if (tok >= base && tok < base + NT * kThreads * kE) {
-      a.tok_logit[r] = token_logit<DT>(cond, uncond, tok, XF, a.cfg_scale, a.inv_T, row_thr);
+        for (int kk = 0; kk < NT; ++kk) {
+#pragma unroll
+          for (int j = 0; j < kE; ++j) l = (kk == k && j == e) ? x.get(kk, j) : l;
+        }
+        a.tok_logit[r] = l;
+      }
     }
   }
   float ct, st;
@@ -134,6 +130,63 @@ __global__ __launch_bounds__(kThreads, 3) void row_stats_kernel(const KArgs a) {
     S = __fadd_rn(S, red_s[2] * exp2_fast(red_c[2] - C));
     S = __fadd_rn(S, red_s[3] * exp2_fast(red_c[3] - C));
     a.part[int64_t(r) * C1 + c] = make_float2(C, S);
+  }
+}
+
+// Statistics of whole rows under top-k truncation (rows of at most 16384 logits): one
+// workgroup of TPB threads per row, 16384 / TPB transformed logits per thread in registers.
+// The k-th largest value of the row is selected first (topk.h); the softmax statistics are then
+// taken over the entries >= that threshold, against the reference exponent of the row maximum
+// (always kept).  Writes the row's threshold, its statistics (one chunk per row) and the masked
+// logit of x~_i.  The work per row is a chain of short block-wide phases bound by instruction
+// issue, so the code is kept lean and the row is spread over enough threads that several rows
+// fit a compute unit.
+constexpr int kThreadsK = 512;
+template <int DT, int AL, int TPB, int GD>
+__global__ __launch_bounds__(TPB, 6) void row_stats_topk_kernel(const KArgs a) {
+  constexpr int kE = Vec<DT>::kE;
+  constexpr int kVW = kChunk / (TPB * kE);             // vectors per thread
+  constexpr int kW = TPB / 64;
+  __shared__ TopkSmem<TPB> ts;
+  __shared__ float red_s[kW];
+  const int r = blockIdx.x;
+  const RowRef rw = row_ref<DT>(a, r);
+  int tok = -1;
+  if (a.tokens != nullptr && rw.i < a.L) tok = min(max(a.tokens[int64_t(rw.b) * a.L + rw.i], 0), a.V - 1);
+  topk_prepare(ts);                                     // the barrier inside topk_threshold orders it
+  RowRegs<DT, true, kVW> x;
+  // vector k of thread t is vector k*TPB + t of the row
+  load_chunk<DT, true, AL, kVW, TPB, 1, 2, GD>(x, rw.cond, rw.uncond, 0, a.V, a.cfg_scale, a.inv_T, -INFINITY);
+  // the raw logits of x~_i, requested now and used at the very end
+  float tok_c = 0.f, tok_u = 0.f;
+  if (tok >= 0 && threadIdx.x == 0) {
+    tok_c = load_elem<DT>(rw.cond, tok);
+    if (rw.uncond) tok_u = load_elem<DT>(rw.uncond, tok);
+  }
+  float row_max;
+  const float thr = topk_threshold<kVW * kE, TPB>(x.w, a.top_k, ts, row_max);
+  const float c = fmaxf(ceilf(row_max * kLog2e), kRefFloor);
+  float s = 0.f;
+#pragma unroll
+  for (int n = 0; n < kVW * kE; ++n) {
+    const float l = __uint_as_float(x.w[n]);
+    const float e = exp2_fast(__fmaf_rn(l, kLog2e, -c));
+    s += (l >= thr) ? e : 0.f;
+  }
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  s = wave_sum(s);
+  if (lane == 0) red_s[wv] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float S = red_s[0];
+#pragma unroll
+    for (int w = 1; w < kW; ++w) S = __fadd_rn(S, red_s[w]);
+    a.part[r] = make_float2(c, S);
+    a.thr[r] = thr;
+    if (tok >= 0) {
+      const float l = transform_logit(tok_c, tok_u, rw.uncond != nullptr, a.cfg_scale, a.inv_T);
+      a.tok_logit[r] = (l >= thr) ? l : -INFINITY;
+    }
   }
 }
 
@@ -375,9 +428,6 @@ __global__ __launch_bounds__(kThreads) void accept_kernel(const KArgs a) {
 // the running mass in ascending token order is simply a prefix sum over threads.  Per thread:
 // one partial mass per vector; block-wide: one scan.  The thread whose interval contains u*R
 // finds the vector among its partials and re-evaluates that vector's elements.
-constexpr int kThreadsW = 1024;
-constexpr int kWavesW = kThreadsW / 64;
-
 struct SmemW {
   int pick[kWavesW];
   int pick_last[kWavesW];
@@ -1017,6 +1067,18 @@ static hipError_t launch_rest(const KArgs& a, hipStream_t stream);
 template <int DT, bool XF, bool AL>
 static hipError_t launch_stats_any(const KArgs& a, hipStream_t stream) {
   constexpr int kT = Vec<DT>::kT;
+  if constexpr (XF) {
+    if (a.top_k > 0) {            // whole rows, one workgroup of 1024 threads each
+      const int64_t grid = int64_t(a.rows_t) + a.rows_d;
+      if (a.tu != nullptr)
+        hipLaunchKernelGGL((row_stats_topk_kernel<DT, AL ? kAligned : kUnaligned, kThreadsK, 1>), dim3((unsigned)grid),
+                           dim3(kThreadsK), 0, stream, a);
+      else
+        hipLaunchKernelGGL((row_stats_topk_kernel<DT, AL ? kAligned : kUnaligned, kThreadsK, 0>), dim3((unsigned)grid),
+                           dim3(kThreadsK), 0, stream, a);
+      return checked("row_stats_topk_kernel");
+    }
+  }
   if (AL && a.stream_loads) {   // large read-once input: nontemporal loads
     if (a.nt1 == kT) return launch_stats<DT, XF, kAlignedStream, kT>(a, stream);
     if (a.nt1 == kT / 2) return launch_stats<DT, XF, kAlignedStream, kT / 2>(a, stream);

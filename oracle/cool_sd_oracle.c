@@ -25,7 +25,9 @@
  * outputs, exact TV vs the Theorem-2 bound, the L=1 closed form, the LP value
  * of Proposition LP, Monte-Carlo accepted length vs Eq. token_exp, schedule
  * closed forms, softmax vs scipy; the Theorem-2 diagnostics against the exact TV at
- * L = 1 and against Monte-Carlo acceptance rates.
+ * L = 1 and against Monte-Carlo acceptance rates; the LANTERN-style variant against
+ * vanilla speculative decoding at lambda = 0, the identity G* = G^van for f >= f^van
+ * (Proposition on the design of G), the exact L = 1 output law and a hand-worked row.
  *
  * Parity unpinned by the paper (fixed only by this build's readings, and
  * checked against brute-force definitions on tiny rows): the inverse-CDF
@@ -388,6 +390,200 @@ int csd_oracle_resample(int B, int V,
     }
     free(l); free(p); free(q); free(g);
     return 0;
+}
+
+/* ===========================================================================
+ * LANTERN-style relaxation by aggregation over latent neighbours (the paper's
+ * comparison system: Eq. p_lantern, Eq. f_lantern, Eq. g_lantern; its resampling
+ * law replaced by G* in the ablation "Principled Resampling Strategy").
+ *
+ * nbr is a table [V, k]: row x lists the k nearest neighbours of token x in the
+ * codebook's latent space, nearest first.  Entries that are negative or equal
+ * to x are skipped (padding / self).
+ * ========================================================================= */
+
+/* Neighbour set A^{k,lambda}(x) for the row p: x itself plus the longest prefix
+ * n_1..n_m of its neighbour list whose aggregated probability stays below
+ * lambda p(x):   sum_{j<=m} p(n_j) < lambda p(x)      (text below Eq. p_lantern).
+ * The running sum never decreases, so "longest prefix" and "stop at the first
+ * violation" are the same set.  Returns m (skipped entries are not counted) and
+ * *p_agg = sum_{y in A} p(y), the numerator of Eq. f_lantern.
+ * member (optional, int[k]) receives the selected neighbours. */
+int csd_oracle_lantern_set(const double *p, int V, int x, const int *nbr_row, int k,
+                           double lambda, double *p_agg, int *member)
+{
+    double cum = 0.0;
+    int m = 0;
+    for (int j = 0; j < k; ++j) {
+        int n = nbr_row[j];
+        if (n < 0 || n >= V || n == x) continue;
+        if (!(cum + p[n] < lambda * p[x])) break;
+        cum += p[n];
+        if (member) member[m] = n;
+        ++m;
+    }
+    *p_agg = p[x] + cum;
+    return m;
+}
+
+/* Eq. f_lantern: f^{k,lambda}(x) = min{1, sum_{y in A(x)} p(y) / q(x)}, 0/0 := 1. */
+double csd_oracle_lantern_accept_prob(const double *p, const double *q, int V, int x,
+                                      const int *nbr, int k, double lambda)
+{
+    double p_agg;
+    csd_oracle_lantern_set(p, V, x, nbr + (size_t)x * k, k, lambda, &p_agg, NULL);
+    return csd_oracle_accept_prob(p_agg, q[x], 1.0);
+}
+
+enum { CSD_RESAMPLE_LANTERN = 2 };
+
+/* Unnormalised resampling law after a rejection of the draft token x_draft.
+ *   OPT     : Eq. opt_G with f = f^{k,lambda}:  g(x) = [p(x) - q(x) f^{k,lambda}(x)]_+ for every
+ *             token x, each with its own neighbour set; q f evaluated as
+ *             min{q(x), sum_{A(x)} p} (the same number, without the quotient's rounding).
+ *   LANTERN : Eq. g_lantern: g = [P^{k,lambda} - q]_+, where P^{k,lambda} (Eq. p_lantern)
+ *             moves the probability of A(x_draft) onto x_draft: the aggregated sum at
+ *             x_draft, 0 at the other members, p elsewhere.
+ *   VANILLA : Eq. g_tsd.
+ * Returns R = sum g; falls back to g = p when R <= 0 (no rejection possible). */
+double csd_oracle_lantern_residual(const double *p, const double *q, int V, const int *nbr, int k,
+                                   double lambda, int mode, int x_draft, double *g)
+{
+    double R = 0.0;
+    if (mode == CSD_RESAMPLE_LANTERN) {
+        int *member = (int *)malloc((size_t)(k > 0 ? k : 1) * sizeof(int));
+        double p_agg;
+        int m = csd_oracle_lantern_set(p, V, x_draft, nbr + (size_t)x_draft * k, k, lambda, &p_agg, member);
+        for (int x = 0; x < V; ++x) g[x] = p[x];           /* P^{k,lambda}, third case */
+        for (int j = 0; j < m; ++j) g[member[j]] = 0.0;    /* second case */
+        g[x_draft] = p_agg;                                /* first case */
+        free(member);
+        for (int x = 0; x < V; ++x) {
+            double v = g[x] - q[x];
+            g[x] = v > 0.0 ? v : 0.0;
+            R += g[x];
+        }
+    } else {
+        for (int x = 0; x < V; ++x) {
+            double v;
+            if (mode == CSD_RESAMPLE_VANILLA) {
+                v = p[x] - q[x];
+            } else {
+                double p_agg;
+                csd_oracle_lantern_set(p, V, x, nbr + (size_t)x * k, k, lambda, &p_agg, NULL);
+                double qf = p_agg < q[x] ? p_agg : q[x];
+                v = p[x] - qf;
+            }
+            g[x] = v > 0.0 ? v : 0.0;
+            R += g[x];
+        }
+    }
+    if (!(R > 0.0)) {
+        R = 0.0;
+        for (int x = 0; x < V; ++x) { g[x] = p[x]; R += g[x]; }
+    }
+    return R;
+}
+
+/* Verification stage of Algorithm 1 with the acceptance probability of Eq. f_lantern in
+ * place of Eq. relax.  Arguments as csd_oracle_verify, without omega; nbr [V, k], lambda.
+ * Extra outputs (each optional): p_agg [B, L] = sum over A(x~_i) of p_i, count [B, L] = number
+ * of neighbours selected.  Returns 0, -1 invalid argument, -2 out of memory. */
+int csd_oracle_verify_lantern(int B, int L, int V, int has_bonus,
+                              const float *target, const float *target_uncond,
+                              long long t_sb, long long t_sl,
+                              const float *draft, const float *draft_uncond,
+                              long long d_sb, long long d_sl,
+                              float cfg_scale, float temperature, int top_k, int resample_mode,
+                              const int *draft_tokens, const int *nbr, int k, float lambda,
+                              const float *u_accept, const float *u_resample,
+                              int *accept_len, int *next_token, double *resid_mass,
+                              double *p_tok, double *q_tok, double *f_out, unsigned char *acc_out,
+                              double *p_agg_out, int *count_out, int num_threads)
+{
+    if (B < 1 || L < 1 || V < 1 || !target || !draft || !draft_tokens || !u_accept || !u_resample ||
+        !accept_len || !next_token || k < 0 || (k > 0 && !nbr) || !(lambda >= 0.0f))
+        return -1;
+    if (!(temperature > 0.0f) || top_k < 0 || top_k > V) return -1;
+    for (long long n = 0; n < (long long)B * L; ++n)
+        if (draft_tokens[n] < 0 || draft_tokens[n] >= V) return -1;
+    int status = 0;
+    int n_rows_t = L + (has_bonus ? 1 : 0);
+#ifdef _OPENMP
+    if (num_threads > 0) omp_set_num_threads(num_threads);
+#else
+    (void)num_threads;
+#endif
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        double *p = (double *)malloc((size_t)n_rows_t * V * sizeof(double));
+        double *q = (double *)malloc((size_t)L * V * sizeof(double));
+        double *g = (double *)malloc((size_t)V * sizeof(double));
+        if (!p || !q || !g) {
+#pragma omp atomic write
+            status = -2;
+            free(p); free(q); free(g);
+            continue;
+        }
+        for (int i = 1; i <= n_rows_t; ++i) {
+            const float *lc = target + (long long)b * t_sb + (long long)(i - 1) * t_sl;
+            const float *lu = target_uncond ? target_uncond + (long long)b * t_sb + (long long)(i - 1) * t_sl : NULL;
+            csd_oracle_transform_row(lc, lu, V, cfg_scale, temperature, top_k, g);
+            csd_oracle_softmax(g, V, p + (size_t)(i - 1) * V);
+        }
+        for (int i = 1; i <= L; ++i) {
+            const float *lc = draft + (long long)b * d_sb + (long long)(i - 1) * d_sl;
+            const float *lu = draft_uncond ? draft_uncond + (long long)b * d_sb + (long long)(i - 1) * d_sl : NULL;
+            csd_oracle_transform_row(lc, lu, V, cfg_scale, temperature, top_k, g);
+            csd_oracle_softmax(g, V, q + (size_t)(i - 1) * V);
+        }
+        /* row-wise quantities of every position */
+        for (int i = 1; i <= L; ++i) {
+            long long o = (long long)b * L + (i - 1);
+            int x = draft_tokens[o];
+            const double *p_i = p + (size_t)(i - 1) * V, *q_i = q + (size_t)(i - 1) * V;
+            double pa;
+            int m = csd_oracle_lantern_set(p_i, V, x, nbr + (size_t)x * k, k, (double)lambda, &pa, NULL);
+            double f = csd_oracle_accept_prob(pa, q_i[x], 1.0);
+            if (p_tok) p_tok[o] = p_i[x];
+            if (q_tok) q_tok[o] = q_i[x];
+            if (f_out) f_out[o] = f;
+            if (acc_out) acc_out[o] = (unsigned char)((double)u_accept[o] <= f);
+            if (p_agg_out) p_agg_out[o] = pa;
+            if (count_out) count_out[o] = m;
+        }
+        /* Algorithm 1, the for-loop with its break */
+        int tau = 0, x_next = -1, rejected = 0;
+        double R = 0.0;
+        for (int i = 1; i <= L; ++i) {
+            long long o = (long long)b * L + (i - 1);
+            int x = draft_tokens[o];
+            const double *p_i = p + (size_t)(i - 1) * V, *q_i = q + (size_t)(i - 1) * V;
+            double f = csd_oracle_lantern_accept_prob(p_i, q_i, V, x, nbr, k, (double)lambda);
+            if ((double)u_accept[o] <= f) {
+                tau = i;
+            } else {
+                R = csd_oracle_lantern_residual(p_i, q_i, V, nbr, k, (double)lambda, resample_mode, x, g);
+                x_next = csd_oracle_inverse_cdf(g, V, (double)u_resample[b] * R);
+                rejected = 1;
+                break;
+            }
+        }
+        if (!rejected) {
+            if (has_bonus) {
+                R = csd_oracle_residual(p + (size_t)L * V, NULL, V, 1.0, CSD_RESAMPLE_OPT, g);
+                x_next = csd_oracle_inverse_cdf(g, V, (double)u_resample[b] * R);
+            } else {
+                x_next = -1;
+                R = 0.0;
+            }
+        }
+        accept_len[b] = tau;
+        next_token[b] = x_next;
+        if (resid_mass) resid_mass[b] = R;
+        free(p); free(q); free(g);
+    }
+    return status;
 }
 
 int csd_oracle_max_threads(void)

@@ -7,11 +7,23 @@ namespace csd {
 
 // Everything a kernel needs, passed by value.  Pointers are device pointers.
 struct KArgs {
+  // --- what the statistics kernels read, kept together at the front (two cache lines of the
+  //     kernel-argument segment instead of five)
   const void* t;            // target logits (conditional)
   const void* tu;           // target unconditional logits or nullptr
   const void* d;            // draft logits (nullptr: stand-alone resample from p)
   const void* du;           // draft unconditional logits or nullptr
   const int32_t* tokens;    // [B, L]
+  float2* part;             // workspace [rows_t + rows_d, c1]  (reference exponent, sum) of every statistics chunk
+  float* tok_logit;         // workspace [rows_t + rows_d]      transformed logit of the row's draft token x~_i
+  float* thr;               // workspace [rows_t + rows_d]      top-k threshold of every row (top_k > 0)
+  int64_t t_sb, t_sl, d_sb, d_sl;          // element strides
+  int32_t B, L, V, has_bonus;
+  int32_t rows_t, rows_d;   // target rows B*(L+has_bonus), draft rows B*L (0: no draft)
+  int32_t c1, top_k;        // statistics chunks per row; top-k (0 = off)
+  float cfg_scale, inv_T;
+  // --- the rest
+  int64_t om_sb;
   const float* omega;       // [L] or [B, L]
   const float* u_acc;       // [B, L]
   const float* u_res;       // [B]
@@ -21,20 +33,13 @@ struct KArgs {
   float* q_tok;
   float* f;
   float* resid_mass;        // [B] or nullptr
-  int64_t t_sb, t_sl, d_sb, d_sl, om_sb;   // element strides
-  int32_t B, L, V, has_bonus, top_k, resample_mode, resample_only, aligned;
+  int32_t resample_mode, resample_only, aligned;
   int32_t stats_only;       // benchmark: launch row_stats_kernel only
   int32_t early_exit;       // verify: stop reading a sequence's rows at its first rejection (one kernel)
   int32_t stream_loads;     // statistics kernel: input larger than the caches, use nontemporal loads
   int32_t nchunks, nt2;     // sampling kernel: chunks per row, tiles per chunk
-  int32_t rows_t, rows_d;   // target rows B*(L+has_bonus), draft rows B*L (0: no draft)
-  int32_t nt1, chunk1, c1;  // statistics kernel: tiles per chunk, logits per chunk, chunks per row
-  float cfg_scale, inv_T;
-  // workspace
-  float2* part;             // [rows_t + rows_d, c1]  (reference exponent, sum) of every statistics chunk
-  float* thr;               // [rows_t + rows_d]      top-k threshold of every row (top_k > 0)
-  float* tok_logit;         // [rows_t + rows_d]      transformed logit of the row's draft token x~_i
-  float2* rowstat;          // [rows_t + rows_d]      combined statistics (written only when c1 > 4)
+  int32_t nt1, chunk1;      // statistics kernel: tiles per chunk, logits per chunk
+  float2* rowstat;          // workspace [rows_t + rows_d]      combined statistics (written only when c1 > 4)
   const float2* stat;       // what the sequence kernel reads: part (cs = c1 <= 4) or rowstat (cs = 1)
   int32_t cs;
   float4* seq_stat;         // [B]           statistics of the sampled row (several-chunk path)

@@ -61,19 +61,31 @@ __device__ __forceinline__ const char* row_ptr(const void* base, int64_t elem_of
 // Softmax statistics of one chunk of one row.  Rows are numbered: target rows first
 // (b*(L+has_bonus) + i), then draft rows (rows_t + b*L + i).
 struct RowRef {
-  int b, i;
+  int r, b, i;
   bool is_draft;
   const char* cond;
   const char* uncond;
 };
-template <int DT> __device__ __forceinline__ RowRef row_ref(const KArgs& a, int r) {
+// Which row a workgroup of a statistics kernel works on.  G3: the grid is (chunks, rows of one
+// sequence -- target rows, then draft rows --, sequences), so no division is needed; otherwise
+// the row number is `lin` (used when a grid dimension would exceed 65535).
+template <int DT, bool G3> __device__ __forceinline__ RowRef row_ref(const KArgs& a, int lin) {
   constexpr int kES = Vec<DT>::kES;
   RowRef o;
-  o.is_draft = r >= a.rows_t;
-  const int rr = o.is_draft ? r - a.rows_t : r;
-  const int per = o.is_draft ? a.L : a.L + a.has_bonus;
-  o.b = rr / per;
-  o.i = rr - o.b * per;
+  const int per_t = a.L + a.has_bonus;
+  if (G3) {
+    o.b = blockIdx.z;
+    o.is_draft = (int)blockIdx.y >= per_t;
+    o.i = o.is_draft ? blockIdx.y - per_t : blockIdx.y;
+    o.r = o.is_draft ? a.rows_t + o.b * a.L + o.i : o.b * per_t + o.i;
+  } else {
+    o.r = lin;
+    o.is_draft = lin >= a.rows_t;
+    const int rr = o.is_draft ? lin - a.rows_t : lin;
+    const int per = o.is_draft ? a.L : per_t;
+    o.b = rr / per;
+    o.i = rr - o.b * per;
+  }
   const int64_t off = o.is_draft ? int64_t(o.b) * a.d_sb + int64_t(o.i) * a.d_sl
                                  : int64_t(o.b) * a.t_sb + int64_t(o.i) * a.t_sl;
   o.cond = row_ptr(o.is_draft ? a.d : a.t, off, kES);
@@ -81,21 +93,29 @@ template <int DT> __device__ __forceinline__ RowRef row_ref(const KArgs& a, int 
   return o;
 }
 
-template <int DT, bool XF, int AL, int NT>
+// The draft token x~_i of a row (or -1), fetched with a per-lane load: a load from an address
+// the compiler can prove uniform would go through the scalar cache and the wait for it would
+// also hold back the chunk's vector loads that follow in program order.
+__device__ __forceinline__ int load_draft_token(const KArgs& a, const RowRef& rw) {
+  if (a.tokens == nullptr || rw.i >= a.L) return -1;
+  int z = 0;
+  asm volatile("" : "+v"(z));
+  return a.tokens[int64_t(rw.b) * a.L + rw.i + z];
+}
+
+template <int DT, bool XF, int AL, int NT, bool G3>
 __global__ __launch_bounds__(kThreads, 3) void row_stats_kernel(const KArgs a) {
   constexpr int kE = Vec<DT>::kE;
   __shared__ float red_c[kWaves], red_s[kWaves];
   const int C1 = a.c1;
-  const int r = blockIdx.x / C1, c = blockIdx.x - r * C1;
-  const RowRef rw = row_ref<DT>(a, r);
+  const int lin = G3 ? 0 : blockIdx.x / C1, c = G3 ? blockIdx.x : blockIdx.x - lin * C1;
+  const RowRef rw = row_ref<DT, G3>(a, lin);
+  const int r = rw.r;
   const int64_t base = int64_t(c) * (NT * kThreads * kE);
-  // the draft token x~_i of this row, if this chunk holds it: requested before the chunk's loads
-  // so that its latency hides behind theirs
-  int tok = -1;
-  if (a.tokens != nullptr && rw.i < a.L) tok = a.tokens[int64_t(rw.b) * a.L + rw.i];
 
   RowRegs<DT, XF, NT> x;
   load_chunk<DT, XF, AL, NT>(x, rw.cond, rw.uncond, base, a.V, a.cfg_scale, a.inv_T, -INFINITY);
+  int tok = load_draft_token(a, rw);     // after the chunk's loads in program order, used after them
   // the (transformed) logit of x~_i for the accept test of the next kernel, taken from the
   // registers of the thread that holds it: element e of vector (tile k, thread t) is token
   // base + (k*256 + t)*kE + e
@@ -142,24 +162,24 @@ __global__ __launch_bounds__(kThreads, 3) void row_stats_kernel(const KArgs a) {
 // issue, so the code is kept lean and the row is spread over enough threads that several rows
 // fit a compute unit.
 constexpr int kThreadsK = 512;
-template <int DT, int AL, int TPB, int GD>
+template <int DT, int AL, int TPB, int GD, bool G3>
 __global__ __launch_bounds__(TPB, 6) void row_stats_topk_kernel(const KArgs a) {
   constexpr int kE = Vec<DT>::kE;
   constexpr int kVW = kChunk / (TPB * kE);             // vectors per thread
   constexpr int kW = TPB / 64;
   __shared__ TopkSmem<TPB> ts;
   __shared__ float red_s[kW];
-  const int r = blockIdx.x;
-  const RowRef rw = row_ref<DT>(a, r);
-  int tok = -1;
-  if (a.tokens != nullptr && rw.i < a.L) tok = min(max(a.tokens[int64_t(rw.b) * a.L + rw.i], 0), a.V - 1);
+  const RowRef rw = row_ref<DT, G3>(a, blockIdx.x);
+  const int r = rw.r;
   topk_prepare(ts);                                     // the barrier inside topk_threshold orders it
   RowRegs<DT, true, kVW> x;
   // vector k of thread t is vector k*TPB + t of the row
   load_chunk<DT, true, AL, kVW, TPB, 1, 2, GD>(x, rw.cond, rw.uncond, 0, a.V, a.cfg_scale, a.inv_T, -INFINITY);
   // the raw logits of x~_i, requested now and used at the very end
+  int tok = load_draft_token(a, rw);
   float tok_c = 0.f, tok_u = 0.f;
   if (tok >= 0 && threadIdx.x == 0) {
+    tok = min(tok, a.V - 1);
     tok_c = load_elem<DT>(rw.cond, tok);
     if (rw.uncond) tok_u = load_elem<DT>(rw.uncond, tok);
   }
@@ -1053,10 +1073,25 @@ static hipError_t checked(const char* what) {
   return e;
 }
 
+// Grid of a statistics kernel: (chunks, rows of one sequence, sequences) when the dimensions
+// allow it, else one dimension.
+static bool stats_grid3(const KArgs& a, dim3& grid) {
+  const int64_t per_seq = int64_t(a.L) + a.has_bonus + (a.rows_d ? a.L : 0);
+  if (a.B <= 65535 && per_seq <= 65535) {
+    grid = dim3((unsigned)a.c1, (unsigned)per_seq, (unsigned)a.B);
+    return true;
+  }
+  grid = dim3((unsigned)((int64_t(a.rows_t) + a.rows_d) * a.c1));
+  return false;
+}
+
 template <int DT, bool XF, int AL, int NT>
 static hipError_t launch_stats(const KArgs& a, hipStream_t stream) {
-  const int64_t grid = (int64_t(a.rows_t) + a.rows_d) * a.c1;
-  hipLaunchKernelGGL((row_stats_kernel<DT, XF, AL, NT>), dim3((unsigned)grid), dim3(kThreads), 0, stream, a);
+  dim3 grid;
+  if (stats_grid3(a, grid))
+    hipLaunchKernelGGL((row_stats_kernel<DT, XF, AL, NT, true>), grid, dim3(kThreads), 0, stream, a);
+  else
+    hipLaunchKernelGGL((row_stats_kernel<DT, XF, AL, NT, false>), grid, dim3(kThreads), 0, stream, a);
   return checked("row_stats_kernel");
 }
 
@@ -1068,14 +1103,15 @@ template <int DT, bool XF, bool AL>
 static hipError_t launch_stats_any(const KArgs& a, hipStream_t stream) {
   constexpr int kT = Vec<DT>::kT;
   if constexpr (XF) {
-    if (a.top_k > 0) {            // whole rows, one workgroup of 1024 threads each
-      const int64_t grid = int64_t(a.rows_t) + a.rows_d;
-      if (a.tu != nullptr)
-        hipLaunchKernelGGL((row_stats_topk_kernel<DT, AL ? kAligned : kUnaligned, kThreadsK, 1>), dim3((unsigned)grid),
-                           dim3(kThreadsK), 0, stream, a);
-      else
-        hipLaunchKernelGGL((row_stats_topk_kernel<DT, AL ? kAligned : kUnaligned, kThreadsK, 0>), dim3((unsigned)grid),
-                           dim3(kThreadsK), 0, stream, a);
+    if (a.top_k > 0) {            // whole rows (c1 = 1), one workgroup each
+      constexpr int kA = AL ? kAligned : kUnaligned;
+      dim3 grid;
+      const bool g3 = stats_grid3(a, grid);
+      const bool guided = a.tu != nullptr;
+      if (g3 && guided) hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsK, 1, true>), grid, dim3(kThreadsK), 0, stream, a);
+      else if (g3) hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsK, 0, true>), grid, dim3(kThreadsK), 0, stream, a);
+      else if (guided) hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsK, 1, false>), grid, dim3(kThreadsK), 0, stream, a);
+      else hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsK, 0, false>), grid, dim3(kThreadsK), 0, stream, a);
       return checked("row_stats_topk_kernel");
     }
   }

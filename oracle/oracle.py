@@ -12,7 +12,7 @@ import numpy as np
 from . import build as _build
 
 SCHED_UNIFORM, SCHED_EXP, SCHED_LINEAR = 0, 1, 2
-RESAMPLE_OPT, RESAMPLE_VANILLA = 0, 1
+RESAMPLE_OPT, RESAMPLE_VANILLA, RESAMPLE_LANTERN = 0, 1, 2
 
 _lib = None
 
@@ -54,6 +54,20 @@ def lib():
             C.c_int, C.c_int, fp, fp, C.c_longlong, fp, fp, C.c_longlong,
             C.c_float, C.c_float, C.c_int, C.c_int, fp, fp, ip, dp, dp]
         L.csd_oracle_resample.restype = C.c_int
+        L.csd_oracle_lantern_set.argtypes = [dp, C.c_int, C.c_int, ip, C.c_int, C.c_double, dp, ip]
+        L.csd_oracle_lantern_set.restype = C.c_int
+        L.csd_oracle_lantern_accept_prob.argtypes = [dp, dp, C.c_int, C.c_int, ip, C.c_int, C.c_double]
+        L.csd_oracle_lantern_accept_prob.restype = C.c_double
+        L.csd_oracle_lantern_residual.argtypes = [dp, dp, C.c_int, ip, C.c_int, C.c_double, C.c_int, C.c_int, dp]
+        L.csd_oracle_lantern_residual.restype = C.c_double
+        L.csd_oracle_verify_lantern.argtypes = [
+            C.c_int, C.c_int, C.c_int, C.c_int,
+            fp, fp, C.c_longlong, C.c_longlong,
+            fp, fp, C.c_longlong, C.c_longlong,
+            C.c_float, C.c_float, C.c_int, C.c_int,
+            ip, ip, C.c_int, C.c_float, fp, fp,
+            ip, ip, dp, dp, dp, dp, u8p, dp, ip, C.c_int]
+        L.csd_oracle_verify_lantern.restype = C.c_int
         L.csd_oracle_max_threads.argtypes = []
         L.csd_oracle_max_threads.restype = C.c_int
         _lib = L
@@ -204,6 +218,79 @@ def resample(target_rows, draft_rows, omega_rows, u, *, target_uncond=None, draf
     if rc != 0:
         raise ValueError("csd_oracle_resample rc=%d" % rc)
     return (token, mass, g) if want_g else (token, mass)
+
+
+def _nbr(nbr, V):
+    nbr = np.ascontiguousarray(nbr, dtype=np.int32)
+    assert nbr.ndim == 2 and nbr.shape[0] == V
+    return nbr
+
+
+def lantern_set(p, x, nbr_row, lam):
+    """Neighbour set of token x under the row p: (m, aggregated probability, selected neighbours)."""
+    p = np.ascontiguousarray(p, dtype=np.float64)
+    row = np.ascontiguousarray(nbr_row, dtype=np.int32)
+    agg = np.empty(1, np.float64)
+    member = np.empty(max(1, row.shape[0]), np.int32)
+    m = lib().csd_oracle_lantern_set(_ptr(p, C.c_double), p.shape[0], int(x), _ptr(row, C.c_int), row.shape[0],
+                                     float(lam), _ptr(agg, C.c_double), _ptr(member, C.c_int))
+    return m, float(agg[0]), member[:m].copy()
+
+
+def lantern_accept_prob(p, q, x, nbr, lam):
+    p = np.ascontiguousarray(p, dtype=np.float64)
+    q = np.ascontiguousarray(q, dtype=np.float64)
+    nbr = _nbr(nbr, p.shape[0])
+    return lib().csd_oracle_lantern_accept_prob(_ptr(p, C.c_double), _ptr(q, C.c_double), p.shape[0], int(x),
+                                                _ptr(nbr, C.c_int), nbr.shape[1], float(lam))
+
+
+def lantern_residual(p, q, nbr, lam, mode, x_draft):
+    """Unnormalised resampling law g and its mass R after the draft token x_draft was rejected."""
+    p = np.ascontiguousarray(p, dtype=np.float64)
+    q = np.ascontiguousarray(q, dtype=np.float64)
+    nbr = _nbr(nbr, p.shape[0])
+    g = np.empty_like(p)
+    R = lib().csd_oracle_lantern_residual(_ptr(p, C.c_double), _ptr(q, C.c_double), p.shape[0], _ptr(nbr, C.c_int),
+                                          nbr.shape[1], float(lam), mode, int(x_draft), _ptr(g, C.c_double))
+    return g, R
+
+
+def verify_lantern(target, draft, draft_tokens, nbr, lam, u_accept, u_resample, *, target_uncond=None,
+                   draft_uncond=None, cfg_scale=1.0, temperature=1.0, top_k=0,
+                   resample_mode=RESAMPLE_OPT, num_threads=1):
+    """Algorithm 1's verification stage with the aggregated acceptance probability (Eq. f_lantern).
+
+    Returns the dict of verify() plus p_agg[B, L] and count[B, L]."""
+    t, d = _f32(target), _f32(draft)
+    tu, du = _f32(target_uncond), _f32(draft_uncond)
+    B, Lt, V = t.shape
+    L = d.shape[1]
+    assert d.shape == (B, L, V) and Lt in (L, L + 1)
+    assert (tu is None) == (du is None) and (tu is None or (tu.shape == t.shape and du.shape == d.shape))
+    has_bonus = int(Lt == L + 1)
+    tok = np.ascontiguousarray(draft_tokens, dtype=np.int32).reshape(B, L)
+    nbr = _nbr(nbr, V)
+    ua = _f32(u_accept).reshape(B, L)
+    ur = _f32(u_resample).reshape(B)
+    out = dict(accept_len=np.empty(B, np.int32), next_token=np.empty(B, np.int32),
+               resid_mass=np.empty(B, np.float64), p_tok=np.empty((B, L), np.float64),
+               q_tok=np.empty((B, L), np.float64), f=np.empty((B, L), np.float64),
+               acc=np.empty((B, L), np.uint8), p_agg=np.empty((B, L), np.float64),
+               count=np.empty((B, L), np.int32))
+    rc = lib().csd_oracle_verify_lantern(
+        B, L, V, has_bonus,
+        _ptr(t, C.c_float), _ptr(tu, C.c_float), Lt * V, V,
+        _ptr(d, C.c_float), _ptr(du, C.c_float), L * V, V,
+        cfg_scale, temperature, top_k, resample_mode,
+        _ptr(tok, C.c_int), _ptr(nbr, C.c_int), nbr.shape[1], float(lam), _ptr(ua, C.c_float), _ptr(ur, C.c_float),
+        _ptr(out["accept_len"], C.c_int), _ptr(out["next_token"], C.c_int),
+        _ptr(out["resid_mass"], C.c_double), _ptr(out["p_tok"], C.c_double),
+        _ptr(out["q_tok"], C.c_double), _ptr(out["f"], C.c_double),
+        _ptr(out["acc"], C.c_ubyte), _ptr(out["p_agg"], C.c_double), _ptr(out["count"], C.c_int), num_threads)
+    if rc != 0:
+        raise ValueError("csd_oracle_verify_lantern rc=%d" % rc)
+    return out
 
 
 def max_threads():

@@ -49,8 +49,10 @@ typedef enum {
 } cool_sd_sched;
 
 typedef enum {
-  COOL_SD_RESAMPLE_OPT = 0,    /* G* = Norm([p - min(q, omega p)]_+)       (Eq. opt_G) */
-  COOL_SD_RESAMPLE_VANILLA = 1 /* G^van = Norm([p - q]_+)                  (Eq. g_tsd) */
+  COOL_SD_RESAMPLE_OPT = 0,     /* G* = Norm([p - min(q, omega p)]_+)       (Eq. opt_G) */
+  COOL_SD_RESAMPLE_VANILLA = 1, /* G^van = Norm([p - q]_+)                  (Eq. g_tsd) */
+  COOL_SD_RESAMPLE_LANTERN = 2  /* Norm([P^{k,lambda} - q]_+)               (Eq. g_lantern);
+                                   cool_sd_verify_lantern only */
 } cool_sd_resample_mode;
 
 typedef enum {
@@ -104,7 +106,7 @@ typedef struct {
  * negative weight). */
 int cool_sd_schedule(int32_t kind, int32_t L, float delta, float param, float* omega_out);
 
-/* Bytes of device workspace cool_sd_verify / cool_sd_resample / cool_sd_diagnostics need for these params
+/* Bytes of device workspace cool_sd_verify / cool_sd_verify_lantern / cool_sd_resample / cool_sd_diagnostics need for these params
  * (for resample only B, V, dtype and top_k matter).  0 on invalid params. */
 size_t cool_sd_workspace_bytes(const cool_sd_params* p);
 
@@ -142,6 +144,43 @@ int cool_sd_verify(const cool_sd_params* p,
                    float* resid_mass_dev,
                    void* workspace_dev, size_t workspace_bytes,
                    void* hip_stream);
+
+/* Verification stage of Algorithm 1 with the acceptance probability of the LANTERN family in
+ * place of Eq. relax (the paper's comparison system, Eq. p_lantern / Eq. f_lantern, and its
+ * ablation "LANTERN++ with G*"):
+ *   A(x~_i)  = {x~_i} and the longest prefix n_1..n_m of x~_i's neighbour list, nearest first,
+ *              with p_i(n_1) + ... + p_i(n_m) < lambda p_i(x~_i)
+ *   f_i      = min{1, sum_{y in A(x~_i)} p_i(y) / q_i(x~_i)}, 0/0 := 1          (Eq. f_lantern)
+ * and x_{tau+1} drawn, by p->resample_mode, from
+ *   OPT      G* of Eq. opt_G for this f.  Because f_i >= f_i^van, G* equals Norm([p - q]_+)
+ *            (Proposition on the design of G), which is what is evaluated;
+ *   VANILLA  Norm([p - q]_+)                                                    (Eq. g_tsd)
+ *   LANTERN  Norm([P^{k,lambda} - q]_+): the probability of A(x~_{tau+1}) moved onto x~_{tau+1}
+ *            (Eq. p_lantern, Eq. g_lantern); rows of at most 16384 logits, else
+ *            COOL_SD_EUNSUPPORTED.
+ *   neighbors_dev  int32 [V, k], row x = the k nearest neighbours of token x in the codebook's
+ *                  latent space, nearest first; entries < 0, >= V or equal to x are skipped;
+ *                  the remaining entries of a row must be distinct.  1 <= k <= 65536
+ *   lambda         >= 0, finite
+ *   p_agg_dev      out float [B, L], optional: sum_{y in A(x~_i)} p_i(y)
+ *   count_dev      out int32 [B, L], optional: m, the neighbours taken into A(x~_i)
+ * Everything else as in cool_sd_verify (there is no omega; COOL_SD_FLAG_EARLY_EXIT is ignored).
+ * The set is decided from fp32 weights p_i(n)/p_i(x~_i); a running sum within rounding of
+ * lambda may fall on either side. */
+int cool_sd_verify_lantern(const cool_sd_params* p,
+                           const void* target_dev, const void* target_uncond_dev,
+                           const void* draft_dev, const void* draft_uncond_dev,
+                           const int32_t* draft_tokens_dev,
+                           const int32_t* neighbors_dev, int32_t k, float lambda,
+                           const float* u_accept_dev,
+                           const float* u_resample_dev,
+                           int32_t* accept_len_dev,
+                           int32_t* next_token_dev,
+                           float* p_tok_dev, float* q_tok_dev, float* f_dev,
+                           float* resid_mass_dev,
+                           float* p_agg_dev, int32_t* count_dev,
+                           void* workspace_dev, size_t workspace_bytes,
+                           void* hip_stream);
 
 /* Stand-alone resampling step (Eq. opt_G / Eq. g_tsd): one (target, draft) row pair per
  * sequence.  p->L, strides_l and has_bonus are ignored; rows are [B, V] with element strides

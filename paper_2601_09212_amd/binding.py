@@ -11,7 +11,7 @@ import numpy as np
 
 COOL_SD_F32, COOL_SD_BF16 = 0, 1
 COOL_SD_SCHED_UNIFORM, COOL_SD_SCHED_EXP, COOL_SD_SCHED_LINEAR = 0, 1, 2
-COOL_SD_RESAMPLE_OPT, COOL_SD_RESAMPLE_VANILLA = 0, 1
+COOL_SD_RESAMPLE_OPT, COOL_SD_RESAMPLE_VANILLA, COOL_SD_RESAMPLE_LANTERN = 0, 1, 2
 COOL_SD_FLAG_EARLY_EXIT = 1
 COOL_SD_OK, COOL_SD_EINVAL, COOL_SD_EWORKSPACE, COOL_SD_ELAUNCH, COOL_SD_EUNSUPPORTED = 0, -1, -2, -3, -4
 
@@ -58,6 +58,9 @@ def lib():
         L.cool_sd_workspace_init.restype = C.c_int
         L.cool_sd_verify.argtypes = [pp] + [vp] * 14 + [vp, C.c_size_t, vp]
         L.cool_sd_verify.restype = C.c_int
+        L.cool_sd_verify_lantern.argtypes = ([pp] + [vp] * 6 + [C.c_int32, C.c_float] + [vp] * 10
+                                             + [vp, C.c_size_t, vp])
+        L.cool_sd_verify_lantern.restype = C.c_int
         L.cool_sd_resample.argtypes = [pp] + [vp] * 8 + [vp, C.c_size_t, vp]
         L.cool_sd_resample.restype = C.c_int
         L.cool_sd_diagnostics.argtypes = [pp] + [vp] * 7 + [vp, C.c_size_t, vp]
@@ -118,6 +121,21 @@ def cool_sd_verify(params, target, target_uncond, draft, draft_uncond, draft_tok
                               _stream(stream))
     if check and rc != 0:
         raise CoolSDError(rc, "cool_sd_verify")
+    return rc
+
+
+def cool_sd_verify_lantern(params, target, target_uncond, draft, draft_uncond, draft_tokens, neighbors, k, lam,
+                           u_accept, u_resample, accept_len, next_token, p_tok, q_tok, f, resid_mass, p_agg,
+                           count, workspace, stream=None, check=True):
+    rc = lib().cool_sd_verify_lantern(C.byref(params), _ptr(target), _ptr(target_uncond), _ptr(draft),
+                                      _ptr(draft_uncond), _ptr(draft_tokens), _ptr(neighbors), int(k), float(lam),
+                                      _ptr(u_accept), _ptr(u_resample), _ptr(accept_len), _ptr(next_token),
+                                      _ptr(p_tok), _ptr(q_tok), _ptr(f), _ptr(resid_mass), _ptr(p_agg),
+                                      _ptr(count), _ptr(workspace),
+                                      0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                      _stream(stream))
+    if check and rc != 0:
+        raise CoolSDError(rc, "cool_sd_verify_lantern")
     return rc
 
 
@@ -196,6 +214,29 @@ def verify_workload(w, omega, *, resample_mode=COOL_SD_RESAMPLE_OPT, workspace=N
     cool_sd_verify(params, w.target, w.target_uncond, w.draft, w.draft_uncond, w.draft_tokens, omega,
                    w.u_accept, w.u_resample, out["accept_len"], out["next_token"], out.get("p_tok"),
                    out.get("q_tok"), out.get("f"), out["resid_mass"], workspace)
+    return out
+
+
+def verify_lantern_workload(w, neighbors, lam, *, resample_mode=COOL_SD_RESAMPLE_OPT, workspace=None):
+    """Allocate outputs, call cool_sd_verify_lantern once ([V, k] int32 neighbour table on the device)."""
+    import torch
+    dev = w.target.device
+    params = make_params(w.target, w.draft, top_k=w.top_k, cfg_scale=w.cfg_scale, temperature=w.temperature,
+                         resample_mode=resample_mode)
+    if workspace is None:
+        workspace = torch.empty(max(cool_sd_workspace_bytes(params), 256), dtype=torch.uint8, device=dev)
+    B, L = w.B, w.L
+    out = dict(accept_len=torch.full((B,), -7, dtype=torch.int32, device=dev),
+               next_token=torch.full((B,), -7, dtype=torch.int32, device=dev),
+               resid_mass=torch.full((B,), float("nan"), dtype=torch.float32, device=dev),
+               count=torch.full((B, L), -7, dtype=torch.int32, device=dev))
+    for key in ("p_tok", "q_tok", "f", "p_agg"):
+        out[key] = torch.full((B, L), float("nan"), dtype=torch.float32, device=dev)
+    assert neighbors.dtype == torch.int32 and neighbors.is_contiguous() and neighbors.shape[0] == w.V
+    cool_sd_verify_lantern(params, w.target, w.target_uncond, w.draft, w.draft_uncond, w.draft_tokens, neighbors,
+                           neighbors.shape[1], lam, w.u_accept, w.u_resample, out["accept_len"], out["next_token"],
+                           out["p_tok"], out["q_tok"], out["f"], out["resid_mass"], out["p_agg"], out["count"],
+                           workspace)
     return out
 
 

@@ -14,12 +14,23 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t seq_stat, chunk_R, thr, tok_logit, rowstat, part, diag_part, total;
+  size_t seq_stat, chunk_R, thr, tok_logit, rowstat, part, diag_part, lan, total;
+};
+
+// cool_sd_verify_lantern only
+struct LanternArgs {
+  const int32_t* nbr;
+  int32_t k;
+  float lambda;
+  float* p_agg;
+  int32_t* count;
 };
 
 // rows: all logit rows (target + draft); c1: statistics chunks per row; C: sampling chunks per row.
 // pairs x CD: (alpha, beta) chunk sums of the diagnostics call (0 pairs: region absent).
-Layout make_layout(int64_t B, int64_t rows, int64_t c1, int64_t C, int64_t pairs = 0, int64_t CD = 0) {
+// lan_pairs: B L of a call with neighbour aggregation (its omega and member counts), else 0.
+Layout make_layout(int64_t B, int64_t rows, int64_t c1, int64_t C, int64_t pairs = 0, int64_t CD = 0,
+                   int64_t lan_pairs = 0) {
   Layout o{};
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes); return at; };
@@ -30,6 +41,7 @@ Layout make_layout(int64_t B, int64_t rows, int64_t c1, int64_t C, int64_t pairs
   o.rowstat = take(size_t(rows) * 8);
   o.part = take(size_t(rows) * c1 * 8);
   o.diag_part = take(size_t(pairs) * CD * 8);
+  o.lan = take(size_t(lan_pairs) * 8);
   o.total = off;
   return o;
 }
@@ -56,7 +68,7 @@ Chunking pick_chunking(const cool_sd_params* p, int64_t rows) {
 }
 
 
-bool params_ok(const cool_sd_params* p, bool for_resample) {
+bool params_ok(const cool_sd_params* p, bool for_resample, bool lantern = false) {
   if (!p) return false;
   if (p->B < 1 || p->V < 1) return false;
   if (!for_resample && (p->L < 1 || p->L > 4096)) return false;
@@ -67,7 +79,9 @@ bool params_ok(const cool_sd_params* p, bool for_resample) {
   if (p->top_k < 0 || p->top_k > p->V) return false;
   if (!(p->temperature > 0.f) || !isfinite(p->temperature)) return false;
   if (!isfinite(p->cfg_scale)) return false;
-  if (p->resample_mode != COOL_SD_RESAMPLE_OPT && p->resample_mode != COOL_SD_RESAMPLE_VANILLA) return false;
+  if (p->resample_mode != COOL_SD_RESAMPLE_OPT && p->resample_mode != COOL_SD_RESAMPLE_VANILLA &&
+      !(lantern && p->resample_mode == COOL_SD_RESAMPLE_LANTERN))
+    return false;
   if ((p->flags & ~COOL_SD_FLAG_EARLY_EXIT) != 0) return false;
   const int64_t L = for_resample ? 1 : p->L;
   const int64_t rows = for_resample ? p->B : int64_t(p->B) * (L + p->has_bonus);
@@ -87,15 +101,16 @@ int run(const cool_sd_params* p, bool resample_only,
         const void* t, const void* tu, const void* d, const void* du,
         const int32_t* tokens, const float* omega, const float* u_acc, const float* u_res,
         int32_t* accept_len, int32_t* next_token, float* p_tok, float* q_tok, float* f,
-        float* resid_mass, void* ws, size_t ws_bytes, void* stream) {
+        float* resid_mass, void* ws, size_t ws_bytes, void* stream, const LanternArgs* lan = nullptr) {
   const int64_t L = resample_only ? 1 : p->L;
   const int hb = resample_only ? 0 : p->has_bonus;
   const int64_t rows = resample_only ? p->B : int64_t(p->B) * (L + hb);
   if (p->top_k > 0 && p->V > csd::kChunk) return COOL_SD_EUNSUPPORTED;
+  if (lan && p->resample_mode == COOL_SD_RESAMPLE_LANTERN && p->V > csd::kChunk) return COOL_SD_EUNSUPPORTED;
   const int64_t rows_t = rows, rows_d = d ? int64_t(p->B) * L : 0;
   const Chunking ch = pick_chunking(p, rows_t + rows_d);
   const int64_t C = ch.c2;
-  const Layout lay = make_layout(p->B, rows_t + rows_d, ch.c1, C);
+  const Layout lay = make_layout(p->B, rows_t + rows_d, ch.c1, C, 0, 0, lan ? int64_t(p->B) * L : 0);
   if (!ws || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0 || ws_bytes < lay.total) return COOL_SD_EWORKSPACE;
 
   const int kE = (p->dtype == COOL_SD_BF16) ? 8 : 4;
@@ -123,8 +138,21 @@ int run(const cool_sd_params* p, bool resample_only,
   a.resample_only = resample_only ? 1 : 0;
   a.aligned = aligned ? 1 : 0;
   a.stats_only = g_stats_only ? 1 : 0;
-  a.early_exit = (!resample_only && aligned && (p->flags & COOL_SD_FLAG_EARLY_EXIT) && p->top_k == 0 && p->V <= csd::kChunk &&
-                  p->L <= 1024) ? 1 : 0;
+  a.early_exit = (!resample_only && !lan && aligned && (p->flags & COOL_SD_FLAG_EARLY_EXIT) && p->top_k == 0 &&
+                  p->V <= csd::kChunk && p->L <= 1024) ? 1 : 0;
+  if (lan) {
+    // Eq. f_lantern is Eq. relax with a data-dependent omega_i >= 1 that lantern_agg_kernel leaves
+    // in the workspace; with f >= f^van the optimal law G* is [p - q]_+ (Proposition on the design
+    // of G), so OPT runs the vanilla residual
+    a.nbr = lan->nbr; a.lan_k = lan->k; a.lan_lambda = lan->lambda;
+    a.lan_omega = reinterpret_cast<float*>(w + lay.lan);
+    a.lan_count = reinterpret_cast<int32_t*>(w + lay.lan + size_t(p->B) * L * 4);
+    a.p_agg_out = lan->p_agg; a.count_out = lan->count;
+    a.lan_resample = p->resample_mode == COOL_SD_RESAMPLE_LANTERN ? 1 : 0;
+    a.omega = a.lan_omega;
+    a.om_sb = L;
+    a.resample_mode = COOL_SD_RESAMPLE_VANILLA;
+  }
   // beyond ~128 MB the logits cannot stay in L2 / Infinity Cache until the sequence kernel re-reads a row
   a.stream_loads = (double(rows_t + rows_d) * p->V * (p->dtype == COOL_SD_BF16 ? 2 : 4) * (tu ? 2 : 1)) > 128e6 ? 1 : 0;
   a.nchunks = (int32_t)C; a.nt2 = ch.nt2;
@@ -229,8 +257,8 @@ int cool_sd_schedule(int32_t kind, int32_t L, float delta, float param, float* o
 }
 
 size_t cool_sd_workspace_bytes(const cool_sd_params* p) {
-  if (!params_ok(p, false) && !params_ok(p, true)) return 0;
-  const bool full = params_ok(p, false);
+  if (!params_ok(p, false, true) && !params_ok(p, true)) return 0;
+  const bool full = params_ok(p, false, true);
   const int64_t L = full ? p->L : 1;
   const int64_t rows = full ? int64_t(p->B) * (2 * L + p->has_bonus) : 2 * int64_t(p->B);
   const Chunking ch = pick_chunking(p, rows);
@@ -238,7 +266,7 @@ size_t cool_sd_workspace_bytes(const cool_sd_params* p) {
   const int64_t c1_max = (int64_t(p->V) + 4095) / 4096;
   (void)ch;
   const int64_t pairs = full ? int64_t(p->B) * L : 0;       // cool_sd_diagnostics: chunks of 8192 logits
-  return make_layout(p->B, rows, c1_max, c1_max, pairs, (int64_t(p->V) + 8191) / 8192).total;
+  return make_layout(p->B, rows, c1_max, c1_max, pairs, (int64_t(p->V) + 8191) / 8192, pairs).total;
 }
 
 int cool_sd_workspace_init(void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
@@ -262,6 +290,24 @@ int cool_sd_verify(const cool_sd_params* p, const void* target_dev, const void* 
   return run(p, false, target_dev, target_uncond_dev, draft_dev, draft_uncond_dev, draft_tokens_dev, omega_dev,
              u_accept_dev, u_resample_dev, accept_len_dev, next_token_dev, p_tok_dev, q_tok_dev, f_dev,
              resid_mass_dev, workspace_dev, workspace_bytes, hip_stream);
+}
+
+int cool_sd_verify_lantern(const cool_sd_params* p, const void* target_dev, const void* target_uncond_dev,
+                           const void* draft_dev, const void* draft_uncond_dev, const int32_t* draft_tokens_dev,
+                           const int32_t* neighbors_dev, int32_t k, float lambda, const float* u_accept_dev,
+                           const float* u_resample_dev, int32_t* accept_len_dev, int32_t* next_token_dev,
+                           float* p_tok_dev, float* q_tok_dev, float* f_dev, float* resid_mass_dev, float* p_agg_dev,
+                           int32_t* count_dev, void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+  if (!params_ok(p, false, true)) return COOL_SD_EINVAL;
+  if (!target_dev || !draft_dev || !draft_tokens_dev || !u_accept_dev || !u_resample_dev || !accept_len_dev ||
+      !next_token_dev)
+    return COOL_SD_EINVAL;
+  if ((target_uncond_dev == nullptr) != (draft_uncond_dev == nullptr)) return COOL_SD_EINVAL;
+  if (k < 1 || k > 65536 || !neighbors_dev || !(lambda >= 0.f) || !isfinite(lambda)) return COOL_SD_EINVAL;
+  const LanternArgs lan{neighbors_dev, k, lambda, p_agg_dev, count_dev};
+  return run(p, false, target_dev, target_uncond_dev, draft_dev, draft_uncond_dev, draft_tokens_dev, nullptr,
+             u_accept_dev, u_resample_dev, accept_len_dev, next_token_dev, p_tok_dev, q_tok_dev, f_dev,
+             resid_mass_dev, workspace_dev, workspace_bytes, hip_stream, &lan);
 }
 
 int cool_sd_resample(const cool_sd_params* p, const void* target_rows_dev, const void* target_uncond_rows_dev,

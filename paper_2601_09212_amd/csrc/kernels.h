@@ -44,6 +44,15 @@ struct KArgs {
   int32_t cs;
   float4* seq_stat;         // [B]           statistics of the sampled row (several-chunk path)
   float* chunk_R;           // [B, nchunks]  residual mass per chunk of the sampled row  (nchunks > 1)
+  // aggregated acceptance over latent neighbours (nbr == nullptr: off)
+  const int32_t* nbr;       // [V, lan_k] neighbour table, nearest first
+  int32_t lan_k;
+  float lan_lambda;
+  float* lan_omega;         // workspace [B, L]: sum over the neighbour set / p(x~_i); read as omega
+  int32_t* lan_count;       // workspace [B, L]: members of the set besides x~_i
+  float* p_agg_out;         // [B, L] out or nullptr
+  int32_t* count_out;       // [B, L] out or nullptr
+  int32_t lan_resample;     // 1: resample with Eq. g_lantern
   // diagnostics call only (nchunks = chunks of 8192 logits per row there, has_bonus = 0)
   float* alpha;             // [B, L] out
   float* beta;              // [B, L] out

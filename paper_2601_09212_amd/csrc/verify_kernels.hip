@@ -262,6 +262,24 @@ __device__ __forceinline__ float resid_elem(float lt, float ld, const ResidCoef&
   return fmaxf(__fsub_rn(p, qf), 0.f);
 }
 
+// Eq. p_lantern as a patch of the target row held by one thread: the members of the rejected
+// token's neighbour set lose their probability (bit n of zmask: this thread's element n is a
+// member) and the rejected token itself carries the aggregated one (p times agg).
+struct LanPatch {
+  uint32_t zmask;
+  int aggpos;       // this thread's element that is the rejected token, or -1
+  float agg;
+};
+// Unnormalised mass [P^{k,lambda} - q]_+ (Eq. g_lantern) of this thread's element n.
+__device__ __forceinline__ float resid_elem_lan(float lt, float ld, const ResidCoef& k, const LanPatch& lp, int n) {
+  float p = __fmul_rn(exp2_fast(__fmaf_rn(lt, kLog2e, -k.Ct)), k.at);
+  if (k.mode == kModeP) return p;
+  p = ((lp.zmask >> n) & 1u) ? 0.f : p;
+  p = (n == lp.aggpos) ? __fmul_rn(p, lp.agg) : p;
+  const float q = __fmul_rn(exp2_fast(__fmaf_rn(ld, kLog2e, -k.Cd)), k.ad);
+  return fmaxf(__fsub_rn(p, q), 0.f);
+}
+
 // Per-thread, per-tile partial masses, then block-wide tile totals T[k] (in sm.tile_tot).
 template <int DT, bool XF, int kT>
 __device__ __forceinline__ void chunk_masses(const RowRegs<DT, XF, kT>& rt, const RowRegs<DT, XF, kT>& rd,
@@ -461,11 +479,17 @@ struct SmemW {
 // element inside the thread whose interval contains u*R.  If the law has no mass (no rejection
 // is possible at this position) it falls back to p.  Returns the token in every thread, R = the
 // law's mass.
-template <int DT, bool XF, int kVW>
+template <int DT, bool XF, int kVW, bool LAN = false>
 __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, const RowRegs<DT, XF, kVW>& rd,
-                                            ResidCoef k, float u, int V, SmemW& sm, float& R) {
+                                            ResidCoef k, float u, int V, SmemW& sm, float& R,
+                                            const LanPatch lp = LanPatch{0u, -1, 1.f}) {
   constexpr int kE = Vec<DT>::kE;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  // mass of element e of this thread's vector v
+  auto relem = [&](int v, int e) -> float {
+    if constexpr (LAN) return resid_elem_lan(rt.get(v, e), rd.get(v, e), k, lp, v * kE + e);
+    else return resid_elem(rt.get(v, e), rd.get(v, e), k);
+  };
   float part[kVW], mine, incl, excl;
   R = 0.f;
   for (int attempt = 0; attempt < 2; ++attempt) {
@@ -474,7 +498,7 @@ __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, cons
     for (int v = 0; v < kVW; ++v) {
       float acc = 0.f;
 #pragma unroll
-      for (int e = 0; e < kE; ++e) acc = __fadd_rn(acc, resid_elem(rt.get(v, e), rd.get(v, e), k));
+      for (int e = 0; e < kE; ++e) acc = __fadd_rn(acc, relem(v, e));
       part[v] = acc;
       mine = __fadd_rn(mine, acc);
     }
@@ -534,7 +558,7 @@ __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, cons
       if (q == vs) {
 #pragma unroll
         for (int e = 0; e < kE; ++e) {
-          const float r = resid_elem(rt.get(q, e), rd.get(q, e), k);
+          const float r = relem(q, e);
           if (r > 0.f) {
             last = e;
             run = __fadd_rn(run, r);
@@ -551,7 +575,7 @@ __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, cons
   return token >= V ? V - 1 : token;
 }
 
-template <int DT, bool XF, bool AL>
+template <int DT, bool XF, bool AL, bool LAN>
 __global__ __launch_bounds__(kThreadsW) void sequence_whole_kernel(const KArgs a) {
   constexpr int kE = Vec<DT>::kE, kES = Vec<DT>::kES;
   constexpr int kVW = kChunk / (kThreadsW * kE);       // vectors per thread: 2 (bf16) / 4 (fp32)
@@ -600,10 +624,105 @@ __global__ __launch_bounds__(kThreadsW) void sequence_whole_kernel(const KArgs a
   else rd.clear();                                    // never read in mode P
 
   float R;
-  const int token = sample_whole<DT, XF, kVW>(rt, rd, k, a.u_res[b], a.V, sm, R);
+  int token;
+  if constexpr (LAN) {
+    // Eq. g_lantern: the law is [P^{k,lambda} - q]_+ around the rejected token x~_j; this thread
+    // owns the kVW*kE consecutive tokens from first_tok on
+    LanPatch lp{0u, -1, 1.f};
+    if (!bonus) {
+      k.mode = kModeVanilla;
+      const int first_tok = threadIdx.x * (kVW * kE);
+      const int xd = min(max(a.tokens[int64_t(b) * a.L + j], 0), a.V - 1);
+      const int m = a.lan_count[int64_t(b) * a.L + j];
+      lp.agg = omega;                                   // sum over the set / p(x~_j), from lantern_agg_kernel
+      const int dx = xd - first_tok;
+      if (dx >= 0 && dx < kVW * kE) lp.aggpos = dx;
+      const int32_t* row = a.nbr + int64_t(xd) * a.lan_k;
+      int taken = 0;
+      for (int jj = 0; jj < a.lan_k && taken < m; ++jj) {   // the first m valid neighbours are the members
+        const int n = row[jj];
+        if (n < 0 || n >= a.V || n == xd) continue;
+        ++taken;
+        const int dn = n - first_tok;
+        if (dn >= 0 && dn < kVW * kE) lp.zmask |= 1u << dn;
+      }
+    }
+    token = sample_whole<DT, XF, kVW, true>(rt, rd, k, a.u_res[b], a.V, sm, R, lp);
+  } else {
+    token = sample_whole<DT, XF, kVW>(rt, rd, k, a.u_res[b], a.V, sm, R);
+  }
   if (threadIdx.x == 0) {
     a.next_token[b] = token;
     if (a.resid_mass) a.resid_mass[b] = R;
+  }
+}
+
+// ============================================================================ neighbour aggregation
+// Eq. f_lantern: the acceptance probability of x~_i uses the probability of its neighbour set
+// A(x~_i) = {x~_i} + the longest prefix of its neighbour list (nearest first) whose summed
+// probability stays below lambda p_i(x~_i).  Relative to p_i(x~_i) the members weigh
+// 2^((l_n - l_x) log2e), which needs no row statistics, so one wave per position gathers the k
+// neighbour logits, scans their weights and leaves agg = sum over A / p_i(x~_i) >= 1 where the
+// accept test reads its relaxation parameter: Eq. f_lantern is Eq. relax with omega_i = agg.
+// Also writes the number of members (for Eq. g_lantern) and the optional outputs.
+__device__ __forceinline__ float token_logit_any(int dt, const char* cond, const char* uncond, int x, bool xf,
+                                                 float s, float inv_T, float thr) {
+  float lc = dt == kDtBF16 ? load_elem<kDtBF16>(cond, x) : load_elem<kDtF32>(cond, x);
+  if (!xf) return lc;
+  float lu = 0.f;
+  if (uncond) lu = dt == kDtBF16 ? load_elem<kDtBF16>(uncond, x) : load_elem<kDtF32>(uncond, x);
+  const float l = transform_logit(lc, lu, uncond != nullptr, s, inv_T);
+  return l >= thr ? l : -INFINITY;
+}
+
+__global__ __launch_bounds__(kThreads) void lantern_agg_kernel(const KArgs a, int dt, int xf) {
+  const int pos = blockIdx.x * kWaves + (threadIdx.x >> 6);       // (b, i)
+  if (pos >= a.B * a.L) return;
+  const int lane = threadIdx.x & 63;
+  const int b = pos / a.L, i = pos - b * a.L;
+  const int rt_ = b * (a.L + a.has_bonus) + i;
+  const int es = dt == kDtBF16 ? 2 : 4;
+  const int64_t off = int64_t(b) * a.t_sb + int64_t(i) * a.t_sl;
+  const char* cond = row_ptr(a.t, off, es);
+  const char* uncond = row_ptr(a.tu, off, es);
+  const float thr = (xf && a.top_k > 0) ? a.thr[rt_] : -INFINITY;
+  const int x = min(max(a.tokens[pos], 0), a.V - 1);
+  const float lx = a.tok_logit[rt_];
+  const int32_t* row = a.nbr + int64_t(x) * a.lan_k;
+  float cum = 0.f;
+  int m = 0;
+  if (lx > -INFINITY) {                       // p(x~) = 0 admits no neighbour: nothing is below 0
+    for (int j0 = 0; j0 < a.lan_k; j0 += 64) {
+      const int j = j0 + lane;
+      const int n = j < a.lan_k ? row[j] : -1;
+      const bool valid = n >= 0 && n < a.V && n != x;
+      const float ln = valid ? token_logit_any(dt, cond, uncond, n, xf != 0, a.cfg_scale, a.inv_T, thr) : -INFINITY;
+      const float w = valid ? exp2_fast(__fmul_rn(__fsub_rn(ln, lx), kLog2e)) : 0.f;
+      const float incl = __fadd_rn(cum, wave_scan_incl(w));
+      const unsigned long long bv = __ballot(valid);
+      const unsigned long long bf = __ballot(valid && !(incl < a.lan_lambda));
+      if (bf) {                                // the first neighbour that does not fit ends the set
+        const int fl = __ffsll((long long)bf) - 1;
+        m += __popcll(bv & ((1ull << fl) - 1ull));
+        // the running sum before lane fl: weights of skipped lanes are zero, so it is the sum
+        // over the members taken so far
+        if (fl > 0) cum = lane_f(incl, fl - 1);
+        break;
+      }
+      m += __popcll(bv);
+      cum = lane_f(incl, 63);
+    }
+  }
+  if (lane == 0) {
+    const float agg = __fadd_rn(1.f, cum);
+    a.lan_omega[pos] = agg;
+    a.lan_count[pos] = m;
+    if (a.count_out) a.count_out[pos] = m;
+    if (a.p_agg_out) {
+      float Ct, St;
+      combine_row(a, rt_, Ct, St);
+      a.p_agg_out[pos] = __fmul_rn(exp2_fast(__fmaf_rn(lx, kLog2e, -Ct)) / St, agg);
+    }
   }
 }
 
@@ -1155,8 +1274,17 @@ static hipError_t launch_rest(const KArgs& a, hipStream_t stream) {
     if (e != hipSuccess) return e;
   }
   const unsigned gB = (unsigned)a.B;
+  if (a.nbr != nullptr) {     // aggregated acceptance: the relaxation parameter of every position
+    const int64_t gl = (int64_t(a.B) * a.L + kWaves - 1) / kWaves;
+    hipLaunchKernelGGL(lantern_agg_kernel, dim3((unsigned)gl), dim3(kThreads), 0, stream, a, DT, XF ? 1 : 0);
+    e = checked("lantern_agg_kernel");
+    if (e != hipSuccess) return e;
+  }
   if (a.nt2 == kT) {          // the sampled row is one chunk: everything per sequence in one workgroup
-    hipLaunchKernelGGL((sequence_whole_kernel<DT, XF, AL>), dim3(gB), dim3(kThreadsW), 0, stream, a);
+    if (a.lan_resample)
+      hipLaunchKernelGGL((sequence_whole_kernel<DT, XF, AL, true>), dim3(gB), dim3(kThreadsW), 0, stream, a);
+    else
+      hipLaunchKernelGGL((sequence_whole_kernel<DT, XF, AL, false>), dim3(gB), dim3(kThreadsW), 0, stream, a);
     return checked("sequence_whole_kernel");
   }
   if (!a.resample_only) {     // several chunks: find tau once per sequence

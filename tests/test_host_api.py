@@ -21,7 +21,8 @@ def test_library_exports_every_declared_symbol(P):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = re.findall(r"\b(cool_sd_[a-z_]+)\s*\(", header)
     assert set(names) >= {"cool_sd_schedule", "cool_sd_workspace_bytes", "cool_sd_workspace_init",
-                          "cool_sd_verify", "cool_sd_resample", "cool_sd_diagnostics", "cool_sd_strerror"}
+                          "cool_sd_verify", "cool_sd_verify_lantern", "cool_sd_resample", "cool_sd_diagnostics",
+                          "cool_sd_strerror"}
     raw = C.CDLL(P.binding.LIB_PATH)
     for n in set(names):
         assert hasattr(raw, n), n
@@ -67,7 +68,7 @@ def test_workspace_bytes_and_invalid_params(P):
                                             t_stride_b=9 * 262144, d_stride_b=8 * 262144))
     assert big > small
     for bad in (dict(B=0), dict(V=0), dict(dtype=3), dict(top_k=-1), dict(top_k=16385), dict(temperature=0.0),
-                dict(temperature=float("inf")), dict(cfg_scale=float("nan")), dict(resample_mode=2),
+                dict(temperature=float("inf")), dict(cfg_scale=float("nan")), dict(resample_mode=3),
                 dict(flags=2), dict(flags=-1), dict(t_stride_b=-1)):
         assert P.cool_sd_workspace_bytes(_params(P, **bad)) == 0, bad
     # L out of range is still a valid stand-alone resample shape (L is ignored there)
@@ -110,6 +111,22 @@ def test_verify_validates_before_touching_the_gpu(P):
     assert d(_params(P), out=null) == E.COOL_SD_EINVAL
     assert d(_params(P)) == E.COOL_SD_EWORKSPACE
     assert d(_params(P), ws=C.c_void_p(0x1000), n=16) == E.COOL_SD_EWORKSPACE
+    # aggregated acceptance over neighbours
+    def lan(params, nbr=fake, k=10, lam=2.0, ws=null, n=0):
+        return lib.cool_sd_verify_lantern(C.byref(params), fake, null, fake, null, fake, nbr, k, C.c_float(lam),
+                                          fake, fake, fake, fake, null, null, null, null, null, null, ws, n, null)
+    assert lan(_params(P), nbr=null) == E.COOL_SD_EINVAL
+    assert lan(_params(P), k=0) == E.COOL_SD_EINVAL
+    assert lan(_params(P), lam=-1.0) == E.COOL_SD_EINVAL
+    assert lan(_params(P), lam=float("inf")) == E.COOL_SD_EINVAL
+    assert lan(_params(P)) == E.COOL_SD_EWORKSPACE
+    assert lan(_params(P, resample_mode=E.COOL_SD_RESAMPLE_LANTERN)) == E.COOL_SD_EWORKSPACE
+    assert lan(_params(P, resample_mode=3)) == E.COOL_SD_EINVAL
+    assert call(_params(P, resample_mode=E.COOL_SD_RESAMPLE_LANTERN)) == E.COOL_SD_EINVAL   # only with neighbours
+    big = _params(P, V=20000, resample_mode=E.COOL_SD_RESAMPLE_LANTERN, t_stride_l=20000, d_stride_l=20000,
+                  t_stride_b=9 * 20000, d_stride_b=8 * 20000)
+    assert lan(big, ws=C.c_void_p(0x1000), n=1 << 24) == E.COOL_SD_EUNSUPPORTED
+    assert P.cool_sd_workspace_bytes(_params(P, resample_mode=E.COOL_SD_RESAMPLE_LANTERN)) > 0
     for code in (0, -1, -2, -3, -4, -99):
         assert isinstance(P.cool_sd_strerror(code), str) and P.cool_sd_strerror(code)
     assert lib.cool_sd_profile_read(None, None) == E.COOL_SD_EINVAL

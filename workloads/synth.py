@@ -167,3 +167,25 @@ def make_workload(cfg: int, *, device="cpu", seed: Optional[int] = None, call: i
                     u_accept=ua, u_resample=ur, target_uncond=t_u, draft_uncond=d_u,
                     cfg_scale=cfg_scale, temperature=temperature, top_k=k,
                     delta=r["delta"], nu=r["nu"], extra=extra)
+
+
+def make_neighbor_table(V: int, k: int, *, device="cpu", seed: int = 7, pad: float = 0.0,
+                        self_entries: bool = False) -> torch.Tensor:
+    """Synthetic stand-in for the codebook's nearest-neighbour table ([V, k] int32, "nearest"
+    first): the real table comes from the trained VQ codebook, which is not available.  Row x
+    holds k distinct tokens other than x: x plus k distinct non-zero offsets (shared by all
+    rows) in a per-row random order.  pad: fraction of entries replaced by -1; self_entries: one
+    entry per row replaced by x itself (both must be skipped by a consumer)."""
+    assert 1 <= k < V
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    offs = torch.randperm(V - 1, generator=gen, device=device)[:k] + 1                  # distinct, in [1, V-1]
+    order = torch.rand((V, k), generator=gen, device=device).argsort(dim=1)
+    x = torch.arange(V, device=device).unsqueeze(1)
+    nbr = (x + offs[order]) % V
+    if pad > 0:
+        nbr = torch.where(torch.rand((V, k), generator=gen, device=device) < pad, torch.full_like(nbr, -1), nbr)
+    if self_entries:
+        col = torch.randint(0, k, (V, 1), generator=gen, device=device)
+        nbr = nbr.scatter(1, col, x)
+    return nbr.to(torch.int32).contiguous()

@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/),
 # scaled by the same counters' reading on a plain copy kernel; None = not measured.
 # Fetched + written bytes of row_stats_kernel per launch.
-MEASURED_TRAFFIC_BYTES = {"cfg1": None, "cfg2": 17.97e6, "cfg3": 74.28e6, "cfg4": 278.04e6, "cfg5": 1143.26e6}
+MEASURED_TRAFFIC_BYTES = {"cfg1": None, "cfg2": 17.96e6, "cfg3": 71.72e6, "cfg4": 277.75e6, "cfg5": 1143.20e6}
 # the same for sequence_early_exit_kernel (--early-exit)
 MEASURED_TRAFFIC_EARLY = {"cfg2": 7.95e6, "cfg4": 51.28e6}
 
@@ -50,6 +50,9 @@ def parse():
                          "roofline object then refers to the single kernel and to the bytes it actually needs")
     ap.add_argument("--diagnostics", action="store_true",
                     help="also time cool_sd_diagnostics (alpha, beta of every position) on the timed workloads")
+    ap.add_argument("--lantern", action="store_true",
+                    help="also time cool_sd_verify_lantern (k = 10 synthetic neighbours, lambda = 2, G* resampling) on "
+                         "the timed workloads")
     ap.add_argument("--kernel-samples", type=int, default=200, help="instrumented calls for the per-kernel time")
     ap.add_argument("--counter-run", action="store_true",
                     help="for rocprofv3 --pmc: a plain device copy of known size (the counters' reference), then "
@@ -215,6 +218,40 @@ def time_diagnostics(r, passes=6):
             "frac": nbytes / sec / 1e9 / HBM_PEAK_GBS}
 
 
+def time_lantern(r, k=10, lam=2.0, passes=6):
+    """Average duration of one cool_sd_verify_lantern call over the pool, replayed from a HIP graph.
+    The neighbour table is synthetic ([V, k] distinct random tokens per row)."""
+    from workloads import make_neighbor_table
+    pkg, torch = r.pkg, r.torch
+    nbr = make_neighbor_table(r.V, k, device="cuda", seed=11)
+    w0 = r.pool[0]
+    params = pkg.make_params(w0.target, w0.draft, top_k=w0.top_k, cfg_scale=w0.cfg_scale, temperature=w0.temperature)
+
+    def one(i):
+        w = r.pool[i % len(r.pool)]
+        pkg.cool_sd_verify_lantern(params, w.target, w.target_uncond, w.draft, w.draft_uncond, w.draft_tokens, nbr, k,
+                                   lam, w.u_accept, w.u_resample, r.accept_len, r.next_token, None, None, None, None,
+                                   None, None, r.ws)
+    for i in range(len(r.pool)):
+        one(i)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for i in range(len(r.pool)):
+            one(i)
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(passes):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    sec = e0.elapsed_time(e1) * 1e-3 / (passes * len(r.pool))
+    return {"us_per_call": sec * 1e6, "k": k, "lambda": lam, "tokens_per_s": r.B * r.L / sec,
+            "mean_accept_len": float(r.accept_len.float().mean().item())}
+
+
 def cpu_baseline(runner, budget_s):
     """The oracle, as it stands, on whole batches of the same pool until the time budget is used."""
     from oracle import oracle as O
@@ -277,7 +314,8 @@ def main():
     done, wall, dev_s = r.time(a.steps, a.warmup, a.launch)
     tokens = done * r.B * r.L
     kern_s, kern_ev_s, call_s = r.kernel_times(a.kernel_samples)
-    kernel_name, kernel_bytes = "row_stats_kernel", r.bytes_per_step
+    kernel_name = "row_stats_topk_kernel" if r.pool[0].top_k > 0 else "row_stats_kernel"
+    kernel_bytes = r.bytes_per_step
     if a.early_exit and r.V <= 16384:
         # one kernel per call; its algorithmic bytes are the rows Algorithm 1 needs: both rows of every
         # position up to and including the rejected one, or all L pairs plus the bonus row
@@ -328,11 +366,15 @@ def main():
                                   "bytes_per_step": rr.bytes_per_step, "pool_batches": len(rr.pool)}
             if a.diagnostics:
                 extra[name]["diagnostics"] = time_diagnostics(rr)
+            if a.lantern:
+                extra[name]["lantern"] = time_lantern(rr)
             del rr
             torch.cuda.empty_cache()
         line["other_workloads"] = extra
     if a.diagnostics:
         line["diagnostics"] = time_diagnostics(r)
+    if a.lantern:
+        line["lantern"] = time_lantern(r)
     if not a.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(r, a.cpu_seconds)
     print(json.dumps(line), flush=True)

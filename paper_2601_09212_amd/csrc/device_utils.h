@@ -9,6 +9,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace csd {
 
@@ -72,15 +73,38 @@ __device__ __forceinline__ int wave_max_i(int v) {
   for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o, 64));
   return v;
 }
-// inclusive prefix sum over the 64 lanes of a wave, ascending lane order
+// Inclusive prefix sum over the 64 lanes of a wave, ascending lane order, without LDS traffic:
+// four DPP row shifts (1, 2, 4, 8; lanes without a source read 0) scan each row of 16 lanes,
+// then the totals of rows 0..2 (lanes 15, 31, 47) are added to the rows after them in a fixed
+// order.
+constexpr int kDppRowShr1 = 0x111, kDppRowShr2 = 0x112, kDppRowShr4 = 0x114, kDppRowShr8 = 0x118;
+constexpr int kDppWaveShr1 = 0x138;    // whole-wave shift by one lane
 __device__ __forceinline__ float wave_scan_incl(float v) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    float n = __shfl_up(v, o, 64);
-    if (lane >= o) v += n;
-  }
-  return v;
+  v = __fadd_rn(v, dpp_f<kDppRowShr1>(v));
+  v = __fadd_rn(v, dpp_f<kDppRowShr2>(v));
+  v = __fadd_rn(v, dpp_f<kDppRowShr4>(v));
+  v = __fadd_rn(v, dpp_f<kDppRowShr8>(v));
+  const float t0 = lane_f(v, 15), t1 = lane_f(v, 31), t2 = lane_f(v, 47);
+  const float t01 = __fadd_rn(t0, t1);
+  const int row = (threadIdx.x & 63) >> 4;
+  const float off = row == 0 ? 0.f : (row == 1 ? t0 : (row == 2 ? t01 : __fadd_rn(t01, t2)));
+  return __fadd_rn(v, off);
+}
+// value of the previous lane (0 in lane 0)
+__device__ __forceinline__ float wave_prev_lane(float v) { return dpp_f<kDppWaveShr1>(v); }
+__device__ __forceinline__ uint32_t wave_scan_incl_u32(uint32_t v) {
+  auto sh = [](uint32_t x, auto ctrl) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, decltype(ctrl)::value, 0xf, 0xf, true);
+  };
+  v += sh(v, std::integral_constant<int, kDppRowShr1>{});
+  v += sh(v, std::integral_constant<int, kDppRowShr2>{});
+  v += sh(v, std::integral_constant<int, kDppRowShr4>{});
+  v += sh(v, std::integral_constant<int, kDppRowShr8>{});
+  const uint32_t t0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 15);
+  const uint32_t t1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 31);
+  const uint32_t t2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 47);
+  const int row = (threadIdx.x & 63) >> 4;
+  return v + (row == 0 ? 0u : (row == 1 ? t0 : (row == 2 ? t0 + t1 : t0 + t1 + t2)));
 }
 
 // ---------------------------------------------------------------- loads

@@ -92,12 +92,7 @@ __device__ __forceinline__ float kth_largest(const uint32_t (&xw)[NVAL], uint32_
     uint32_t h[kPer], local = 0;
 #pragma unroll
     for (int j = 0; j < kPer; ++j) { h[j] = ts.hist[tid * kPer + j]; local += h[j]; }
-    uint32_t incl = local;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      uint32_t t = __shfl_up(incl, o, 64);
-      if (lane >= o) incl += t;
-    }
+    const uint32_t incl = wave_scan_incl_u32(local);
     if (lane == 63) ts.wave_tot[wv] = incl;
     __syncthreads();
     uint32_t before = incl - local, total = 0;

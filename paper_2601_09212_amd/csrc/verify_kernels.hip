@@ -347,8 +347,7 @@ __device__ __forceinline__ int chunk_select(const RowRegs<DT, XF, kT>& rt, const
 #pragma unroll
   for (int t = 0; t < kT; ++t) if (t == ks) my = part[t];
   const float incl_w = wave_scan_incl(my);
-  float excl_w = __shfl_up(incl_w, 1, 64);
-  if (lane == 0) excl_w = 0.f;
+  const float excl_w = wave_prev_lane(incl_w);
   if (lane == 63) sm.scan_tot[wv] = incl_w;
   __syncthreads();
   float woff = 0.f;
@@ -490,6 +489,7 @@ __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, cons
     if constexpr (LAN) return resid_elem_lan(rt.get(v, e), rd.get(v, e), k, lp, v * kE + e);
     else return resid_elem(rt.get(v, e), rd.get(v, e), k);
   };
+  float r[kVW * kE];           // masses of this thread's tokens, kept for the final search
   float part[kVW], mine, incl, excl;
   R = 0.f;
   for (int attempt = 0; attempt < 2; ++attempt) {
@@ -498,13 +498,15 @@ __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, cons
     for (int v = 0; v < kVW; ++v) {
       float acc = 0.f;
 #pragma unroll
-      for (int e = 0; e < kE; ++e) acc = __fadd_rn(acc, relem(v, e));
+      for (int e = 0; e < kE; ++e) {
+        r[v * kE + e] = relem(v, e);
+        acc = __fadd_rn(acc, r[v * kE + e]);
+      }
       part[v] = acc;
       mine = __fadd_rn(mine, acc);
     }
     const float incl_w = wave_scan_incl(mine);
-    float excl_w = __shfl_up(incl_w, 1, 64);
-    if (lane == 0) excl_w = 0.f;
+    const float excl_w = wave_prev_lane(incl_w);
     __syncthreads();                                  // earlier readers of scan_tot are done
     if (lane == 63) sm.scan_tot[wv] = incl_w;
     __syncthreads();
@@ -555,15 +557,13 @@ __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, cons
     float run = 0.f;
 #pragma unroll
     for (int q = 0; q < kVW; ++q) {
-      if (q == vs) {
 #pragma unroll
-        for (int e = 0; e < kE; ++e) {
-          const float r = relem(q, e);
-          if (r > 0.f) {
-            last = e;
-            run = __fadd_rn(run, r);
-            if (found < 0 && run > v3) found = e;
-          }
+      for (int e = 0; e < kE; ++e) {
+        const float re = r[q * kE + e];
+        if (q == vs && re > 0.f) {
+          last = e;
+          run = __fadd_rn(run, re);
+          if (found < 0 && run > v3) found = e;
         }
       }
     }

@@ -169,6 +169,10 @@ int run(const cool_sd_params* p, bool resample_only,
   const bool direct = ch.c1 <= 4;
   a.stat = direct ? a.part : a.rowstat;
   a.cs = direct ? (int32_t)ch.c1 : 1;
+  // with many chunks per row the verify path folds their combination into accept_kernel; the
+  // stand-alone resample has no such kernel, and the neighbour aggregation reads row statistics
+  // before it
+  a.accept_combines = (!direct && !resample_only && !lan) ? 1 : 0;
 
   const bool xf = (tu != nullptr) || (p->temperature != 1.0f) || (p->top_k > 0);
   hipError_t e = csd::launch_verify(a, p->dtype, xf, static_cast<hipStream_t>(stream), g_profile ? g_ev : nullptr);

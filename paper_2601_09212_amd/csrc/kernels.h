@@ -42,6 +42,7 @@ struct KArgs {
   float2* rowstat;          // workspace [rows_t + rows_d]      combined statistics (written only when c1 > 4)
   const float2* stat;       // what the sequence kernel reads: part (cs = c1 <= 4) or rowstat (cs = 1)
   int32_t cs;
+  int32_t accept_combines;  // long rows: accept_kernel combines the chunk statistics of its own rows (no combine_rows launch)
   float4* seq_stat;         // [B]           statistics of the sampled row (several-chunk path)
   float* chunk_R;           // [B, nchunks]  residual mass per chunk of the sampled row  (nchunks > 1)
   // aggregated acceptance over latent neighbours (nbr == nullptr: off)

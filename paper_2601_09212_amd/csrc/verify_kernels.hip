@@ -214,9 +214,7 @@ __global__ __launch_bounds__(TPB, 6) void row_stats_topk_kernel(const KArgs a) {
 // combines the row's chunk statistics into one (reference exponent, sum) pair.  Lanes take
 // chunks cc = lane, lane+64, ...; the reference is the maximum, sums are rescaled by exact
 // powers of two and added in a fixed order.
-__global__ __launch_bounds__(kThreads) void combine_rows_kernel(const KArgs a) {
-  const int r = blockIdx.x * kWaves + (threadIdx.x >> 6);
-  if (r >= a.rows_t + a.rows_d) return;
+__device__ __forceinline__ void combine_row_wave(const KArgs& a, int r) {
   const int lane = threadIdx.x & 63;
   const float2* p = a.part + int64_t(r) * a.c1;
   float m = kRefFloor;
@@ -226,6 +224,11 @@ __global__ __launch_bounds__(kThreads) void combine_rows_kernel(const KArgs a) {
   for (int cc = lane; cc < a.c1; cc += 64) s = __fadd_rn(s, p[cc].y * exp2_fast(p[cc].x - m));
   s = wave_sum(s);
   if (lane == 0) a.rowstat[r] = make_float2(m, s);
+}
+__global__ __launch_bounds__(kThreads) void combine_rows_kernel(const KArgs a) {
+  const int r = blockIdx.x * kWaves + (threadIdx.x >> 6);
+  if (r >= a.rows_t + a.rows_d) return;
+  combine_row_wave(a, r);
 }
 
 // Statistics of row r from at most kMaxDirect entries (a.stat, a.cs entries per row), all
@@ -452,6 +455,14 @@ template <int DT, bool XF>
 __global__ __launch_bounds__(kThreads) void accept_kernel(const KArgs a) {
   __shared__ Smem sm;
   const int b = blockIdx.x;
+  if (a.accept_combines) {
+    // rows of many statistics chunks: combine the chunks of this sequence's rows first, one wave
+    // per row (what combine_rows_kernel does for all rows), then read them back below
+    const int rps = a.L + a.has_bonus;
+    for (int q = threadIdx.x >> 6; q < rps + a.L; q += kWaves)
+      combine_row_wave(a, q < rps ? b * rps + q : a.rows_t + b * a.L + (q - rps));
+    __syncthreads();          // the rows' statistics are visible to the whole workgroup
+  }
   const int j = find_tau<DT, XF, kThreads>(a, b, true, sm.pick_first, &sm.rowstat);
   if (threadIdx.x == 0) a.seq_stat[b] = sm.rowstat;
   (void)j;
@@ -949,11 +960,10 @@ __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
       sm.rowstat = make_float4(Ct, St, Cd, Sd);
     }
     __syncthreads();
-  } else {
-    if (threadIdx.x == 0) sm.rowstat = a.seq_stat[b];
-    __syncthreads();
   }
-  const float4 rs = sm.rowstat;
+  // the statistics of the sampled row are the same for every thread: read straight from the
+  // workspace (a scalar load that is in flight while the chunk's vector loads are issued)
+  const float4 rs = a.resample_only ? sm.rowstat : a.seq_stat[b];
   const char* t_c = row_ptr(a.t, int64_t(b) * a.t_sb + int64_t(j) * a.t_sl, kES);
   const char* t_u = row_ptr(a.tu, int64_t(b) * a.t_sb + int64_t(j) * a.t_sl, kES);
   const char* d_c = bonus ? nullptr : row_ptr(a.d, int64_t(b) * a.d_sb + int64_t(j) * a.d_sl, kES);
@@ -961,22 +971,36 @@ __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
   const float thr_t = masked ? a.thr[rt_] : -INFINITY;
   const float thr_d = (masked && !bonus) ? a.thr[rd_] : -INFINITY;
   const float omega = bonus ? 1.f : a.omega[int64_t(b) * a.om_sb + j];
-  ResidCoef k{rs.x, 1.f / rs.y, rs.z, bonus ? 1.f : 1.f / rs.w, omega,
-              bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
 
   RowRegs<DT, XF, kT> rt, rd;
   float part[kT];
   auto load_pair = [&](int cc) {
     const int64_t base = int64_t(cc) * kChunk2;
-    load_chunk<DT, XF, AL, kT>(rt, t_c, t_u, base, a.V, a.cfg_scale, a.inv_T, thr_t);
-    if (!bonus) load_chunk<DT, XF, AL, kT>(rd, d_c, d_u, base, a.V, a.cfg_scale, a.inv_T, thr_d);
+    // the mass pass reads every chunk of the row exactly once: nontemporal loads
+    constexpr int kA = AL ? (STAGE == kMasses ? kAlignedStream : kAligned) : kUnaligned;
+    load_chunk<DT, XF, kA, kT>(rt, t_c, t_u, base, a.V, a.cfg_scale, a.inv_T, thr_t);
+    if (!bonus) load_chunk<DT, XF, kA, kT>(rd, d_c, d_u, base, a.V, a.cfg_scale, a.inv_T, thr_d);
     else rd.clear();                                  // never read in mode P
   };
+  if constexpr (STAGE == kMasses) load_pair(c);       // in flight before anything waits for the statistics
+  ResidCoef k{rs.x, 1.f / rs.y, rs.z, bonus ? 1.f : 1.f / rs.w, omega,
+              bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
 
   if constexpr (STAGE == kMasses) {
-    load_pair(c);
-    chunk_masses<DT, XF, kT>(rt, rd, k, part, sm);
-    if (threadIdx.x == 0) a.chunk_R[int64_t(b) * C + c] = chunk_total<kT>(sm);
+    // only the chunk's total is needed here: per-thread sum in ascending tile order, one wave
+    // reduction, one barrier (the selection launch forms its own tile totals for the chunk it picks)
+    constexpr int kE = Vec<DT>::kE;
+    float acc = 0.f;
+#pragma unroll
+    for (int t = 0; t < kT; ++t) {
+#pragma unroll
+      for (int e = 0; e < kE; ++e) acc = __fadd_rn(acc, resid_elem(rt.get(t, e), rd.get(t, e), k));
+    }
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) sm.scan_tot[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0)
+      a.chunk_R[int64_t(b) * C + c] = __fadd_rn(__fadd_rn(sm.scan_tot[0], sm.scan_tot[1]), __fadd_rn(sm.scan_tot[2], sm.scan_tot[3]));
     return;
   }
 
@@ -1267,7 +1291,7 @@ template <int DT, bool XF, bool AL>
 static hipError_t launch_rest(const KArgs& a, hipStream_t stream) {
   constexpr int kT = Vec<DT>::kT;
   hipError_t e;
-  if (a.cs != a.c1) {   // rows have many statistics chunks: pre-combine them, one wave per row
+  if (a.cs != a.c1 && !a.accept_combines) {   // rows have many statistics chunks: pre-combine them, one wave per row
     const int64_t gridc = (int64_t(a.rows_t) + a.rows_d + kWaves - 1) / kWaves;
     hipLaunchKernelGGL(combine_rows_kernel, dim3((unsigned)gridc), dim3(kThreads), 0, stream, a);
     e = checked("combine_rows_kernel");

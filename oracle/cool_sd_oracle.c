@@ -93,7 +93,8 @@ int csd_oracle_schedule(int kind, int L, double delta, double param, double *ome
  * Logit transform of one row (input-side option; the paper only says that the
  * draft's speculation uses classifier-free guidance, App. implementation
  * details; formula, temperature and top-k are this build's readings):
- *   1. guidance     l = l_u + s*(l_c - l_u)        (skipped when l_u == NULL)
+ *   1. guidance     l = l_u + s*(l_c - l_u)        (skipped when l_u == NULL; -inf where
+ *                   both logits are -inf)
  *   2. temperature  l = l * fl32(1/T)
  *   3. top-k        keep l >= (k-th largest l of the row), others -> -inf;
  *                   ties at the threshold are all kept   (skipped when k == 0)
@@ -123,6 +124,9 @@ int csd_oracle_transform_row(const float *l_cond, const float *l_uncond, int V,
             v = fmaf(cfg_scale, d, l_uncond[x]);    /* one rounding */
         }
         l[x] = v * inv_T;                           /* rounded to fp32 */
+        /* a token excluded on both inputs (-inf and -inf) stays excluded: the difference of
+         * two -inf is not a number, and -inf is what "excluded" means for every later step */
+        if (isnan(l[x])) l[x] = -INFINITY;
     }
     float thr = -INFINITY;
     if (top_k > 0) {

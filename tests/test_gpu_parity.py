@@ -211,6 +211,31 @@ def test_topk_ties_and_temperature(P, oracle):
     compare_verify(oracle, w2, om2, _run(P, oracle, w2, om2))
 
 
+def test_topk_with_excluded_tokens(P, oracle):
+    """Rows that already hold -inf logits (tokens excluded upstream), alone and under guidance where the
+    conditional and unconditional entries may both be -inf; fewer finite entries than k in one row."""
+    for cfg, dtype, V, k in ((3, "bf16", 16384, 1000), (3, "f32", 16384, 300), (2, "bf16", 16384, 64),
+                             (3, "bf16", 6000, 5000)):
+        w = make_workload(cfg, device="cuda", B=3, L=3, V=V, dtype=dtype, top_k=k if cfg == 3 else None)
+        w.top_k = k
+        g = torch.Generator(device="cuda").manual_seed(5)
+        drop = torch.rand((3, 4, V), device="cuda", generator=g) < 0.3
+        ninf = float("-inf")
+        w.target[drop] = ninf
+        w.draft[drop[:, :3]] = ninf
+        if w.target_uncond is not None:
+            w.target_uncond[drop] = ninf                 # same tokens excluded on both inputs
+            w.draft_uncond[drop[:, :3]] = ninf
+        # one target row keeps fewer finite entries than k
+        w.target[0, 1, 40:] = ninf
+        if w.target_uncond is not None:
+            w.target_uncond[0, 1, 40:] = ninf
+        om = _omega(P, w)
+        print("case excluded", cfg, dtype, V, k, flush=True)
+        st = compare_verify(oracle, w, om, _run(P, oracle, w, om))
+        assert st["tau_exempt"] + st["token_exempt"] <= 1
+
+
 def test_topk_long_rows_are_refused(P):
     w = make_workload(3, device="cuda", B=1, L=1, V=20000, top_k=10)
     om = torch.ones(1, device="cuda")

@@ -372,3 +372,27 @@ def test_transform_topk_ties_and_guidance(oracle):
     out = oracle.transform_row(lc, lu, 4.0, 1.0, 10)
     guided = lu + np.float32(4.0) * (lc - lu)
     np.testing.assert_array_equal(np.isfinite(out), guided >= np.sort(guided)[::-1][9])
+
+
+def test_transform_keeps_excluded_tokens_excluded(oracle):
+    """A token that carries -inf on both inputs (excluded upstream) stays -inf under guidance, also
+    when truncation sorts the row; the k-th largest is taken over what remains."""
+    rng = np.random.default_rng(31)
+    V = 200
+    lu = rng.standard_normal(V).astype(np.float32)
+    lc = (lu + rng.standard_normal(V).astype(np.float32)).astype(np.float32)
+    gone = rng.random(V) < 0.3
+    lc[gone] = -np.inf
+    lu[gone] = -np.inf
+    guided = np.where(gone, -np.inf, lu + np.float32(4.0) * (lc - np.where(gone, 0, lu))).astype(np.float32)
+    guided[gone] = -np.inf
+    out = oracle.transform_row(lc, lu, 4.0, 1.0, 0)
+    assert not np.isnan(out).any()
+    np.testing.assert_array_equal(out, guided.astype(np.float64))
+    for k in (1, 10, int((~gone).sum()), V):
+        out = oracle.transform_row(lc, lu, 4.0, 1.0, k)
+        assert not np.isnan(out).any()
+        thr = np.sort(guided)[::-1][k - 1]            # -inf once k exceeds the finite entries
+        np.testing.assert_array_equal(np.isfinite(out), (guided >= thr) & ~gone)
+        p = oracle.softmax(out)
+        assert abs(p.sum() - 1) < 1e-12 and np.all(p[gone] == 0)

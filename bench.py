@@ -53,6 +53,10 @@ def parse():
     ap.add_argument("--lantern", action="store_true",
                     help="also time cool_sd_verify_lantern (k = 10 synthetic neighbours, lambda = 2, G* resampling) on "
                          "the timed workloads")
+    ap.add_argument("--concurrent", action="store_true",
+                    help="also time the same steps issued on two streams (independent batches, each stream with its "
+                         "own workspace and outputs), so that one call's per-sequence kernel overlaps the next "
+                         "call's statistics kernel; reported as extra keys, `value` stays the one-stream figure")
     ap.add_argument("--kernel-samples", type=int, default=200, help="instrumented calls for the per-kernel time")
     ap.add_argument("--counter-run", action="store_true",
                     help="for rocprofv3 --pmc: a plain device copy of known size (the counters' reference), then "
@@ -131,6 +135,46 @@ class Runner:
         wall = time.perf_counter() - t0
         return done, wall, e0.elapsed_time(e1) * 1e-3
 
+
+    def time_two_streams(self, passes=8):
+        """Throughput when the pool's batches (independent of each other) are verified on two streams:
+        even steps on one, odd steps on the other, each with its own workspace and outputs, captured
+        as one graph with a fork and a join.  Returns seconds per step."""
+        pkg, torch = self.pkg, self.torch
+        ws2 = torch.empty_like(self.ws)
+        al2, nt2 = torch.zeros_like(self.accept_len), torch.zeros_like(self.next_token)
+        side = torch.cuda.Stream()
+
+        def body():
+            main = torch.cuda.current_stream()
+            side.wait_stream(main)
+            for i, w in enumerate(self.pool):
+                if i % 2 == 0:
+                    self.step(i)
+                else:
+                    with torch.cuda.stream(side):
+                        pkg.cool_sd_verify(self.params, w.target, w.target_uncond, w.draft, w.draft_uncond,
+                                           w.draft_tokens, self.omega, w.u_accept, w.u_resample, al2, nt2,
+                                           None, None, None, None, ws2)
+            main.wait_stream(side)
+        warm = torch.cuda.Stream()
+        warm.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(warm):
+            body()
+        torch.cuda.current_stream().wait_stream(warm)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            body()
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(passes):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / (passes * len(self.pool))
 
     def kernel_times(self, n):
         """Average duration of the statistics kernel and of the whole call, over the pool.
@@ -368,6 +412,10 @@ def main():
                 extra[name]["diagnostics"] = time_diagnostics(rr)
             if a.lantern:
                 extra[name]["lantern"] = time_lantern(rr)
+            if a.concurrent:
+                sec = rr.time_two_streams(passes=4)
+                extra[name]["two_streams"] = {"us_per_step": sec * 1e6, "tokens_per_s": rr.B * rr.L / sec,
+                                              "whole_call_GBps": rr.bytes_per_step / sec / 1e9}
             del rr
             torch.cuda.empty_cache()
         line["other_workloads"] = extra
@@ -375,6 +423,10 @@ def main():
         line["diagnostics"] = time_diagnostics(r)
     if a.lantern:
         line["lantern"] = time_lantern(r)
+    if a.concurrent:
+        sec = r.time_two_streams()
+        line["two_streams"] = {"us_per_step": sec * 1e6, "tokens_per_s": r.B * r.L / sec,
+                               "whole_call_GBps": r.bytes_per_step / sec / 1e9}
     if not a.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(r, a.cpu_seconds)
     print(json.dumps(line), flush=True)

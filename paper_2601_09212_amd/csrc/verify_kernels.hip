@@ -174,7 +174,7 @@ __global__ __launch_bounds__(TPB, 6) void row_stats_topk_kernel(const KArgs a) {
   topk_prepare(ts);                                     // the barrier inside topk_threshold orders it
   RowRegs<DT, true, kVW> x;
   // vector k of thread t is vector k*TPB + t of the row
-  load_chunk<DT, true, AL, kVW, TPB, 1, 2, GD>(x, rw.cond, rw.uncond, 0, a.V, a.cfg_scale, a.inv_T, -INFINITY);
+  load_chunk<DT, true, AL, kVW, TPB, 1, 4, GD>(x, rw.cond, rw.uncond, 0, a.V, a.cfg_scale, a.inv_T, -INFINITY);
   // the raw logits of x~_i, requested now and used at the very end
   int tok = load_draft_token(a, rw);
   float tok_c = 0.f, tok_u = 0.f;

@@ -99,3 +99,68 @@ def test_acceptance_rises_with_lambda(P):
             assert (gpu["f"] >= prev_f).all() and (gpu["accept_len"] >= prev_tau).all()
         prev_f, prev_tau = gpu["f"], gpu["accept_len"]
     assert prev_tau.sum() > 0
+
+
+@pytest.mark.parametrize("cfg,n_check,mode", [(2, None, 0), (2, None, 2), (4, 48, 0), (4, 48, 2), (5, 12, 0)])
+def test_full_size_configurations(P, oracle, cfg, n_check, mode):
+    """Benchmark-size batches with the comparison system's setting (k = 10, lambda = 2); every
+    sequence, or a seeded sample of them, against the oracle."""
+    from tests.parity_util import subset
+    print("full lantern cfg", cfg, mode, flush=True)
+    w = make_workload(cfg, device="cuda")
+    nbr = make_neighbor_table(w.V, 10, device="cuda", seed=11)
+    gpu = _run(P, w, nbr, 2.0, mode)
+    assert gpu["accept_len"].min() >= 0 and gpu["accept_len"].max() <= w.L
+    assert gpu["next_token"].min() >= 0 and gpu["next_token"].max() < w.V
+    if n_check is None:
+        st = compare_verify_lantern(oracle, w, nbr.cpu().numpy(), 2.0, gpu, resample_mode=mode)
+    else:
+        idx = np.sort(np.random.default_rng(cfg).choice(w.B, n_check, replace=False))
+        st = compare_verify_lantern(oracle, subset(w, idx), nbr.cpu().numpy(), 2.0,
+                                    {k: v[idx] for k, v in gpu.items()}, resample_mode=mode)
+    print("exemptions", st, flush=True)
+    assert st["tau_exempt"] + st["token_exempt"] + st["set_exempt"] <= 2
+
+
+def test_repeat_calls_and_graph_replays_are_identical(P):
+    """Same inputs, shared workspace: every eager call and every replay of a captured call returns
+    the same bits (no kernel depends on the order in which workgroups run)."""
+    w = make_workload(2, device="cuda", B=16, L=8, V=16384)
+    nbr = make_neighbor_table(16384, 10, device="cuda", seed=5)
+    params = P.make_params(w.target, w.draft, resample_mode=P.COOL_SD_RESAMPLE_LANTERN)
+    ws = torch.empty(P.cool_sd_workspace_bytes(params), dtype=torch.uint8, device="cuda")
+    a = torch.zeros(w.B, dtype=torch.int32, device="cuda")
+    n = torch.zeros_like(a)
+    f = torch.zeros((w.B, w.L), device="cuda")
+    r = torch.zeros(w.B, device="cuda")
+
+    def call():
+        P.cool_sd_verify_lantern(params, w.target, None, w.draft, None, w.draft_tokens, nbr, 10, 0.3, w.u_accept,
+                                 w.u_resample, a, n, None, None, f, r, None, None, ws)
+    call()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (a, n, f, r)]
+    for _ in range(3):
+        for t in (a, n, f, r):
+            t.zero_()
+        call()
+        torch.cuda.synchronize()
+        for t, e in zip((a, n, f, r), ref):
+            assert torch.equal(t, e)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        call()
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        call()
+    for _ in range(3):
+        for t in (a, n, f, r):
+            t.zero_()                      # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for t, e in zip((a, n, f, r), ref):
+            assert torch.equal(t, e)

@@ -398,38 +398,63 @@ __device__ __forceinline__ int chunk_select(const RowRegs<DT, XF, kT>& rt, const
 // Leaves the combined statistics (Ct, St, Cd, Sd) of the row that will be sampled from --
 // position tau+1, or the bonus row L+1 -- in sm.rowstat and returns tau.  With `emit` it also
 // writes accept_len and the per-position diagnostics.
+// Position i of sequence b: statistics of its row pair (or of the bonus row alone), f_i of
+// Eq. relax and the accept test.  Returns true when x~_i is rejected.  With `emit` it writes the
+// per-position diagnostics.
+__device__ __forceinline__ bool eval_position(const KArgs& a, int b, int i, bool emit, float& Ct, float& St,
+                                              float& Cd, float& Sd) {
+  const int rps = a.L + a.has_bonus;
+  const int rt_ = b * rps + i;
+  combine_row(a, rt_, Ct, St);
+  if (i >= a.L) return false;                       // the bonus row has no draft token
+  const int rd_ = a.rows_t + b * a.L + i;
+  combine_row(a, rd_, Cd, Sd);
+  // logits of the draft token, left by the statistics kernel
+  const float lt = a.tok_logit[rt_], ld = a.tok_logit[rd_];
+  // exponents of p(x~) and q(x~) in base-2 units; the ratio p/q is formed from their
+  // difference so that it survives when both probabilities underflow fp32
+  const float et = __fmaf_rn(lt, kLog2e, -Ct), ed = __fmaf_rn(ld, kLog2e, -Cd);
+  const float ratio = __fmul_rn(exp2_fast(__fsub_rn(et, ed)), Sd / St);
+  const float omega = a.omega[int64_t(b) * a.om_sb + i];
+  // f = min{1, omega p/q}; a token the draft excludes (q = 0) has f = 1, also at 0/0
+  const float fi = (ld == -INFINITY) ? 1.f : ((omega > 0.f) ? fminf(1.f, __fmul_rn(omega, ratio)) : 0.f);
+  if (emit) {
+    const int64_t o = int64_t(b) * a.L + i;
+    if (a.p_tok) a.p_tok[o] = exp2_fast(et) / St;
+    if (a.q_tok) a.q_tok[o] = exp2_fast(ed) / Sd;
+    if (a.f) a.f[o] = fi;
+  }
+  return !(a.u_acc[int64_t(b) * a.L + i] <= fi);
+}
+
 template <int DT, bool XF, int TPB>
 __device__ __forceinline__ int find_tau(const KArgs& a, int b, bool emit, int* pick /*[TPB/64]*/, float4* rowstat) {
   const int rps = a.L + a.has_bonus;
+  if (rps <= 64) {
+    // the usual case: one wave holds every position, the first rejection is the lowest set bit
+    // of a ballot, and one barrier hands tau and the sampled row's statistics to the others
+    if (threadIdx.x < 64) {
+      const int i = threadIdx.x;
+      float Ct = kRefFloor, St = 0.f, Cd = kRefFloor, Sd = 0.f;
+      bool rej = false;
+      if (i < rps) rej = eval_position(a, b, i, emit, Ct, St, Cd, Sd);
+      const unsigned long long br = __ballot(rej);
+      const int w = br ? __ffsll((long long)br) - 1 : a.L;
+      if (i == w) *rowstat = make_float4(Ct, St, Cd, Sd);      // position w, or the bonus row when w == L
+      if (i == 0) {
+        pick[0] = w;
+        if (emit) a.accept_len[b] = w;
+      }
+    }
+    __syncthreads();
+    return pick[0];
+  }
   int first = a.L;
   for (int i0 = 0; i0 < rps; i0 += TPB) {
     const int i = i0 + threadIdx.x;
     float Ct = kRefFloor, St = 0.f, Cd = kRefFloor, Sd = 0.f;
-    if (i < rps) {
-      const int rt_ = b * rps + i;
-      combine_row(a, rt_, Ct, St);
-      if (i < a.L) {
-        const int rd_ = a.rows_t + b * a.L + i;
-        combine_row(a, rd_, Cd, Sd);
-        // logits of the draft token, left by the statistics kernel
-        const float lt = a.tok_logit[rt_], ld = a.tok_logit[rd_];
-        // exponents of p(x~) and q(x~) in base-2 units; the ratio p/q is formed from their
-        // difference so that it survives when both probabilities underflow fp32
-        const float et = __fmaf_rn(lt, kLog2e, -Ct), ed = __fmaf_rn(ld, kLog2e, -Cd);
-        const float ratio = __fmul_rn(exp2_fast(__fsub_rn(et, ed)), Sd / St);
-        const float omega = a.omega[int64_t(b) * a.om_sb + i];
-        // f = min{1, omega p/q}; a token the draft excludes (q = 0) has f = 1, also at 0/0
-        const float fi = (ld == -INFINITY) ? 1.f : ((omega > 0.f) ? fminf(1.f, __fmul_rn(omega, ratio)) : 0.f);
-        if (!(a.u_acc[int64_t(b) * a.L + i] <= fi)) first = min(first, i);
-        if (emit) {
-          const int64_t o = int64_t(b) * a.L + i;
-          if (a.p_tok) a.p_tok[o] = exp2_fast(et) / St;
-          if (a.q_tok) a.q_tok[o] = exp2_fast(ed) / Sd;
-          if (a.f) a.f[o] = fi;
-        }
-      }
-    }
-    // the first rejection among positions < i0 + 256 is final once it is below that bound
+    if (i < rps && eval_position(a, b, i, emit, Ct, St, Cd, Sd)) first = min(first, i);
+    // the first rejection among positions < i0 + TPB is final once it is below that bound
     int w = wave_min_i(first);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) pick[threadIdx.x >> 6] = w;
@@ -521,13 +546,16 @@ __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, cons
     __syncthreads();                                  // earlier readers of scan_tot are done
     if (lane == 63) sm.scan_tot[wv] = incl_w;
     __syncthreads();
-    float woff = 0.f;
-    R = 0.f;
-#pragma unroll
-    for (int w = 0; w < kWavesW; ++w) {
-      if (w == wv) woff = R;
-      R = __fadd_rn(R, sm.scan_tot[w]);
-    }
+    // every wave scans the 16 wave totals for itself (one LDS read per lane, one row of DPP
+    // shifts): its own offset is the exclusive value at lane wv, R the inclusive value at lane 15
+    static_assert(kWavesW == 16, "one DPP row holds the wave totals");
+    float tot = lane < kWavesW ? sm.scan_tot[lane] : 0.f;
+    tot = __fadd_rn(tot, dpp_f<kDppRowShr1>(tot));
+    tot = __fadd_rn(tot, dpp_f<kDppRowShr2>(tot));
+    tot = __fadd_rn(tot, dpp_f<kDppRowShr4>(tot));
+    tot = __fadd_rn(tot, dpp_f<kDppRowShr8>(tot));
+    R = lane_f(tot, kWavesW - 1);
+    const float woff = wv == 0 ? 0.f : lane_f(tot, wv - 1);
     incl = __fadd_rn(woff, incl_w);
     excl = __fadd_rn(woff, excl_w);
     if (R > 0.f || k.mode == kModeP) break;
@@ -564,18 +592,21 @@ __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, cons
     }
     if (vs < 0) { vs = vlast; vbase = vbase_last; }
     const float v3 = v2 - vbase;
+    float rv[kE];                 // the selected vector's masses
+#pragma unroll
+    for (int e = 0; e < kE; ++e) {
+      rv[e] = r[e];
+#pragma unroll
+      for (int q = 1; q < kVW; ++q) rv[e] = (q == vs) ? r[q * kE + e] : rv[e];
+    }
     int found = -1, last = 0;
     float run = 0.f;
 #pragma unroll
-    for (int q = 0; q < kVW; ++q) {
-#pragma unroll
-      for (int e = 0; e < kE; ++e) {
-        const float re = r[q * kE + e];
-        if (q == vs && re > 0.f) {
-          last = e;
-          run = __fadd_rn(run, re);
-          if (found < 0 && run > v3) found = e;
-        }
+    for (int e = 0; e < kE; ++e) {
+      if (rv[e] > 0.f) {
+        last = e;
+        run = __fadd_rn(run, rv[e]);
+        if (found < 0 && run > v3) found = e;
       }
     }
     if (found < 0) found = last;

@@ -512,11 +512,12 @@ struct SmemW {
 // One draw from the resampling law of a row pair that 1024 threads hold in registers (thread t
 // owns the kVW consecutive vectors t*kVW ..): per-vector masses, one block scan, then vector and
 // element inside the thread whose interval contains u*R.  If the law has no mass (no rejection
-// is possible at this position) it falls back to p.  Returns the token in every thread, R = the
-// law's mass.
+// is possible at this position) it falls back to p.  The token is returned in ONE thread, the one
+// that found it (writer = true there), so that no barrier is spent on handing it around; R, the
+// law's mass, is known to every thread.
 template <int DT, bool XF, int kVW, bool LAN = false>
 __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, const RowRegs<DT, XF, kVW>& rd,
-                                            ResidCoef k, float u, int V, SmemW& sm, float& R,
+                                            ResidCoef k, float u, int V, SmemW& sm, float& R, bool& writer,
                                             const LanPatch lp = LanPatch{0u, -1, 1.f}) {
   constexpr int kE = Vec<DT>::kE;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -571,12 +572,13 @@ __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, cons
     sm.pick[wv] = bh ? (wv * 64 + __ffsll((long long)bh) - 1) : 0x7fffffff;
     sm.pick_last[wv] = bp ? (wv * 64 + 63 - __clzll((long long)bp)) : -1;
   }
-  if (threadIdx.x == 0) sm.token = 0;
   __syncthreads();
   int win = 0x7fffffff, last_pos = -1;
 #pragma unroll
   for (int w = 0; w < kWavesW; ++w) { win = min(win, sm.pick[w]); last_pos = max(last_pos, sm.pick_last[w]); }
   if (win == 0x7fffffff) win = last_pos;
+  writer = win >= 0 ? (int)threadIdx.x == win : threadIdx.x == 0;   // a row without any mass: token 0
+  int token = 0;
   if ((int)threadIdx.x == win) {
     // vector, then element: same rule at each level
     const float v2 = v - excl;
@@ -610,10 +612,8 @@ __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, cons
       }
     }
     if (found < 0) found = last;
-    sm.token = (win * kVW + vs) * kE + found;
+    token = (win * kVW + vs) * kE + found;
   }
-  __syncthreads();
-  const int token = sm.token;
   return token >= V ? V - 1 : token;
 }
 
@@ -667,6 +667,7 @@ __global__ __launch_bounds__(kThreadsW) void sequence_whole_kernel(const KArgs a
 
   float R;
   int token;
+  bool writer;
   if constexpr (LAN) {
     // Eq. g_lantern: the law is [P^{k,lambda} - q]_+ around the rejected token x~_j; this thread
     // owns the kVW*kE consecutive tokens from first_tok on
@@ -689,11 +690,11 @@ __global__ __launch_bounds__(kThreadsW) void sequence_whole_kernel(const KArgs a
         if (dn >= 0 && dn < kVW * kE) lp.zmask |= 1u << dn;
       }
     }
-    token = sample_whole<DT, XF, kVW, true>(rt, rd, k, a.u_res[b], a.V, sm, R, lp);
+    token = sample_whole<DT, XF, kVW, true>(rt, rd, k, a.u_res[b], a.V, sm, R, writer, lp);
   } else {
-    token = sample_whole<DT, XF, kVW>(rt, rd, k, a.u_res[b], a.V, sm, R);
+    token = sample_whole<DT, XF, kVW>(rt, rd, k, a.u_res[b], a.V, sm, R, writer);
   }
-  if (threadIdx.x == 0) {
+  if (writer) {
     a.next_token[b] = token;
     if (a.resid_mass) a.resid_mass[b] = R;
   }
@@ -943,8 +944,9 @@ __global__ __launch_bounds__(kThreadsW) void sequence_early_exit_kernel(const KA
   ResidCoef k{Ct, 1.f / St, Cd, bonus ? 1.f : 1.f / Sd, bonus ? 1.f : sm.om[j],
               bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
   float R;
-  const int token = sample_whole<DT, XF, kVW>(rt, rd, k, a.u_res[b], a.V, sm.w, R);
-  if (tid == 0) {
+  bool writer;
+  const int token = sample_whole<DT, XF, kVW>(rt, rd, k, a.u_res[b], a.V, sm.w, R, writer);
+  if (writer) {
     a.next_token[b] = token;
     if (a.resid_mass) a.resid_mass[b] = R;
   }

@@ -262,6 +262,19 @@ def time_diagnostics(r, passes=6):
             "frac": nbytes / sec / 1e9 / HBM_PEAK_GBS}
 
 
+def run_lantern(r, n, k=10, lam=2.0):
+    """n direct cool_sd_verify_lantern calls cycling through the pool (for profiler runs)."""
+    from workloads import make_neighbor_table
+    pkg, torch = r.pkg, r.torch
+    nbr = make_neighbor_table(r.V, k, device="cuda", seed=11)
+    for i in range(n):
+        w = r.pool[i % len(r.pool)]
+        pkg.cool_sd_verify_lantern(r.params, w.target, w.target_uncond, w.draft, w.draft_uncond, w.draft_tokens, nbr,
+                                   k, lam, w.u_accept, w.u_resample, r.accept_len, r.next_token, None, None, None,
+                                   None, None, None, r.ws)
+    torch.cuda.synchronize()
+
+
 def time_lantern(r, k=10, lam=2.0, passes=6):
     """Average duration of one cool_sd_verify_lantern call over the pool, replayed from a HIP graph.
     The neighbour table is synthetic ([V, k] distinct random tokens per row)."""
@@ -352,6 +365,8 @@ def main():
         torch.cuda.synchronize()
         if a.diagnostics:
             run_diagnostics(r, a.steps)
+        if a.lantern:
+            run_lantern(r, a.steps)
         print(json.dumps({"counter_run": a.workload, "steps": a.steps, "copy_bytes_each_way": src.numel() * 4,
                           "bytes_per_step": r.bytes_per_step}))
         return

@@ -60,7 +60,8 @@ typedef enum {
   COOL_SD_EINVAL = -1,       /* null pointer, bad shape / stride / dtype / option           */
   COOL_SD_EWORKSPACE = -2,   /* workspace missing, misaligned or smaller than required       */
   COOL_SD_ELAUNCH = -3,      /* the HIP runtime refused a launch                             */
-  COOL_SD_EUNSUPPORTED = -4  /* valid request the kernels do not implement (see top_k)       */
+  COOL_SD_EUNSUPPORTED = -4  /* valid request the kernels do not implement
+                                (see cool_sd_verify_lantern)                                  */
 } cool_sd_status;
 
 /* Options of cool_sd_verify (cool_sd_params.flags). */
@@ -91,7 +92,8 @@ typedef struct {
   int32_t has_bonus;     /* 1: target holds L+1 rows per sequence; 0: L rows, no bonus token  */
   int32_t top_k;         /* 0 = off; else 1..V: keep logits >= the k-th largest of the row
                             (ties kept), on BOTH models, after guidance and temperature.
-                            Implemented for V <= 16384 (else COOL_SD_EUNSUPPORTED)            */
+                            Rows of at most 16384 logits are selected inside the statistics
+                            kernel; longer rows by three radix passes over the row first     */
   float cfg_scale;       /* s of l = l_u + s (l_c - l_u); used iff the *_uncond pointers are
                             given (classifier-free guidance, App. implementation details)     */
   float temperature;     /* > 0; logits are multiplied by fl32(1/temperature); 1 = off        */

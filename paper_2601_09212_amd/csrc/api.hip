@@ -14,7 +14,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t seq_stat, chunk_R, thr, tok_logit, rowstat, part, diag_part, lan, total;
+  size_t seq_stat, chunk_R, thr, tok_logit, rowstat, part, diag_part, lan, rk_hist, rk_state, total;
 };
 
 // cool_sd_verify_lantern only
@@ -29,8 +29,9 @@ struct LanternArgs {
 // rows: all logit rows (target + draft); c1: statistics chunks per row; C: sampling chunks per row.
 // pairs x CD: (alpha, beta) chunk sums of the diagnostics call (0 pairs: region absent).
 // lan_pairs: B L of a call with neighbour aggregation (its omega and member counts), else 0.
+// rk_rows: rows of a call that selects top-k thresholds by radix passes (long rows), else 0.
 Layout make_layout(int64_t B, int64_t rows, int64_t c1, int64_t C, int64_t pairs = 0, int64_t CD = 0,
-                   int64_t lan_pairs = 0) {
+                   int64_t lan_pairs = 0, int64_t rk_rows = 0) {
   Layout o{};
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes); return at; };
@@ -42,6 +43,8 @@ Layout make_layout(int64_t B, int64_t rows, int64_t c1, int64_t C, int64_t pairs
   o.part = take(size_t(rows) * c1 * 8);
   o.diag_part = take(size_t(pairs) * CD * 8);
   o.lan = take(size_t(lan_pairs) * 8);
+  o.rk_hist = take(size_t(rk_rows) * 2048 * 4);
+  o.rk_state = take(size_t(rk_rows) * 8);
   o.total = off;
   return o;
 }
@@ -54,7 +57,7 @@ Chunking pick_chunking(const cool_sd_params* p, int64_t rows) {
   const int kE = (p->dtype == COOL_SD_BF16) ? 8 : 4;
   const bool one_chunk = p->V <= csd::kChunk;     // the sampled row fits one workgroup's registers
   int nt = kT / 2;
-  if (p->top_k > 0) nt = kT;
+  if (p->top_k > 0 && one_chunk) nt = kT;      // the top-k kernel holds a whole row
   else if (one_chunk && rows * ((p->V + 8191) / 8192) < 2048) nt = kT / 4;
   Chunking c;
   c.nt1 = nt;
@@ -105,12 +108,13 @@ int run(const cool_sd_params* p, bool resample_only,
   const int64_t L = resample_only ? 1 : p->L;
   const int hb = resample_only ? 0 : p->has_bonus;
   const int64_t rows = resample_only ? p->B : int64_t(p->B) * (L + hb);
-  if (p->top_k > 0 && p->V > csd::kChunk) return COOL_SD_EUNSUPPORTED;
   if (lan && p->resample_mode == COOL_SD_RESAMPLE_LANTERN && p->V > csd::kChunk) return COOL_SD_EUNSUPPORTED;
   const int64_t rows_t = rows, rows_d = d ? int64_t(p->B) * L : 0;
   const Chunking ch = pick_chunking(p, rows_t + rows_d);
   const int64_t C = ch.c2;
-  const Layout lay = make_layout(p->B, rows_t + rows_d, ch.c1, C, 0, 0, lan ? int64_t(p->B) * L : 0);
+  const bool radix = p->top_k > 0 && p->V > csd::kChunk;
+  const Layout lay = make_layout(p->B, rows_t + rows_d, ch.c1, C, 0, 0, lan ? int64_t(p->B) * L : 0,
+                                 radix ? rows_t + rows_d : 0);
   if (!ws || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0 || ws_bytes < lay.total) return COOL_SD_EWORKSPACE;
 
   const int kE = (p->dtype == COOL_SD_BF16) ? 8 : 4;
@@ -166,6 +170,8 @@ int run(const cool_sd_params* p, bool resample_only,
   a.tok_logit = reinterpret_cast<float*>(w + lay.tok_logit);
   a.part = reinterpret_cast<float2*>(w + lay.part);
   a.rowstat = reinterpret_cast<float2*>(w + lay.rowstat);
+  a.rk_hist = reinterpret_cast<uint32_t*>(w + lay.rk_hist);
+  a.rk_state = reinterpret_cast<uint32_t*>(w + lay.rk_state);
   const bool direct = ch.c1 <= 4;
   a.stat = direct ? a.part : a.rowstat;
   a.cs = direct ? (int32_t)ch.c1 : 1;
@@ -184,12 +190,12 @@ int run(const cool_sd_params* p, bool resample_only,
 // target tensor has one, is skipped through the strides.
 int run_diag(const cool_sd_params* p, const void* t, const void* tu, const void* d, const void* du,
              const float* omega, float* alpha, float* beta, void* ws, size_t ws_bytes, void* stream) {
-  if (p->top_k > 0 && p->V > csd::kChunk) return COOL_SD_EUNSUPPORTED;
   const int64_t pairs = int64_t(p->B) * p->L;
   const Chunking ch = pick_chunking(p, 2 * pairs);
   const bool local = p->top_k == 0 && p->V <= csd::kChunk;
   const int64_t CD = local ? 1 : (int64_t(p->V) + 8191) / 8192;
-  const Layout lay = make_layout(p->B, 2 * pairs, ch.c1, 1, pairs, CD);
+  const bool radix = p->top_k > 0 && p->V > csd::kChunk;
+  const Layout lay = make_layout(p->B, 2 * pairs, ch.c1, 1, pairs, CD, 0, radix ? 2 * pairs : 0);
   if (!ws || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0 || ws_bytes < lay.total) return COOL_SD_EWORKSPACE;
 
   const int kE = (p->dtype == COOL_SD_BF16) ? 8 : 4;
@@ -217,6 +223,8 @@ int run_diag(const cool_sd_params* p, const void* t, const void* tu, const void*
   a.part = reinterpret_cast<float2*>(w + lay.part);
   a.rowstat = reinterpret_cast<float2*>(w + lay.rowstat);
   a.diag_part = reinterpret_cast<float2*>(w + lay.diag_part);
+  a.rk_hist = reinterpret_cast<uint32_t*>(w + lay.rk_hist);
+  a.rk_state = reinterpret_cast<uint32_t*>(w + lay.rk_state);
   const bool direct = ch.c1 <= 4;
   a.stat = direct ? a.part : a.rowstat;
   a.cs = direct ? (int32_t)ch.c1 : 1;
@@ -270,7 +278,8 @@ size_t cool_sd_workspace_bytes(const cool_sd_params* p) {
   const int64_t c1_max = (int64_t(p->V) + 4095) / 4096;
   (void)ch;
   const int64_t pairs = full ? int64_t(p->B) * L : 0;       // cool_sd_diagnostics: chunks of 8192 logits
-  return make_layout(p->B, rows, c1_max, c1_max, pairs, (int64_t(p->V) + 8191) / 8192, pairs).total;
+  const bool radix = p->top_k > 0 && p->V > csd::kChunk;
+  return make_layout(p->B, rows, c1_max, c1_max, pairs, (int64_t(p->V) + 8191) / 8192, pairs, radix ? rows : 0).total;
 }
 
 int cool_sd_workspace_init(void* workspace_dev, size_t workspace_bytes, void* hip_stream) {

@@ -45,6 +45,9 @@ struct KArgs {
   int32_t accept_combines;  // long rows: accept_kernel combines the chunk statistics of its own rows (no combine_rows launch)
   float4* seq_stat;         // [B]           statistics of the sampled row (several-chunk path)
   float* chunk_R;           // [B, nchunks]  residual mass per chunk of the sampled row  (nchunks > 1)
+  // top-k on rows longer than one workgroup: radix-select state in the workspace
+  uint32_t* rk_hist;        // [rows_t + rows_d, 2048] digit counts of the current pass
+  uint32_t* rk_state;       // [rows_t + rows_d, 2]    key bits fixed so far, rank still to find
   // aggregated acceptance over latent neighbours (nbr == nullptr: off)
   const int32_t* nbr;       // [V, lan_k] neighbour table, nearest first
   int32_t lan_k;

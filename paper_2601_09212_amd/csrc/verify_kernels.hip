@@ -113,8 +113,13 @@ __global__ __launch_bounds__(kThreads, 3) void row_stats_kernel(const KArgs a) {
   const int r = rw.r;
   const int64_t base = int64_t(c) * (NT * kThreads * kE);
 
+  // rows longer than one workgroup under top-k: the threshold was selected by the radix passes
+  float thr = -INFINITY;
+  if constexpr (XF) {
+    if (a.top_k > 0) thr = a.thr[r];
+  }
   RowRegs<DT, XF, NT> x;
-  load_chunk<DT, XF, AL, NT>(x, rw.cond, rw.uncond, base, a.V, a.cfg_scale, a.inv_T, -INFINITY);
+  load_chunk<DT, XF, AL, NT>(x, rw.cond, rw.uncond, base, a.V, a.cfg_scale, a.inv_T, thr);
   int tok = load_draft_token(a, rw);     // after the chunk's loads in program order, used after them
   // the (transformed) logit of x~_i for the accept test of the next kernel, taken from the
   // registers of the thread that holds it: element e of vector (tile k, thread t) is token
@@ -206,6 +211,89 @@ __global__ __launch_bounds__(TPB, 6) void row_stats_topk_kernel(const KArgs a) {
     if (tok >= 0) {
       const float l = transform_logit(tok_c, tok_u, rw.uncond != nullptr, a.cfg_scale, a.inv_T);
       a.tok_logit[r] = (l >= thr) ? l : -INFINITY;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------- top-k, long rows
+// Rows that do not fit one workgroup: the k-th largest transformed logit is found by a radix
+// select on the order-preserving 32-bit key in three passes of 11, 11 and 10 bits.  A pass is two
+// launches: every chunk's workgroup counts, in LDS, the digit of its values whose higher bits
+// match what earlier passes fixed and adds the non-empty buckets to the row's histogram in the
+// workspace (integer atomics: the sums do not depend on the order); then one workgroup per row
+// walks the histogram from the top, fixes the digit that holds the k-th largest and clears the
+// histogram for the next pass.  After the third pass the key is exact, ties included, and the
+// ordinary statistics kernel masks with its value.  Elements beyond the end of a row count as
+// -inf: they are the smallest keys and never change which value is the k-th largest among at
+// least k real ones.
+constexpr int kRadixBuckets = 2048;
+__device__ __forceinline__ int radix_shift(int pass) { return pass == 0 ? 21 : (pass == 1 ? 10 : 0); }
+__device__ __forceinline__ int radix_bits(int pass) { return pass == 2 ? 10 : 11; }
+
+template <int DT, int AL, int NT, bool G3>
+__global__ __launch_bounds__(kThreads) void topk_radix_hist_kernel(const KArgs a, int pass) {
+  constexpr int kE = Vec<DT>::kE;
+  __shared__ uint32_t hist[kRadixBuckets];
+  const int C1 = a.c1;
+  const int lin = G3 ? 0 : blockIdx.x / C1, c = G3 ? blockIdx.x : blockIdx.x - lin * C1;
+  const RowRef rw = row_ref<DT, G3>(a, lin);
+  const int r = rw.r;
+  for (int i = threadIdx.x; i < kRadixBuckets; i += kThreads) hist[i] = 0u;
+  RowRegs<DT, true, NT> x;
+  load_chunk<DT, true, AL, NT>(x, rw.cond, rw.uncond, int64_t(c) * (NT * kThreads * kE), a.V, a.cfg_scale, a.inv_T,
+                               -INFINITY);
+  const int shift = radix_shift(pass), bits = radix_bits(pass);
+  const uint32_t prefix = pass > 0 ? a.rk_state[2 * r] : 0u;
+  const int hshift = shift + bits;                        // bits above the digit, fixed by earlier passes
+  __syncthreads();
+#pragma unroll
+  for (int n = 0; n < NT * kE; ++n) {
+    const uint32_t key = order_key(__uint_as_float(x.w[n]));
+    const bool match = pass == 0 || (key >> hshift) == (prefix >> hshift);
+    if (match) atomicAdd(&hist[(key >> shift) & ((1u << bits) - 1u)], 1u);
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < kRadixBuckets; i += kThreads) {
+    const uint32_t h = hist[i];
+    if (h) atomicAdd(&a.rk_hist[int64_t(r) * kRadixBuckets + i], h);
+  }
+}
+
+// One workgroup per row: the digit of this pass that holds the k-th largest key.  Thread t owns
+// the eight buckets 2047 - 8t .. 2040 - 8t, so that ascending thread order is descending key order.
+__global__ __launch_bounds__(kThreads) void topk_radix_select_kernel(const KArgs a, int pass) {
+  __shared__ uint32_t wave_tot[kWaves];
+  const int r = blockIdx.x;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  uint32_t* hist = a.rk_hist + int64_t(r) * kRadixBuckets;
+  const uint32_t k_rem = pass == 0 ? (uint32_t)a.top_k : a.rk_state[2 * r + 1];
+  const uint32_t prefix = pass == 0 ? 0u : a.rk_state[2 * r];
+  uint32_t h[8], local = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int bkt = kRadixBuckets - 1 - (threadIdx.x * 8 + j);
+    h[j] = hist[bkt];
+    hist[bkt] = 0u;                                       // ready for the next pass / the next call
+    local += h[j];
+  }
+  const uint32_t incl = wave_scan_incl_u32(local);
+  if (lane == 63) wave_tot[wv] = incl;
+  __syncthreads();
+  uint32_t before = incl - local;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) before += (w < wv) ? wave_tot[w] : 0u;
+  if (before < k_rem && k_rem <= before + local) {        // exactly one thread
+    uint32_t cum = before;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (cum < k_rem && k_rem <= cum + h[j]) {
+        const uint32_t digit = (uint32_t)(kRadixBuckets - 1 - (threadIdx.x * 8 + j));
+        const uint32_t np = prefix | (digit << radix_shift(pass));
+        a.rk_state[2 * r] = np;
+        a.rk_state[2 * r + 1] = k_rem - cum;
+        if (pass == 2) a.thr[r] = key_value(np);
+      }
+      cum += h[j];
     }
   }
 }
@@ -1279,7 +1367,23 @@ template <int DT, bool XF, bool AL>
 static hipError_t launch_stats_any(const KArgs& a, hipStream_t stream) {
   constexpr int kT = Vec<DT>::kT;
   if constexpr (XF) {
-    if (a.top_k > 0) {            // whole rows (c1 = 1), one workgroup each
+    if (a.top_k > 0 && a.V > kChunk) {   // long rows: three radix passes leave every row's threshold
+      constexpr int kA = AL ? kAligned : kUnaligned;
+      dim3 grid;
+      const bool g3 = stats_grid3(a, grid);
+      const unsigned rows = (unsigned)(a.rows_t + a.rows_d);
+      hipError_t e = launch_zero(reinterpret_cast<uint32_t*>(a.rk_hist), size_t(rows) * kRadixBuckets, stream);
+      if (e != hipSuccess) return e;
+      for (int pass = 0; pass < 3; ++pass) {
+        if (g3) hipLaunchKernelGGL((topk_radix_hist_kernel<DT, kA, kT / 2, true>), grid, dim3(kThreads), 0, stream, a, pass);
+        else hipLaunchKernelGGL((topk_radix_hist_kernel<DT, kA, kT / 2, false>), grid, dim3(kThreads), 0, stream, a, pass);
+        e = checked("topk_radix_hist_kernel");
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(topk_radix_select_kernel, dim3(rows), dim3(kThreads), 0, stream, a, pass);
+        e = checked("topk_radix_select_kernel");
+        if (e != hipSuccess) return e;
+      }
+    } else if (a.top_k > 0) {            // whole rows (c1 = 1), one workgroup each
       constexpr int kA = AL ? kAligned : kUnaligned;
       dim3 grid;
       const bool g3 = stats_grid3(a, grid);

@@ -10,13 +10,17 @@ import numpy as np
 U_TOL = 1e-6
 REL_TOL = 1e-5
 ABS_FLOOR = 1e-37          # below fp32's normal range the GPU flushes to zero
+# A residual mass is a sum of differences p - q f of probabilities that each carry a few fp32 ulps
+# of error (2^-24 ~ 6e-8 relative to values up to 1): where the differences nearly cancel, the
+# mass cannot be relatively accurate, only accurate to that many ulps of the probabilities.
+MASS_ABS = 3e-7
 
 
-def _close(gpu, ref, what):
+def _close(gpu, ref, what, abs_tol=ABS_FLOOR):
     gpu = np.asarray(gpu, np.float64)
     ref = np.asarray(ref, np.float64)
     err = np.abs(gpu - ref)
-    bad = err > REL_TOL * np.abs(ref) + ABS_FLOOR
+    bad = err > REL_TOL * np.abs(ref) + abs_tol
     assert not bad.any(), "%s: %d values off, worst rel %.3g at %s (gpu %r ref %r)" % (
         what, bad.sum(), (err / np.maximum(np.abs(ref), 1e-300)).max(), np.argwhere(bad)[0],
         gpu[tuple(np.argwhere(bad)[0])], ref[tuple(np.argwhere(bad)[0])])
@@ -103,11 +107,11 @@ def compare_verify(O, w, omega, gpu, ref=None, resample_mode=0, has_bonus=True, 
             assert xg == -1
             continue
         if tg == ref["accept_len"][b] and xg == ref["next_token"][b]:
-            _close(gpu["resid_mass"][b:b + 1], ref["resid_mass"][b:b + 1], "resid_mass")
+            _close(gpu["resid_mass"][b:b + 1], ref["resid_mass"][b:b + 1], "resid_mass", MASS_ABS)
             continue
         # token differs (or tau took the exempt branch): check against the oracle's law of that row
         xo, R, g = _oracle_row_law(O, w, b, tg, om_b[min(tg, L - 1)], resample_mode)
-        _close(gpu["resid_mass"][b:b + 1], [R], "resid_mass")
+        _close(gpu["resid_mass"][b:b + 1], [R], "resid_mass", MASS_ABS)
         if xg != xo:
             assert 0 <= xg < w.V and g[xg] > 0, "seq %d: gpu token %d has zero mass" % (b, xg)
             C = np.cumsum(g)
@@ -189,7 +193,7 @@ def compare_verify_lantern(O, w, nbr, lam, gpu, resample_mode=0, num_threads=16)
             stats["tau_exempt"] += 1
         xg = int(gpu["next_token"][b])
         if tg == ref["accept_len"][b] and xg == ref["next_token"][b] and not loose[b, min(tg, L - 1)]:
-            _close(gpu["resid_mass"][b:b + 1], ref["resid_mass"][b:b + 1], "resid_mass")
+            _close(gpu["resid_mass"][b:b + 1], ref["resid_mass"][b:b + 1], "resid_mass", MASS_ABS)
             continue
         p, q = _oracle_rows(O, w, b, tg)
         if q is None:
@@ -198,7 +202,7 @@ def compare_verify_lantern(O, w, nbr, lam, gpu, resample_mode=0, num_threads=16)
             g, R = O.lantern_residual(p, q, nbr, lam, resample_mode, int(tok[b, tg]))
         if loose[b, min(tg, L - 1)] and resample_mode == 2:
             continue                              # the law itself depends on the undecided set
-        _close(gpu["resid_mass"][b:b + 1], [R], "resid_mass")
+        _close(gpu["resid_mass"][b:b + 1], [R], "resid_mass", MASS_ABS)
         xo = O.inverse_cdf(g, ur[b] * R)
         if xg != xo:
             assert 0 <= xg < V and g[xg] > 0, "seq %d: gpu token %d has zero mass" % (b, xg)

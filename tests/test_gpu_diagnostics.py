@@ -113,3 +113,13 @@ def test_diagnostics_predict_the_acceptance_rate(P, oracle):
     rate = float((tau >= 1).float().mean())
     a = float(alpha[0, 0])
     assert abs(rate - a) < 5 * np.sqrt(a * (1 - a) / n)
+
+
+def test_diagnostics_topk_on_long_rows(P, oracle):
+    """Truncation on rows longer than one workgroup (thresholds from the radix passes), with and
+    without guidance."""
+    for cfg, V, k in ((3, 40000, 1000), (2, 20001, 64)):
+        w = make_workload(cfg, device="cuda", B=2, L=3, V=V, top_k=k if cfg == 3 else None)
+        w.top_k = k
+        print("case long top-k", cfg, V, k, flush=True)
+        _check(P, oracle, w, P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, 3, 2.0, w.nu))

@@ -92,7 +92,7 @@ typedef struct {
   int32_t has_bonus;     /* 1: target holds L+1 rows per sequence; 0: L rows, no bonus token  */
   int32_t top_k;         /* 0 = off; else 1..V: keep logits >= the k-th largest of the row
                             (ties kept), on BOTH models, after guidance and temperature.
-                            Rows of at most 16384 logits are selected inside the statistics
+                            Rows of at most 65536 logits are selected inside the statistics
                             kernel; longer rows by three radix passes over the row first     */
   float cfg_scale;       /* s of l = l_u + s (l_c - l_u); used iff the *_uncond pointers are
                             given (classifier-free guidance, App. implementation details)     */

@@ -112,7 +112,7 @@ int run(const cool_sd_params* p, bool resample_only,
   const int64_t rows_t = rows, rows_d = d ? int64_t(p->B) * L : 0;
   const Chunking ch = pick_chunking(p, rows_t + rows_d);
   const int64_t C = ch.c2;
-  const bool radix = p->top_k > 0 && p->V > csd::kChunk;
+  const bool radix = p->top_k > 0 && p->V > 4 * csd::kChunk;
   const Layout lay = make_layout(p->B, rows_t + rows_d, ch.c1, C, 0, 0, lan ? int64_t(p->B) * L : 0,
                                  radix ? rows_t + rows_d : 0);
   if (!ws || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0 || ws_bytes < lay.total) return COOL_SD_EWORKSPACE;
@@ -194,7 +194,7 @@ int run_diag(const cool_sd_params* p, const void* t, const void* tu, const void*
   const Chunking ch = pick_chunking(p, 2 * pairs);
   const bool local = p->top_k == 0 && p->V <= csd::kChunk;
   const int64_t CD = local ? 1 : (int64_t(p->V) + 8191) / 8192;
-  const bool radix = p->top_k > 0 && p->V > csd::kChunk;
+  const bool radix = p->top_k > 0 && p->V > 4 * csd::kChunk;
   const Layout lay = make_layout(p->B, 2 * pairs, ch.c1, 1, pairs, CD, 0, radix ? 2 * pairs : 0);
   if (!ws || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0 || ws_bytes < lay.total) return COOL_SD_EWORKSPACE;
 
@@ -278,7 +278,7 @@ size_t cool_sd_workspace_bytes(const cool_sd_params* p) {
   const int64_t c1_max = (int64_t(p->V) + 4095) / 4096;
   (void)ch;
   const int64_t pairs = full ? int64_t(p->B) * L : 0;       // cool_sd_diagnostics: chunks of 8192 logits
-  const bool radix = p->top_k > 0 && p->V > csd::kChunk;
+  const bool radix = p->top_k > 0 && p->V > 4 * csd::kChunk;
   return make_layout(p->B, rows, c1_max, c1_max, pairs, (int64_t(p->V) + 8191) / 8192, pairs, radix ? rows : 0).total;
 }
 

@@ -158,22 +158,27 @@ __global__ __launch_bounds__(kThreads, 3) void row_stats_kernel(const KArgs a) {
   }
 }
 
-// Statistics of whole rows under top-k truncation (rows of at most 16384 logits): one
-// workgroup of TPB threads per row, 16384 / TPB transformed logits per thread in registers.
-// The k-th largest value of the row is selected first (topk.h); the softmax statistics are then
-// taken over the entries >= that threshold, against the reference exponent of the row maximum
-// (always kept).  Writes the row's threshold, its statistics (one chunk per row) and the masked
-// logit of x~_i.  The work per row is a chain of short block-wide phases bound by instruction
-// issue, so the code is kept lean and the row is spread over enough threads that several rows
-// fit a compute unit.
+// Statistics of whole rows under top-k truncation: one workgroup of TPB threads per row,
+// ROW / TPB transformed logits per thread in registers (ROW = 16384 with 512 threads, or 65536
+// with 1024 threads for vocabularies up to 64K).  The k-th largest value of the row is selected
+// first (topk.h); the softmax statistics are then taken over the entries >= that threshold,
+// against the reference exponent of the row maximum (always kept).  Writes the row's threshold,
+// its statistics -- one pair per row, or for the long form one pair per 8192 logits, the layout
+// the sampling kernels of long rows expect -- and the masked logit of x~_i.  The work per row is
+// a chain of short block-wide phases bound by instruction issue, so the code is kept lean and
+// the row is spread over enough threads that several rows fit a compute unit.
 constexpr int kThreadsK = 512;
-template <int DT, int AL, int TPB, int GD, bool G3>
-__global__ __launch_bounds__(TPB, 6) void row_stats_topk_kernel(const KArgs a) {
+constexpr int kRowMid = 4 * kChunk;      // longest row the one-workgroup form takes (1024 threads)
+template <int DT, int AL, int TPB, int GD, bool G3, int ROW>
+__global__ __launch_bounds__(TPB, ROW == kChunk ? 6 : 4) void row_stats_topk_kernel(const KArgs a) {
   constexpr int kE = Vec<DT>::kE;
-  constexpr int kVW = kChunk / (TPB * kE);             // vectors per thread
+  constexpr int kVW = ROW / (TPB * kE);                // vectors per thread
   constexpr int kW = TPB / 64;
+  constexpr int kSub = ROW == kChunk ? 1 : ROW / 8192; // statistics pairs per row
+  constexpr int kTS = kVW / kSub;                      // this thread's vectors per pair: tile k covers
+                                                       // TPB*kE consecutive logits, 8192 / (TPB*kE) tiles per pair
   __shared__ TopkSmem<TPB> ts;
-  __shared__ float red_s[kW];
+  __shared__ float red_s[kSub][kW];
   const RowRef rw = row_ref<DT, G3>(a, blockIdx.x);
   const int r = rw.r;
   topk_prepare(ts);                                     // the barrier inside topk_threshold orders it
@@ -191,22 +196,27 @@ __global__ __launch_bounds__(TPB, 6) void row_stats_topk_kernel(const KArgs a) {
   float row_max;
   const float thr = topk_threshold<kVW * kE, TPB>(x.w, a.top_k, ts, row_max);
   const float c = fmaxf(ceilf(row_max * kLog2e), kRefFloor);
-  float s = 0.f;
-#pragma unroll
-  for (int n = 0; n < kVW * kE; ++n) {
-    const float l = __uint_as_float(x.w[n]);
-    const float e = exp2_fast(__fmaf_rn(l, kLog2e, -c));
-    s += (l >= thr) ? e : 0.f;
-  }
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  s = wave_sum(s);
-  if (lane == 0) red_s[wv] = s;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    float S = red_s[0];
 #pragma unroll
-    for (int w = 1; w < kW; ++w) S = __fadd_rn(S, red_s[w]);
-    a.part[r] = make_float2(c, S);
+  for (int sub = 0; sub < kSub; ++sub) {
+    float s = 0.f;
+#pragma unroll
+    for (int n = sub * kTS * kE; n < (sub + 1) * kTS * kE; ++n) {
+      const float l = __uint_as_float(x.w[n]);
+      const float e = exp2_fast(__fmaf_rn(l, kLog2e, -c));
+      s += (l >= thr) ? e : 0.f;
+    }
+    s = wave_sum(s);
+    if (lane == 0) red_s[sub][wv] = s;
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < kSub && (int)threadIdx.x < a.c1) {
+    float S = red_s[threadIdx.x][0];
+#pragma unroll
+    for (int w = 1; w < kW; ++w) S = __fadd_rn(S, red_s[threadIdx.x][w]);
+    a.part[int64_t(r) * a.c1 + threadIdx.x] = make_float2(c, S);
+  }
+  if (threadIdx.x == 0) {
     a.thr[r] = thr;
     if (tok >= 0) {
       const float l = transform_logit(tok_c, tok_u, rw.uncond != nullptr, a.cfg_scale, a.inv_T);
@@ -1367,7 +1377,7 @@ template <int DT, bool XF, bool AL>
 static hipError_t launch_stats_any(const KArgs& a, hipStream_t stream) {
   constexpr int kT = Vec<DT>::kT;
   if constexpr (XF) {
-    if (a.top_k > 0 && a.V > kChunk) {   // long rows: three radix passes leave every row's threshold
+    if (a.top_k > 0 && a.V > kRowMid) {  // rows beyond one workgroup: three radix passes leave every row's threshold
       constexpr int kA = AL ? kAligned : kUnaligned;
       dim3 grid;
       const bool g3 = stats_grid3(a, grid);
@@ -1383,15 +1393,23 @@ static hipError_t launch_stats_any(const KArgs& a, hipStream_t stream) {
         e = checked("topk_radix_select_kernel");
         if (e != hipSuccess) return e;
       }
-    } else if (a.top_k > 0) {            // whole rows (c1 = 1), one workgroup each
+    } else if (a.top_k > 0) {            // whole rows, one workgroup each
       constexpr int kA = AL ? kAligned : kUnaligned;
       dim3 grid;
       const bool g3 = stats_grid3(a, grid);
+      if (g3) grid.x = 1; else grid.x = (unsigned)(a.rows_t + a.rows_d);
       const bool guided = a.tu != nullptr;
-      if (g3 && guided) hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsK, 1, true>), grid, dim3(kThreadsK), 0, stream, a);
-      else if (g3) hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsK, 0, true>), grid, dim3(kThreadsK), 0, stream, a);
-      else if (guided) hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsK, 1, false>), grid, dim3(kThreadsK), 0, stream, a);
-      else hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsK, 0, false>), grid, dim3(kThreadsK), 0, stream, a);
+      if (a.V <= kChunk) {
+        if (g3 && guided) hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsK, 1, true, kChunk>), grid, dim3(kThreadsK), 0, stream, a);
+        else if (g3) hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsK, 0, true, kChunk>), grid, dim3(kThreadsK), 0, stream, a);
+        else if (guided) hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsK, 1, false, kChunk>), grid, dim3(kThreadsK), 0, stream, a);
+        else hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsK, 0, false, kChunk>), grid, dim3(kThreadsK), 0, stream, a);
+      } else {                           // 16384 < V <= 65536: 1024 threads, statistics per 8192 logits
+        if (g3 && guided) hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsW, 1, true, kRowMid>), grid, dim3(kThreadsW), 0, stream, a);
+        else if (g3) hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsW, 0, true, kRowMid>), grid, dim3(kThreadsW), 0, stream, a);
+        else if (guided) hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsW, 1, false, kRowMid>), grid, dim3(kThreadsW), 0, stream, a);
+        else hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsW, 0, false, kRowMid>), grid, dim3(kThreadsW), 0, stream, a);
+      }
       return checked("row_stats_topk_kernel");
     }
   }

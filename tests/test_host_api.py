@@ -94,8 +94,8 @@ def test_verify_validates_before_touching_the_gpu(P):
     assert call(_params(P)) == E.COOL_SD_EWORKSPACE                    # no workspace
     assert call(_params(P), ws=C.c_void_p(0x1004), ws_bytes=1 << 20) == E.COOL_SD_EWORKSPACE   # misaligned
     assert call(_params(P), ws=C.c_void_p(0x1000), ws_bytes=16) == E.COOL_SD_EWORKSPACE         # too small
-    # top-k on rows longer than one workgroup needs the radix-select state in the workspace
-    long_rows = dict(V=20000, t_stride_l=20000, d_stride_l=20000, t_stride_b=9 * 20000, d_stride_b=8 * 20000)
+    # top-k on rows longer than one workgroup (65536 logits) needs the radix-select state in the workspace
+    long_rows = dict(V=70000, t_stride_l=70000, d_stride_l=70000, t_stride_b=9 * 70000, d_stride_b=8 * 70000)
     plain = P.cool_sd_workspace_bytes(_params(P, **long_rows))
     with_k = P.cool_sd_workspace_bytes(_params(P, top_k=5, **long_rows))
     assert with_k >= plain + 4 * 17 * 2048 * 4

@@ -243,9 +243,11 @@ def test_topk_with_excluded_tokens(P, oracle):
     (1, 2, 2, 33000, "f32", 1),          # greedy support on fp32 rows
     (5, 2, 2, 262144, "bf16", 4096),     # the large-vocabulary configuration's rows
     (2, 2, 2, 16392, "bf16", 16392),     # k = V on a row that barely needs a second chunk
+    (2, 2, 2, 70001, "bf16", 300),       # beyond one workgroup: radix passes, element-wise loads
+    (3, 2, 2, 66000, "f32", 77),         # radix passes on guided fp32 rows
 ])
 def test_topk_on_long_rows(P, oracle, cfg, B, L, V, dtype, top_k):
-    """Rows longer than one workgroup: the threshold comes from three radix passes."""
+    """Rows beyond 16384 logits: one workgroup of 1024 threads up to 65536, three radix passes beyond."""
     print("case long top-k", cfg, B, L, V, dtype, top_k, flush=True)
     w = make_workload(cfg, device="cuda", B=B, L=L, V=V, dtype=dtype, top_k=top_k if cfg == 3 else None)
     w.top_k = top_k

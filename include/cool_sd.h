@@ -60,8 +60,7 @@ typedef enum {
   COOL_SD_EINVAL = -1,       /* null pointer, bad shape / stride / dtype / option           */
   COOL_SD_EWORKSPACE = -2,   /* workspace missing, misaligned or smaller than required       */
   COOL_SD_ELAUNCH = -3,      /* the HIP runtime refused a launch                             */
-  COOL_SD_EUNSUPPORTED = -4  /* valid request the kernels do not implement
-                                (see cool_sd_verify_lantern)                                  */
+  COOL_SD_EUNSUPPORTED = -4  /* valid request the kernels do not implement (none at present)  */
 } cool_sd_status;
 
 /* Options of cool_sd_verify (cool_sd_params.flags). */
@@ -158,8 +157,7 @@ int cool_sd_verify(const cool_sd_params* p,
  *            (Proposition on the design of G), which is what is evaluated;
  *   VANILLA  Norm([p - q]_+)                                                    (Eq. g_tsd)
  *   LANTERN  Norm([P^{k,lambda} - q]_+): the probability of A(x~_{tau+1}) moved onto x~_{tau+1}
- *            (Eq. p_lantern, Eq. g_lantern); rows of at most 16384 logits, else
- *            COOL_SD_EUNSUPPORTED.
+ *            (Eq. p_lantern, Eq. g_lantern).
  *   neighbors_dev  int32 [V, k], row x = the k nearest neighbours of token x in the codebook's
  *                  latent space, nearest first; entries < 0, >= V or equal to x are skipped;
  *                  the remaining entries of a row must be distinct.  1 <= k <= 65536

@@ -108,7 +108,6 @@ int run(const cool_sd_params* p, bool resample_only,
   const int64_t L = resample_only ? 1 : p->L;
   const int hb = resample_only ? 0 : p->has_bonus;
   const int64_t rows = resample_only ? p->B : int64_t(p->B) * (L + hb);
-  if (lan && p->resample_mode == COOL_SD_RESAMPLE_LANTERN && p->V > csd::kChunk) return COOL_SD_EUNSUPPORTED;
   const int64_t rows_t = rows, rows_d = d ? int64_t(p->B) * L : 0;
   const Chunking ch = pick_chunking(p, rows_t + rows_d);
   const int64_t C = ch.c2;

@@ -382,16 +382,26 @@ __device__ __forceinline__ float resid_elem_lan(float lt, float ld, const ResidC
 }
 
 // Per-thread, per-tile partial masses, then block-wide tile totals T[k] (in sm.tile_tot).
-template <int DT, bool XF, int kT>
+// Mass of element j of tile t of a chunk in the tile layout: Eq. opt_G / Eq. g_tsd / p, or with LAN
+// Eq. g_lantern through the thread's patch (bit t*kE + j).
+template <int DT, bool XF, int kT, bool LAN>
+__device__ __forceinline__ float tile_elem(const RowRegs<DT, XF, kT>& rt, const RowRegs<DT, XF, kT>& rd,
+                                           const ResidCoef& k, const LanPatch& lp, int t, int j) {
+  if constexpr (LAN) return resid_elem_lan(rt.get(t, j), rd.get(t, j), k, lp, t * Vec<DT>::kE + j);
+  else return resid_elem(rt.get(t, j), rd.get(t, j), k);
+}
+
+template <int DT, bool XF, int kT, bool LAN = false>
 __device__ __forceinline__ void chunk_masses(const RowRegs<DT, XF, kT>& rt, const RowRegs<DT, XF, kT>& rd,
-                                             const ResidCoef& k, float (&part)[kT], Smem& sm) {
+                                             const ResidCoef& k, float (&part)[kT], Smem& sm,
+                                             const LanPatch lp = LanPatch{0u, -1, 1.f}) {
   constexpr int kE = Vec<DT>::kE;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
 #pragma unroll
   for (int t = 0; t < kT; ++t) {
     float acc = 0.f;
 #pragma unroll
-    for (int j = 0; j < kE; ++j) acc = __fadd_rn(acc, resid_elem(rt.get(t, j), rd.get(t, j), k));
+    for (int j = 0; j < kE; ++j) acc = __fadd_rn(acc, tile_elem<DT, XF, kT, LAN>(rt, rd, k, lp, t, j));
     part[t] = acc;
   }
   __syncthreads();  // previous readers of tile_part / tile_tot are done
@@ -422,10 +432,10 @@ template <int kT> __device__ __forceinline__ float chunk_total(const Smem& sm) {
 // exceeds the remainder, else the last positive-mass entry", so the result always has
 // positive mass even when the levels' roundings disagree.  Returns the offset in the chunk
 // (same value in every thread), or -1 if the chunk holds no mass.
-template <int DT, bool XF, int kT>
+template <int DT, bool XF, int kT, bool LAN = false>
 __device__ __forceinline__ int chunk_select(const RowRegs<DT, XF, kT>& rt, const RowRegs<DT, XF, kT>& rd,
                                             const ResidCoef& k, const float (&part)[kT],
-                                            float v, Smem& sm) {
+                                            float v, Smem& sm, const LanPatch lp = LanPatch{0u, -1, 1.f}) {
   constexpr int kE = Vec<DT>::kE;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   // level 1: tile
@@ -475,7 +485,7 @@ __device__ __forceinline__ int chunk_select(const RowRegs<DT, XF, kT>& rt, const
       if (t == ks) {
 #pragma unroll
         for (int j = 0; j < kE; ++j) {
-          const float r = resid_elem(rt.get(t, j), rd.get(t, j), k);
+          const float r = tile_elem<DT, XF, kT, LAN>(rt, rd, k, lp, t, j);
           if (r > 0.f) {
             last = j;
             run = __fadd_rn(run, r);
@@ -1057,7 +1067,7 @@ __global__ __launch_bounds__(kThreadsW) void sequence_early_exit_kernel(const KA
 //   kSelect  grid = B.      Rows of C chunks: pick the chunk that holds u*R, load it, inverse CDF.
 enum { kMasses = 1, kSelect = 2 };
 
-template <int DT, bool XF, bool AL, int kT, int STAGE>
+template <int DT, bool XF, bool AL, int kT, int STAGE, bool LAN>
 __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
   constexpr int kES = Vec<DT>::kES;
   constexpr int kChunk2 = kT * kThreads * Vec<DT>::kE;   // logits per sampling chunk
@@ -1116,16 +1126,49 @@ __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
   if constexpr (STAGE == kMasses) load_pair(c);       // in flight before anything waits for the statistics
   ResidCoef k{rs.x, 1.f / rs.y, rs.z, bonus ? 1.f : 1.f / rs.w, omega,
               bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
+  // Eq. g_lantern: this thread's part of the patch for chunk cc -- which of its tokens belong to the
+  // rejected token's neighbour set (element j of tile t is token cc*kChunk2 + (t*256 + tid)*kE + j)
+  auto lan_patch = [&](int cc) -> LanPatch {
+    LanPatch lp{0u, -1, 1.f};
+    if constexpr (LAN) {
+      if (!bonus) {
+        constexpr int kE = Vec<DT>::kE;
+        const int64_t base = int64_t(cc) * kChunk2;
+        auto slot = [&](int tokn) -> int {              // bit of token tokn in this thread, or -1
+          const int64_t rel = int64_t(tokn) - base;
+          if (rel < 0 || rel >= kChunk2) return -1;
+          const int vec = int(rel) / kE;
+          if ((vec & (kThreads - 1)) != (int)threadIdx.x) return -1;
+          return (vec / kThreads) * kE + (int(rel) - vec * kE);
+        };
+        const int xd = min(max(a.tokens[int64_t(b) * a.L + j], 0), a.V - 1);
+        const int m = a.lan_count[int64_t(b) * a.L + j];
+        lp.agg = omega;
+        lp.aggpos = slot(xd);
+        const int32_t* row = a.nbr + int64_t(xd) * a.lan_k;
+        int taken = 0;
+        for (int jj = 0; jj < a.lan_k && taken < m; ++jj) {
+          const int n = row[jj];
+          if (n < 0 || n >= a.V || n == xd) continue;
+          ++taken;
+          const int sl = slot(n);
+          if (sl >= 0) lp.zmask |= 1u << sl;
+        }
+      }
+    }
+    return lp;
+  };
 
   if constexpr (STAGE == kMasses) {
     // only the chunk's total is needed here: per-thread sum in ascending tile order, one wave
     // reduction, one barrier (the selection launch forms its own tile totals for the chunk it picks)
     constexpr int kE = Vec<DT>::kE;
+    const LanPatch lp = lan_patch(c);
     float acc = 0.f;
 #pragma unroll
     for (int t = 0; t < kT; ++t) {
 #pragma unroll
-      for (int e = 0; e < kE; ++e) acc = __fadd_rn(acc, resid_elem(rt.get(t, e), rd.get(t, e), k));
+      for (int e = 0; e < kE; ++e) acc = __fadd_rn(acc, tile_elem<DT, XF, kT, LAN>(rt, rd, k, lp, t, e));
     }
     acc = wave_sum(acc);
     if ((threadIdx.x & 63) == 0) sm.scan_tot[threadIdx.x >> 6] = acc;
@@ -1137,6 +1180,7 @@ __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
 
   float R, vsel;     // total mass; remaining mass to walk inside the selected chunk
   int cs = 0;        // selected chunk
+  LanPatch lp_sel{0u, -1, 1.f};
   {
     // chunk masses are staged in LDS by all threads (one latency), then walked in ascending
     // order; rows with more than kStage chunks walk global memory instead
@@ -1190,9 +1234,10 @@ __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
     if (cs < 0) cs = 0;
     vsel = v - cbase;
     load_pair(cs);
-    chunk_masses<DT, XF, kT>(rt, rd, k, part, sm);
+    lp_sel = lan_patch(cs);
+    chunk_masses<DT, XF, kT, LAN>(rt, rd, k, part, sm, lp_sel);
   }
-  const int off = chunk_select<DT, XF, kT>(rt, rd, k, part, vsel, sm);
+  const int off = chunk_select<DT, XF, kT, LAN>(rt, rd, k, part, vsel, sm, lp_sel);
   int token = cs * kChunk2 + max(off, 0);
   if (token >= a.V) token = a.V - 1;
   if (threadIdx.x == 0) {
@@ -1472,10 +1517,16 @@ static hipError_t launch_rest(const KArgs& a, hipStream_t stream) {
     if (e != hipSuccess) return e;
   }
   const int64_t grid2 = int64_t(a.B) * a.nchunks;
-  hipLaunchKernelGGL((sequence_kernel<DT, XF, AL, kT / 2, kMasses>), dim3((unsigned)grid2), dim3(kThreads), 0, stream, a);
+  if (a.lan_resample)
+    hipLaunchKernelGGL((sequence_kernel<DT, XF, AL, kT / 2, kMasses, true>), dim3((unsigned)grid2), dim3(kThreads), 0, stream, a);
+  else
+    hipLaunchKernelGGL((sequence_kernel<DT, XF, AL, kT / 2, kMasses, false>), dim3((unsigned)grid2), dim3(kThreads), 0, stream, a);
   e = checked("sequence_kernel (masses)");
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((sequence_kernel<DT, XF, AL, kT / 2, kSelect>), dim3(gB), dim3(kThreads), 0, stream, a);
+  if (a.lan_resample)
+    hipLaunchKernelGGL((sequence_kernel<DT, XF, AL, kT / 2, kSelect, true>), dim3(gB), dim3(kThreads), 0, stream, a);
+  else
+    hipLaunchKernelGGL((sequence_kernel<DT, XF, AL, kT / 2, kSelect, false>), dim3(gB), dim3(kThreads), 0, stream, a);
   return checked("sequence_kernel");
 }
 

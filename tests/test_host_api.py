@@ -127,9 +127,6 @@ def test_verify_validates_before_touching_the_gpu(P):
     assert lan(_params(P, resample_mode=E.COOL_SD_RESAMPLE_LANTERN)) == E.COOL_SD_EWORKSPACE
     assert lan(_params(P, resample_mode=3)) == E.COOL_SD_EINVAL
     assert call(_params(P, resample_mode=E.COOL_SD_RESAMPLE_LANTERN)) == E.COOL_SD_EINVAL   # only with neighbours
-    big = _params(P, V=20000, resample_mode=E.COOL_SD_RESAMPLE_LANTERN, t_stride_l=20000, d_stride_l=20000,
-                  t_stride_b=9 * 20000, d_stride_b=8 * 20000)
-    assert lan(big, ws=C.c_void_p(0x1000), n=1 << 24) == E.COOL_SD_EUNSUPPORTED
     assert P.cool_sd_workspace_bytes(_params(P, resample_mode=E.COOL_SD_RESAMPLE_LANTERN)) > 0
     for code in (0, -1, -2, -3, -4, -99):
         assert isinstance(P.cool_sd_strerror(code), str) and P.cool_sd_strerror(code)

@@ -27,8 +27,9 @@
  *   - The workspace holds only intermediate results of one call (chunk statistics, masses);
  *     nothing persists between calls and it needs no initialisation.  Calls that share a
  *     workspace must be ordered on one stream.
- *   - No kernel uses atomics, fences or waits on another workgroup; for given inputs the
- *     outputs are bit-identical from run to run.
+ *   - No kernel uses fences or waits on another workgroup, and the only global atomics are
+ *     integer counts whose sums do not depend on the order (top-k on rows beyond 65536 logits);
+ *     for given inputs the outputs are bit-identical from run to run.
  */
 #ifndef COOL_SD_H
 #define COOL_SD_H

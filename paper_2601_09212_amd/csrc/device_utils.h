@@ -68,11 +68,6 @@ __device__ __forceinline__ int wave_min_i(int v) {
   for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, 64));
   return v;
 }
-__device__ __forceinline__ int wave_max_i(int v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o, 64));
-  return v;
-}
 // Inclusive prefix sum over the 64 lanes of a wave, ascending lane order, without LDS traffic:
 // four DPP row shifts (1, 2, 4, 8; lanes without a source read 0) scan each row of 16 lanes,
 // then the totals of rows 0..2 (lanes 15, 31, 47) are added to the rows after them in a fixed

@@ -8,23 +8,29 @@
 // p_{L+1} when nothing was rejected (Algorithm 1, bonus token).
 //
 // Two launches per verify call.
-//   row_stats_kernel   grid = (target rows + draft rows) x chunks.  The HBM-bound pass: every
+//   row_stats_kernel   grid = (chunks, rows of a sequence, sequences).  The HBM-bound pass: every
 //                      logit is read once.  A workgroup streams one small chunk (4K-16K logits)
 //                      of one row through registers and writes the chunk's softmax statistics
 //                      (integer base-2 reference exponent, sum).  No workgroup talks to another;
-//                      few registers, so many workgroups per CU keep loads in flight.  With
-//                      top-k it also selects the row's threshold (row = one chunk then).
-//   sequence_kernel    grid = B.  Per sequence: combine the chunk statistics of its rows, accept
-//                      test at each position, tau = first rejection; then re-read ONLY row tau+1
-//                      (one row pair of 2L+1, usually still in L2 / Infinity Cache), keep it in
-//                      registers, form the residual masses and draw x_{tau+1} by a hierarchical
-//                      inverse CDF.
+//                      few registers, so many workgroups per CU keep loads in flight.
+//                      Under top-k truncation row_stats_topk_kernel takes its place: one workgroup
+//                      holds a whole row (up to 65536 logits) and selects the threshold first.
+//   sequence_whole_kernel  grid = B.  Per sequence: combine the chunk statistics of its rows,
+//                      accept test at each position, tau = first rejection; then re-read ONLY row
+//                      tau+1 (one row pair of 2L+1, usually still in L2 / Infinity Cache), keep it
+//                      in registers, form the residual masses and draw x_{tau+1} by a
+//                      hierarchical inverse CDF.
 // Rows longer than 16384 logits do not fit one workgroup's registers; the second step is then
-// split at kernel boundaries: combine_rows_kernel (one wave per row), accept_kernel (tau, one
-// workgroup per sequence), sequence_kernel<kMasses> (mass of every 8192-logit chunk of the
-// sampled rows, streaming) and sequence_kernel<kSelect> (pick the chunk that holds u*R, re-read
-// it, inverse CDF).  No workgroup ever communicates with another one inside a launch: there are
-// no atomics, fences or spin waits anywhere, and every kernel is a pure function of its inputs.
+// split at kernel boundaries: accept_kernel (chunk statistics combined, tau; one workgroup per
+// sequence), sequence_kernel<kMasses> (mass of every 8192-logit chunk of the sampled rows,
+// streaming) and sequence_kernel<kSelect> (pick the chunk that holds u*R, re-read it, inverse
+// CDF).  Other entry points add: lantern_agg_kernel (neighbour aggregation of the LANTERN-style
+// acceptance), sequence_early_exit_kernel (the whole call per sequence, stopping at the first
+// rejection), diag_kernel (per-position terms of Theorem 2), and for top-k on rows beyond 65536
+// logits three radix passes (topk_radix_*).
+// No workgroup ever waits for another one inside a launch: there are no fences or spin waits
+// anywhere, the only global atomics are the integer histogram adds of the radix passes (whose
+// sums do not depend on the order), and every output is a pure function of the inputs.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
@@ -41,15 +47,12 @@ constexpr int kWavesW = kThreadsW / 64;
 
 
 struct Smem {
-  float red_c[2][kWaves];
-  float red_s[2][kWaves];
   float tile_part[kWaves][16];
   float tile_tot[16];
   float scan_tot[kWaves];
   int pick_first[kWaves];
   int pick_last[kWaves];
   int bcast_i;
-  int flag;
   float4 rowstat;
 };
 
@@ -418,14 +421,6 @@ __device__ __forceinline__ void chunk_masses(const RowRegs<DT, XF, kT>& rt, cons
   __syncthreads();
 }
 
-// Sum of the tile totals in ascending order (the chunk's mass).
-template <int kT> __device__ __forceinline__ float chunk_total(const Smem& sm) {
-  float R = 0.f;
-#pragma unroll
-  for (int t = 0; t < kT; ++t) R = __fadd_rn(R, sm.tile_tot[t]);
-  return R;
-}
-
 // Inverse CDF inside one chunk held in registers: the smallest element offset whose running
 // mass (ascending token order: tile, then thread, then element) exceeds v.  Hierarchical:
 // tile -> thread -> element, each level "first positive-mass entry whose inclusive sum
@@ -614,7 +609,6 @@ struct SmemW {
   int pick_last[kWavesW];
   float scan_tot[kWavesW];
   float4 rowstat;
-  int token;
 };
 
 // One draw from the resampling law of a row pair that 1024 threads hold in registers (thread t

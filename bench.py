@@ -57,6 +57,10 @@ def parse():
                     help="also time the same steps issued on two streams (independent batches, each stream with its "
                          "own workspace and outputs), so that one call's per-sequence kernel overlaps the next "
                          "call's statistics kernel; reported as extra keys, `value` stays the one-stream figure")
+    ap.add_argument("--delta-sweep", action="store_true",
+                    help="also report acceptance statistics of the timed workload under the lossless baseline and "
+                         "the annealed schedule at delta = 1, 1.1, 2, 3, 4 (accepted length, its prediction, "
+                         "estimate of the total-variation bound); extra key `delta_sweep`")
     ap.add_argument("--kernel-samples", type=int, default=200, help="instrumented calls for the per-kernel time")
     ap.add_argument("--counter-run", action="store_true",
                     help="for rocprofv3 --pmc: a plain device copy of known size (the counters' reference), then "
@@ -309,6 +313,40 @@ def time_lantern(r, k=10, lam=2.0, passes=6):
             "mean_accept_len": float(r.accept_len.float().mean().item())}
 
 
+def delta_sweep(r, deltas=(1.0, 1.1, 2.0, 3.0, 4.0)):
+    """Acceptance statistics of the timed workload's pool under the relaxation budgets of the paper's
+    speed/quality sweep: the lossless baseline (uniform schedule, delta = 1) and the annealed
+    schedule at each delta.  Per setting, over all sequences of the pool: the realised mean
+    accepted length, its prediction sum_i prod_{j<=i} f_j (Eq. token_exp, one drafted path per
+    sequence) and the same-path estimate of Theorem 2's bound with G*,
+    sum_i prod_{k<i} f_k * beta_i, with beta_i from cool_sd_diagnostics.  Kernel time does not
+    depend on delta (every row is read whatever the outcome), so nothing is timed here."""
+    torch, pkg = r.torch, r.pkg
+    w0 = r.pool[0]
+    params = pkg.make_params(w0.target, w0.draft, top_k=w0.top_k, cfg_scale=w0.cfg_scale, temperature=w0.temperature)
+    f = torch.empty((r.B, r.L), dtype=torch.float32, device="cuda")
+    alpha, beta = torch.empty_like(f), torch.empty_like(f)
+    out = []
+    for kind, name, delta in [(pkg.COOL_SD_SCHED_UNIFORM, "uniform", 1.0)] + \
+                             [(pkg.COOL_SD_SCHED_EXP, "exp", d) for d in deltas]:
+        om = torch.from_numpy(pkg.cool_sd_schedule(kind, r.L, delta, w0.nu)).cuda()
+        tau_sum = pred_sum = bound_sum = 0.0
+        for w in r.pool:
+            pkg.cool_sd_verify(params, w.target, w.target_uncond, w.draft, w.draft_uncond, w.draft_tokens, om,
+                               w.u_accept, w.u_resample, r.accept_len, r.next_token, None, None, f, None, r.ws)
+            pkg.cool_sd_diagnostics(params, w.target, w.target_uncond, w.draft, w.draft_uncond, om, alpha, beta, r.ws)
+            reach = torch.cumprod(f.double(), dim=1)                       # prod_{j<=i} f_j
+            before = torch.cat([torch.ones_like(reach[:, :1]), reach[:, :-1]], dim=1)
+            tau_sum += float(r.accept_len.double().sum())
+            pred_sum += float(reach.sum())
+            bound_sum += float((before * beta.double()).sum())
+        n = len(r.pool) * r.B
+        out.append({"schedule": name, "delta": delta, "nu": w0.nu if name == "exp" else None, "sequences": n,
+                    "mean_accept_len": tau_sum / n, "tokens_per_call": tau_sum / n + 1.0,
+                    "predicted_accept_len": pred_sum / n, "tv_bound_estimate": bound_sum / n})
+    return out
+
+
 def cpu_baseline(runner, budget_s):
     """The oracle, as it stands, on whole batches of the same pool until the time budget is used."""
     from oracle import oracle as O
@@ -442,6 +480,8 @@ def main():
         sec = r.time_two_streams()
         line["two_streams"] = {"us_per_step": sec * 1e6, "tokens_per_s": r.B * r.L / sec,
                                "whole_call_GBps": r.bytes_per_step / sec / 1e9}
+    if a.delta_sweep:
+        line["delta_sweep"] = delta_sweep(r)
     if not a.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(r, a.cpu_seconds)
     print(json.dumps(line), flush=True)

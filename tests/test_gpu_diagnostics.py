@@ -123,3 +123,33 @@ def test_diagnostics_topk_on_long_rows(P, oracle):
         w.top_k = k
         print("case long top-k", cfg, V, k, flush=True)
         _check(P, oracle, w, P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, 3, 2.0, w.nu))
+
+
+def test_accepted_length_matches_its_prediction_at_full_size(P):
+    """Eq. token_exp on one drafted path per sequence: given the draft tokens, tau has expectation
+    sum_i prod_{j<=i} f_j over the acceptance uniforms; over the 256 sequences of configuration 4
+    the realised mean must agree within sampling error.  With the lossless setting (uniform
+    schedule, delta = 1) every beta_i is exactly zero, with a relaxed one some are positive."""
+    w = make_workload(4, device="cuda")
+    params = P.make_params(w.target, w.draft)
+    ws = torch.empty(P.cool_sd_workspace_bytes(params), dtype=torch.uint8, device="cuda")
+    tau = torch.empty(w.B, dtype=torch.int32, device="cuda")
+    nxt = torch.empty_like(tau)
+    f = torch.empty((w.B, w.L), device="cuda")
+    alpha, beta = torch.empty_like(f), torch.empty_like(f)
+    for kind, delta in ((P.COOL_SD_SCHED_UNIFORM, 1.0), (P.COOL_SD_SCHED_EXP, 2.0)):
+        om = torch.from_numpy(P.cool_sd_schedule(kind, w.L, delta, w.nu)).cuda()
+        P.cool_sd_verify(params, w.target, None, w.draft, None, w.draft_tokens, om, w.u_accept, w.u_resample, tau, nxt,
+                         None, None, f, None, ws)
+        P.cool_sd_diagnostics(params, w.target, None, w.draft, None, om, alpha, beta, ws)
+        torch.cuda.synchronize()
+        pred = torch.cumprod(f.double(), 1).sum(1)
+        diff = (tau.double() - pred).cpu().numpy()
+        se = diff.std(ddof=1) / np.sqrt(w.B)
+        print("delta", delta, "mean tau", float(tau.double().mean()), "predicted", float(pred.mean()), "se", se, flush=True)
+        assert abs(diff.mean()) < 5 * se + 1e-9
+        if kind == P.COOL_SD_SCHED_UNIFORM:
+            assert float(beta.abs().max()) == 0.0
+        else:
+            assert float(beta.max()) > 0.0 and float(beta.min()) >= 0.0
+        assert float(alpha.min()) > 0.0 and float(alpha.max()) <= 1.0 + 1e-6

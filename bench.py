@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0
 # Fetched + written bytes of row_stats_kernel per launch.
 MEASURED_TRAFFIC_BYTES = {"cfg1": None, "cfg2": 17.96e6, "cfg3": 71.72e6, "cfg4": 277.75e6, "cfg5": 1143.20e6}
 # the same for sequence_early_exit_kernel (--early-exit)
-MEASURED_TRAFFIC_EARLY = {"cfg2": 7.95e6, "cfg4": 51.28e6}
+MEASURED_TRAFFIC_EARLY = {"cfg2": 8.11e6, "cfg4": 51.46e6}
 
 
 def parse():
@@ -421,7 +421,10 @@ def main():
             r.step(i)
             tau = r.accept_len.cpu().numpy().astype("int64")
             need += int(((tau + 1).clip(max=r.L) * 2 + (tau == r.L)).sum()) * r.V * r.pool[0].target.element_size()
-        kernel_name, kernel_bytes = "sequence_early_exit_kernel", need / len(r.pool)
+        # bf16 rows without a logit transform take the 256-thread form of the kernel
+        plain_bf16 = r.pool[0].dtype == "bf16" and r.pool[0].target_uncond is None and r.pool[0].temperature == 1.0
+        kernel_name = "sequence_early_exit_tile_kernel" if plain_bf16 else "sequence_early_exit_kernel"
+        kernel_bytes = need / len(r.pool)
         kern_s = dev_s / done
     achieved = kernel_bytes / kern_s / 1e9
     dtype = r.pool[0].dtype

@@ -25,8 +25,8 @@
 // sequence), sequence_kernel<kMasses> (mass of every 8192-logit chunk of the sampled rows,
 // streaming) and sequence_kernel<kSelect> (pick the chunk that holds u*R, re-read it, inverse
 // CDF).  Other entry points add: lantern_agg_kernel (neighbour aggregation of the LANTERN-style
-// acceptance), sequence_early_exit_kernel (the whole call per sequence, stopping at the first
-// rejection), diag_kernel (per-position terms of Theorem 2), and for top-k on rows beyond 65536
+// acceptance), sequence_early_exit_tile_kernel / sequence_early_exit_kernel (the whole call per
+// sequence, stopping at the first rejection), diag_kernel (per-position terms of Theorem 2), and for top-k on rows beyond 65536
 // logits three radix passes (topk_radix_*).
 // No workgroup ever waits for another one inside a launch: there are no fences or spin waits
 // anywhere, the only global atomics are the integer histogram adds of the radix passes (whose
@@ -496,11 +496,6 @@ __device__ __forceinline__ int chunk_select(const RowRegs<DT, XF, kT>& rt, const
   return sm.bcast_i;
 }
 
-// Accept test at every position of sequence b (Eq. relax) and tau = first rejection
-// (Algorithm 1), by all 256 threads of a workgroup: thread i takes positions i, i+256, ...
-// Leaves the combined statistics (Ct, St, Cd, Sd) of the row that will be sampled from --
-// position tau+1, or the bonus row L+1 -- in sm.rowstat and returns tau.  With `emit` it also
-// writes accept_len and the per-position diagnostics.
 // Position i of sequence b: statistics of its row pair (or of the bonus row alone), f_i of
 // Eq. relax and the accept test.  Returns true when x~_i is rejected.  With `emit` it writes the
 // per-position diagnostics.
@@ -530,6 +525,10 @@ __device__ __forceinline__ bool eval_position(const KArgs& a, int b, int i, bool
   return !(a.u_acc[int64_t(b) * a.L + i] <= fi);
 }
 
+// Accept test at every position of sequence b (Eq. relax) and tau = first rejection (Algorithm 1)
+// by the TPB threads of a workgroup.  Leaves the combined statistics (Ct, St, Cd, Sd) of the row
+// that will be sampled from -- position tau+1, or the bonus row L+1 -- in *rowstat and returns tau.
+// With `emit` it also writes accept_len and the per-position diagnostics.
 template <int DT, bool XF, int TPB>
 __device__ __forceinline__ int find_tau(const KArgs& a, int b, bool emit, int* pick /*[TPB/64]*/, float4* rowstat) {
   const int rps = a.L + a.has_bonus;
@@ -1054,6 +1053,162 @@ __global__ __launch_bounds__(kThreadsW) void sequence_early_exit_kernel(const KA
   }
 }
 
+// The same walk for bf16 rows without a logit transform, with a workgroup of 256 threads per
+// sequence.  Such rows stay packed in registers (32 words per row and thread), so a thread can
+// hold 64 logits of each row plus the next pair in flight, and the fixed cost of a step
+// (reductions, accept test, barrier) is spread over four times as many logits per thread as in
+// the 1024-thread form: about half the instructions per logit, and up to three sequences share a
+// compute unit.  Layout: tiles as in the statistics kernel (vector k*256 + t), so every load is
+// contiguous per wave; the draw at the end is the tile -> thread -> element search of the
+// long-row kernels.  The logits of x~_i are fetched by one extra load per row, issued with the
+// pair, instead of being searched for in the registers.
+// The next pair's loads are issued before the current pair is worked on (one unneeded pair per
+// sequence).  Fetching a pair only once its predecessor has been accepted, with three workgroups
+// per compute unit to hide the latency instead, was measured and is slower at every batch size.
+struct SmemT {
+  Smem s;
+  float red_c[2][2][kWaves];     // [step parity][target / draft][wave]
+  float red_s[2][2][kWaves];
+  int tok[kMaxLEarly];
+  float u[kMaxLEarly];
+  float om[kMaxLEarly];
+};
+
+__global__ __launch_bounds__(kThreads) void sequence_early_exit_tile_kernel(const KArgs a) {
+  constexpr int DT = kDtBF16;
+  constexpr bool XF = false;
+  constexpr int kE = Vec<DT>::kE, kES = Vec<DT>::kES, kT = Vec<DT>::kT;
+  static_assert(RowRegs<DT, XF, kT>::kRaw, "rows stay packed");
+  __shared__ SmemT sm;
+  const int b = blockIdx.x, L = a.L, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  for (int i = tid; i < L; i += kThreads) {
+    sm.tok[i] = min(max(a.tokens[int64_t(b) * L + i], 0), a.V - 1);
+    sm.u[i] = a.u_acc[int64_t(b) * L + i];
+    sm.om[i] = a.omega[int64_t(b) * a.om_sb + i];
+  }
+  __syncthreads();                                      // tok / u / om are visible
+  struct Slot { uint4 tc[kT], dc[kT]; float tl, dl; };
+  // vector k of this thread starts at element (k*256 + tid)*kE; 32-bit offsets from the (uniform)
+  // row pointer.  Vectors beyond the end of the row are fetched from its last vector and read
+  // as -inf.
+  auto fetch = [&](const char* row, int k) -> uint4 {
+    const int e = (k * kThreads + tid) * kE;
+    return *reinterpret_cast<const uint4*>(row + uint32_t(e < a.V ? e : a.V - kE) * kES);
+  };
+  auto unpack = [&](RowRegs<DT, XF, kT>& r, const uint4 (&rc)[kT]) {
+#pragma unroll
+    for (int k = 0; k < kT; ++k) {
+      const bool in = (k * kThreads + tid) * kE < a.V;
+      r.w[k * 4 + 0] = in ? rc[k].x : 0xFF80FF80u; r.w[k * 4 + 1] = in ? rc[k].y : 0xFF80FF80u;
+      r.w[k * 4 + 2] = in ? rc[k].z : 0xFF80FF80u; r.w[k * 4 + 3] = in ? rc[k].w : 0xFF80FF80u;
+    }
+  };
+  // Always the same number of loads, whatever i is (row indices are clamped to the last valid
+  // row, whose re-read is harmless), so that the compiler can count the loads in flight.
+  auto fetch_pair = [&](Slot& sl, int i) {
+    const int it = min(i, L + a.has_bonus - 1), id = min(i, L - 1);
+    const char* tc = row_ptr(a.t, int64_t(b) * a.t_sb + int64_t(it) * a.t_sl, kES);
+    const char* dc = row_ptr(a.d, int64_t(b) * a.d_sb + int64_t(id) * a.d_sl, kES);
+#pragma unroll
+    for (int k = 0; k < kT; ++k) {
+      sl.tc[k] = fetch(tc, k);
+      sl.dc[k] = fetch(dc, k);
+    }
+    const int x = sm.tok[id];
+    sl.tl = load_elem<DT>(tc, x);
+    sl.dl = load_elem<DT>(dc, x);
+  };
+  Slot slot;
+  fetch_pair(slot, 0);
+  RowRegs<DT, XF, kT> rt, rd;
+  rd.clear();
+
+  // statistics of one row over the workgroup: per-wave partials to LDS slot (par, which)
+  auto stats_write = [&](const RowRegs<DT, XF, kT>& r, int par, int which) {
+    float c, s;
+    thread_stats<DT, XF, kT>(r, c, s);
+    const float wc = wave_max(c);
+    const float ws = wave_sum(s * exp2_fast(c - wc));
+    if (lane == 0) { sm.red_c[par][which][wv] = wc; sm.red_s[par][which][wv] = ws; }
+  };
+  auto stats_read = [&](int par, int which, float& C, float& S) {
+    float c[kWaves], sv[kWaves];
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) { c[w] = sm.red_c[par][which][w]; sv[w] = sm.red_s[par][which][w]; }
+    C = fmaxf(fmaxf(c[0], c[1]), fmaxf(c[2], c[3]));
+    S = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) S = __fadd_rn(S, sv[w] * exp2_fast(c[w] - C));
+  };
+
+  int j = L;                                            // first rejected position
+  float Ct = kRefFloor, St = 1.f, Cd = kRefFloor, Sd = 1.f;
+  for (int i = 0; i < L; ++i) {
+    unpack(rt, slot.tc);
+    unpack(rd, slot.dc);
+    const float lt = slot.tl, ld = slot.dl;
+    fetch_pair(slot, i + 1);                            // the next pair is in flight during this step
+    const int par = i & 1;
+    stats_write(rt, par, 0);
+    stats_write(rd, par, 1);
+    __syncthreads();       // the only barrier of a step: LDS slots alternate with the step parity
+    stats_read(par, 0, Ct, St);
+    stats_read(par, 1, Cd, Sd);
+    // same evaluation of f_i = min{1, omega_i p_i(x~_i) / q_i(x~_i)} as the all-rows path (Eq. relax)
+    const float et = __fmaf_rn(lt, kLog2e, -Ct), ed = __fmaf_rn(ld, kLog2e, -Cd);
+    const float ratio = __fmul_rn(exp2_fast(__fsub_rn(et, ed)), Sd / St);
+    const float omega = sm.om[i];
+    const float fi = (ld == -INFINITY) ? 1.f : ((omega > 0.f) ? fminf(1.f, __fmul_rn(omega, ratio)) : 0.f);
+    if (tid == 0) {
+      const int64_t o = int64_t(b) * L + i;
+      if (a.p_tok) a.p_tok[o] = exp2_fast(et) / St;
+      if (a.q_tok) a.q_tok[o] = exp2_fast(ed) / Sd;
+      if (a.f) a.f[o] = fi;
+    }
+    if (!(sm.u[i] <= fi)) { j = i; break; }             // uniform: every thread sees the same values
+  }
+  // positions that were never evaluated
+  for (int i = j + 1 + tid; i < L; i += kThreads) {
+    const int64_t o = int64_t(b) * L + i;
+    if (a.p_tok) a.p_tok[o] = NAN;
+    if (a.q_tok) a.q_tok[o] = NAN;
+    if (a.f) a.f[o] = NAN;
+  }
+  if (tid == 0) a.accept_len[b] = j;
+  const bool bonus = j == L;
+  if (bonus) {
+    if (!a.has_bonus) {
+      if (tid == 0) {
+        a.next_token[b] = -1;
+        if (a.resid_mass) a.resid_mass[b] = 0.f;
+      }
+      return;
+    }
+    // everything was accepted: the slot holds row L+1 of the target (fetched as "pair" L during
+    // the last step); its statistics go to the LDS slot of parity L & 1, last used two steps ago
+    unpack(rt, slot.tc);
+    stats_write(rt, L & 1, 0);
+    __syncthreads();
+    stats_read(L & 1, 0, Ct, St);
+  }
+  ResidCoef k{Ct, 1.f / St, Cd, bonus ? 1.f : 1.f / Sd, bonus ? 1.f : sm.om[j],
+              bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
+  float part[kT], R = 0.f;
+  for (int attempt = 0; attempt < 2; ++attempt) {
+    chunk_masses<DT, XF, kT>(rt, rd, k, part, sm.s);
+    R = 0.f;
+#pragma unroll
+    for (int t = 0; t < kT; ++t) R = __fadd_rn(R, sm.s.tile_tot[t]);
+    if (R > 0.f || k.mode == kModeP) break;
+    k.mode = kModeP;       // no rejection possible at this position: any law is optimal, use p
+  }
+  const int off = chunk_select<DT, XF, kT>(rt, rd, k, part, __fmul_rn(a.u_res[b], R), sm.s);
+  if (tid == 0) {
+    a.next_token[b] = min(max(off, 0), a.V - 1);
+    if (a.resid_mass) a.resid_mass[b] = R;
+  }
+}
+
 // ============================================================================ kernel 2, long rows
 // Long rows (more than 16384 logits): the draw x_{tau+1} from the resampling law of the sampled
 // row (Eq. opt_G / Eq. g_tsd / p_{L+1}) in two launches.  STAGE selects what one launch does:
@@ -1468,7 +1623,10 @@ static hipError_t launch_typed(const KArgs& a, hipStream_t stream, hipEvent_t* e
   if (ev) (void)hipEventRecord(ev[0], stream);
   if (a.early_exit && !a.stats_only) {   // one launch; there is no separate statistics pass to time
     if (ev) (void)hipEventRecord(ev[1], stream);
-    hipLaunchKernelGGL((sequence_early_exit_kernel<DT, XF, 1>), dim3((unsigned)a.B), dim3(kThreadsW), 0, stream, a);
+    if constexpr (DT == kDtBF16 && !XF)
+      hipLaunchKernelGGL(sequence_early_exit_tile_kernel, dim3((unsigned)a.B), dim3(kThreads), 0, stream, a);
+    else
+      hipLaunchKernelGGL((sequence_early_exit_kernel<DT, XF, 1>), dim3((unsigned)a.B), dim3(kThreadsW), 0, stream, a);
     hipError_t ee = checked("sequence_early_exit_kernel");
     if (ev) (void)hipEventRecord(ev[2], stream);
     return ee;

@@ -272,10 +272,8 @@ size_t cool_sd_workspace_bytes(const cool_sd_params* p) {
   const bool full = params_ok(p, false, true);
   const int64_t L = full ? p->L : 1;
   const int64_t rows = full ? int64_t(p->B) * (2 * L + p->has_bonus) : 2 * int64_t(p->B);
-  const Chunking ch = pick_chunking(p, rows);
   // sized for the finest chunking so that the answer does not depend on optional inputs
   const int64_t c1_max = (int64_t(p->V) + 4095) / 4096;
-  (void)ch;
   const int64_t pairs = full ? int64_t(p->B) * L : 0;       // cool_sd_diagnostics: chunks of 8192 logits
   const bool radix = p->top_k > 0 && p->V > 4 * csd::kChunk;
   return make_layout(p->B, rows, c1_max, c1_max, pairs, (int64_t(p->V) + 8191) / 8192, pairs, radix ? rows : 0).total;

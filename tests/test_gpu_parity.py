@@ -295,7 +295,7 @@ def test_hip_graph_replays_match_eager(P, oracle):
     """bench.py replays verify calls from a HIP graph: every replay must reproduce the eager result,
     also with other eager work and synchronisations between replays (both launch shapes: one-chunk
     rows and long rows)."""
-    for cfg, kw in ((2, dict(B=8, L=8, V=16384)), (5, dict(B=4, L=4, V=40000))):
+    for cfg, kw in ((2, dict(B=32, L=8, V=16384)), (5, dict(B=4, L=4, V=40000))):   # config 2 at its full size
         pool = [make_workload(cfg, device="cuda", call=c, **kw) for c in range(3)]
         om = torch.from_numpy(_omega(P, pool[0])).cuda()
         params = P.make_params(pool[0].target, pool[0].draft)

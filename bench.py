@@ -315,8 +315,8 @@ def time_lantern(r, k=10, lam=2.0, passes=6):
 
 def delta_sweep(r, deltas=(1.0, 1.1, 2.0, 3.0, 4.0)):
     """Acceptance statistics of the timed workload's pool under the relaxation budgets of the paper's
-    speed/quality sweep: the lossless baseline (uniform schedule, delta = 1) and the annealed
-    schedule at each delta.  Per setting, over all sequences of the pool: the realised mean
+    speed/quality sweep: the lossless baseline (uniform schedule, delta = 1), the annealed
+    schedules (exponential, Eq. sdar; linear, schedule ablation) and the uniform relaxation at each delta.  Per setting, over all sequences of the pool: the realised mean
     accepted length, its prediction sum_i prod_{j<=i} f_j (Eq. token_exp, one drafted path per
     sequence) and the same-path estimate of Theorem 2's bound with G*,
     sum_i prod_{k<i} f_k * beta_i, with beta_i from cool_sd_diagnostics.  Kernel time does not
@@ -327,9 +327,13 @@ def delta_sweep(r, deltas=(1.0, 1.1, 2.0, 3.0, 4.0)):
     f = torch.empty((r.B, r.L), dtype=torch.float32, device="cuda")
     alpha, beta = torch.empty_like(f), torch.empty_like(f)
     out = []
-    for kind, name, delta in [(pkg.COOL_SD_SCHED_UNIFORM, "uniform", 1.0)] + \
-                             [(pkg.COOL_SD_SCHED_EXP, "exp", d) for d in deltas]:
-        om = torch.from_numpy(pkg.cool_sd_schedule(kind, r.L, delta, w0.nu)).cuda()
+    ell = float(max(8, r.L))          # the paper's ablation uses ell = 8; the slope must not cross zero inside the window
+    settings = [(pkg.COOL_SD_SCHED_UNIFORM, "uniform", 1.0, 0.0)]                      # lossless baseline
+    settings += [(pkg.COOL_SD_SCHED_EXP, "exp", d, w0.nu) for d in deltas]              # annealed, Eq. sdar
+    settings += [(pkg.COOL_SD_SCHED_LINEAR, "linear", d, ell) for d in deltas]          # annealed, linear decay
+    settings += [(pkg.COOL_SD_SCHED_UNIFORM, "uniform", d, 0.0) for d in deltas if d != 1.0]   # uniform relaxation
+    for kind, name, delta, param in settings:
+        om = torch.from_numpy(pkg.cool_sd_schedule(kind, r.L, delta, param)).cuda()
         tau_sum = pred_sum = bound_sum = 0.0
         for w in r.pool:
             pkg.cool_sd_verify(params, w.target, w.target_uncond, w.draft, w.draft_uncond, w.draft_tokens, om,
@@ -341,7 +345,7 @@ def delta_sweep(r, deltas=(1.0, 1.1, 2.0, 3.0, 4.0)):
             pred_sum += float(reach.sum())
             bound_sum += float((before * beta.double()).sum())
         n = len(r.pool) * r.B
-        out.append({"schedule": name, "delta": delta, "nu": w0.nu if name == "exp" else None, "sequences": n,
+        out.append({"schedule": name, "delta": delta, "param": param if name != "uniform" else None, "sequences": n,
                     "mean_accept_len": tau_sum / n, "tokens_per_call": tau_sum / n + 1.0,
                     "predicted_accept_len": pred_sum / n, "tv_bound_estimate": bound_sum / n})
     return out

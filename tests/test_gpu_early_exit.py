@@ -92,3 +92,30 @@ def test_early_exit_falls_back_where_not_supported(P, oracle):
         compare_verify(oracle, w, om, early)
         for k in early:
             np.testing.assert_array_equal(early[k], full[k])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_early_exit_degenerate_rows(P, oracle, dtype):
+    """Identical models, one-hot and flat rows, all-equal logits, large logits, a draft token the
+    target excludes, u = 0 and u next to 1 -- through both early-exit kernels (1024 threads for
+    fp32 rows, 256 threads for packed bf16 rows)."""
+    B, L, V = 8, 4, 16384
+    w = make_workload(1, device="cuda", B=B, L=L, V=V, dtype=dtype)
+    t, d = w.target, w.draft
+    d[0] = t[0, :L]
+    t[1] = float("-inf"); t[1, :, 77] = 0.0
+    d[1] = 0.0
+    t[2] = 3.0; d[2] = -2.0
+    t[3] = t[3] * 25.0
+    d[3] = d[3] * 25.0
+    t[4, :, :] = torch.where(torch.arange(V, device="cuda") % 2 == 0, t[4], torch.full_like(t[4], float("-inf")))
+    w.draft_tokens[4] = torch.tensor([1, 3, 5, 2], dtype=torch.int32)
+    w.u_accept[5] = 0.0
+    w.u_resample[5] = 0.0
+    w.u_accept[6] = 1.0 - 2.0 ** -24
+    w.u_resample[6] = 1.0 - 2.0 ** -24
+    w.draft_tokens[7] = V - 1
+    for om in (np.ones(L, np.float32), np.array([2.0, 1.0, 0.5, 0.25], np.float32)):
+        early, _ = _both(P, w, om)
+        compare_verify(oracle, w, om, early, early_exit=True)
+        assert early["accept_len"][0] == L or om[-1] < 1.0       # identical models: nothing rejected at omega >= 1

@@ -57,6 +57,9 @@ def parse():
                     help="also time the same steps issued on two streams (independent batches, each stream with its "
                          "own workspace and outputs), so that one call's per-sequence kernel overlaps the next "
                          "call's statistics kernel; reported as extra keys, `value` stays the one-stream figure")
+    ap.add_argument("--draft-sampler", action="store_true",
+                    help="also time the drafting stage's sampling step (cool_sd_resample on the draft rows alone: one "
+                         "call draws one token for each of the B sequences); extra key `draft_sampler`")
     ap.add_argument("--delta-sweep", action="store_true",
                     help="also report acceptance statistics of the timed workload under the lossless baseline and "
                          "the annealed schedule at delta = 1, 1.1, 2, 3, 4 (accepted length, its prediction, "
@@ -313,6 +316,48 @@ def time_lantern(r, k=10, lam=2.0, passes=6):
             "mean_accept_len": float(r.accept_len.float().mean().item())}
 
 
+def time_draft_sampler(r, passes=20):
+    """The drafting stage's sampling step on the same tensors (Algorithm 1, drafting loop): one
+    cool_sd_resample call draws x~ ~ q for the B sequences of a batch at one position (guidance,
+    temperature and top-k as configured, then an inverse-CDF draw; no target involved).  The L
+    positions of every pool batch are issued in turn and replayed from a HIP graph."""
+    torch, pkg = r.torch, r.pkg
+    w0 = r.pool[0]
+    rows = lambda w, i: (w.draft[:, i:i + 1], None if w.draft_uncond is None else w.draft_uncond[:, i:i + 1])
+    d0, _ = rows(w0, 0)
+    params = pkg.make_params(d0, d0, has_bonus=0, top_k=w0.top_k, cfg_scale=w0.cfg_scale, temperature=w0.temperature)
+    ws = torch.empty(max(pkg.cool_sd_workspace_bytes(params), 256), dtype=torch.uint8, device="cuda")
+    tok = torch.empty(r.B, dtype=torch.int32, device="cuda")
+
+    def issue():
+        for w in r.pool:
+            for i in range(r.L):
+                d, du = rows(w, i)
+                pkg.cool_sd_resample(params, d, du, None, None, None, w.u_resample, tok, None, ws)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        issue()
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        issue()
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(passes):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    n = passes * len(r.pool) * r.L
+    sec = e0.elapsed_time(e1) * 1e-3 / n
+    nbytes = r.B * r.V * w0.draft.element_size() * (2 if w0.draft_uncond is not None else 1)
+    return {"us_per_call": sec * 1e6, "draft_tokens_per_s": r.B / sec, "rows_per_call": r.B,
+            "algorithmic_bytes_per_call": nbytes, "GBps": nbytes / sec / 1e9, "calls_timed": n}
+
+
 def delta_sweep(r, deltas=(1.0, 1.1, 2.0, 3.0, 4.0)):
     """Acceptance statistics of the timed workload's pool under the relaxation budgets of the paper's
     speed/quality sweep: the lossless baseline (uniform schedule, delta = 1), the annealed
@@ -472,6 +517,8 @@ def main():
                 extra[name]["diagnostics"] = time_diagnostics(rr)
             if a.lantern:
                 extra[name]["lantern"] = time_lantern(rr)
+            if a.draft_sampler:
+                extra[name]["draft_sampler"] = time_draft_sampler(rr, passes=4)
             if a.concurrent:
                 sec = rr.time_two_streams(passes=4)
                 extra[name]["two_streams"] = {"us_per_step": sec * 1e6, "tokens_per_s": rr.B * rr.L / sec,
@@ -487,6 +534,8 @@ def main():
         sec = r.time_two_streams()
         line["two_streams"] = {"us_per_step": sec * 1e6, "tokens_per_s": r.B * r.L / sec,
                                "whole_call_GBps": r.bytes_per_step / sec / 1e9}
+    if a.draft_sampler:
+        line["draft_sampler"] = time_draft_sampler(r)
     if a.delta_sweep:
         line["delta_sweep"] = delta_sweep(r)
     if not a.no_cpu_baseline:

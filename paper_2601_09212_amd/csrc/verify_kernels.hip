@@ -24,7 +24,8 @@
 // split at kernel boundaries: accept_kernel (chunk statistics combined, tau; one workgroup per
 // sequence), sequence_kernel<kMasses> (mass of every 8192-logit chunk of the sampled rows,
 // streaming) and sequence_kernel<kSelect> (pick the chunk that holds u*R, re-read it, inverse
-// CDF).  Other entry points add: lantern_agg_kernel (neighbour aggregation of the LANTERN-style
+// CDF).  cool_sd_resample on short rows is one launch (resample_whole_kernel, resample_topk_kernel).
+// Other entry points add: lantern_agg_kernel (neighbour aggregation of the LANTERN-style
 // acceptance), sequence_early_exit_tile_kernel / sequence_early_exit_kernel (the whole call per
 // sequence, stopping at the first rejection), diag_kernel (per-position terms of Theorem 2), and for top-k on rows beyond 65536
 // logits three radix passes (topk_radix_*).
@@ -225,6 +226,125 @@ __global__ __launch_bounds__(TPB, ROW == kChunk ? 6 : 4) void row_stats_topk_ker
       const float l = transform_logit(tok_c, tok_u, rw.uncond != nullptr, a.cfg_scale, a.inv_T);
       a.tok_logit[r] = (l >= thr) ? l : -INFINITY;
     }
+  }
+}
+
+// The drafting stage's draw under top-k truncation, in ONE launch: cool_sd_resample without a draft
+// on rows of at most 16384 logits.  Same selection of the threshold as row_stats_topk_kernel; the
+// kept entries' weights 2^(l log2e - c) then stay in the registers and x~ is drawn from them by
+// the tile -> thread -> element search (tile k of the row is the TPB*kE consecutive logits from
+// k*TPB*kE on; thread t owns vector t of each tile), each level "first positive-mass entry whose
+// inclusive sum exceeds the remainder, else the last positive-mass entry".
+template <int DT, int AL, int GD>
+__global__ __launch_bounds__(kThreadsK) void resample_topk_kernel(const KArgs a) {
+  constexpr int TPB = kThreadsK, kE = Vec<DT>::kE, kES = Vec<DT>::kES;
+  constexpr int kVW = kChunk / (TPB * kE);             // tiles: 4 (bf16) / 8 (fp32)
+  constexpr int kW = TPB / 64;
+  static_assert(kVW <= 8, "tile_part holds up to 8 tiles");
+  __shared__ TopkSmem<TPB> ts;
+  __shared__ float tile_part[kW][8];
+  __shared__ float scan_tot[kW];
+  __shared__ int pick_first[kW], pick_last[kW];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  topk_prepare(ts);
+  RowRegs<DT, true, kVW> x;
+  load_chunk<DT, true, AL, kVW, TPB, 1, 4, GD>(x, row_ptr(a.t, int64_t(b) * a.t_sb, kES), row_ptr(a.tu, int64_t(b) * a.t_sb, kES),
+                                                0, a.V, a.cfg_scale, a.inv_T, -INFINITY);
+  const float u = a.u_res[b];
+  float row_max;
+  const float thr = topk_threshold<kVW * kE, TPB>(x.w, a.top_k, ts, row_max);
+  const float c = fmaxf(ceilf(row_max * kLog2e), kRefFloor);
+  // weights of the kept entries, in place of the logits; per-tile partial sums
+  float part[kVW];
+#pragma unroll
+  for (int k = 0; k < kVW; ++k) {
+    float acc = 0.f;
+#pragma unroll
+    for (int j = 0; j < kE; ++j) {
+      const float l = __uint_as_float(x.w[k * kE + j]);
+      const float e = exp2_fast(__fmaf_rn(l, kLog2e, -c));
+      const float m = (l >= thr) ? e : 0.f;
+      x.w[k * kE + j] = __float_as_uint(m);
+      acc = __fadd_rn(acc, m);
+    }
+    part[k] = acc;
+  }
+#pragma unroll
+  for (int k = 0; k < kVW; ++k) {
+    const float v = wave_sum(part[k]);
+    if (lane == 0) tile_part[wv][k] = v;
+  }
+  __syncthreads();
+  // level 1: tile
+  float T[kVW], R = 0.f;
+#pragma unroll
+  for (int k = 0; k < kVW; ++k) {
+    float tsum = 0.f;
+#pragma unroll
+    for (int w = 0; w < kW; ++w) tsum = __fadd_rn(tsum, tile_part[w][k]);
+    T[k] = tsum;
+    R = __fadd_rn(R, tsum);
+  }
+  const float v = __fmul_rn(u, R);
+  int ks = -1, klast = -1;
+  float base = 0.f, base_last = 0.f, cum = 0.f;
+#pragma unroll
+  for (int k = 0; k < kVW; ++k) {
+    if (T[k] > 0.f) {
+      if (ks < 0 && __fadd_rn(cum, T[k]) > v) { ks = k; base = cum; }
+      klast = k; base_last = cum;
+    }
+    cum = __fadd_rn(cum, T[k]);
+  }
+  if (ks < 0) { ks = klast; base = base_last; }
+  if (ks < 0) {            // a row without any finite logit: outside the contract, answer token 0
+    if (tid == 0) { a.next_token[b] = 0; if (a.resid_mass) a.resid_mass[b] = 0.f; }
+    return;
+  }
+  const float v2 = v - base;
+  // level 2: thread
+  float my = 0.f;
+#pragma unroll
+  for (int k = 0; k < kVW; ++k) my = (k == ks) ? part[k] : my;
+  const float incl_w = wave_scan_incl(my);
+  const float excl_w = wave_prev_lane(incl_w);
+  if (lane == 63) scan_tot[wv] = incl_w;
+  __syncthreads();
+  float woff = 0.f;
+#pragma unroll
+  for (int w = 0; w < kW; ++w) woff = (w < wv) ? __fadd_rn(woff, scan_tot[w]) : woff;
+  const float incl = __fadd_rn(woff, incl_w), excl = __fadd_rn(woff, lane == 0 ? 0.f : excl_w);
+  const bool pos = my > 0.f;
+  const bool hit = pos && (incl > v2);
+  const unsigned long long bh = __ballot(hit), bp = __ballot(pos);
+  if (lane == 0) {
+    pick_first[wv] = bh ? (wv * 64 + __ffsll((long long)bh) - 1) : 0x7fffffff;
+    pick_last[wv] = bp ? (wv * 64 + 63 - __clzll((long long)bp)) : -1;
+  }
+  __syncthreads();
+  int win = 0x7fffffff, last_pos = -1;
+#pragma unroll
+  for (int w = 0; w < kW; ++w) { win = min(win, pick_first[w]); last_pos = max(last_pos, pick_last[w]); }
+  if (win == 0x7fffffff) win = last_pos;
+  // level 3: element, by the winning thread
+  if (tid == win) {
+    const float v3 = v2 - excl;
+    int found = -1, last = 0;
+    float run = 0.f;
+#pragma unroll
+    for (int j = 0; j < kE; ++j) {
+      float m = 0.f;
+#pragma unroll
+      for (int k = 0; k < kVW; ++k) m = (k == ks) ? __uint_as_float(x.w[k * kE + j]) : m;
+      if (m > 0.f) {
+        last = j;
+        run = __fadd_rn(run, m);
+        if (found < 0 && run > v3) found = j;
+      }
+    }
+    if (found < 0) found = last;
+    a.next_token[b] = min((ks * TPB + win) * kE + found, a.V - 1);
+    if (a.resid_mass) a.resid_mass[b] = 1.f;             // the law is p itself
   }
 }
 
@@ -880,10 +1000,13 @@ __global__ __launch_bounds__(kThreads) void lantern_agg_kernel(const KArgs a, in
 // L <= kMaxLEarly and no top-k.  Per-position outputs after the rejected position are set to NaN.
 constexpr int kMaxLEarly = 1024;
 
-struct SmemE {
-  SmemW w;
+struct RedW {
   float red_c[2][2][kWavesW];    // [step parity][target / draft][wave]
   float red_s[2][2][kWavesW];
+};
+struct SmemE {
+  SmemW w;
+  RedW red;
   float tokl[2][2];              // [step parity][target / draft] logit of the draft token
   int tok[kMaxLEarly];
   float u[kMaxLEarly];
@@ -894,14 +1017,14 @@ struct SmemE {
 // per wave and left in LDS (slot par, row which); after the caller's barrier block_stats_read
 // combines the 16 wave entries (reference = max, sums rescaled by exact powers of two, fixed tree).
 template <int DT, bool XF, int kVW>
-__device__ __forceinline__ void block_stats_write(const RowRegs<DT, XF, kVW>& r, SmemE& sm, int par, int which) {
+__device__ __forceinline__ void block_stats_write(const RowRegs<DT, XF, kVW>& r, RedW& sm, int par, int which) {
   float c, s;
   thread_stats<DT, XF, kVW>(r, c, s);
   const float wc = wave_max(c);
   const float ws = wave_sum(s * exp2_fast(c - wc));
   if ((threadIdx.x & 63) == 0) { sm.red_c[par][which][threadIdx.x >> 6] = wc; sm.red_s[par][which][threadIdx.x >> 6] = ws; }
 }
-__device__ __forceinline__ void block_stats_read(const SmemE& sm, int par, int which, float& C, float& S) {
+__device__ __forceinline__ void block_stats_read(const RedW& sm, int par, int which, float& C, float& S) {
   // every wave reduces the 16 entries for itself, one per lane, instead of every thread reading all
   const int lane = threadIdx.x & 63;
   const float c = lane < kWavesW ? sm.red_c[par][which][lane] : kRefFloor;
@@ -976,8 +1099,8 @@ __global__ __launch_bounds__(kThreadsW) void sequence_early_exit_kernel(const KA
     finish_chunk<DT, XF, kVW>(rd, sl.dc, sl.du, first, a.V, guided, a.cfg_scale, a.inv_T, -INFINITY);
     fetch_pair(sl, i + D);                              // refill the slot before working on the pair
     const int par = i & 1;
-    block_stats_write<DT, XF, kVW>(rt, sm, par, 0);
-    block_stats_write<DT, XF, kVW>(rd, sm, par, 1);
+    block_stats_write<DT, XF, kVW>(rt, sm.red, par, 0);
+    block_stats_write<DT, XF, kVW>(rd, sm.red, par, 1);
     // the thread that holds x~_i publishes its two logits
     const int idx = sm.tok[i] - tid * kPer;
     float lt = 0.f, ld = 0.f;
@@ -992,8 +1115,8 @@ __global__ __launch_bounds__(kThreadsW) void sequence_early_exit_kernel(const KA
       if (idx >= 0 && idx < kPer) { sm.tokl[par][0] = lt; sm.tokl[par][1] = ld; }
     }
     __syncthreads();       // the only barrier of a step: LDS slots alternate with the step parity
-    block_stats_read(sm, par, 0, Ct, St);
-    block_stats_read(sm, par, 1, Cd, Sd);
+    block_stats_read(sm.red, par, 0, Ct, St);
+    block_stats_read(sm.red, par, 1, Cd, Sd);
     lt = sm.tokl[par][0];
     ld = sm.tokl[par][1];
     // same evaluation of f_i = min{1, omega_i p_i(x~_i) / q_i(x~_i)} as the all-rows path (Eq. relax)
@@ -1038,15 +1161,54 @@ __global__ __launch_bounds__(kThreadsW) void sequence_early_exit_kernel(const KA
     // L & 1, last used two steps ago or never)
     fetch_pair(slot[0], L);
     finish_chunk<DT, XF, kVW>(rt, slot[0].tc, slot[0].tu, first, a.V, guided, a.cfg_scale, a.inv_T, -INFINITY);
-    block_stats_write<DT, XF, kVW>(rt, sm, L & 1, 0);
+    block_stats_write<DT, XF, kVW>(rt, sm.red, L & 1, 0);
     __syncthreads();
-    block_stats_read(sm, L & 1, 0, Ct, St);
+    block_stats_read(sm.red, L & 1, 0, Ct, St);
   }
   ResidCoef k{Ct, 1.f / St, Cd, bonus ? 1.f : 1.f / Sd, bonus ? 1.f : sm.om[j],
               bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
   float R;
   bool writer;
   const int token = sample_whole<DT, XF, kVW>(rt, rd, k, a.u_res[b], a.V, sm.w, R, writer);
+  if (writer) {
+    a.next_token[b] = token;
+    if (a.resid_mass) a.resid_mass[b] = R;
+  }
+}
+
+// cool_sd_resample on rows of at most 16384 logits without top-k, in ONE launch: a workgroup of
+// 1024 threads holds the row pair (or the single row when no draft is given), forms its softmax
+// statistics block-wide and draws the token from the registers.  The drafting loop calls this once
+// per drafted token, so its latency (one launch instead of two) is what matters.
+template <int DT, bool XF, bool AL>
+__global__ __launch_bounds__(kThreadsW) void resample_whole_kernel(const KArgs a) {
+  constexpr int kE = Vec<DT>::kE, kES = Vec<DT>::kES;
+  constexpr int kVW = kChunk / (kThreadsW * kE);
+  __shared__ SmemW sm;
+  __shared__ RedW red;
+  const int b = blockIdx.x;
+  const bool bonus = a.d == nullptr;                    // no draft: the law is p itself
+  const char* t_c = row_ptr(a.t, int64_t(b) * a.t_sb, kES);
+  const char* t_u = row_ptr(a.tu, int64_t(b) * a.t_sb, kES);
+  const char* d_c = bonus ? nullptr : row_ptr(a.d, int64_t(b) * a.d_sb, kES);
+  const char* d_u = bonus ? nullptr : row_ptr(a.du, int64_t(b) * a.d_sb, kES);
+  RowRegs<DT, XF, kVW> rt, rd;
+  load_chunk<DT, XF, AL, kVW, 1, kVW>(rt, t_c, t_u, 0, a.V, a.cfg_scale, a.inv_T, -INFINITY);
+  if (!bonus) load_chunk<DT, XF, AL, kVW, 1, kVW>(rd, d_c, d_u, 0, a.V, a.cfg_scale, a.inv_T, -INFINITY);
+  else rd.clear();
+  const float omega = bonus ? 1.f : a.omega[int64_t(b) * a.om_sb];
+  const float u = a.u_res[b];
+  block_stats_write<DT, XF, kVW>(rt, red, 0, 0);
+  if (!bonus) block_stats_write<DT, XF, kVW>(rd, red, 0, 1);
+  __syncthreads();
+  float Ct, St, Cd = kRefFloor, Sd = 1.f;
+  block_stats_read(red, 0, 0, Ct, St);
+  if (!bonus) block_stats_read(red, 0, 1, Cd, Sd);
+  ResidCoef k{Ct, 1.f / St, Cd, bonus ? 1.f : 1.f / Sd, omega,
+              bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
+  float R;
+  bool writer;
+  const int token = sample_whole<DT, XF, kVW>(rt, rd, k, u, a.V, sm, R, writer);
   if (writer) {
     a.next_token[b] = token;
     if (a.resid_mass) a.resid_mass[b] = R;
@@ -1630,6 +1792,25 @@ static hipError_t launch_typed(const KArgs& a, hipStream_t stream, hipEvent_t* e
     hipError_t ee = checked("sequence_early_exit_kernel");
     if (ev) (void)hipEventRecord(ev[2], stream);
     return ee;
+  }
+  if constexpr (XF) {
+    if (a.resample_only && a.top_k > 0 && a.d == nullptr && a.V <= kChunk && !a.stats_only) {
+      // the drafting stage's draw under truncation: one launch
+      constexpr int kA = AL ? kAligned : kUnaligned;
+      if (ev) (void)hipEventRecord(ev[1], stream);
+      if (a.tu != nullptr) hipLaunchKernelGGL((resample_topk_kernel<DT, kA, 1>), dim3((unsigned)a.B), dim3(kThreadsK), 0, stream, a);
+      else hipLaunchKernelGGL((resample_topk_kernel<DT, kA, 0>), dim3((unsigned)a.B), dim3(kThreadsK), 0, stream, a);
+      hipError_t er = checked("resample_topk_kernel");
+      if (ev) (void)hipEventRecord(ev[2], stream);
+      return er;
+    }
+  }
+  if (a.resample_only && a.top_k == 0 && a.V <= kChunk && !a.stats_only) {   // short rows: one launch
+    if (ev) (void)hipEventRecord(ev[1], stream);
+    hipLaunchKernelGGL((resample_whole_kernel<DT, XF, AL>), dim3((unsigned)a.B), dim3(kThreadsW), 0, stream, a);
+    hipError_t er = checked("resample_whole_kernel");
+    if (ev) (void)hipEventRecord(ev[2], stream);
+    return er;
   }
   hipError_t e = launch_stats_any<DT, XF, AL>(a, stream);
   if (e != hipSuccess || a.stats_only) return e;

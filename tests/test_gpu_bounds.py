@@ -110,3 +110,9 @@ def test_entry_points_stay_inside_their_buffers(P, cfg, B, L, V, dtype, top_k):
     torch.cuda.synchronize()
     assert all(g.intact() for g in (tok, mass, rws)), "cool_sd_resample"
     assert int(tok.t.min()) >= 0 and int(tok.t.max()) < V
+    # the drafting stage's draw: no draft rows
+    P.cool_sd_resample(rp, w.draft[:, 0], None if w.draft_uncond is None else w.draft_uncond[:, 0], None, None, None,
+                       w.u_resample, tok.t, mass.t, rws.t)
+    torch.cuda.synchronize()
+    assert all(g.intact() for g in (tok, mass, rws)), "cool_sd_resample without a draft"
+    assert int(tok.t.min()) >= 0 and int(tok.t.max()) < V

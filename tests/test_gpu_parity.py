@@ -352,30 +352,52 @@ def test_long_draft_windows_and_tiny_shapes(P, oracle):
     compare_verify(oracle, w, np.zeros(8, np.float32), gpu)
 
 
-def test_draft_side_sampling_through_resample(P, oracle):
+@pytest.mark.parametrize("V,dtype,guided,top_k,temperature", [
+    (16384, "bf16", True, 200, 0.9),       # the guided, truncated sampler of the paper's larger models
+    (16384, "f32", False, 1000, 1.0),
+    (5001, "bf16", True, 50, 1.0),          # element-wise loads
+    (1003, "f32", False, 7, 1.3),
+    (16384, "bf16", False, 16384, 1.0),     # k = V: nothing is cut
+    (8, "f32", False, 1, 1.0),              # k = 1: the arg max
+    (16384, "bf16", False, 0, 1.0),         # no truncation: the plain one-launch draw
+    (40000, "bf16", True, 300, 1.0),        # rows of several chunks: statistics pass + sampling kernels
+])
+def test_draft_side_sampling_through_resample(P, oracle, V, dtype, guided, top_k, temperature):
     """Drawing x~ ~ Q (Algorithm 1, drafting stage) is cool_sd_resample with the draft's logits as the
     only distribution: guidance, temperature and top-k apply, then an inverse-CDF draw from q."""
-    w = make_workload(3, device="cuda", B=16, L=1, V=16384, top_k=200)
-    d, du = w.draft[:, 0].contiguous(), w.draft_uncond[:, 0].contiguous()
-    params = P.make_params(d.unsqueeze(1), d.unsqueeze(1), has_bonus=0, top_k=200, cfg_scale=4.0, temperature=0.9)
+    print("case", V, dtype, guided, top_k, temperature, flush=True)
+    B = 16
+    w = make_workload(3 if guided else 1, device="cuda", B=B, L=1, V=V, dtype=dtype, top_k=top_k if guided else None)
+    d = w.draft[:, 0].contiguous()
+    du = w.draft_uncond[:, 0].contiguous() if guided else None
+    if dtype == "bf16":
+        d[3, : V // 2] = d[3, 0]                                  # heavy ties around the threshold in one row
+    scale = w.cfg_scale if guided else 1.0
+    params = P.make_params(d.unsqueeze(1), d.unsqueeze(1), has_bonus=0, top_k=top_k, cfg_scale=scale,
+                           temperature=temperature)
     ws = torch.empty(P.cool_sd_workspace_bytes(params), dtype=torch.uint8, device="cuda")
-    u = uniforms24(torch.Generator(device="cuda").manual_seed(9), (16,), "cuda")
-    tok = torch.full((16,), -7, dtype=torch.int32, device="cuda")
-    mass = torch.zeros(16, device="cuda")
+    P.cool_sd_workspace_init(ws)
+    u = uniforms24(torch.Generator(device="cuda").manual_seed(9), (B,), "cuda")
+    u[0] = 0.0
+    u[1] = 1.0 - 2.0 ** -24
+    tok = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    mass = torch.zeros(B, device="cuda")
     P.cool_sd_resample(params, d, du, None, None, None, u, tok, mass, ws)
     torch.cuda.synchronize()
     ot, om_, g = oracle.resample(d.float().cpu().numpy(), None, None, u.cpu().numpy(),
-                                 target_uncond=du.float().cpu().numpy(), cfg_scale=4.0, temperature=0.9, top_k=200,
-                                 want_g=True)
+                                 target_uncond=None if du is None else du.float().cpu().numpy(), cfg_scale=scale,
+                                 temperature=temperature, top_k=top_k, want_g=True)
     np.testing.assert_allclose(mass.cpu().numpy(), om_, rtol=1e-5)
     t = tok.cpu().numpy()
-    for b in range(16):
-        assert g[b][t[b]] > 0 and (g[b] > 0).sum() >= 200
+    for b in range(B):
+        assert 0 <= t[b] < V and g[b][t[b]] > 0
+        if top_k:
+            assert (g[b] > 0).sum() >= min(top_k, V)
         if t[b] != ot[b]:
             C = np.cumsum(g[b]); v = float(u[b]) * om_[b]
             gap = (v - C[t[b]]) / om_[b] if t[b] < ot[b] else (C[t[b] - 1] - v) / om_[b]
             assert 0 <= gap <= 1e-6
-    assert (t == ot).sum() >= 15
+    assert (t == ot).sum() >= B - 1
 
 
 def test_random_shapes_and_options(P, oracle):

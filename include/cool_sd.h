@@ -186,8 +186,13 @@ int cool_sd_verify_lantern(const cool_sd_params* p,
 /* Stand-alone resampling step (Eq. opt_G / Eq. g_tsd): one (target, draft) row pair per
  * sequence.  p->L, strides_l and has_bonus are ignored; rows are [B, V] with element strides
  * t_stride_b / d_stride_b.  omega_rows_dev float [B], u_dev float [B].
- * draft_rows_dev == NULL samples from p itself (the bonus draw of Algorithm 1).
- *   token_dev out int32 [B], resid_mass_dev out float [B] (optional). */
+ * draft_rows_dev == NULL samples from p itself: the bonus draw of Algorithm 1, and, with the
+ * draft model's logits passed as "target", the drafting loop's draw x~ ~ q (guidance,
+ * temperature and top-k apply as configured).
+ *   token_dev out int32 [B], resid_mass_dev out float [B] (optional; the mass of the law that
+ *   was sampled: R of Eq. opt_G / Eq. g_tsd, 1 when the law is p itself).
+ * Rows of at most 16384 logits are served by a single kernel launch (except truncated rows with
+ * a draft), so a call per drafted token costs one launch latency. */
 int cool_sd_resample(const cool_sd_params* p,
                      const void* target_rows_dev, const void* target_uncond_rows_dev,
                      const void* draft_rows_dev, const void* draft_uncond_rows_dev,

@@ -97,6 +97,32 @@ def test_unaligned_rows(P, oracle):
     compare_verify(oracle, w, om, _run(P, oracle, w, om))
 
 
+@pytest.mark.parametrize("cfg,V,Vpad,dtype", [(2, 16000, 16384, "bf16"), (2, 5001, 5120, "bf16"), (1, 1000, 1024, "f32"),
+                                              (5, 40000, 40960, "bf16"), (3, 16000, 16384, "bf16")])
+def test_rows_inside_a_padded_vocabulary(P, oracle, cfg, V, Vpad, dtype):
+    """Logit tensors whose rows are longer than the vocabulary (padding up to a multiple of some
+    block, as a model's output layer often has): the row stride is Vpad, only the first V entries
+    belong to the row, and what follows (large values here) must never be read as logits."""
+    print("case", cfg, V, Vpad, dtype, flush=True)
+    w = make_workload(cfg, device="cuda", B=3, L=3, V=V, dtype=dtype)
+
+    def pad(t):
+        if t is None:
+            return None
+        big = torch.full(t.shape[:-1] + (Vpad,), 60.0, dtype=t.dtype, device="cuda")
+        big[..., :V] = t
+        return big[..., :V]
+    w.target, w.draft = pad(w.target), pad(w.draft)
+    w.target_uncond, w.draft_uncond = pad(w.target_uncond), pad(w.draft_uncond)
+    assert w.target.stride(1) == Vpad
+    om = _omega(P, w)
+    gpu = _run(P, oracle, w, om)
+    compare_verify(oracle, w, om, gpu)
+    early = to_numpy(P.verify_workload(w, torch.from_numpy(om).cuda(), flags=P.COOL_SD_FLAG_EARLY_EXIT))
+    compare_verify(oracle, w, om, early, early_exit=(cfg in (1, 2) and V % (8 if dtype == "bf16" else 4) == 0))
+    assert gpu["next_token"].max() < V and early["next_token"].max() < V
+
+
 def test_edge_rows(P, oracle):
     """Degenerate rows: identical models, one-hot rows, all-equal logits, extreme logits,
     a draft token the target excludes, u = 0 and u next to 1."""

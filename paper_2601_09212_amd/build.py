@@ -38,5 +38,23 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     return LIB
 
 
+EXAMPLE_SRC = os.path.join(PKG, "examples", "verify_example.c")
+EXAMPLE_BIN = os.path.join(PKG, "examples", "verify_example")
+
+
+def build_example(verbose: bool = False) -> str:
+    """Compile examples/verify_example.c, a plain-C user of the C ABI, with gcc against the built
+    library and the HIP runtime (the macro is the one HIP's own headers ask a host compiler for)."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-O2", "-Wall", "-std=c11", EXAMPLE_SRC, "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"),
+           "-I", os.path.join(ROOT, "include"), "-L", PKG, "-lcool_sd", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+           "-lm", "-Wl,-rpath,$ORIGIN/..", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", EXAMPLE_BIN]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return EXAMPLE_BIN
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_example(verbose=True))

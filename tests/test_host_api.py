@@ -148,3 +148,23 @@ def test_product_never_imports_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower(), os.path.join(dirpath, f)
+
+
+def test_header_is_plain_c_and_the_example_builds(tmp_path):
+    """include/cool_sd.h must be usable from C (the boundary is a C ABI): the example program is
+    compiled with gcc -std=c11 -Wall -Werror against the built library, and without arguments it
+    prints its usage before touching the GPU."""
+    import subprocess
+    from paper_2601_09212_amd import build as hb
+    if not os.path.exists(hb.LIB):
+        pytest.skip("library not built")
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    exe = str(tmp_path / "verify_example")
+    cmd = ["gcc", "-O1", "-Wall", "-Werror", "-std=c11", "-pedantic", hb.EXAMPLE_SRC, "-D__HIP_PLATFORM_AMD__",
+           "-isystem", os.path.join(rocm, "include"), "-I", os.path.join(hb.ROOT, "include"), "-L", hb.PKG, "-lcool_sd",
+           "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-lm", "-Wl,-rpath," + hb.PKG,
+           "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", exe]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+    assert r.returncode == 1 and "usage" in r.stderr

@@ -13,14 +13,6 @@ GUARD = 4096            # bytes of sentinel on each side
 SENT = 0xA5
 
 
-@pytest.fixture(scope="module")
-def P():
-    assert torch.cuda.is_available(), "these tests need the MI355X"
-    import paper_2601_09212_amd as pkg
-    pkg.binding.lib()
-    return pkg
-
-
 class Guarded:
     """A device buffer of `nbytes` (256-byte aligned start) between two sentinel regions."""
 

@@ -15,14 +15,6 @@ from workloads import make_workload
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(scope="module")
-def P():
-    assert torch.cuda.is_available(), "these tests need the MI355X"
-    import paper_2601_09212_amd as pkg
-    pkg.binding.lib()
-    return pkg
-
-
 def _oracle_diag(oracle, w, om):
     kw = dict(cfg_scale=w.cfg_scale, temperature=w.temperature, top_k=w.top_k)
     tu = None if w.target_uncond is None else w.target_uncond.float().cpu().numpy()

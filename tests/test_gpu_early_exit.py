@@ -10,14 +10,6 @@ from workloads import make_workload
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(scope="module")
-def P():
-    assert torch.cuda.is_available(), "these tests need the MI355X"
-    import paper_2601_09212_amd as pkg
-    pkg.binding.lib()
-    return pkg
-
-
 def _both(P, w, om, **kw):
     omega = torch.from_numpy(np.ascontiguousarray(om, dtype=np.float32)).cuda()
     early = to_numpy(P.verify_workload(w, omega, flags=P.COOL_SD_FLAG_EARLY_EXIT, **kw))

@@ -9,14 +9,6 @@ from workloads import make_neighbor_table, make_workload
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(scope="module")
-def P():
-    assert torch.cuda.is_available(), "these tests need the MI355X"
-    import paper_2601_09212_amd as pkg
-    pkg.binding.lib()
-    return pkg
-
-
 def _replay_equals_eager(call, outs):
     call()
     torch.cuda.synchronize()

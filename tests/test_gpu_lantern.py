@@ -13,14 +13,6 @@ from workloads import make_neighbor_table, make_workload
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(scope="module")
-def P():
-    assert torch.cuda.is_available(), "these tests need the MI355X"
-    import paper_2601_09212_amd as pkg
-    pkg.binding.lib()
-    return pkg
-
-
 def _run(P, w, nbr, lam, mode):
     out = P.verify_lantern_workload(w, nbr, lam, resample_mode=mode)
     torch.cuda.synchronize()

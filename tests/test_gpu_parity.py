@@ -9,14 +9,6 @@ from workloads import make_workload, uniforms24
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(scope="module")
-def P():
-    assert torch.cuda.is_available(), "these tests need the MI355X"
-    import paper_2601_09212_amd as pkg
-    pkg.binding.lib()
-    return pkg
-
-
 def _omega(P, w, L=None, delta=None):
     om = P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, w.L if L is None else L, w.delta if delta is None else delta, w.nu)
     return om

@@ -9,13 +9,6 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-@pytest.fixture(scope="module")
-def P():
-    import paper_2601_09212_amd as pkg
-    pkg.binding.lib()
-    return pkg
-
-
 def test_library_exports_every_declared_symbol(P):
     header = open(os.path.join(ROOT, "include", "cool_sd.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)

@@ -11,9 +11,13 @@ U_TOL = 1e-6
 REL_TOL = 1e-5
 ABS_FLOOR = 1e-37          # below fp32's normal range the GPU flushes to zero
 # A residual mass is a sum of differences p - q f of probabilities that each carry a few fp32 ulps
-# of error (2^-24 ~ 6e-8 relative to values up to 1): where the differences nearly cancel, the
-# mass cannot be relatively accurate, only accurate to that many ulps of the probabilities.
-MASS_ABS = 3e-7
+# of relative error, part of it common to a whole row (its normaliser): where the differences
+# nearly cancel, the mass cannot be relatively accurate.  With probabilities good to ~2.5e-7
+# relative, |error of R| <= 2.5e-7 (sum p + sum q f) <= 5e-7, plus the rounding of the sums.
+MASS_ABS = 1e-6
+# ... and a law whose whole mass is below this is not determined by fp32 probabilities at all: the
+# sampled token is then only required to be valid (in range, positive probability under p).
+R_FLOOR = 1e-6
 
 
 def _close(gpu, ref, what, abs_tol=ABS_FLOOR):
@@ -24,6 +28,26 @@ def _close(gpu, ref, what, abs_tol=ABS_FLOOR):
     assert not bad.any(), "%s: %d values off, worst rel %.3g at %s (gpu %r ref %r)" % (
         what, bad.sum(), (err / np.maximum(np.abs(ref), 1e-300)).max(), np.argwhere(bad)[0],
         gpu[tuple(np.argwhere(bad)[0])], ref[tuple(np.argwhere(bad)[0])])
+
+
+def mass_close(gpu_R, ref_R, exact_R, what="resid_mass"):
+    """A residual mass against the oracle's.  A law whose exact mass is zero (p and q f coincide:
+    any law is optimal there and the oracle falls back to p, mass 1) or below what fp32
+    probabilities resolve (R_FLOOR) may look either way to the GPU: a few ulps of rounding dust,
+    which it samples from and reports, or an exact zero, after which it falls back to p and
+    reports 1.  Both answers are accepted there."""
+    g = float(gpu_R)
+    if exact_R < R_FLOOR and (0.0 <= g <= MASS_ABS or abs(g - 1.0) <= REL_TOL):
+        return
+    _close(np.asarray([gpu_R]), np.asarray([ref_R]), what, MASS_ABS)
+
+
+def exact_residual_mass(p, q, omega, mode):
+    """sum_x [p - q f]_+ in fp64 before any fallback (q None: the law is p, mass 1)."""
+    if q is None:
+        return 1.0
+    qf = q if mode == 1 else np.minimum(q, omega * p)
+    return float(np.maximum(p - qf, 0.0).sum())
 
 
 def subset(w, idx):
@@ -106,12 +130,21 @@ def compare_verify(O, w, omega, gpu, ref=None, resample_mode=0, has_bonus=True, 
         if tg == L and not has_bonus:
             assert xg == -1
             continue
+        def exact_R():
+            p, q = _oracle_rows(O, w, b, tg)
+            return exact_residual_mass(p, q, float(om_b[min(tg, L - 1)]), resample_mode)
         if tg == ref["accept_len"][b] and xg == ref["next_token"][b]:
-            _close(gpu["resid_mass"][b:b + 1], ref["resid_mass"][b:b + 1], "resid_mass", MASS_ABS)
+            if abs(float(gpu["resid_mass"][b]) - float(ref["resid_mass"][b])) > REL_TOL * abs(float(ref["resid_mass"][b])):
+                mass_close(gpu["resid_mass"][b], ref["resid_mass"][b], exact_R())
             continue
         # token differs (or tau took the exempt branch): check against the oracle's law of that row
         xo, R, g = _oracle_row_law(O, w, b, tg, om_b[min(tg, L - 1)], resample_mode)
-        _close(gpu["resid_mass"][b:b + 1], [R], "resid_mass", MASS_ABS)
+        mass_close(gpu["resid_mass"][b], R, exact_R())
+        if xg != xo and R < R_FLOOR:
+            p, _ = _oracle_rows(O, w, b, tg)
+            assert 0 <= xg < w.V and p[xg] > 0, "seq %d: gpu token %d has no probability" % (b, xg)
+            stats["token_exempt"] += 1
+            continue
         if xg != xo:
             assert 0 <= xg < w.V and g[xg] > 0, "seq %d: gpu token %d has zero mass" % (b, xg)
             C = np.cumsum(g)

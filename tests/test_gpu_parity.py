@@ -172,6 +172,37 @@ def test_resample_entry_point(P, oracle):
         assert (tok.cpu().numpy() == ot).sum() >= 5
 
 
+def test_resample_where_the_law_has_no_mass(P, oracle):
+    """p and q that coincide (here: both one-hot on the same token after top-1 truncation, from
+    different logits) leave [p - q]_+ without mass: any law is optimal there, the oracle falls
+    back to p (mass 1).  fp32 may see one ulp of dust instead of an exact zero; either way the
+    token must be the one token that has probability, and the reported mass is 1 or that dust."""
+    from tests.parity_util import MASS_ABS
+    B, V = 64, 2
+    g = torch.Generator(device="cuda").manual_seed(3)
+    t = torch.randn((B, V), generator=g, device="cuda") * 3
+    d = t + 0.1 * torch.randn((B, V), generator=g, device="cuda")
+    same_top = (t.argmax(1) == d.argmax(1))
+    assert same_top.sum() > B // 2
+    u = uniforms24(g, (B,), "cuda")
+    om = torch.full((B,), 2.0, device="cuda")
+    for mode in (0, 1):
+        params = P.make_params(t.unsqueeze(1), d.unsqueeze(1), has_bonus=0, top_k=1, resample_mode=mode)
+        ws = torch.empty(max(P.cool_sd_workspace_bytes(params), 256), dtype=torch.uint8, device="cuda")
+        tok = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+        mass = torch.full((B,), -1.0, device="cuda")
+        P.cool_sd_resample(params, t, None, d, None, om, u, tok, mass, ws)
+        torch.cuda.synchronize()
+        ot, om_, _ = oracle.resample(t.cpu().numpy(), d.cpu().numpy(), om.cpu().numpy(), u.cpu().numpy(), top_k=1,
+                                     resample_mode=mode, want_g=True)
+        np.testing.assert_array_equal(tok.cpu().numpy(), ot)            # the target's arg max, always
+        np.testing.assert_array_equal(ot, t.argmax(1).cpu().numpy())
+        m = mass.cpu().numpy()
+        same = same_top.cpu().numpy()
+        assert ((np.abs(m[same] - 1.0) <= 1e-5) | ((m[same] >= 0) & (m[same] <= MASS_ABS))).all()
+        np.testing.assert_allclose(m[~same], om_[~same], rtol=1e-5)     # disjoint supports: mass 1
+
+
 def test_repeat_calls_share_workspace_and_are_deterministic(P, oracle):
     w = make_workload(2, device="cuda", B=8, L=8, V=16384)
     om = torch.from_numpy(_omega(P, w)).cuda()

@@ -1,0 +1,121 @@
+"""Seeded random sweep over every entry point: shapes from two tokens to 70000, both dtypes,
+guidance, temperature, top-k, excluded tokens, with and without the bonus row, all schedules and
+resampling laws; verify (all-rows and early-exit), diagnostics, neighbour aggregation and the
+stand-alone resampling step (with a draft row and as the drafting stage's draw) are each compared
+with the oracle on the same inputs."""
+import numpy as np
+import pytest
+import torch
+
+from tests.parity_util import MASS_ABS, R_FLOOR, REL_TOL, U_TOL, compare_verify, compare_verify_lantern, to_numpy
+from tests.test_gpu_diagnostics import _check as check_diagnostics
+from workloads import make_neighbor_table, make_workload, uniforms24
+
+pytestmark = pytest.mark.gpu
+
+VOCABS = [2, 3, 9, 64, 257, 1000, 1024, 4096, 4097, 8192, 8200, 12000, 16384, 16385, 16392, 20001, 32768, 33000,
+          65536, 65540, 70000]
+
+
+def _check_resample(P, oracle, w, omega0, mode, case, exempt):
+    """cool_sd_resample on the rows of position 1: with the draft row, then the draft-less draw from q."""
+    B, V = w.B, w.V
+    f = lambda x: None if x is None else x[:, 0].contiguous()
+    t, tu, d, du = f(w.target), f(w.target_uncond), f(w.draft), f(w.draft_uncond)
+    n = lambda x: None if x is None else x.float().cpu().numpy()
+    rp = P.make_params(t.unsqueeze(1), d.unsqueeze(1), has_bonus=0, top_k=w.top_k, cfg_scale=w.cfg_scale,
+                       temperature=w.temperature, resample_mode=mode)
+    ws = torch.empty(max(P.cool_sd_workspace_bytes(rp), 256), dtype=torch.uint8, device="cuda")
+    P.cool_sd_workspace_init(ws)
+    u = uniforms24(torch.Generator(device="cuda").manual_seed(case), (B,), "cuda")
+    om = torch.full((B,), float(omega0), device="cuda")
+    tok = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    mass = torch.zeros(B, device="cuda")
+    kw = dict(cfg_scale=w.cfg_scale, temperature=w.temperature, top_k=w.top_k, want_g=True)
+    for with_draft in (True, False):
+        if with_draft:
+            P.cool_sd_resample(rp, t, tu, d, du, om, u, tok, mass, ws)
+            ot, R, g = oracle.resample(n(t), n(d), om.cpu().numpy(), u.cpu().numpy(), target_uncond=n(tu),
+                                       draft_uncond=n(du), resample_mode=mode, **kw)
+        else:
+            P.cool_sd_resample(rp, d, du, None, None, None, u, tok, mass, ws)
+            ot, R, g = oracle.resample(n(d), None, None, u.cpu().numpy(), target_uncond=n(du), **kw)
+        torch.cuda.synchronize()
+        tk, ms = tok.cpu().numpy(), mass.cpu().numpy().astype(np.float64)
+        for b in range(B):
+            assert 0 <= tk[b] < V
+            # R == 1 exactly: the law is p, or the oracle's fall-back where the law had no mass
+            unresolved = R[b] < R_FLOOR or (R[b] == 1.0 and ms[b] <= MASS_ABS)
+            if unresolved:
+                assert 0 <= ms[b] <= MASS_ABS or abs(ms[b] - 1.0) <= REL_TOL
+                exempt.append(("mass", case, b))
+                continue
+            assert abs(ms[b] - R[b]) <= REL_TOL * R[b] + MASS_ABS
+            assert g[b][tk[b]] > 0
+            if tk[b] != ot[b]:
+                C = np.cumsum(g[b])
+                v = float(u[b]) * R[b]
+                gap = (v - C[tk[b]]) / R[b] if tk[b] < ot[b] else (C[tk[b] - 1] - v) / R[b]
+                assert 0 <= gap <= U_TOL, (b, tk[b], ot[b], gap)
+                exempt.append(("token", case, b))
+
+
+@pytest.mark.parametrize("seed", [101, 202])
+def test_random_cases_through_every_entry_point(P, oracle, seed):
+    rng = np.random.default_rng(seed)
+    exempt = []
+    for case in range(150):
+        dtype = "bf16" if rng.random() < 0.6 else "f32"
+        V = int(rng.choice(VOCABS))
+        B, L = int(rng.integers(1, 7)), int(rng.integers(1, 12))
+        if rng.random() < 0.05:
+            L, V = int(rng.integers(60, 130)), min(V, 4097)
+        guided = rng.random() < 0.35
+        cfg = 3 if guided else int(rng.choice([1, 2, 4, 5]))
+        top_k = int(rng.integers(1, V + 1)) if rng.random() < 0.45 else 0
+        if top_k and rng.random() < 0.5:
+            top_k = int(rng.integers(1, min(V, 2000) + 1))
+        w = make_workload(cfg, device="cuda", B=B, L=L, V=V, dtype=dtype, seed=9000 + seed * 1000 + case,
+                          top_k=top_k if guided else None)
+        if not guided:
+            w.top_k = top_k
+        if rng.random() < 0.3:
+            w.temperature = float(rng.choice([0.5, 0.8, 1.3]))
+        bonus = rng.random() >= 0.25
+        if not bonus:
+            w.target = w.target[:, :L]
+            if w.target_uncond is not None:
+                w.target_uncond = w.target_uncond[:, :L]
+        if rng.random() < 0.15:                      # tokens the draft model excludes; every row keeps one finite logit
+            m = torch.rand(V, device="cuda") < 0.3
+            m[int(rng.integers(0, V))] = False
+            w.draft[..., m] = float("-inf")
+            if w.draft_uncond is not None:
+                w.draft_uncond[..., m] = float("-inf")
+        mode = int(rng.integers(0, 2))
+        delta = float(rng.choice([0.5, 1.0, 1.1, 2.0, 4.0, 20.0]))
+        kind = int(rng.choice([P.COOL_SD_SCHED_EXP, P.COOL_SD_SCHED_UNIFORM]))
+        om = P.cool_sd_schedule(kind, L, delta, 0.7)
+        print("case", case, dict(cfg=cfg, B=B, L=L, V=V, dtype=dtype, top_k=w.top_k, T=w.temperature, bonus=bonus,
+                                 mode=mode, delta=delta, kind=kind), flush=True)
+        omt = torch.from_numpy(om).cuda()
+        gpu = to_numpy(P.verify_workload(w, omt, resample_mode=mode))
+        st = compare_verify(oracle, w, om, gpu, resample_mode=mode, has_bonus=bonus)
+        exempt += [("verify", case)] * (st["tau_exempt"] + st["token_exempt"])
+        early = to_numpy(P.verify_workload(w, omt, resample_mode=mode, flags=P.COOL_SD_FLAG_EARLY_EXIT))
+        honoured = w.top_k == 0 and V <= 16384 and V % (8 if dtype == "bf16" else 4) == 0
+        st = compare_verify(oracle, w, om, early, resample_mode=mode, has_bonus=bonus, early_exit=honoured)
+        exempt += [("early", case)] * (st["tau_exempt"] + st["token_exempt"])
+        if bonus:
+            check_diagnostics(P, oracle, w, om)
+        if V > 2 and bonus and L <= 20:
+            k = int(min(V - 1, rng.choice([1, 3, 10, 70])))
+            lam = float(rng.choice([0.0, 0.02, 0.3, 2.0]))
+            nbr = make_neighbor_table(V, k, device="cuda", seed=case, pad=0.1 if k > 2 else 0.0, self_entries=k > 3)
+            lmode = int(rng.integers(0, 3))
+            g2 = to_numpy(P.verify_lantern_workload(w, nbr, lam, resample_mode=lmode))
+            st = compare_verify_lantern(oracle, w, nbr.cpu().numpy(), lam, g2, resample_mode=lmode)
+            exempt += [("lantern", case)] * (st["tau_exempt"] + st["token_exempt"] + st["set_exempt"])
+        _check_resample(P, oracle, w, om[0], mode, case, exempt)
+    print("exemptions", exempt, flush=True)
+    assert len(exempt) <= 6

@@ -183,6 +183,35 @@ class Runner:
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e-3 / (passes * len(self.pool))
 
+    def read_probe_time(self, n):
+        """Yardstick for the statistics kernel: a plain streaming read of the same logit tensors in one
+        launch of the same shape (cool_sd_profile_read_probe), replayed back to back from a graph
+        exactly as kernel_times() replays the statistics kernel.  Guided workloads need two launches
+        (conditional pair, unconditional pair).  Returns seconds per step and launches per step."""
+        pkg, torch = self.pkg, self.torch
+        out = torch.empty(self.bytes_per_step // 8192 + 64, dtype=torch.int32, device="cuda")
+
+        def issue():
+            for w in self.pool:
+                pkg.cool_sd_profile_read_probe(w.target, w.draft, out)
+                if w.target_uncond is not None:
+                    pkg.cool_sd_profile_read_probe(w.target_uncond, w.draft_uncond, out)
+        issue()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            issue()
+        reps = max(2, -(-n // len(self.pool)))
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / (reps * len(self.pool)), 2 if self.pool[0].target_uncond is not None else 1
+
     def kernel_times(self, n):
         """Average duration of the statistics kernel and of the whole call, over the pool.
 
@@ -460,6 +489,7 @@ def main():
     done, wall, dev_s = r.time(a.steps, a.warmup, a.launch)
     tokens = done * r.B * r.L
     kern_s, kern_ev_s, call_s = r.kernel_times(a.kernel_samples)
+    probe_s, probe_launches = r.read_probe_time(a.kernel_samples)
     kernel_name = "row_stats_topk_kernel" if r.pool[0].top_k > 0 else "row_stats_kernel"
     kernel_bytes = r.bytes_per_step
     if a.early_exit and r.V <= 16384:
@@ -492,6 +522,10 @@ def main():
                      "kernel": kernel_name, "algorithmic_bytes_per_launch": kernel_bytes,
                      "us_per_launch": kern_s * 1e6,
                      "us_per_launch_lone_events": kern_ev_s * 1e6,
+                     # a plain read of the same tensors in one launch of the same shape: what the chip
+                     # delivers for this many bytes per launch, start-up included
+                     "read_probe": {"us": probe_s * 1e6, "GBps": r.bytes_per_step / probe_s / 1e9,
+                                    "launches": probe_launches, "kernel_over_probe": kern_s / probe_s},
                      "whole_call_us": call_s * 1e6, "whole_call_GBps": r.bytes_per_step / call_s / 1e9,
                      "graph_step_us": dev_s / done * 1e6},
     }
@@ -506,12 +540,15 @@ def main():
                         flags=flags, B=big)
             d2, w2, s2 = rr.time(max(64, 8 * len(rr.pool)), 2 * len(rr.pool), a.launch)
             k2, _, c2 = rr.kernel_times(40)
+            p2, pl2 = rr.read_probe_time(40)
             name = "cfg%d" % c + ("_B%d" % big if big else "")
             extra[name] = {"tokens_per_s": d2 * rr.B * rr.L / w2, "us_per_step": s2 / d2 * 1e6,
                                   "whole_call_GBps": rr.bytes_per_step / (s2 / d2) / 1e9,
                                   "whole_call_frac": rr.bytes_per_step / (s2 / d2) / 1e9 / HBM_PEAK_GBS,
                                   "row_stats_us": k2 * 1e6, "row_stats_GBps": rr.bytes_per_step / k2 / 1e9,
                                   "row_stats_frac": rr.bytes_per_step / k2 / 1e9 / HBM_PEAK_GBS,
+                                  "read_probe_us": p2 * 1e6, "read_probe_GBps": rr.bytes_per_step / p2 / 1e9,
+                                  "read_probe_launches": pl2,
                                   "bytes_per_step": rr.bytes_per_step, "pool_batches": len(rr.pool)}
             if a.diagnostics:
                 extra[name]["diagnostics"] = time_diagnostics(rr)

@@ -230,6 +230,16 @@ int cool_sd_diagnostics(const cool_sd_params* p,
 int cool_sd_profile_enable(int mode);
 int cool_sd_profile_read(float* stats_kernel_ms, float* call_ms);
 
+/* Benchmark instrumentation: a plain streaming read of two device buffers in ONE launch with the
+ * launch shape of the row-statistics kernel on short rows (256 threads, 16 bytes per lane and
+ * load, 8 KiB per workgroup) and no arithmetic beyond an exclusive-or of the words -- what this
+ * GPU delivers for that many bytes in one launch, start-up included, as a live yardstick beside
+ * the statistics kernel's own time.  a_dev / b_dev: 16-byte aligned, sizes multiples of 16
+ * (b_bytes may be 0); workspace_dev: at least 4 bytes per 8 KiB read (rounded up per buffer),
+ * receives one word per workgroup.  Asynchronous on hip_stream. */
+int cool_sd_profile_read_probe(const void* a_dev, size_t a_bytes, const void* b_dev, size_t b_bytes,
+                               void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
 /* Static description of a cool_sd_status. */
 const char* cool_sd_strerror(int code);
 

@@ -69,6 +69,8 @@ def lib():
         L.cool_sd_profile_enable.restype = C.c_int
         L.cool_sd_profile_read.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.cool_sd_profile_read.restype = C.c_int
+        L.cool_sd_profile_read_probe.argtypes = [vp, C.c_size_t, vp, C.c_size_t, vp, C.c_size_t, vp]
+        L.cool_sd_profile_read_probe.restype = C.c_int
         L.cool_sd_strerror.argtypes = [C.c_int]
         L.cool_sd_strerror.restype = C.c_char_p
         _lib = L
@@ -159,6 +161,15 @@ def cool_sd_diagnostics(params, target, target_uncond, draft, draft_uncond, omeg
                                    _stream(stream))
     if check and rc != 0:
         raise CoolSDError(rc, "cool_sd_diagnostics")
+    return rc
+
+
+def cool_sd_profile_read_probe(a, b, workspace, stream=None, check=True):
+    """Streaming read of tensors a and b (b may be None) in one launch; see include/cool_sd.h."""
+    nb = lambda t: 0 if t is None else t.numel() * t.element_size()
+    rc = lib().cool_sd_profile_read_probe(_ptr(a), nb(a), _ptr(b), nb(b), _ptr(workspace), nb(workspace), _stream(stream))
+    if check and rc != 0:
+        raise CoolSDError(rc, "cool_sd_profile_read_probe")
     return rc
 
 

@@ -366,6 +366,22 @@ int cool_sd_profile_read(float* stats_kernel_ms, float* call_ms) {
   return COOL_SD_OK;
 }
 
+int cool_sd_profile_read_probe(const void* a_dev, size_t a_bytes, const void* b_dev, size_t b_bytes,
+                               void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+  if (!a_dev || a_bytes == 0 || (a_bytes % 16) != 0 || (b_bytes % 16) != 0 || !is_aligned16(a_dev) ||
+      (b_bytes != 0 && (!b_dev || !is_aligned16(b_dev))))
+    return COOL_SD_EINVAL;
+  const size_t na = a_bytes / 16, nb = b_bytes / 16;
+  const size_t groups = (na + csd::kProbeVecsPerGroup - 1) / csd::kProbeVecsPerGroup +
+                        (nb + csd::kProbeVecsPerGroup - 1) / csd::kProbeVecsPerGroup;
+  if (groups > 0x7fffffffULL) return COOL_SD_EINVAL;
+  if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) % 4) != 0 || workspace_bytes < groups * 4)
+    return COOL_SD_EWORKSPACE;
+  hipError_t e = csd::launch_read_probe(static_cast<const uint4*>(a_dev), na, static_cast<const uint4*>(b_dev), nb,
+                                        static_cast<uint32_t*>(workspace_dev), static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? COOL_SD_OK : COOL_SD_ELAUNCH;
+}
+
 const char* cool_sd_strerror(int code) {
   switch (code) {
     case COOL_SD_OK: return "ok";

@@ -75,5 +75,8 @@ hipError_t launch_diagnostics(const KArgs& a, int dtype, bool xf, bool local, hi
 
 // Zero n 32-bit words.
 hipError_t launch_zero(uint32_t* p, size_t n, hipStream_t stream);
+// benchmark yardstick: streaming read of two buffers (sizes in 16-byte vectors), one word out per workgroup
+hipError_t launch_read_probe(const uint4* a, size_t na, const uint4* b, size_t nb, uint32_t* out, hipStream_t stream);
+constexpr size_t kProbeVecsPerGroup = 512;   // 8 KiB
 
 }  // namespace csd

@@ -1913,6 +1913,34 @@ hipError_t launch_diagnostics(const KArgs& a, int dtype, bool xf, bool local, hi
                    : launch_diag_typed<kDtF32, false, false>(a, local, stream);
 }
 
+// Streaming-read yardstick (cool_sd_profile_read_probe): workgroup g reads 512 consecutive
+// vectors of buffer a (g < ga) or b, two loads per thread in flight, and leaves the
+// exclusive-or of what it read.
+__global__ __launch_bounds__(kThreads) void read_probe_kernel(const uint4* __restrict__ a, size_t na,
+                                                             const uint4* __restrict__ b, size_t nb, unsigned ga,
+                                                             uint32_t* __restrict__ out) {
+  __shared__ uint32_t red[kWaves];
+  const bool first = blockIdx.x < ga;
+  const uint4* src = first ? a : b;
+  const size_t n = first ? na : nb;
+  const size_t base = size_t(first ? blockIdx.x : blockIdx.x - ga) * kProbeVecsPerGroup;
+  size_t i0 = base + threadIdx.x, i1 = base + kThreads + threadIdx.x;
+  const uint4 v0 = src[i0 < n ? i0 : n - 1], v1 = src[i1 < n ? i1 : n - 1];
+  uint32_t x = v0.x ^ v0.y ^ v0.z ^ v0.w ^ v1.x ^ v1.y ^ v1.z ^ v1.w;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) x ^= __shfl_xor(x, off);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
+  __syncthreads();
+  if (threadIdx.x == 0) out[blockIdx.x] = red[0] ^ red[1] ^ red[2] ^ red[3];
+}
+
+hipError_t launch_read_probe(const uint4* a, size_t na, const uint4* b, size_t nb, uint32_t* out, hipStream_t stream) {
+  const size_t ga = (na + kProbeVecsPerGroup - 1) / kProbeVecsPerGroup, gb = (nb + kProbeVecsPerGroup - 1) / kProbeVecsPerGroup;
+  (void)hipGetLastError();
+  hipLaunchKernelGGL(read_probe_kernel, dim3((unsigned)(ga + gb)), dim3(kThreads), 0, stream, a, na, b, nb, (unsigned)ga, out);
+  return checked("read_probe_kernel");
+}
+
 hipError_t launch_zero(uint32_t* p, size_t n, hipStream_t stream) {
   if (n == 0) return hipSuccess;
   size_t blocks = (n + 255) / 256;

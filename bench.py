@@ -114,23 +114,45 @@ class Runner:
             for i in range(len(self.pool)):
                 self.step(i)
         self.graph = g
+        self.part_graphs = {}
+
+    def _partial(self, k):
+        """A graph of the first k < len(pool) steps of a pass (for step counts that are not whole passes)."""
+        if k not in self.part_graphs:
+            torch = self.torch
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for i in range(k):
+                    self.step(i)
+            self.part_graphs[k] = g
+        return self.part_graphs[k]
 
     def run(self, steps, launch):
-        """Enqueue `steps` steps (rounded up to whole pool passes in graph mode); returns steps issued."""
+        """Enqueue exactly `steps` steps: whole pool passes plus, in graph mode, one replay of a
+        shorter graph for the remainder (captured beforehand by prepare())."""
         if launch == "graph":
             n = len(self.pool)
-            reps = -(-steps // n)
-            for _ in range(reps):
+            for _ in range(steps // n):
                 self.graph.replay()
-            return reps * n
+            if steps % n:
+                self.part_graphs[steps % n].replay()
+            return steps
         for i in range(steps):
             self.step(i)
         return steps
 
+    def prepare(self, counts, launch):
+        if launch == "graph":
+            if self.graph is None:
+                self.capture()
+            for c in counts:
+                if c % len(self.pool):
+                    self._partial(c % len(self.pool))
+
     def time(self, steps, warmup, launch):
         torch = self.torch
-        if launch == "graph" and self.graph is None:
-            self.capture()
+        self.prepare((steps, warmup), launch)
         self.run(warmup, launch)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

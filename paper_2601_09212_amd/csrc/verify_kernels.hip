@@ -456,14 +456,17 @@ __global__ __launch_bounds__(kThreads) void combine_rows_kernel(const KArgs a) {
 // loaded before any is used: reference = max, sum rescaled by exact powers of two.
 constexpr int kMaxDirect = 4;
 constexpr int kStage = 1024;   // chunk masses staged in LDS by the sampling kernel
-__device__ __forceinline__ void combine_row(const KArgs& a, int r, float& C, float& S) {
+// In two halves, for callers that want the loads of several rows in flight before anything waits
+// for the first of them.
+__device__ __forceinline__ void load_row_parts(const KArgs& a, int r, float2 (&v)[kMaxDirect]) {
   const float2* p = a.stat + int64_t(r) * a.cs;
-  float2 v[kMaxDirect];
 #pragma unroll
-  for (int cc = 0; cc < kMaxDirect; ++cc) {
-    v[cc] = p[cc < a.cs ? cc : 0];
+  for (int cc = 0; cc < kMaxDirect; ++cc) v[cc] = p[cc < a.cs ? cc : 0];
+}
+__device__ __forceinline__ void combine_parts(const KArgs& a, float2 (&v)[kMaxDirect], float& C, float& S) {
+#pragma unroll
+  for (int cc = 0; cc < kMaxDirect; ++cc)
     if (cc >= a.cs) v[cc] = make_float2(kRefFloor, 0.f);
-  }
   float m = kRefFloor;
 #pragma unroll
   for (int cc = 0; cc < kMaxDirect; ++cc) m = fmaxf(m, v[cc].x);
@@ -471,6 +474,11 @@ __device__ __forceinline__ void combine_row(const KArgs& a, int r, float& C, flo
 #pragma unroll
   for (int cc = 0; cc < kMaxDirect; ++cc) s = __fadd_rn(s, v[cc].y * exp2_fast(v[cc].x - m));
   C = m; S = s;
+}
+__device__ __forceinline__ void combine_row(const KArgs& a, int r, float& C, float& S) {
+  float2 v[kMaxDirect];
+  load_row_parts(a, r, v);
+  combine_parts(a, v, C, S);
 }
 
 // Unnormalised resampling mass of one token.  p = 2^(lt*log2e - Ct) / St etc.
@@ -621,28 +629,42 @@ __device__ __forceinline__ int chunk_select(const RowRegs<DT, XF, kT>& rt, const
 // per-position diagnostics.
 __device__ __forceinline__ bool eval_position(const KArgs& a, int b, int i, bool emit, float& Ct, float& St,
                                               float& Cd, float& Sd) {
+  // This runs in one wave while the rest of the workgroup waits for tau, so what matters is the
+  // number of dependent memory round trips: everything the position needs -- the statistics of
+  // both rows, the two logits of the draft token, omega_i and u_i -- is requested before the first
+  // value is used, with no branch in between (the bonus row has no draft: it re-reads the last
+  // draft position's entries and ignores them).
   const int rps = a.L + a.has_bonus;
-  const int rt_ = b * rps + i;
-  combine_row(a, rt_, Ct, St);
-  if (i >= a.L) return false;                       // the bonus row has no draft token
-  const int rd_ = a.rows_t + b * a.L + i;
-  combine_row(a, rd_, Cd, Sd);
-  // logits of the draft token, left by the statistics kernel
+  const bool has_draft = i < a.L;
+  const int id = has_draft ? i : a.L - 1;
+  const int rt_ = b * rps + i, rd_ = a.rows_t + b * a.L + id;
+  float2 vt[kMaxDirect], vd[kMaxDirect];
+  load_row_parts(a, rt_, vt);
+  load_row_parts(a, rd_, vd);
+  // logits of the draft token, left by the statistics kernel (nothing was left for a bonus row:
+  // whatever the slot holds is read and ignored)
   const float lt = a.tok_logit[rt_], ld = a.tok_logit[rd_];
+  float omega = a.omega[int64_t(b) * a.om_sb + id];
+  float u = a.u_acc[int64_t(b) * a.L + id];
+  // the empty statement keeps the compiler from sinking these two loads down to their uses,
+  // behind the wait for the others
+  asm volatile("" : "+v"(omega), "+v"(u));
+  combine_parts(a, vt, Ct, St);
+  combine_parts(a, vd, Cd, Sd);
   // exponents of p(x~) and q(x~) in base-2 units; the ratio p/q is formed from their
   // difference so that it survives when both probabilities underflow fp32
   const float et = __fmaf_rn(lt, kLog2e, -Ct), ed = __fmaf_rn(ld, kLog2e, -Cd);
   const float ratio = __fmul_rn(exp2_fast(__fsub_rn(et, ed)), Sd / St);
-  const float omega = a.omega[int64_t(b) * a.om_sb + i];
   // f = min{1, omega p/q}; a token the draft excludes (q = 0) has f = 1, also at 0/0
   const float fi = (ld == -INFINITY) ? 1.f : ((omega > 0.f) ? fminf(1.f, __fmul_rn(omega, ratio)) : 0.f);
-  if (emit) {
+  if (emit && has_draft) {
     const int64_t o = int64_t(b) * a.L + i;
     if (a.p_tok) a.p_tok[o] = exp2_fast(et) / St;
     if (a.q_tok) a.q_tok[o] = exp2_fast(ed) / Sd;
     if (a.f) a.f[o] = fi;
   }
-  return !(a.u_acc[int64_t(b) * a.L + i] <= fi);
+  if (!has_draft) { Cd = kRefFloor; Sd = 0.f; }         // the bonus row stands alone
+  return has_draft && !(u <= fi);
 }
 
 // Accept test at every position of sequence b (Eq. relax) and tau = first rejection (Algorithm 1)

@@ -1265,12 +1265,6 @@ __global__ __launch_bounds__(kThreads) void sequence_early_exit_tile_kernel(cons
   static_assert(RowRegs<DT, XF, kT>::kRaw, "rows stay packed");
   __shared__ SmemT sm;
   const int b = blockIdx.x, L = a.L, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  for (int i = tid; i < L; i += kThreads) {
-    sm.tok[i] = min(max(a.tokens[int64_t(b) * L + i], 0), a.V - 1);
-    sm.u[i] = a.u_acc[int64_t(b) * L + i];
-    sm.om[i] = a.omega[int64_t(b) * a.om_sb + i];
-  }
-  __syncthreads();                                      // tok / u / om are visible
   struct Slot { uint4 tc[kT], dc[kT]; float tl, dl; };
   // vector k of this thread starts at element (k*256 + tid)*kE; 32-bit offsets from the (uniform)
   // row pointer.  Vectors beyond the end of the row are fetched from its last vector and read
@@ -1289,7 +1283,7 @@ __global__ __launch_bounds__(kThreads) void sequence_early_exit_tile_kernel(cons
   };
   // Always the same number of loads, whatever i is (row indices are clamped to the last valid
   // row, whose re-read is harmless), so that the compiler can count the loads in flight.
-  auto fetch_pair = [&](Slot& sl, int i) {
+  auto fetch_vectors = [&](Slot& sl, int i) {
     const int it = min(i, L + a.has_bonus - 1), id = min(i, L - 1);
     const char* tc = row_ptr(a.t, int64_t(b) * a.t_sb + int64_t(it) * a.t_sl, kES);
     const char* dc = row_ptr(a.d, int64_t(b) * a.d_sb + int64_t(id) * a.d_sl, kES);
@@ -1298,12 +1292,28 @@ __global__ __launch_bounds__(kThreads) void sequence_early_exit_tile_kernel(cons
       sl.tc[k] = fetch(tc, k);
       sl.dc[k] = fetch(dc, k);
     }
-    const int x = sm.tok[id];
-    sl.tl = load_elem<DT>(tc, x);
-    sl.dl = load_elem<DT>(dc, x);
   };
+  auto fetch_token_logits = [&](Slot& sl, int i) {
+    const int it = min(i, L + a.has_bonus - 1), id = min(i, L - 1);
+    const int x = sm.tok[id];
+    sl.tl = load_elem<DT>(row_ptr(a.t, int64_t(b) * a.t_sb + int64_t(it) * a.t_sl, kES), x);
+    sl.dl = load_elem<DT>(row_ptr(a.d, int64_t(b) * a.d_sb + int64_t(id) * a.d_sl, kES), x);
+  };
+  auto fetch_pair = [&](Slot& sl, int i) {
+    fetch_vectors(sl, i);
+    fetch_token_logits(sl, i);
+  };
+  // the first pair's vectors are requested before anything else: they do not depend on the
+  // per-position inputs that are staged in LDS next
   Slot slot;
-  fetch_pair(slot, 0);
+  fetch_vectors(slot, 0);
+  for (int i = tid; i < L; i += kThreads) {
+    sm.tok[i] = min(max(a.tokens[int64_t(b) * L + i], 0), a.V - 1);
+    sm.u[i] = a.u_acc[int64_t(b) * L + i];
+    sm.om[i] = a.omega[int64_t(b) * a.om_sb + i];
+  }
+  __syncthreads();                                      // tok / u / om are visible
+  fetch_token_logits(slot, 0);
   RowRegs<DT, XF, kT> rt, rd;
   rd.clear();
 

@@ -718,21 +718,31 @@ __device__ __forceinline__ int find_tau(const KArgs& a, int b, bool emit, int* p
   return a.L;   // not reached
 }
 
+// Shared memory of the kernels that run 1024 threads per sequence.
+struct SmemW {
+  int pick[kWavesW];
+  int pick_last[kWavesW];
+  float scan_tot[kWavesW];
+  float4 rowstat;
+};
+
 // Middle kernel of the several-chunk path: one workgroup per sequence finds tau and leaves
 // accept_len[b] and the sampled row's statistics for the sampling kernel.
 template <int DT, bool XF>
-__global__ __launch_bounds__(kThreads) void accept_kernel(const KArgs a) {
-  __shared__ Smem sm;
+__global__ __launch_bounds__(kThreadsW) void accept_kernel(const KArgs a) {
+  __shared__ SmemW sm;
   const int b = blockIdx.x;
   if (a.accept_combines) {
     // rows of many statistics chunks: combine the chunks of this sequence's rows first, one wave
-    // per row (what combine_rows_kernel does for all rows), then read them back below
+    // per row (what combine_rows_kernel does for all rows), then read them back below.  Sixteen
+    // waves, so that a window of eight positions is one or two rows per wave: each row is a
+    // memory round trip of its own.
     const int rps = a.L + a.has_bonus;
-    for (int q = threadIdx.x >> 6; q < rps + a.L; q += kWaves)
+    for (int q = threadIdx.x >> 6; q < rps + a.L; q += kWavesW)
       combine_row_wave(a, q < rps ? b * rps + q : a.rows_t + b * a.L + (q - rps));
     __syncthreads();          // the rows' statistics are visible to the whole workgroup
   }
-  const int j = find_tau<DT, XF, kThreads>(a, b, true, sm.pick_first, &sm.rowstat);
+  const int j = find_tau<DT, XF, kThreadsW>(a, b, true, sm.pick, &sm.rowstat);
   if (threadIdx.x == 0) a.seq_stat[b] = sm.rowstat;
   (void)j;
 }
@@ -745,12 +755,6 @@ __global__ __launch_bounds__(kThreads) void accept_kernel(const KArgs a) {
 // the running mass in ascending token order is simply a prefix sum over threads.  Per thread:
 // one partial mass per vector; block-wide: one scan.  The thread whose interval contains u*R
 // finds the vector among its partials and re-evaluates that vector's elements.
-struct SmemW {
-  int pick[kWavesW];
-  int pick_last[kWavesW];
-  float scan_tot[kWavesW];
-  float4 rowstat;
-};
 
 // One draw from the resampling law of a row pair that 1024 threads hold in registers (thread t
 // owns the kVW consecutive vectors t*kVW ..): per-vector masses, one block scan, then vector and
@@ -1877,7 +1881,7 @@ static hipError_t launch_rest(const KArgs& a, hipStream_t stream) {
     return checked("sequence_whole_kernel");
   }
   if (!a.resample_only) {     // several chunks: find tau once per sequence
-    hipLaunchKernelGGL((accept_kernel<DT, XF>), dim3(gB), dim3(kThreads), 0, stream, a);
+    hipLaunchKernelGGL((accept_kernel<DT, XF>), dim3(gB), dim3(kThreadsW), 0, stream, a);
     e = checked("accept_kernel");
     if (e != hipSuccess) return e;
   }

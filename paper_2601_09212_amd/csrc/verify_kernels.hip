@@ -25,10 +25,11 @@
 // sequence), sequence_kernel<kMasses> (mass of every 8192-logit chunk of the sampled rows,
 // streaming) and sequence_kernel<kSelect> (pick the chunk that holds u*R, re-read it, inverse
 // CDF).  cool_sd_resample on short rows is one launch (resample_whole_kernel, resample_topk_kernel).
-// Other entry points add: lantern_agg_kernel (neighbour aggregation of the LANTERN-style
-// acceptance), sequence_early_exit_tile_kernel / sequence_early_exit_kernel (the whole call per
-// sequence, stopping at the first rejection), diag_kernel (per-position terms of Theorem 2), and for top-k on rows beyond 65536
-// logits three radix passes (topk_radix_*).
+// Other entry points add: lantern_agg_position (neighbour aggregation of the LANTERN-style
+// acceptance: extra workgroups of the statistics launch, or lantern_agg_kernel under top-k),
+// sequence_early_exit_tile_kernel / sequence_early_exit_kernel (the whole call per sequence,
+// stopping at the first rejection), diag_kernel (per-position terms of Theorem 2), and for top-k
+// on rows beyond 65536 logits three radix passes (topk_radix_*).
 // No workgroup ever waits for another one inside a launch: there are no fences or spin waits
 // anywhere, the only global atomics are the integer histogram adds of the radix passes (whose
 // sums do not depend on the order), and every output is a pure function of the inputs.
@@ -107,11 +108,83 @@ __device__ __forceinline__ int load_draft_token(const KArgs& a, const RowRef& rw
   return a.tokens[int64_t(rw.b) * a.L + rw.i + z];
 }
 
-template <int DT, bool XF, int AL, int NT, bool G3>
+__device__ __forceinline__ float token_logit_any(int dt, const char* cond, const char* uncond, int x, bool xf,
+                                                 float s, float inv_T, float thr) {
+  float lc = dt == kDtBF16 ? load_elem<kDtBF16>(cond, x) : load_elem<kDtF32>(cond, x);
+  if (!xf) return lc;
+  float lu = 0.f;
+  if (uncond) lu = dt == kDtBF16 ? load_elem<kDtBF16>(uncond, x) : load_elem<kDtF32>(uncond, x);
+  const float l = transform_logit(lc, lu, uncond != nullptr, s, inv_T);
+  return l >= thr ? l : -INFINITY;
+}
+
+// Eq. f_lantern for position pos = (b, i), by one wave: gathers the k neighbour logits of x~_i,
+// scans their weights 2^((l_n - l_x) log2e) and leaves agg = (sum over the set) / p_i(x~_i) >= 1
+// and the member count in the workspace (plus the optional count output).  Needs no row
+// statistics; under top-k it needs the row's threshold, which the statistics pass leaves.
+__device__ __forceinline__ void lantern_agg_position(const KArgs& a, int pos, int dt, bool xf) {
+  const int lane = threadIdx.x & 63;
+  const int b = pos / a.L, i = pos - b * a.L;
+  const int rt_ = b * (a.L + a.has_bonus) + i;
+  const int es = dt == kDtBF16 ? 2 : 4;
+  const int64_t off = int64_t(b) * a.t_sb + int64_t(i) * a.t_sl;
+  const char* cond = row_ptr(a.t, off, es);
+  const char* uncond = row_ptr(a.tu, off, es);
+  const float thr = (xf && a.top_k > 0) ? a.thr[rt_] : -INFINITY;
+  const int x = min(max(a.tokens[pos], 0), a.V - 1);
+  // the (transformed, masked) logit of x~_i: the same value the statistics kernel leaves in
+  // tok_logit, formed here so that this does not have to wait for that kernel
+  const float lx = token_logit_any(dt, cond, uncond, x, xf, a.cfg_scale, a.inv_T, thr);
+  const int32_t* row = a.nbr + int64_t(x) * a.lan_k;
+  float cum = 0.f;
+  int m = 0;
+  if (lx > -INFINITY) {                       // p(x~) = 0 admits no neighbour: nothing is below 0
+    for (int j0 = 0; j0 < a.lan_k; j0 += 64) {
+      const int j = j0 + lane;
+      const int n = j < a.lan_k ? row[j] : -1;
+      const bool valid = n >= 0 && n < a.V && n != x;
+      const float ln = valid ? token_logit_any(dt, cond, uncond, n, xf, a.cfg_scale, a.inv_T, thr) : -INFINITY;
+      const float w = valid ? exp2_fast(__fmul_rn(__fsub_rn(ln, lx), kLog2e)) : 0.f;
+      const float incl = __fadd_rn(cum, wave_scan_incl(w));
+      const unsigned long long bv = __ballot(valid);
+      const unsigned long long bf = __ballot(valid && !(incl < a.lan_lambda));
+      if (bf) {                                // the first neighbour that does not fit ends the set
+        const int fl = __ffsll((long long)bf) - 1;
+        m += __popcll(bv & ((1ull << fl) - 1ull));
+        // the running sum before lane fl: weights of skipped lanes are zero, so it is the sum
+        // over the members taken so far
+        if (fl > 0) cum = lane_f(incl, fl - 1);
+        break;
+      }
+      m += __popcll(bv);
+      cum = lane_f(incl, 63);
+    }
+  }
+  if (lane == 0) {
+    a.lan_omega[pos] = __fadd_rn(1.f, cum);
+    a.lan_count[pos] = m;
+    if (a.count_out) a.count_out[pos] = m;
+  }
+}
+
+// LAN: cool_sd_verify_lantern without top-k appends workgroups to this launch that do the
+// neighbour aggregation (one wave per position) instead of statistics -- it needs nothing the
+// statistics produce, so it costs no launch of its own.  They are the grid's z-slices from B on
+// (G3) or the workgroups after the last chunk.
+template <int DT, bool XF, int AL, int NT, bool G3, bool LAN = false>
 __global__ __launch_bounds__(kThreads, 3) void row_stats_kernel(const KArgs a) {
   constexpr int kE = Vec<DT>::kE;
   __shared__ float red_c[kWaves], red_s[kWaves];
   const int C1 = a.c1;
+  if constexpr (LAN) {
+    const int64_t extra = G3 ? (int64_t(blockIdx.z) - a.B) * (int64_t(gridDim.y) * gridDim.x) + int64_t(blockIdx.y) * gridDim.x + blockIdx.x
+                             : int64_t(blockIdx.x) - (int64_t(a.rows_t) + a.rows_d) * C1;
+    if (G3 ? (int)blockIdx.z >= a.B : extra >= 0) {
+      const int64_t pos = extra * kWaves + (threadIdx.x >> 6);
+      if (pos < int64_t(a.B) * a.L) lantern_agg_position(a, (int)pos, DT, XF);
+      return;
+    }
+  }
   const int lin = G3 ? 0 : blockIdx.x / C1, c = G3 ? blockIdx.x : blockIdx.x - lin * C1;
   const RowRef rw = row_ref<DT, G3>(a, lin);
   const int r = rw.r;
@@ -659,6 +732,9 @@ __device__ __forceinline__ bool eval_position(const KArgs& a, int b, int i, bool
   const float fi = (ld == -INFINITY) ? 1.f : ((omega > 0.f) ? fminf(1.f, __fmul_rn(omega, ratio)) : 0.f);
   if (emit && has_draft) {
     const int64_t o = int64_t(b) * a.L + i;
+    // aggregated probability of the neighbour set (Eq. p_lantern at x~_i): p_i(x~_i) times agg,
+    // which the LANTERN-style call passes as omega_i
+    if (a.p_agg_out) a.p_agg_out[o] = __fmul_rn(exp2_fast(et) / St, omega);
     if (a.p_tok) a.p_tok[o] = exp2_fast(et) / St;
     if (a.q_tok) a.q_tok[o] = exp2_fast(ed) / Sd;
     if (a.f) a.f[o] = fi;
@@ -924,7 +1000,7 @@ __global__ __launch_bounds__(kThreadsW) void sequence_whole_kernel(const KArgs a
       const int first_tok = threadIdx.x * (kVW * kE);
       const int xd = min(max(a.tokens[int64_t(b) * a.L + j], 0), a.V - 1);
       const int m = a.lan_count[int64_t(b) * a.L + j];
-      lp.agg = omega;                                   // sum over the set / p(x~_j), from lantern_agg_kernel
+      lp.agg = omega;                                   // sum over the set / p(x~_j), from lantern_agg_position
       const int dx = xd - first_tok;
       if (dx >= 0 && dx < kVW * kE) lp.aggpos = dx;
       const int32_t* row = a.nbr + int64_t(xd) * a.lan_k;
@@ -955,65 +1031,9 @@ __global__ __launch_bounds__(kThreadsW) void sequence_whole_kernel(const KArgs a
 // neighbour logits, scans their weights and leaves agg = sum over A / p_i(x~_i) >= 1 where the
 // accept test reads its relaxation parameter: Eq. f_lantern is Eq. relax with omega_i = agg.
 // Also writes the number of members (for Eq. g_lantern) and the optional outputs.
-__device__ __forceinline__ float token_logit_any(int dt, const char* cond, const char* uncond, int x, bool xf,
-                                                 float s, float inv_T, float thr) {
-  float lc = dt == kDtBF16 ? load_elem<kDtBF16>(cond, x) : load_elem<kDtF32>(cond, x);
-  if (!xf) return lc;
-  float lu = 0.f;
-  if (uncond) lu = dt == kDtBF16 ? load_elem<kDtBF16>(uncond, x) : load_elem<kDtF32>(uncond, x);
-  const float l = transform_logit(lc, lu, uncond != nullptr, s, inv_T);
-  return l >= thr ? l : -INFINITY;
-}
-
 __global__ __launch_bounds__(kThreads) void lantern_agg_kernel(const KArgs a, int dt, int xf) {
   const int pos = blockIdx.x * kWaves + (threadIdx.x >> 6);       // (b, i)
-  if (pos >= a.B * a.L) return;
-  const int lane = threadIdx.x & 63;
-  const int b = pos / a.L, i = pos - b * a.L;
-  const int rt_ = b * (a.L + a.has_bonus) + i;
-  const int es = dt == kDtBF16 ? 2 : 4;
-  const int64_t off = int64_t(b) * a.t_sb + int64_t(i) * a.t_sl;
-  const char* cond = row_ptr(a.t, off, es);
-  const char* uncond = row_ptr(a.tu, off, es);
-  const float thr = (xf && a.top_k > 0) ? a.thr[rt_] : -INFINITY;
-  const int x = min(max(a.tokens[pos], 0), a.V - 1);
-  const float lx = a.tok_logit[rt_];
-  const int32_t* row = a.nbr + int64_t(x) * a.lan_k;
-  float cum = 0.f;
-  int m = 0;
-  if (lx > -INFINITY) {                       // p(x~) = 0 admits no neighbour: nothing is below 0
-    for (int j0 = 0; j0 < a.lan_k; j0 += 64) {
-      const int j = j0 + lane;
-      const int n = j < a.lan_k ? row[j] : -1;
-      const bool valid = n >= 0 && n < a.V && n != x;
-      const float ln = valid ? token_logit_any(dt, cond, uncond, n, xf != 0, a.cfg_scale, a.inv_T, thr) : -INFINITY;
-      const float w = valid ? exp2_fast(__fmul_rn(__fsub_rn(ln, lx), kLog2e)) : 0.f;
-      const float incl = __fadd_rn(cum, wave_scan_incl(w));
-      const unsigned long long bv = __ballot(valid);
-      const unsigned long long bf = __ballot(valid && !(incl < a.lan_lambda));
-      if (bf) {                                // the first neighbour that does not fit ends the set
-        const int fl = __ffsll((long long)bf) - 1;
-        m += __popcll(bv & ((1ull << fl) - 1ull));
-        // the running sum before lane fl: weights of skipped lanes are zero, so it is the sum
-        // over the members taken so far
-        if (fl > 0) cum = lane_f(incl, fl - 1);
-        break;
-      }
-      m += __popcll(bv);
-      cum = lane_f(incl, 63);
-    }
-  }
-  if (lane == 0) {
-    const float agg = __fadd_rn(1.f, cum);
-    a.lan_omega[pos] = agg;
-    a.lan_count[pos] = m;
-    if (a.count_out) a.count_out[pos] = m;
-    if (a.p_agg_out) {
-      float Ct, St;
-      combine_row(a, rt_, Ct, St);
-      a.p_agg_out[pos] = __fmul_rn(exp2_fast(__fmaf_rn(lx, kLog2e, -Ct)) / St, agg);
-    }
-  }
+  if (pos < a.B * a.L) lantern_agg_position(a, pos, dt, xf != 0);
 }
 
 // ============================================================================ early-exit variant
@@ -1751,10 +1771,30 @@ static bool stats_grid3(const KArgs& a, dim3& grid) {
   return false;
 }
 
+// The neighbour aggregation rides on the statistics launch when it needs no top-k threshold.
+static bool lantern_fused(const KArgs& a) { return a.nbr != nullptr && a.top_k == 0 && !a.stats_only; }
+
 template <int DT, bool XF, int AL, int NT>
 static hipError_t launch_stats(const KArgs& a, hipStream_t stream) {
   dim3 grid;
-  if (stats_grid3(a, grid))
+  const bool g3 = stats_grid3(a, grid);
+  if (lantern_fused(a)) {
+    const int64_t groups = (int64_t(a.B) * a.L + kWaves - 1) / kWaves;      // one wave per position
+    if (g3) {
+      const int64_t per_slice = int64_t(grid.x) * grid.y;
+      const int64_t slices = (groups + per_slice - 1) / per_slice;
+      if (int64_t(grid.z) + slices <= 65535) {
+        grid.z += (unsigned)slices;
+        hipLaunchKernelGGL((row_stats_kernel<DT, XF, AL, NT, true, true>), grid, dim3(kThreads), 0, stream, a);
+        return checked("row_stats_kernel");
+      }
+      grid = dim3((unsigned)((int64_t(a.rows_t) + a.rows_d) * a.c1));      // too many slices: one dimension
+    }
+    grid.x += (unsigned)groups;
+    hipLaunchKernelGGL((row_stats_kernel<DT, XF, AL, NT, false, true>), grid, dim3(kThreads), 0, stream, a);
+    return checked("row_stats_kernel");
+  }
+  if (g3)
     hipLaunchKernelGGL((row_stats_kernel<DT, XF, AL, NT, true>), grid, dim3(kThreads), 0, stream, a);
   else
     hipLaunchKernelGGL((row_stats_kernel<DT, XF, AL, NT, false>), grid, dim3(kThreads), 0, stream, a);
@@ -1867,7 +1907,7 @@ static hipError_t launch_rest(const KArgs& a, hipStream_t stream) {
     if (e != hipSuccess) return e;
   }
   const unsigned gB = (unsigned)a.B;
-  if (a.nbr != nullptr) {     // aggregated acceptance: the relaxation parameter of every position
+  if (a.nbr != nullptr && !lantern_fused(a)) {   // aggregated acceptance under top-k: after the thresholds are known
     const int64_t gl = (int64_t(a.B) * a.L + kWaves - 1) / kWaves;
     hipLaunchKernelGGL(lantern_agg_kernel, dim3((unsigned)gl), dim3(kThreads), 0, stream, a, DT, XF ? 1 : 0);
     e = checked("lantern_agg_kernel");

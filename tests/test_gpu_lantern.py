@@ -46,6 +46,17 @@ def test_lantern_against_oracle(P, oracle, cfg, B, L, V, dtype, k, lam, mode):
     assert st["set_exempt"] <= 1
 
 
+def test_more_sequences_than_a_grid_dimension(P, oracle):
+    """B beyond 65535: the statistics launch (with the aggregation's workgroups appended) falls
+    back to a one-dimensional grid."""
+    w = make_workload(1, device="cuda", B=70000, L=1, V=8, dtype="f32")
+    nbr = make_neighbor_table(8, 3, device="cuda", seed=2)
+    gpu = _run(P, w, nbr, 2.0, 0)
+    st = compare_verify_lantern(oracle, w, nbr.cpu().numpy(), 2.0, gpu)
+    print(st, flush=True)
+    assert st["tau_exempt"] + st["token_exempt"] + st["set_exempt"] <= 8
+
+
 def test_sets_are_partial_and_full(P, oracle):
     """The cases above must exercise all three outcomes: empty sets, sets that end inside the
     list and sets that take the whole list."""

@@ -26,7 +26,7 @@
 // streaming) and sequence_kernel<kSelect> (pick the chunk that holds u*R, re-read it, inverse
 // CDF).  cool_sd_resample on short rows is one launch (resample_whole_kernel, resample_topk_kernel).
 // Other entry points add: lantern_agg_position (neighbour aggregation of the LANTERN-style
-// acceptance: extra workgroups of the statistics launch, or lantern_agg_kernel under top-k),
+// acceptance: part of the statistics launch, or lantern_agg_kernel after the radix passes),
 // sequence_early_exit_tile_kernel / sequence_early_exit_kernel (the whole call per sequence,
 // stopping at the first rejection), diag_kernel (per-position terms of Theorem 2), and for top-k
 // on rows beyond 65536 logits three radix passes (topk_radix_*).
@@ -121,16 +121,14 @@ __device__ __forceinline__ float token_logit_any(int dt, const char* cond, const
 // Eq. f_lantern for position pos = (b, i), by one wave: gathers the k neighbour logits of x~_i,
 // scans their weights 2^((l_n - l_x) log2e) and leaves agg = (sum over the set) / p_i(x~_i) >= 1
 // and the member count in the workspace (plus the optional count output).  Needs no row
-// statistics; under top-k it needs the row's threshold, which the statistics pass leaves.
-__device__ __forceinline__ void lantern_agg_position(const KArgs& a, int pos, int dt, bool xf) {
+// statistics; under top-k it needs the target row's threshold thr (-inf: no truncation).
+__device__ __forceinline__ void lantern_agg_position(const KArgs& a, int pos, int dt, bool xf, float thr) {
   const int lane = threadIdx.x & 63;
   const int b = pos / a.L, i = pos - b * a.L;
-  const int rt_ = b * (a.L + a.has_bonus) + i;
   const int es = dt == kDtBF16 ? 2 : 4;
   const int64_t off = int64_t(b) * a.t_sb + int64_t(i) * a.t_sl;
   const char* cond = row_ptr(a.t, off, es);
   const char* uncond = row_ptr(a.tu, off, es);
-  const float thr = (xf && a.top_k > 0) ? a.thr[rt_] : -INFINITY;
   const int x = min(max(a.tokens[pos], 0), a.V - 1);
   // the (transformed, masked) logit of x~_i: the same value the statistics kernel leaves in
   // tok_logit, formed here so that this does not have to wait for that kernel
@@ -181,7 +179,7 @@ __global__ __launch_bounds__(kThreads, 3) void row_stats_kernel(const KArgs a) {
                              : int64_t(blockIdx.x) - (int64_t(a.rows_t) + a.rows_d) * C1;
     if (G3 ? (int)blockIdx.z >= a.B : extra >= 0) {
       const int64_t pos = extra * kWaves + (threadIdx.x >> 6);
-      if (pos < int64_t(a.B) * a.L) lantern_agg_position(a, (int)pos, DT, XF);
+      if (pos < int64_t(a.B) * a.L) lantern_agg_position(a, (int)pos, DT, XF, -INFINITY);
       return;
     }
   }
@@ -246,7 +244,7 @@ __global__ __launch_bounds__(kThreads, 3) void row_stats_kernel(const KArgs a) {
 // the row is spread over enough threads that several rows fit a compute unit.
 constexpr int kThreadsK = 512;
 constexpr int kRowMid = 4 * kChunk;      // longest row the one-workgroup form takes (1024 threads)
-template <int DT, int AL, int TPB, int GD, bool G3, int ROW>
+template <int DT, int AL, int TPB, int GD, bool G3, int ROW, bool LAN = false>
 __global__ __launch_bounds__(TPB, ROW == kChunk ? 6 : 4) void row_stats_topk_kernel(const KArgs a) {
   constexpr int kE = Vec<DT>::kE;
   constexpr int kVW = ROW / (TPB * kE);                // vectors per thread
@@ -299,6 +297,12 @@ __global__ __launch_bounds__(TPB, ROW == kChunk ? 6 : 4) void row_stats_topk_ker
       const float l = transform_logit(tok_c, tok_u, rw.uncond != nullptr, a.cfg_scale, a.inv_T);
       a.tok_logit[r] = (l >= thr) ? l : -INFINITY;
     }
+  }
+  if constexpr (LAN) {
+    // cool_sd_verify_lantern: the workgroup of a target row has that row's threshold, which is all
+    // the neighbour aggregation of its position needs; its first wave does it here instead of in
+    // a launch of its own
+    if (!rw.is_draft && rw.i < a.L && threadIdx.x < 64) lantern_agg_position(a, rw.b * a.L + rw.i, DT, true, thr);
   }
 }
 
@@ -1033,7 +1037,9 @@ __global__ __launch_bounds__(kThreadsW) void sequence_whole_kernel(const KArgs a
 // Also writes the number of members (for Eq. g_lantern) and the optional outputs.
 __global__ __launch_bounds__(kThreads) void lantern_agg_kernel(const KArgs a, int dt, int xf) {
   const int pos = blockIdx.x * kWaves + (threadIdx.x >> 6);       // (b, i)
-  if (pos < a.B * a.L) lantern_agg_position(a, pos, dt, xf != 0);
+  if (pos >= a.B * a.L) return;
+  const int b = pos / a.L, rt_ = b * (a.L + a.has_bonus) + (pos - b * a.L);
+  lantern_agg_position(a, pos, dt, xf != 0, (xf && a.top_k > 0) ? a.thr[rt_] : -INFINITY);
 }
 
 // ============================================================================ early-exit variant
@@ -1772,7 +1778,10 @@ static bool stats_grid3(const KArgs& a, dim3& grid) {
 }
 
 // The neighbour aggregation rides on the statistics launch when it needs no top-k threshold.
-static bool lantern_fused(const KArgs& a) { return a.nbr != nullptr && a.top_k == 0 && !a.stats_only; }
+// Under top-k the workgroup that selects a target row's threshold does it (rows of one workgroup).
+static bool lantern_fused(const KArgs& a) {
+  return a.nbr != nullptr && !a.stats_only && (a.top_k == 0 || a.V <= 4 * kChunk);
+}
 
 template <int DT, bool XF, int AL, int NT>
 static hipError_t launch_stats(const KArgs& a, hipStream_t stream) {
@@ -1831,17 +1840,24 @@ static hipError_t launch_stats_any(const KArgs& a, hipStream_t stream) {
       const bool g3 = stats_grid3(a, grid);
       if (g3) grid.x = 1; else grid.x = (unsigned)(a.rows_t + a.rows_d);
       const bool guided = a.tu != nullptr;
+      const bool lanf = lantern_fused(a);
+#define CSD_TOPK_LAUNCH(TPB_, GD_, G3_, ROW_)                                                                             \
+  do {                                                                                                                    \
+    if (lanf) hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, TPB_, GD_, G3_, ROW_, true>), grid, dim3(TPB_), 0, stream, a); \
+    else hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, TPB_, GD_, G3_, ROW_, false>), grid, dim3(TPB_), 0, stream, a);      \
+  } while (0)
       if (a.V <= kChunk) {
-        if (g3 && guided) hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsK, 1, true, kChunk>), grid, dim3(kThreadsK), 0, stream, a);
-        else if (g3) hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsK, 0, true, kChunk>), grid, dim3(kThreadsK), 0, stream, a);
-        else if (guided) hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsK, 1, false, kChunk>), grid, dim3(kThreadsK), 0, stream, a);
-        else hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsK, 0, false, kChunk>), grid, dim3(kThreadsK), 0, stream, a);
+        if (g3 && guided) CSD_TOPK_LAUNCH(kThreadsK, 1, true, kChunk);
+        else if (g3) CSD_TOPK_LAUNCH(kThreadsK, 0, true, kChunk);
+        else if (guided) CSD_TOPK_LAUNCH(kThreadsK, 1, false, kChunk);
+        else CSD_TOPK_LAUNCH(kThreadsK, 0, false, kChunk);
       } else {                           // 16384 < V <= 65536: 1024 threads, statistics per 8192 logits
-        if (g3 && guided) hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsW, 1, true, kRowMid>), grid, dim3(kThreadsW), 0, stream, a);
-        else if (g3) hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsW, 0, true, kRowMid>), grid, dim3(kThreadsW), 0, stream, a);
-        else if (guided) hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsW, 1, false, kRowMid>), grid, dim3(kThreadsW), 0, stream, a);
-        else hipLaunchKernelGGL((row_stats_topk_kernel<DT, kA, kThreadsW, 0, false, kRowMid>), grid, dim3(kThreadsW), 0, stream, a);
+        if (g3 && guided) CSD_TOPK_LAUNCH(kThreadsW, 1, true, kRowMid);
+        else if (g3) CSD_TOPK_LAUNCH(kThreadsW, 0, true, kRowMid);
+        else if (guided) CSD_TOPK_LAUNCH(kThreadsW, 1, false, kRowMid);
+        else CSD_TOPK_LAUNCH(kThreadsW, 0, false, kRowMid);
       }
+#undef CSD_TOPK_LAUNCH
       return checked("row_stats_topk_kernel");
     }
   }
@@ -1907,7 +1923,7 @@ static hipError_t launch_rest(const KArgs& a, hipStream_t stream) {
     if (e != hipSuccess) return e;
   }
   const unsigned gB = (unsigned)a.B;
-  if (a.nbr != nullptr && !lantern_fused(a)) {   // aggregated acceptance under top-k: after the thresholds are known
+  if (a.nbr != nullptr && !lantern_fused(a)) {   // aggregated acceptance on rows whose thresholds came from the radix passes
     const int64_t gl = (int64_t(a.B) * a.L + kWaves - 1) / kWaves;
     hipLaunchKernelGGL(lantern_agg_kernel, dim3((unsigned)gl), dim3(kThreads), 0, stream, a, DT, XF ? 1 : 0);
     e = checked("lantern_agg_kernel");

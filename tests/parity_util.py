@@ -17,6 +17,10 @@ ABS_FLOOR = 1e-37          # below fp32's normal range the GPU flushes to zero
 MASS_ABS = 1e-6
 # ... and a law whose whole mass is below this is not determined by fp32 probabilities at all: the
 # sampled token is then only required to be valid (in range, positive probability under p).
+# What the paper fixes there (proof of the proposition on the optimal G, App.): when the rejection
+# mass sum_x (1 - f(x)) q(x) vanishes any G attains the infimum of the bound, and a row is reached
+# with exactly that probability; the oracle's fall-back to p is one such choice, the GPU's draw
+# from the few ulps it sees is another.
 R_FLOOR = 1e-6
 
 

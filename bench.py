@@ -44,7 +44,10 @@ def parse():
     ap.add_argument("--pool-mb", type=float, default=600.0, help="distinct input batches cycled, total size")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="time budget of the CPU oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--others", action="store_true", help="also time configurations 1, 3, 4, 5 (extra JSON keys)")
+    ap.add_argument("--others", action="store_true", default=True,
+                    help="also time configurations 1, 3, 4, 5 and configuration 4's recipe at B = 2048 (extra key "
+                         "`other_workloads`; on by default, a few seconds)")
+    ap.add_argument("--no-others", dest="others", action="store_false", help="time the named workload only")
     ap.add_argument("--early-exit", action="store_true",
                     help="time the early-exit form (COOL_SD_FLAG_EARLY_EXIT) instead of the all-rows form; the "
                          "roofline object then refers to the single kernel and to the bytes it actually needs")

@@ -322,8 +322,33 @@ def time_diagnostics(r, passes=6):
     sec = e0.elapsed_time(e1) * 1e-3 / n
     w0 = r.pool[0]
     nbytes = 2 * r.B * r.L * r.V * w0.target.element_size() * (2 if w0.target_uncond is not None else 1)
+
+    # the verify call and the diagnostics in one call (one pass over the logits for short rows
+    # without top-k), replayed from a graph like the timed verify steps
+    def both(i):
+        w = r.pool[i % len(r.pool)]
+        pkg.cool_sd_verify_diagnostics(r.params, w.target, w.target_uncond, w.draft, w.draft_uncond, w.draft_tokens,
+                                       r.omega, w.u_accept, w.u_resample, r.accept_len, r.next_token, None, None,
+                                       None, None, alpha, beta, r.ws)
+    for i in range(len(r.pool)):
+        both(i)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for i in range(len(r.pool)):
+            both(i)
+    g.replay()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(passes):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    sec_both = e0.elapsed_time(e1) * 1e-3 / (passes * len(r.pool))
     return {"us_per_call": sec * 1e6, "algorithmic_bytes": nbytes, "GBps": nbytes / sec / 1e9,
-            "frac": nbytes / sec / 1e9 / HBM_PEAK_GBS}
+            "frac": nbytes / sec / 1e9 / HBM_PEAK_GBS,
+            "verify_and_diagnostics_us_per_call": sec_both * 1e6,
+            "verify_and_diagnostics_GBps": r.bytes_per_step / sec_both / 1e9}
 
 
 def run_lantern(r, n, k=10, lam=2.0):

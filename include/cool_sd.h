@@ -108,7 +108,8 @@ typedef struct {
  * negative weight). */
 int cool_sd_schedule(int32_t kind, int32_t L, float delta, float param, float* omega_out);
 
-/* Bytes of device workspace cool_sd_verify / cool_sd_verify_lantern / cool_sd_resample / cool_sd_diagnostics need for these params
+/* Bytes of device workspace cool_sd_verify / cool_sd_verify_lantern / cool_sd_verify_diagnostics /
+ * cool_sd_resample / cool_sd_diagnostics need for these params
  * (for resample only B, V, dtype and top_k matter).  0 on invalid params. */
 size_t cool_sd_workspace_bytes(const cool_sd_params* p);
 
@@ -219,6 +220,29 @@ int cool_sd_diagnostics(const cool_sd_params* p,
                         float* alpha_dev, float* beta_dev,
                         void* workspace_dev, size_t workspace_bytes,
                         void* hip_stream);
+
+/* cool_sd_verify and cool_sd_diagnostics in one call (Algorithm 1's verification stage plus the
+ * per-position terms of Theorem 2 for the same relaxation): same arguments and results as the
+ * two calls, alpha_dev / beta_dev required.  For rows of at most 16384 logits without top-k every
+ * logit is read ONCE for both (the workgroup that holds a row pair leaves its softmax statistics,
+ * the logits of x~_i, alpha_i and beta_i; the per-sequence kernel follows), so that a caller who
+ * tunes delta online against a total-variation budget pays no second pass; otherwise the two
+ * calls run one after the other on the stream.  COOL_SD_FLAG_EARLY_EXIT is ignored (the
+ * diagnostics need every row). */
+int cool_sd_verify_diagnostics(const cool_sd_params* p,
+                               const void* target_dev, const void* target_uncond_dev,
+                               const void* draft_dev, const void* draft_uncond_dev,
+                               const int32_t* draft_tokens_dev,
+                               const float* omega_dev,
+                               const float* u_accept_dev,
+                               const float* u_resample_dev,
+                               int32_t* accept_len_dev,
+                               int32_t* next_token_dev,
+                               float* p_tok_dev, float* q_tok_dev, float* f_dev,
+                               float* resid_mass_dev,
+                               float* alpha_dev, float* beta_dev,
+                               void* workspace_dev, size_t workspace_bytes,
+                               void* hip_stream);
 
 /* Benchmark instrumentation (not for production paths, not thread-safe).  mode 0: off.
  * mode 1 (not usable while the stream is being captured into a graph): cool_sd_verify /

@@ -61,6 +61,8 @@ def lib():
         L.cool_sd_verify_lantern.argtypes = ([pp] + [vp] * 6 + [C.c_int32, C.c_float] + [vp] * 10
                                              + [vp, C.c_size_t, vp])
         L.cool_sd_verify_lantern.restype = C.c_int
+        L.cool_sd_verify_diagnostics.argtypes = [pp] + [vp] * 16 + [vp, C.c_size_t, vp]
+        L.cool_sd_verify_diagnostics.restype = C.c_int
         L.cool_sd_resample.argtypes = [pp] + [vp] * 8 + [vp, C.c_size_t, vp]
         L.cool_sd_resample.restype = C.c_int
         L.cool_sd_diagnostics.argtypes = [pp] + [vp] * 7 + [vp, C.c_size_t, vp]
@@ -123,6 +125,21 @@ def cool_sd_verify(params, target, target_uncond, draft, draft_uncond, draft_tok
                               _stream(stream))
     if check and rc != 0:
         raise CoolSDError(rc, "cool_sd_verify")
+    return rc
+
+
+def cool_sd_verify_diagnostics(params, target, target_uncond, draft, draft_uncond, draft_tokens, omega, u_accept,
+                               u_resample, accept_len, next_token, p_tok, q_tok, f, resid_mass, alpha, beta, workspace,
+                               stream=None, check=True):
+    rc = lib().cool_sd_verify_diagnostics(C.byref(params), _ptr(target), _ptr(target_uncond), _ptr(draft),
+                                          _ptr(draft_uncond), _ptr(draft_tokens), _ptr(omega), _ptr(u_accept),
+                                          _ptr(u_resample), _ptr(accept_len), _ptr(next_token), _ptr(p_tok),
+                                          _ptr(q_tok), _ptr(f), _ptr(resid_mass), _ptr(alpha), _ptr(beta),
+                                          _ptr(workspace),
+                                          0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                          _stream(stream))
+    if check and rc != 0:
+        raise CoolSDError(rc, "cool_sd_verify_diagnostics")
     return rc
 
 

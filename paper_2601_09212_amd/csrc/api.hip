@@ -233,6 +233,53 @@ int run_diag(const cool_sd_params* p, const void* t, const void* tu, const void*
   return e == hipSuccess ? COOL_SD_OK : COOL_SD_ELAUNCH;
 }
 
+// cool_sd_verify_diagnostics on rows of one chunk without top-k: one pass over the logits leaves
+// the verify call's statistics and alpha, beta; the per-sequence kernel follows.
+int run_verify_diag(const cool_sd_params* p, const void* t, const void* tu, const void* d, const void* du,
+                    const int32_t* tokens, const float* omega, const float* u_acc, const float* u_res,
+                    int32_t* accept_len, int32_t* next_token, float* p_tok, float* q_tok, float* f,
+                    float* resid_mass, float* alpha, float* beta, void* ws, size_t ws_bytes, void* stream) {
+  const int64_t L = p->L;
+  const int64_t rows_t = int64_t(p->B) * (L + p->has_bonus), rows_d = int64_t(p->B) * L;
+  const Layout lay = make_layout(p->B, rows_t + rows_d, 1, 1);
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0 || ws_bytes < lay.total) return COOL_SD_EWORKSPACE;
+  const int kE = (p->dtype == COOL_SD_BF16) ? 8 : 4;
+  bool aligned = (p->V % kE == 0) && is_aligned16(t) && is_aligned16(d) && (p->t_stride_b % kE == 0) &&
+                 (p->t_stride_l % kE == 0) && (p->d_stride_b % kE == 0) && (p->d_stride_l % kE == 0);
+  if (tu) aligned = aligned && is_aligned16(tu) && is_aligned16(du);
+
+  char* w = static_cast<char*>(ws);
+  csd::KArgs a{};
+  a.t = t; a.tu = tu; a.d = d; a.du = du;
+  a.tokens = tokens; a.omega = omega; a.u_acc = u_acc; a.u_res = u_res;
+  a.accept_len = accept_len; a.next_token = next_token;
+  a.p_tok = p_tok; a.q_tok = q_tok; a.f = f; a.resid_mass = resid_mass;
+  a.alpha = alpha; a.beta = beta;
+  a.t_sb = p->t_stride_b; a.t_sl = p->t_stride_l; a.d_sb = p->d_stride_b; a.d_sl = p->d_stride_l;
+  a.om_sb = p->omega_stride_b;
+  a.B = p->B; a.L = (int32_t)L; a.V = p->V; a.has_bonus = p->has_bonus;
+  a.top_k = 0; a.resample_mode = p->resample_mode;
+  a.aligned = aligned ? 1 : 0;
+  a.nchunks = 1;                                  // one sampling chunk, one diagnostics chunk
+  const int kT = (p->dtype == COOL_SD_BF16) ? 8 : 16;
+  a.nt2 = kT;
+  a.cfg_scale = p->cfg_scale;
+  a.inv_T = 1.0f / p->temperature;
+  a.rows_t = (int32_t)rows_t; a.rows_d = (int32_t)rows_d;
+  a.nt1 = kT; a.chunk1 = csd::kChunk; a.c1 = 1;   // one statistics pair per row
+  a.chunk_R = reinterpret_cast<float*>(w + lay.chunk_R);
+  a.seq_stat = reinterpret_cast<float4*>(w + lay.seq_stat);
+  a.thr = reinterpret_cast<float*>(w + lay.thr);
+  a.tok_logit = reinterpret_cast<float*>(w + lay.tok_logit);
+  a.part = reinterpret_cast<float2*>(w + lay.part);
+  a.rowstat = reinterpret_cast<float2*>(w + lay.rowstat);
+  a.stat = a.part;
+  a.cs = 1;
+  const bool xf = (tu != nullptr) || (p->temperature != 1.0f);
+  hipError_t e = csd::launch_verify_diagnostics(a, p->dtype, xf, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? COOL_SD_OK : COOL_SD_ELAUNCH;
+}
+
 }  // namespace
 
 extern "C" {
@@ -343,6 +390,33 @@ int cool_sd_diagnostics(const cool_sd_params* p, const void* target_dev, const v
   if (!target_dev || !draft_dev || !omega_dev || !alpha_dev || !beta_dev) return COOL_SD_EINVAL;
   if ((target_uncond_dev == nullptr) != (draft_uncond_dev == nullptr)) return COOL_SD_EINVAL;
   return run_diag(p, target_dev, target_uncond_dev, draft_dev, draft_uncond_dev, omega_dev, alpha_dev, beta_dev,
+                  workspace_dev, workspace_bytes, hip_stream);
+}
+
+int cool_sd_verify_diagnostics(const cool_sd_params* p, const void* target_dev, const void* target_uncond_dev,
+                               const void* draft_dev, const void* draft_uncond_dev, const int32_t* draft_tokens_dev,
+                               const float* omega_dev, const float* u_accept_dev, const float* u_resample_dev,
+                               int32_t* accept_len_dev, int32_t* next_token_dev, float* p_tok_dev, float* q_tok_dev,
+                               float* f_dev, float* resid_mass_dev, float* alpha_dev, float* beta_dev,
+                               void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+  if (!params_ok(p, false)) return COOL_SD_EINVAL;
+  if (!target_dev || !draft_dev || !draft_tokens_dev || !omega_dev || !u_accept_dev || !u_resample_dev ||
+      !accept_len_dev || !next_token_dev || !alpha_dev || !beta_dev)
+    return COOL_SD_EINVAL;
+  if ((target_uncond_dev == nullptr) != (draft_uncond_dev == nullptr)) return COOL_SD_EINVAL;
+  if (p->top_k == 0 && p->V <= csd::kChunk && !g_profile && !g_stats_only)
+    return run_verify_diag(p, target_dev, target_uncond_dev, draft_dev, draft_uncond_dev, draft_tokens_dev, omega_dev,
+                           u_accept_dev, u_resample_dev, accept_len_dev, next_token_dev, p_tok_dev, q_tok_dev, f_dev,
+                           resid_mass_dev, alpha_dev, beta_dev, workspace_dev, workspace_bytes, hip_stream);
+  // top-k or rows of several chunks: the two calls one after the other (the early-exit flag is not
+  // honoured here, the diagnostics need every row anyway)
+  cool_sd_params q = *p;
+  q.flags = 0;
+  const int rc = run(&q, false, target_dev, target_uncond_dev, draft_dev, draft_uncond_dev, draft_tokens_dev, omega_dev,
+                     u_accept_dev, u_resample_dev, accept_len_dev, next_token_dev, p_tok_dev, q_tok_dev, f_dev,
+                     resid_mass_dev, workspace_dev, workspace_bytes, hip_stream);
+  if (rc != COOL_SD_OK) return rc;
+  return run_diag(&q, target_dev, target_uncond_dev, draft_dev, draft_uncond_dev, omega_dev, alpha_dev, beta_dev,
                   workspace_dev, workspace_bytes, hip_stream);
 }
 

@@ -73,6 +73,10 @@ hipError_t launch_verify(const KArgs& a, int dtype, bool xf, hipStream_t stream,
 // are one chunk and need no statistics pass.
 hipError_t launch_diagnostics(const KArgs& a, int dtype, bool xf, bool local, hipStream_t stream);
 
+// Enqueue the kernels of one cool_sd_verify_diagnostics call on rows of one chunk without top-k
+// (every logit read once for both results).
+hipError_t launch_verify_diagnostics(const KArgs& a, int dtype, bool xf, hipStream_t stream);
+
 // Zero n 32-bit words.
 hipError_t launch_zero(uint32_t* p, size_t n, hipStream_t stream);
 // benchmark yardstick: streaming read of two buffers (sizes in 16-byte vectors), one word out per workgroup

@@ -28,7 +28,8 @@
 // Other entry points add: lantern_agg_position (neighbour aggregation of the LANTERN-style
 // acceptance: part of the statistics launch, or lantern_agg_kernel after the radix passes),
 // sequence_early_exit_tile_kernel / sequence_early_exit_kernel (the whole call per sequence,
-// stopping at the first rejection), diag_kernel (per-position terms of Theorem 2), and for top-k
+// stopping at the first rejection), diag_kernel (per-position terms of Theorem 2; in
+// cool_sd_verify_diagnostics it also plays the statistics pass), and for top-k
 // on rows beyond 65536 logits three radix passes (topk_radix_*).
 // No workgroup ever waits for another one inside a launch: there are no fences or spin waits
 // anywhere, the only global atomics are the integer histogram adds of the radix passes (whose
@@ -1632,18 +1633,26 @@ __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
 //           the registers, every logit is read once, results go straight to alpha / beta.
 //   else    statistics come from row_stats_kernel; grid = B L x CD chunks of 8192 logits; the
 //           chunk sums go to diag_part and diag_combine_kernel adds them in ascending order.
-template <int DT, bool XF, int AL, int NT, bool LOCAL>
+//   VER     (with LOCAL) cool_sd_verify_diagnostics: the same workgroups also leave what the
+//           verify call's statistics pass leaves -- (c, S) of both rows and the logits of x~_i --
+//           and B more workgroups take the bonus rows, so that the per-sequence kernel can follow
+//           and no logit is read a second time for the diagnostics.
+template <int DT, bool XF, int AL, int NT, bool LOCAL, bool VER = false>
 __global__ __launch_bounds__(LOCAL ? 512 : kThreads) void diag_kernel(const KArgs a) {
+  static_assert(LOCAL || !VER, "the fused form holds whole rows");
   constexpr int kE = Vec<DT>::kE, kES = Vec<DT>::kES;
   // the one-chunk form spreads the row pair over 512 threads so that both rows cost 64 registers
   constexpr int kTPB = LOCAL ? 512 : kThreads, kW = kTPB / 64;
   __shared__ float red[4][kW];
   const int CD = a.nchunks;
-  const int rp = blockIdx.x / CD, c = blockIdx.x - rp * CD;     // row pair (b, i), chunk
-  const int b = rp / a.L, i = rp - b * a.L;
-  const int rt_ = rp, rd_ = a.rows_t + rp;                       // has_bonus is 0 here
+  const int pairs = a.B * a.L;
+  const bool bonus_wg = VER && (int)blockIdx.x >= pairs;          // a bonus row: target only, statistics only
+  const int rp = bonus_wg ? 0 : blockIdx.x / CD, c = bonus_wg ? 0 : blockIdx.x - rp * CD;   // row pair (b, i), chunk
+  const int b = bonus_wg ? (int)blockIdx.x - pairs : rp / a.L, i = bonus_wg ? a.L : rp - b * a.L;
+  // rows are numbered as in the verify call; the plain diagnostics call sets has_bonus = 0
+  const int rt_ = b * (a.L + a.has_bonus) + i, rd_ = a.rows_t + b * a.L + (bonus_wg ? a.L - 1 : i);
   const int64_t offt = int64_t(b) * a.t_sb + int64_t(i) * a.t_sl;
-  const int64_t offd = int64_t(b) * a.d_sb + int64_t(i) * a.d_sl;
+  const int64_t offd = int64_t(b) * a.d_sb + int64_t(bonus_wg ? a.L - 1 : i) * a.d_sl;
   const int64_t base = int64_t(c) * (NT * kTPB * kE);
   const bool masked = XF && !LOCAL && a.top_k > 0;
   const float thr_t = masked ? a.thr[rt_] : -INFINITY;
@@ -1653,9 +1662,19 @@ __global__ __launch_bounds__(LOCAL ? 512 : kThreads) void diag_kernel(const KArg
   RowRegs<DT, XF, NT> rt, rd;
   load_chunk<DT, XF, AL, NT, kTPB, 1>(rt, row_ptr(a.t, offt, kES), row_ptr(a.tu, offt, kES), base, a.V,
                                       a.cfg_scale, a.inv_T, thr_t);
+  // (a bonus workgroup re-reads the last draft row and ignores it: one code path, B workgroups)
   load_chunk<DT, XF, AL, NT, kTPB, 1>(rd, row_ptr(a.d, offd, kES), row_ptr(a.du, offd, kES), base, a.V,
                                       a.cfg_scale, a.inv_T, thr_d);
-  const float omega = a.omega[int64_t(b) * a.om_sb + i];
+  const float omega = bonus_wg ? 1.f : a.omega[int64_t(b) * a.om_sb + i];
+  // the logits of x~_i for the accept test, by one thread, requested together with the rows
+  float tok_t = 0.f, tok_d = 0.f;
+  if constexpr (VER) {
+    if (threadIdx.x == 0 && !bonus_wg) {
+      const int x = min(max(a.tokens[rp], 0), a.V - 1);
+      tok_t = token_logit_any(DT, row_ptr(a.t, offt, kES), row_ptr(a.tu, offt, kES), x, XF, a.cfg_scale, a.inv_T, -INFINITY);
+      tok_d = token_logit_any(DT, row_ptr(a.d, offd, kES), row_ptr(a.du, offd, kES), x, XF, a.cfg_scale, a.inv_T, -INFINITY);
+    }
+  }
   float sa = 0.f, sb = 0.f;
   if constexpr (LOCAL) {
     // the arithmetic is what limits this form (two exponentials per logit would), so each
@@ -1693,6 +1712,17 @@ __global__ __launch_bounds__(LOCAL ? 512 : kThreads) void diag_kernel(const KArg
     float St = 0.f, Sd = 0.f;
 #pragma unroll
     for (int w = 0; w < kW; ++w) { St = __fadd_rn(St, red[2][w]); Sd = __fadd_rn(Sd, red[3][w]); }
+    if constexpr (VER) {
+      if (threadIdx.x == 0) {
+        a.part[int64_t(rt_) * a.c1] = make_float2(Ct, St);
+        if (!bonus_wg) {
+          a.part[int64_t(rd_) * a.c1] = make_float2(Cd, Sd);
+          a.tok_logit[rt_] = tok_t;
+          a.tok_logit[rd_] = tok_d;
+        }
+      }
+      if (bonus_wg) return;
+    }
     const float at = 1.f / St, ad = 1.f / Sd;
 #pragma unroll
     for (int n = 0; n < NT * kE; ++n) {
@@ -1990,6 +2020,33 @@ static hipError_t launch_diag_typed(const KArgs& a, bool local, hipStream_t stre
   hipLaunchKernelGGL(diag_combine_kernel, dim3((unsigned)((pairs + kThreads - 1) / kThreads)), dim3(kThreads), 0,
                      stream, a);
   return checked("diag_combine_kernel");
+}
+
+// cool_sd_verify_diagnostics on rows of one chunk without top-k: the pair kernel (statistics,
+// token logits, alpha, beta; B more workgroups for the bonus rows), then the per-sequence kernel.
+template <int DT, bool XF, bool AL>
+static hipError_t launch_verify_diag_typed(const KArgs& a, hipStream_t stream) {
+  constexpr int kT = Vec<DT>::kT;
+  constexpr int kA = AL ? kAligned : kUnaligned;
+  (void)hipGetLastError();
+  const int64_t groups = int64_t(a.B) * a.L + (a.has_bonus ? a.B : 0);
+  hipLaunchKernelGGL((diag_kernel<DT, XF, kA, kT / 2, true, true>), dim3((unsigned)groups), dim3(512), 0, stream, a);
+  hipError_t e = checked("diag_kernel (with the verify call's statistics)");
+  if (e != hipSuccess) return e;
+  return launch_rest<DT, XF, AL>(a, stream);
+}
+
+hipError_t launch_verify_diagnostics(const KArgs& a, int dtype, bool xf, hipStream_t stream) {
+  if (dtype == kDtBF16) {
+    if (xf) return a.aligned ? launch_verify_diag_typed<kDtBF16, true, true>(a, stream)
+                             : launch_verify_diag_typed<kDtBF16, true, false>(a, stream);
+    return a.aligned ? launch_verify_diag_typed<kDtBF16, false, true>(a, stream)
+                     : launch_verify_diag_typed<kDtBF16, false, false>(a, stream);
+  }
+  if (xf) return a.aligned ? launch_verify_diag_typed<kDtF32, true, true>(a, stream)
+                           : launch_verify_diag_typed<kDtF32, true, false>(a, stream);
+  return a.aligned ? launch_verify_diag_typed<kDtF32, false, true>(a, stream)
+                   : launch_verify_diag_typed<kDtF32, false, false>(a, stream);
 }
 
 hipError_t launch_diagnostics(const KArgs& a, int dtype, bool xf, bool local, hipStream_t stream) {

@@ -77,6 +77,12 @@ def test_entry_points_stay_inside_their_buffers(P, cfg, B, L, V, dtype, top_k):
     torch.cuda.synchronize()
     assert all(g.intact() for g in everything + [alpha, beta]), "cool_sd_diagnostics"
 
+    P.cool_sd_verify_diagnostics(params, w.target, w.target_uncond, w.draft, w.draft_uncond, w.draft_tokens, om,
+                                 w.u_accept, w.u_resample, o["accept_len"].t, o["next_token"].t, o["p_tok"].t,
+                                 o["q_tok"].t, o["f"].t, o["resid_mass"].t, alpha.t, beta.t, ws.t)
+    torch.cuda.synchronize()
+    assert all(g.intact() for g in everything + [alpha, beta]), "cool_sd_verify_diagnostics"
+
     k = min(10, V - 1)
     if k >= 1:
         nbr = make_neighbor_table(V, k, device="cuda", seed=3, pad=0.1)

@@ -145,3 +145,62 @@ def test_accepted_length_matches_its_prediction_at_full_size(P):
         else:
             assert float(beta.max()) > 0.0 and float(beta.min()) >= 0.0
         assert float(alpha.min()) > 0.0 and float(alpha.max()) <= 1.0 + 1e-6
+
+
+def _verify_diag(P, w, om, mode=0):
+    """cool_sd_verify_diagnostics on a workload; returns (verify outputs as numpy dict, alpha, beta)."""
+    from tests.parity_util import to_numpy
+    omega = torch.from_numpy(np.ascontiguousarray(om, dtype=np.float32)).cuda()
+    params = P.make_params(w.target, w.draft, top_k=w.top_k, cfg_scale=w.cfg_scale, temperature=w.temperature,
+                           resample_mode=mode, omega_stride_b=0 if omega.dim() == 1 else omega.stride(0))
+    ws = torch.empty(max(P.cool_sd_workspace_bytes(params), 256), dtype=torch.uint8, device="cuda")
+    B, L = w.B, w.L
+    out = dict(accept_len=torch.full((B,), -9, dtype=torch.int32, device="cuda"),
+               next_token=torch.full((B,), -9, dtype=torch.int32, device="cuda"),
+               p_tok=torch.zeros((B, L), device="cuda"), q_tok=torch.zeros((B, L), device="cuda"),
+               f=torch.zeros((B, L), device="cuda"), resid_mass=torch.zeros(B, device="cuda"))
+    alpha, beta = torch.zeros((B, L), device="cuda"), torch.zeros((B, L), device="cuda")
+    P.cool_sd_verify_diagnostics(params, w.target, w.target_uncond, w.draft, w.draft_uncond, w.draft_tokens, omega,
+                                 w.u_accept, w.u_resample, out["accept_len"], out["next_token"], out["p_tok"],
+                                 out["q_tok"], out["f"], out["resid_mass"], alpha, beta, ws)
+    torch.cuda.synchronize()
+    return to_numpy(out), alpha.cpu().numpy().astype(np.float64), beta.cpu().numpy().astype(np.float64)
+
+
+# (cfg recipe, B, L, V, dtype, top_k): one-chunk rows take the single-pass form; top-k and long rows
+# run the two calls one after the other
+FUSED = [(2, 6, 8, 16384, "bf16", 0), (1, 2, 4, 16384, "f32", 0), (2, 3, 5, 4104, "bf16", 0), (2, 3, 3, 5001, "bf16", 0),
+         (1, 2, 2, 8, "f32", 0), (3, 3, 4, 16384, "bf16", 0), (4, 5, 16, 16384, "bf16", 0), (2, 2, 70, 512, "bf16", 0),
+         (3, 3, 4, 16384, "bf16", 800), (5, 2, 3, 40000, "bf16", 0)]
+
+
+@pytest.mark.parametrize("cfg,B,L,V,dtype,top_k", FUSED)
+def test_verify_and_diagnostics_in_one_call(P, oracle, cfg, B, L, V, dtype, top_k):
+    from tests.parity_util import compare_verify
+    print("case", cfg, B, L, V, dtype, top_k, flush=True)
+    w = make_workload(cfg, device="cuda", B=B, L=L, V=V, dtype=dtype, top_k=top_k if cfg == 3 else None)
+    if cfg == 3 and top_k == 0:
+        w.temperature = 0.8
+    for mode, delta in ((0, 2.0), (1, 0.7)):
+        om = P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, L, delta, w.nu)
+        gpu, alpha, beta = _verify_diag(P, w, om, mode)
+        compare_verify(oracle, w, om, gpu, resample_mode=mode)
+        a_ref, b_ref = _oracle_diag(oracle, w, om)
+        np.testing.assert_allclose(alpha, a_ref, rtol=1e-5, atol=1e-9)
+        np.testing.assert_allclose(beta, b_ref, rtol=1e-5, atol=2e-6)
+        assert (beta[np.broadcast_to(om, beta.shape) <= 1.0] == 0.0).all()
+
+
+def test_verify_and_diagnostics_without_bonus_and_with_per_sequence_omega(P, oracle):
+    from tests.parity_util import compare_verify
+    w = make_workload(2, device="cuda", B=5, L=6, V=16384)
+    w.target = w.target[:, :6]                                    # no bonus row (a strided view)
+    om = np.tile(P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, 6, 3.0, w.nu), (5, 1)).astype(np.float32)
+    om[1] = 0.0
+    om[3] *= 20.0
+    gpu, alpha, beta = _verify_diag(P, w, om)
+    compare_verify(oracle, w, om, gpu, has_bonus=False)
+    a_ref, b_ref = _oracle_diag(oracle, w, om)
+    np.testing.assert_allclose(alpha, a_ref, rtol=1e-5, atol=1e-9)
+    np.testing.assert_allclose(beta, b_ref, rtol=1e-5, atol=2e-6)
+    assert (gpu["accept_len"][1] == 0) and (alpha[1] == 0).all()

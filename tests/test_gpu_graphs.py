@@ -65,6 +65,11 @@ def test_entry_points_replay(P, cfg, B, L, V, top_k):
     _replay_equals_eager(lambda: P.cool_sd_diagnostics(params, w.target, w.target_uncond, w.draft, w.draft_uncond, om,
                                                        alpha, beta, ws), [alpha, beta])
 
+    _replay_equals_eager(lambda: P.cool_sd_verify_diagnostics(params, w.target, w.target_uncond, w.draft, w.draft_uncond,
+                                                              w.draft_tokens, om, w.u_accept, w.u_resample, tau, nxt,
+                                                              None, None, f, R, alpha, beta, ws),
+                         [tau, nxt, f, R, alpha, beta])
+
     nbr = make_neighbor_table(V, 10, device="cuda", seed=3)
     agg, cnt = torch.zeros((B, L), device="cuda"), torch.zeros((B, L), dtype=torch.int32, device="cuda")
     for mode in (P.COOL_SD_RESAMPLE_OPT, P.COOL_SD_RESAMPLE_LANTERN):

@@ -8,7 +8,7 @@ import pytest
 import torch
 
 from tests.parity_util import MASS_ABS, R_FLOOR, REL_TOL, U_TOL, compare_verify, compare_verify_lantern, to_numpy
-from tests.test_gpu_diagnostics import _check as check_diagnostics
+from tests.test_gpu_diagnostics import _check as check_diagnostics, _oracle_diag, _verify_diag
 from workloads import make_neighbor_table, make_workload, uniforms24
 
 pytestmark = pytest.mark.gpu
@@ -108,6 +108,12 @@ def test_random_cases_through_every_entry_point(P, oracle, seed):
         exempt += [("early", case)] * (st["tau_exempt"] + st["token_exempt"])
         if bonus:
             check_diagnostics(P, oracle, w, om)
+            both, alpha, beta = _verify_diag(P, w, om, mode)        # the two in one call
+            st = compare_verify(oracle, w, om, both, resample_mode=mode)
+            exempt += [("verify+diagnostics", case)] * (st["tau_exempt"] + st["token_exempt"])
+            a_ref, b_ref = _oracle_diag(oracle, w, om)
+            np.testing.assert_allclose(alpha, a_ref, rtol=1e-5, atol=1e-9)
+            np.testing.assert_allclose(beta, b_ref, rtol=1e-5, atol=2e-6)
         if V > 2 and bonus and L <= 20:
             k = int(min(V - 1, rng.choice([1, 3, 10, 70])))
             lam = float(rng.choice([0.0, 0.02, 0.3, 2.0]))
@@ -118,4 +124,4 @@ def test_random_cases_through_every_entry_point(P, oracle, seed):
             exempt += [("lantern", case)] * (st["tau_exempt"] + st["token_exempt"] + st["set_exempt"])
         _check_resample(P, oracle, w, om[0], mode, case, exempt)
     print("exemptions", exempt, flush=True)
-    assert len(exempt) <= 6
+    assert len(exempt) <= 8

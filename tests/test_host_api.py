@@ -108,6 +108,21 @@ def test_verify_validates_before_touching_the_gpu(P):
     assert d(_params(P), out=null) == E.COOL_SD_EINVAL
     assert d(_params(P)) == E.COOL_SD_EWORKSPACE
     assert d(_params(P), ws=C.c_void_p(0x1000), n=16) == E.COOL_SD_EWORKSPACE
+    # verify and diagnostics in one call
+    def both(params, alpha=fake, beta=fake, target=fake, ws=null, n=0):
+        return lib.cool_sd_verify_diagnostics(C.byref(params), target, null, fake, null, fake, fake, fake, fake, fake,
+                                              fake, null, null, null, null, alpha, beta, ws, n, null)
+    assert both(_params(P), alpha=null) == E.COOL_SD_EINVAL
+    assert both(_params(P), beta=null) == E.COOL_SD_EINVAL
+    assert both(_params(P), target=null) == E.COOL_SD_EINVAL
+    assert both(_params(P, L=0)) == E.COOL_SD_EINVAL
+    assert both(_params(P)) == E.COOL_SD_EWORKSPACE
+    assert both(_params(P), ws=C.c_void_p(0x1000), n=16) == E.COOL_SD_EWORKSPACE
+    assert both(_params(P, top_k=5), ws=C.c_void_p(0x1000), n=16) == E.COOL_SD_EWORKSPACE     # the two-pass form
+    # read probe
+    assert lib.cool_sd_profile_read_probe(null, 16, null, 0, fake, 64, null) == E.COOL_SD_EINVAL
+    assert lib.cool_sd_profile_read_probe(fake, 24, null, 0, fake, 64, null) == E.COOL_SD_EINVAL
+    assert lib.cool_sd_profile_read_probe(fake, 1 << 20, null, 0, fake, 64, null) == E.COOL_SD_EWORKSPACE
     # aggregated acceptance over neighbours
     def lan(params, nbr=fake, k=10, lam=2.0, ws=null, n=0):
         return lib.cool_sd_verify_lantern(C.byref(params), fake, null, fake, null, fake, nbr, k, C.c_float(lam),

@@ -287,7 +287,8 @@ class Runner:
 
 
 def run_diagnostics(r, n):
-    """n direct cool_sd_diagnostics calls cycling through the pool (for profiler runs)."""
+    """n direct cool_sd_diagnostics calls, then n cool_sd_verify_diagnostics calls, cycling through the
+    pool (for profiler runs)."""
     pkg, torch = r.pkg, r.torch
     alpha = torch.empty((r.B, r.L), dtype=torch.float32, device="cuda")
     beta = torch.empty_like(alpha)
@@ -295,6 +296,11 @@ def run_diagnostics(r, n):
         w = r.pool[i % len(r.pool)]
         pkg.cool_sd_diagnostics(r.params, w.target, w.target_uncond, w.draft, w.draft_uncond, r.omega, alpha, beta,
                                 r.ws)
+    for i in range(n):
+        w = r.pool[i % len(r.pool)]
+        pkg.cool_sd_verify_diagnostics(r.params, w.target, w.target_uncond, w.draft, w.draft_uncond, w.draft_tokens,
+                                       r.omega, w.u_accept, w.u_resample, r.accept_len, r.next_token, None, None,
+                                       None, None, alpha, beta, r.ws)
     torch.cuda.synchronize()
 
 

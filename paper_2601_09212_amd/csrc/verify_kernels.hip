@@ -1662,9 +1662,11 @@ __global__ __launch_bounds__(LOCAL ? 512 : kThreads) void diag_kernel(const KArg
   RowRegs<DT, XF, NT> rt, rd;
   load_chunk<DT, XF, AL, NT, kTPB, 1>(rt, row_ptr(a.t, offt, kES), row_ptr(a.tu, offt, kES), base, a.V,
                                       a.cfg_scale, a.inv_T, thr_t);
-  // (a bonus workgroup re-reads the last draft row and ignores it: one code path, B workgroups)
-  load_chunk<DT, XF, AL, NT, kTPB, 1>(rd, row_ptr(a.d, offd, kES), row_ptr(a.du, offd, kES), base, a.V,
-                                      a.cfg_scale, a.inv_T, thr_d);
+  if (!bonus_wg)
+    load_chunk<DT, XF, AL, NT, kTPB, 1>(rd, row_ptr(a.d, offd, kES), row_ptr(a.du, offd, kES), base, a.V,
+                                        a.cfg_scale, a.inv_T, thr_d);
+  else
+    rd.clear();                                         // a bonus row has no draft: zeros, results ignored
   const float omega = bonus_wg ? 1.f : a.omega[int64_t(b) * a.om_sb + i];
   // the logits of x~_i for the accept test, by one thread, requested together with the rows
   float tok_t = 0.f, tok_d = 0.f;

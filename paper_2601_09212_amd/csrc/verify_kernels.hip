@@ -1687,33 +1687,36 @@ __global__ __launch_bounds__(LOCAL ? 512 : kThreads) void diag_kernel(const KArg
 #pragma unroll
       for (int j = 0; j < kE; ++j) { mt = fmaxf(mt, rt.get(t, j)); md = fmaxf(md, rd.get(t, j)); }
     }
-    mt = wave_max(mt);
-    md = wave_max(md);
-    if (lane == 0) { red[0][wv] = mt; red[1][wv] = md; }
-    __syncthreads();
-    mt = red[0][0]; md = red[1][0];
-#pragma unroll
-    for (int w = 1; w < kW; ++w) { mt = fmaxf(mt, red[0][w]); md = fmaxf(md, red[1][w]); }
-    const float Ct = fmaxf(ceilf(mt * kLog2e), kRefFloor), Cd = fmaxf(ceilf(md * kLog2e), kRefFloor);
+    // Each wave takes its own integer reference exponent (the ceiling of its maximum), so the
+    // exponentials need not wait for a workgroup-wide maximum: changing from a wave's reference to
+    // the row's is an exact power-of-two scaling, applied once per wave below.
+    const float cwt = fmaxf(ceilf(wave_max(mt) * kLog2e), kRefFloor);
+    const float cwd = fmaxf(ceilf(wave_max(md) * kLog2e), kRefFloor);
     float et[NT * kE], ed[NT * kE];
     float st = 0.f, sd = 0.f;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
 #pragma unroll
       for (int j = 0; j < kE; ++j) {
-        et[t * kE + j] = exp2_fast(__fmaf_rn(rt.get(t, j), kLog2e, -Ct));
-        ed[t * kE + j] = exp2_fast(__fmaf_rn(rd.get(t, j), kLog2e, -Cd));
+        et[t * kE + j] = exp2_fast(__fmaf_rn(rt.get(t, j), kLog2e, -cwt));
+        ed[t * kE + j] = exp2_fast(__fmaf_rn(rd.get(t, j), kLog2e, -cwd));
         st = __fadd_rn(st, et[t * kE + j]);
         sd = __fadd_rn(sd, ed[t * kE + j]);
       }
     }
     st = wave_sum(st);
     sd = wave_sum(sd);
-    if (lane == 0) { red[2][wv] = st; red[3][wv] = sd; }
+    if (lane == 0) { red[0][wv] = cwt; red[1][wv] = cwd; red[2][wv] = st; red[3][wv] = sd; }
     __syncthreads();
+    float Ct = red[0][0], Cd = red[1][0];
+#pragma unroll
+    for (int w = 1; w < kW; ++w) { Ct = fmaxf(Ct, red[0][w]); Cd = fmaxf(Cd, red[1][w]); }
     float St = 0.f, Sd = 0.f;
 #pragma unroll
-    for (int w = 0; w < kW; ++w) { St = __fadd_rn(St, red[2][w]); Sd = __fadd_rn(Sd, red[3][w]); }
+    for (int w = 0; w < kW; ++w) {
+      St = __fadd_rn(St, red[2][w] * exp2_fast(red[0][w] - Ct));
+      Sd = __fadd_rn(Sd, red[3][w] * exp2_fast(red[1][w] - Cd));
+    }
     if constexpr (VER) {
       if (threadIdx.x == 0) {
         a.part[int64_t(rt_) * a.c1] = make_float2(Ct, St);
@@ -1725,7 +1728,8 @@ __global__ __launch_bounds__(LOCAL ? 512 : kThreads) void diag_kernel(const KArg
       }
       if (bonus_wg) return;
     }
-    const float at = 1.f / St, ad = 1.f / Sd;
+    // 1/S and this wave's change of reference in one factor
+    const float at = __fmul_rn(exp2_fast(cwt - Ct), 1.f / St), ad = __fmul_rn(exp2_fast(cwd - Cd), 1.f / Sd);
 #pragma unroll
     for (int n = 0; n < NT * kE; ++n) {
       const float p = __fmul_rn(et[n], at), q = __fmul_rn(ed[n], ad);

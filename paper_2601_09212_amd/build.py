@@ -7,7 +7,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcool_sd.so")
 SOURCES = ["api.hip", "verify_kernels.hip"]
-HEADERS = ["device_utils.h", "kernels.h", "topk.h"]
+HEADERS = ["device_utils.h", "kernels.h", "topk.h", "stats_kernels.h", "topk_kernels.h", "sequence_common.h",
+           "sequence_whole.h", "early_exit_kernels.h", "sequence_long.h", "diagnostics_kernels.h"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

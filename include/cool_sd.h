@@ -21,7 +21,9 @@
  *   - Inputs are read-only; every output element is overwritten.
  *   - Functions return COOL_SD_OK (0) or a negative cool_sd_status.  Argument errors are
  *     detected on the host before anything is enqueued.  Draft tokens outside [0, V) are a
- *     contract violation and are not checked on the device.
+ *     contract violation that no status reports: wherever a token is used as an address the
+ *     kernels clamp it into [0, V-1] first, so nothing outside the rows is read, but the
+ *     results of that sequence are unspecified.
  *   - Logits must be finite or -inf (-inf = token excluded); every row needs at least one
  *     finite logit.  Uniforms lie in [0, 1).
  *   - The workspace holds only intermediate results of one call (chunk statistics, masses);

@@ -4,158 +4,223 @@
 #pragma once
 
 // ============================================================================ kernel 2, long rows
-// Long rows (more than 16384 logits): the draw x_{tau+1} from the resampling law of the sampled
-// row (Eq. opt_G / Eq. g_tsd / p_{L+1}) in two launches.  STAGE selects what one launch does:
-//   kMasses  grid = B x C.  Rows of C chunks: workgroup (b, c) writes the mass of chunk c.
-//   kSelect  grid = B.      Rows of C chunks: pick the chunk that holds u*R, load it, inverse CDF.
-enum { kMasses = 1, kSelect = 2 };
+// Rows too long for one workgroup's registers: the draw x_{tau+1} from the resampling law of the
+// sampled row (Eq. opt_G / Eq. g_tsd / p_{L+1}) in two launches after accept_kernel.
+//   sequence_masses_kernel  grid = B x C, 256 threads.  Rows of C chunks of 8192 logits:
+//                           workgroup (b, c) writes the mass of chunk c (the bandwidth part: the
+//                           row pair is streamed once).
+//   sequence_select_kernel  grid = B, 1024 threads.  Walks the C chunk masses, loads the chunk that
+//                           holds u*R and finds the token in it.
 
-template <int DT, bool XF, bool AL, int kT, int STAGE, bool LAN>
-__global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
+// What both kernels need to know about the row that sequence b samples from.
+struct SampledRow {
+  int j;                  // position tau+1 (0-based row index), L for the bonus row
+  bool bonus, none;       // none: tau == L without a bonus row, nothing to sample
+  int rt_, rd_;           // row numbers in the statistics arrays
+  const char *t_c, *t_u, *d_c, *d_u;
+  float thr_t, thr_d, omega;
+};
+
+template <int DT, bool XF>
+__device__ __forceinline__ SampledRow sampled_row(const KArgs& a, int b) {
   constexpr int kES = Vec<DT>::kES;
-  constexpr int kChunk2 = kT * kThreads * Vec<DT>::kE;   // logits per sampling chunk
-  __shared__ Smem sm;
-  const int C = a.nchunks;
-  const int b = (STAGE == kMasses) ? blockIdx.x / C : blockIdx.x;
-  const int c = (STAGE == kMasses) ? blockIdx.x - b * C : 0;
+  SampledRow r;
   const int rps = a.L + a.has_bonus;
   const bool masked = XF && a.top_k > 0;
-
-  int j = 0;
-  if (!a.resample_only) {
-    j = a.accept_len[b];
-    if (j >= a.L && !a.has_bonus) {
-      if (STAGE != kMasses && threadIdx.x == 0) {
-        a.next_token[b] = -1;
-        if (a.resid_mass) a.resid_mass[b] = 0.f;
-      }
-      return;
-    }
+  r.j = a.resample_only ? 0 : a.accept_len[b];
+  r.none = !a.resample_only && r.j >= a.L && !a.has_bonus;
+  r.bonus = a.resample_only ? (a.d == nullptr) : (r.j == a.L);
+  r.rt_ = b * rps + r.j;
+  r.rd_ = a.rows_t + b * a.L + r.j;
+  r.t_c = row_ptr(a.t, int64_t(b) * a.t_sb + int64_t(r.j) * a.t_sl, kES);
+  r.t_u = row_ptr(a.tu, int64_t(b) * a.t_sb + int64_t(r.j) * a.t_sl, kES);
+  r.d_c = r.bonus ? nullptr : row_ptr(a.d, int64_t(b) * a.d_sb + int64_t(r.j) * a.d_sl, kES);
+  r.d_u = r.bonus ? nullptr : row_ptr(a.du, int64_t(b) * a.d_sb + int64_t(r.j) * a.d_sl, kES);
+  r.thr_t = r.thr_d = -INFINITY;
+  r.omega = 1.f;
+  if (!r.none) {
+    if (masked) r.thr_t = a.thr[r.rt_];
+    if (masked && !r.bonus) r.thr_d = a.thr[r.rd_];
+    if (!r.bonus) r.omega = a.omega[int64_t(b) * a.om_sb + r.j];
   }
+  return r;
+}
 
-  // ---- the row that is sampled from: position tau+1, or the bonus row (Algorithm 1)
-  const bool bonus = a.resample_only ? (a.d == nullptr) : (j == a.L);
-  const int rt_ = b * rps + j, rd_ = a.rows_t + b * a.L + j;
-  if (a.resample_only) {
-    if (threadIdx.x == 0) {
-      float Ct, St, Cd = kRefFloor, Sd = 0.f;
-      combine_row(a, rt_, Ct, St);
-      if (!bonus) combine_row(a, rd_, Cd, Sd);
-      sm.rowstat = make_float4(Ct, St, Cd, Sd);
-    }
-    __syncthreads();
+// Statistics (Ct, St, Cd, Sd) of the sampled row: left by accept_kernel, or, for the stand-alone
+// resampling call, combined here by one thread.  All threads must call it.
+__device__ __forceinline__ float4 sampled_row_stats(const KArgs& a, int b, const SampledRow& r, float4* slot) {
+  if (!a.resample_only) return a.seq_stat[b];
+  if (threadIdx.x == 0) {
+    float Ct, St, Cd = kRefFloor, Sd = 0.f;
+    combine_row(a, r.rt_, Ct, St);
+    if (!r.bonus) combine_row(a, r.rd_, Cd, Sd);
+    *slot = make_float4(Ct, St, Cd, Sd);
   }
-  // the statistics of the sampled row are the same for every thread: read straight from the
-  // workspace (a scalar load that is in flight while the chunk's vector loads are issued)
-  const float4 rs = a.resample_only ? sm.rowstat : a.seq_stat[b];
-  const char* t_c = row_ptr(a.t, int64_t(b) * a.t_sb + int64_t(j) * a.t_sl, kES);
-  const char* t_u = row_ptr(a.tu, int64_t(b) * a.t_sb + int64_t(j) * a.t_sl, kES);
-  const char* d_c = bonus ? nullptr : row_ptr(a.d, int64_t(b) * a.d_sb + int64_t(j) * a.d_sl, kES);
-  const char* d_u = bonus ? nullptr : row_ptr(a.du, int64_t(b) * a.d_sb + int64_t(j) * a.d_sl, kES);
-  const float thr_t = masked ? a.thr[rt_] : -INFINITY;
-  const float thr_d = (masked && !bonus) ? a.thr[rd_] : -INFINITY;
-  const float omega = bonus ? 1.f : a.omega[int64_t(b) * a.om_sb + j];
+  __syncthreads();
+  return *slot;
+}
 
+// Eq. g_lantern for a thread that owns tokens first_tok .. first_tok + span - 1 (span <= 32) of
+// the row of position j: which of them belong to the rejected token's neighbour set, and where the
+// rejected token itself sits (-1: not here).
+__device__ __forceinline__ LanPatch lan_patch_span(const KArgs& a, int b, int j, float omega, int64_t first_tok, int span) {
+  LanPatch lp{0u, -1, 1.f};
+  const int xd = min(max(a.tokens[int64_t(b) * a.L + j], 0), a.V - 1);
+  const int m = a.lan_count[int64_t(b) * a.L + j];
+  lp.agg = omega;                                     // sum over the set / p(x~_j), from lantern_agg_position
+  const int64_t dx = int64_t(xd) - first_tok;
+  if (dx >= 0 && dx < span) lp.aggpos = (int)dx;
+  const int32_t* row = a.nbr + int64_t(xd) * a.lan_k;
+  int taken = 0;
+  for (int jj = 0; jj < a.lan_k && taken < m; ++jj) {   // the first m valid neighbours are the members
+    const int n = row[jj];
+    if (n < 0 || n >= a.V || n == xd) continue;
+    ++taken;
+    const int64_t dn = int64_t(n) - first_tok;
+    if (dn >= 0 && dn < span) lp.zmask |= 1u << (int)dn;
+  }
+  return lp;
+}
+
+template <int DT, bool XF, bool AL, int kT, bool LAN>
+__global__ __launch_bounds__(kThreads) void sequence_masses_kernel(const KArgs a) {
+  constexpr int kE = Vec<DT>::kE;
+  constexpr int kChunk2 = kT * kThreads * kE;            // logits per sampling chunk
+  __shared__ Smem sm;
+  const int C = a.nchunks;
+  const int b = blockIdx.x / C, c = blockIdx.x - b * C;
+  const SampledRow r = sampled_row<DT, XF>(a, b);
+  if (r.none) return;
+
+  // the mass pass reads every chunk of the row exactly once: nontemporal loads.  They are in
+  // flight before anything waits for the statistics.
+  constexpr int kA = AL ? kAlignedStream : kUnaligned;
+  const int64_t base = int64_t(c) * kChunk2;
   RowRegs<DT, XF, kT> rt, rd;
-  float part[kT];
-  auto load_pair = [&](int cc) {
-    const int64_t base = int64_t(cc) * kChunk2;
-    // the mass pass reads every chunk of the row exactly once: nontemporal loads
-    constexpr int kA = AL ? (STAGE == kMasses ? kAlignedStream : kAligned) : kUnaligned;
-    load_chunk<DT, XF, kA, kT>(rt, t_c, t_u, base, a.V, a.cfg_scale, a.inv_T, thr_t);
-    if (!bonus) load_chunk<DT, XF, kA, kT>(rd, d_c, d_u, base, a.V, a.cfg_scale, a.inv_T, thr_d);
-    else rd.clear();                                  // never read in mode P
-  };
-  if constexpr (STAGE == kMasses) load_pair(c);       // in flight before anything waits for the statistics
-  ResidCoef k{rs.x, 1.f / rs.y, rs.z, bonus ? 1.f : 1.f / rs.w, omega,
-              bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
-  // Eq. g_lantern: this thread's part of the patch for chunk cc -- which of its tokens belong to the
-  // rejected token's neighbour set (element j of tile t is token cc*kChunk2 + (t*256 + tid)*kE + j)
-  auto lan_patch = [&](int cc) -> LanPatch {
-    LanPatch lp{0u, -1, 1.f};
-    if constexpr (LAN) {
-      if (!bonus) {
-        constexpr int kE = Vec<DT>::kE;
-        const int64_t base = int64_t(cc) * kChunk2;
-        auto slot = [&](int tokn) -> int {              // bit of token tokn in this thread, or -1
-          const int64_t rel = int64_t(tokn) - base;
-          if (rel < 0 || rel >= kChunk2) return -1;
-          const int vec = int(rel) / kE;
-          if ((vec & (kThreads - 1)) != (int)threadIdx.x) return -1;
-          return (vec / kThreads) * kE + (int(rel) - vec * kE);
-        };
-        const int xd = min(max(a.tokens[int64_t(b) * a.L + j], 0), a.V - 1);
-        const int m = a.lan_count[int64_t(b) * a.L + j];
-        lp.agg = omega;
-        lp.aggpos = slot(xd);
-        const int32_t* row = a.nbr + int64_t(xd) * a.lan_k;
-        int taken = 0;
-        for (int jj = 0; jj < a.lan_k && taken < m; ++jj) {
-          const int n = row[jj];
-          if (n < 0 || n >= a.V || n == xd) continue;
-          ++taken;
-          const int sl = slot(n);
-          if (sl >= 0) lp.zmask |= 1u << sl;
-        }
+  load_chunk<DT, XF, kA, kT>(rt, r.t_c, r.t_u, base, a.V, a.cfg_scale, a.inv_T, r.thr_t);
+  if (!r.bonus) load_chunk<DT, XF, kA, kT>(rd, r.d_c, r.d_u, base, a.V, a.cfg_scale, a.inv_T, r.thr_d);
+  else rd.clear();                                    // never read in mode P
+  const float4 rs = sampled_row_stats(a, b, r, &sm.rowstat);
+  const ResidCoef k{rs.x, 1.f / rs.y, rs.z, r.bonus ? 1.f : 1.f / rs.w, r.omega,
+                    r.bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
+  // Eq. g_lantern: this thread's part of the patch -- which of its tokens belong to the rejected
+  // token's neighbour set (element e of tile t is token base + (t*256 + tid)*kE + e, bit t*kE + e)
+  LanPatch lp{0u, -1, 1.f};
+  if constexpr (LAN) {
+    if (!r.bonus) {
+      auto slot = [&](int tokn) -> int {              // bit of token tokn in this thread, or -1
+        const int64_t rel = int64_t(tokn) - base;
+        if (rel < 0 || rel >= kChunk2) return -1;
+        const int vec = int(rel) / kE;
+        if ((vec & (kThreads - 1)) != (int)threadIdx.x) return -1;
+        return (vec / kThreads) * kE + (int(rel) - vec * kE);
+      };
+      const int xd = min(max(a.tokens[int64_t(b) * a.L + r.j], 0), a.V - 1);
+      const int m = a.lan_count[int64_t(b) * a.L + r.j];
+      lp.agg = r.omega;
+      lp.aggpos = slot(xd);
+      const int32_t* row = a.nbr + int64_t(xd) * a.lan_k;
+      int taken = 0;
+      for (int jj = 0; jj < a.lan_k && taken < m; ++jj) {   // the first m valid neighbours are the members
+        const int n = row[jj];
+        if (n < 0 || n >= a.V || n == xd) continue;
+        ++taken;
+        const int sl = slot(n);
+        if (sl >= 0) lp.zmask |= 1u << sl;
       }
     }
-    return lp;
-  };
+  }
+  // only the chunk's total is needed: per-thread sum in ascending tile order, one wave reduction,
+  // one barrier
+  float acc = 0.f;
+#pragma unroll
+  for (int t = 0; t < kT; ++t) {
+#pragma unroll
+    for (int e = 0; e < kE; ++e) acc = __fadd_rn(acc, tile_elem<DT, XF, kT, LAN>(rt, rd, k, lp, t, e));
+  }
+  acc = wave_sum(acc);
+  if ((threadIdx.x & 63) == 0) sm.scan_tot[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0)
+    a.chunk_R[int64_t(b) * C + c] = __fadd_rn(__fadd_rn(sm.scan_tot[0], sm.scan_tot[1]), __fadd_rn(sm.scan_tot[2], sm.scan_tot[3]));
+}
 
-  if constexpr (STAGE == kMasses) {
-    // only the chunk's total is needed here: per-thread sum in ascending tile order, one wave
-    // reduction, one barrier (the selection launch forms its own tile totals for the chunk it picks)
-    constexpr int kE = Vec<DT>::kE;
-    const LanPatch lp = lan_patch(c);
-    float acc = 0.f;
-#pragma unroll
-    for (int t = 0; t < kT; ++t) {
-#pragma unroll
-      for (int e = 0; e < kE; ++e) acc = __fadd_rn(acc, tile_elem<DT, XF, kT, LAN>(rt, rd, k, lp, t, e));
+template <int DT, bool XF, bool AL, bool LAN>
+__global__ __launch_bounds__(kThreadsW) void sequence_select_kernel(const KArgs a) {
+  constexpr int kE = Vec<DT>::kE;
+  constexpr int kChunk2 = kChunk / 2;                     // logits per sampling chunk (8192)
+  constexpr int kVS = kChunk2 / (kThreadsW * kE);         // consecutive vectors per thread: 1 (bf16) / 2 (fp32)
+  __shared__ SmemW sm;
+  __shared__ float cm[kStage];
+  const int C = a.nchunks;
+  const int b = blockIdx.x;
+  const SampledRow r = sampled_row<DT, XF>(a, b);
+  if (r.none) {
+    if (threadIdx.x == 0) {
+      a.next_token[b] = -1;
+      if (a.resid_mass) a.resid_mass[b] = 0.f;
     }
-    acc = wave_sum(acc);
-    if ((threadIdx.x & 63) == 0) sm.scan_tot[threadIdx.x >> 6] = acc;
-    __syncthreads();
-    if (threadIdx.x == 0)
-      a.chunk_R[int64_t(b) * C + c] = __fadd_rn(__fadd_rn(sm.scan_tot[0], sm.scan_tot[1]), __fadd_rn(sm.scan_tot[2], sm.scan_tot[3]));
     return;
   }
+  const float4 rs = sampled_row_stats(a, b, r, &sm.rowstat);
+  ResidCoef k{rs.x, 1.f / rs.y, rs.z, r.bonus ? 1.f : 1.f / rs.w, r.omega,
+              r.bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
 
-  float R, vsel;     // total mass; remaining mass to walk inside the selected chunk
-  int cs = 0;        // selected chunk
-  LanPatch lp_sel{0u, -1, 1.f};
-  {
-    // chunk masses are staged in LDS by all threads (one latency), then walked in ascending
-    // order; rows with more than kStage chunks walk global memory instead
-    __shared__ float cm[kStage];
+  // mass of chunk cc under the fallback law p, from the chunk statistics of the statistics pass
+  const int per = kChunk2 / a.chunk1;
+  auto p_mass = [&](int cc) -> float {
+    float m = 0.f;
+    for (int q = cc * per; q < min((cc + 1) * per, a.c1); ++q) {
+      const float2 pp = a.part[int64_t(r.rt_) * a.c1 + q];
+      m = __fadd_rn(m, __fmul_rn(__fmul_rn(pp.y, exp2_fast(pp.x - rs.x)), k.at));
+    }
+    return m;
+  };
+  // The chunk that holds u*R: first with positive mass whose inclusive sum exceeds u*R, else the
+  // last with mass.
+  float R, cbase = 0.f;
+  int cs = -1;
+  bool fallback = false;
+  if (C <= 64) {
+    // up to 64 chunks (rows of 524288 logits): lane c of every wave takes chunk c, one memory
+    // round trip and a wave scan, no LDS and no barrier; every wave gets the same answer
+    const int lane = threadIdx.x & 63;
+    float m = lane < C ? a.chunk_R[int64_t(b) * C + lane] : 0.f;
+    float incl = wave_scan_incl(m);
+    R = lane_f(incl, 63);
+    if (!(R > 0.f)) {    // no rejection possible at this position: any law is optimal, use p
+      fallback = true;
+      k.mode = kModeP;
+      m = lane < C ? p_mass(lane) : 0.f;
+      incl = wave_scan_incl(m);
+      R = lane_f(incl, 63);
+    }
+    const float v = __fmul_rn(a.u_res[b], R);
+    const float excl = wave_prev_lane(incl);
+    const bool pos = m > 0.f;
+    const unsigned long long bh = __ballot(pos && incl > v), bp = __ballot(pos);
+    cs = bh ? __ffsll((long long)bh) - 1 : (bp ? 63 - __clzll((long long)bp) : 0);
+    cbase = lane_f(excl, cs);
+  } else {
+    // longer rows: chunk masses staged in LDS by all threads (one latency), then walked in
+    // ascending order by every thread for itself; more than kStage chunks walk global memory
     const bool staged = C <= kStage;
-    // mass of chunk cc under the fallback law p, from the chunk statistics of kernel 1
-    const int per = kChunk2 / a.chunk1;
-    auto p_mass = [&](int cc) -> float {
-      float m = 0.f;
-      for (int q = cc * per; q < min((cc + 1) * per, a.c1); ++q) {
-        const float2 pp = a.part[int64_t(rt_) * a.c1 + q];
-        m = __fadd_rn(m, __fmul_rn(__fmul_rn(pp.y, exp2_fast(pp.x - rs.x)), k.at));
-      }
-      return m;
-    };
-    bool fallback = false;
     auto chunk_mass = [&](int cc) -> float {
       if (staged) return cm[cc];
       return fallback ? p_mass(cc) : a.chunk_R[int64_t(b) * C + cc];
     };
     if (staged) {
-      for (int cc = threadIdx.x; cc < C; cc += kThreads) cm[cc] = a.chunk_R[int64_t(b) * C + cc];
+      for (int cc = threadIdx.x; cc < C; cc += kThreadsW) cm[cc] = a.chunk_R[int64_t(b) * C + cc];
       __syncthreads();
     }
     R = 0.f;
     for (int cc = 0; cc < C; ++cc) R = __fadd_rn(R, chunk_mass(cc));
-    if (!(R > 0.f)) {    // no rejection possible at this position: any law is optimal, use p
+    if (!(R > 0.f)) {
       fallback = true;
       k.mode = kModeP;
       if (staged) {
         __syncthreads();
-        for (int cc = threadIdx.x; cc < C; cc += kThreads) cm[cc] = p_mass(cc);
+        for (int cc = threadIdx.x; cc < C; cc += kThreadsW) cm[cc] = p_mass(cc);
         __syncthreads();
       }
       R = 0.f;
@@ -163,8 +228,7 @@ __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
     }
     const float v = __fmul_rn(a.u_res[b], R);
     int clast = -1;
-    float cbase = 0.f, cbase_last = 0.f, cum = 0.f;
-    cs = -1;
+    float cbase_last = 0.f, cum = 0.f;
     for (int cc = 0; cc < C; ++cc) {
       const float m = chunk_mass(cc);
       if (m > 0.f) {
@@ -175,16 +239,25 @@ __global__ __launch_bounds__(kThreads) void sequence_kernel(const KArgs a) {
     }
     if (cs < 0) { cs = clast; cbase = cbase_last; }
     if (cs < 0) cs = 0;
-    vsel = v - cbase;
-    load_pair(cs);
-    lp_sel = lan_patch(cs);
-    chunk_masses<DT, XF, kT, LAN>(rt, rd, k, part, sm, lp_sel);
   }
-  const int off = chunk_select<DT, XF, kT, LAN>(rt, rd, k, part, vsel, sm, lp_sel);
-  int token = cs * kChunk2 + max(off, 0);
-  if (token >= a.V) token = a.V - 1;
-  if (threadIdx.x == 0) {
-    a.next_token[b] = token;
+  const float v_in = __fsub_rn(__fmul_rn(a.u_res[b], R), cbase);   // mass left to walk inside the chunk
+
+  // the chosen chunk, thread t holding its vectors t*kVS ..: same search as on short rows, for
+  // the mass that is left to walk inside the chunk
+  const int64_t base = int64_t(cs) * kChunk2;
+  RowRegs<DT, XF, kVS> rt, rd;
+  load_chunk<DT, XF, AL, kVS, 1, kVS>(rt, r.t_c, r.t_u, base, a.V, a.cfg_scale, a.inv_T, r.thr_t);
+  if (!r.bonus) load_chunk<DT, XF, AL, kVS, 1, kVS>(rd, r.d_c, r.d_u, base, a.V, a.cfg_scale, a.inv_T, r.thr_d);
+  else rd.clear();                                    // never read in mode P
+  LanPatch lp{0u, -1, 1.f};
+  if constexpr (LAN) {
+    if (!r.bonus && !fallback) lp = lan_patch_span(a, b, r.j, r.omega, base + int64_t(threadIdx.x) * (kVS * kE), kVS * kE);
+  }
+  float R_chunk;
+  bool writer;
+  const int off = sample_whole<DT, XF, kVS, LAN, true>(rt, rd, k, v_in, a.V - (int)base, sm, R_chunk, writer, lp);
+  if (writer) {
+    a.next_token[b] = (int)base + off;
     if (a.resid_mass) a.resid_mass[b] = R;
   }
 }

@@ -19,7 +19,10 @@
 // is possible at this position) it falls back to p.  The token is returned in ONE thread, the one
 // that found it (writer = true there), so that no barrier is spent on handing it around; R, the
 // law's mass, is known to every thread.
-template <int DT, bool XF, int kVW, bool LAN = false>
+// ABS: `u` is not the uniform but the mass to walk itself (the caller has taken u*R of a longer
+// row and subtracted what lies before this part of it); V is then the number of tokens from the
+// first one held here to the end of the row.
+template <int DT, bool XF, int kVW, bool LAN = false, bool ABS = false>
 __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, const RowRegs<DT, XF, kVW>& rd,
                                             ResidCoef k, float u, int V, SmemW& sm, float& R, bool& writer,
                                             const LanPatch lp = LanPatch{0u, -1, 1.f}) {
@@ -68,7 +71,7 @@ __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, cons
   }
 
   // thread: first with positive mass whose inclusive sum exceeds u*R, else the last with mass
-  const float v = __fmul_rn(u, R);
+  const float v = ABS ? u : __fmul_rn(u, R);
   const bool pos = mine > 0.f;
   const bool hit = pos && (incl > v);
   const unsigned long long bh = __ballot(hit), bp = __ballot(pos);
@@ -121,10 +124,16 @@ __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, cons
   return token >= V ? V - 1 : token;
 }
 
-template <int DT, bool XF, bool AL, bool LAN>
+// MUL = 2: the same for rows of up to 32768 logits, whose pair still fits the registers of 1024
+// threads (32 words per row and thread) -- one launch where the long-row form needs three.  (Four
+// times the row, 65536 packed bf16 logits, was measured too: it spills and is slower than the
+// three launches.)
+template <int DT, bool XF, bool AL, bool LAN, int MUL = 1>
 __global__ __launch_bounds__(kThreadsW) void sequence_whole_kernel(const KArgs a) {
   constexpr int kE = Vec<DT>::kE, kES = Vec<DT>::kES;
-  constexpr int kVW = kChunk / (kThreadsW * kE);       // vectors per thread: 2 (bf16) / 4 (fp32)
+  constexpr int kVW = MUL * kChunk / (kThreadsW * kE);   // vectors per thread: MUL * 2 (bf16) / MUL * 4 (fp32)
+  static_assert(MUL == 1 || (MUL == 2 && !LAN), "the neighbour patch is one 32-bit mask per thread");
+  static_assert((RowRegs<DT, XF, kVW>::kRaw ? kVW * 4 : kVW * kE) <= 32, "a row pair must fit the registers");
   __shared__ SmemW sm;
   const int b = blockIdx.x;
   const int rps = a.L + a.has_bonus;

@@ -22,8 +22,8 @@
 //                      hierarchical inverse CDF.
 // Rows longer than 16384 logits do not fit one workgroup's registers; the second step is then
 // split at kernel boundaries: accept_kernel (chunk statistics combined, tau; one workgroup per
-// sequence), sequence_kernel<kMasses> (mass of every 8192-logit chunk of the sampled rows,
-// streaming) and sequence_kernel<kSelect> (pick the chunk that holds u*R, re-read it, inverse
+// sequence), sequence_masses_kernel (mass of every 8192-logit chunk of the sampled rows,
+// streaming) and sequence_select_kernel (pick the chunk that holds u*R, re-read it, inverse
 // CDF).  cool_sd_resample on short rows is one launch (resample_whole_kernel, resample_topk_kernel).
 // Other entry points add: lantern_agg_position (neighbour aggregation of the LANTERN-style
 // acceptance: part of the statistics launch, or lantern_agg_kernel after the radix passes),
@@ -70,7 +70,7 @@ __device__ __forceinline__ const char* row_ptr(const void* base, int64_t elem_of
 #include "sequence_common.h"        // combine_rows_kernel, residual law, eval_position, find_tau, accept_kernel
 #include "sequence_whole.h"         // sequence_whole_kernel, lantern_agg_kernel
 #include "early_exit_kernels.h"     // sequence_early_exit_*kernel, resample_whole_kernel
-#include "sequence_long.h"          // sequence_kernel<kMasses / kSelect>
+#include "sequence_long.h"          // sequence_masses_kernel, sequence_select_kernel
 #include "diagnostics_kernels.h"    // diag_kernel, diag_combine_kernel
 
 // ============================================================================ host side: launches
@@ -260,6 +260,14 @@ static hipError_t launch_rest(const KArgs& a, hipStream_t stream) {
       hipLaunchKernelGGL((sequence_whole_kernel<DT, XF, AL, false>), dim3(gB), dim3(kThreadsW), 0, stream, a);
     return checked("sequence_whole_kernel");
   }
+  if constexpr (AL) {
+    // aligned rows of up to 32768 logits (four statistics chunks, read directly) still fit the
+    // registers of one workgroup: the one-launch form
+    if (!a.lan_resample && a.V <= 2 * kChunk) {
+      hipLaunchKernelGGL((sequence_whole_kernel<DT, XF, AL, false, 2>), dim3(gB), dim3(kThreadsW), 0, stream, a);
+      return checked("sequence_whole_kernel");
+    }
+  }
   if (!a.resample_only) {     // several chunks: find tau once per sequence
     hipLaunchKernelGGL((accept_kernel<DT, XF>), dim3(gB), dim3(kThreadsW), 0, stream, a);
     e = checked("accept_kernel");
@@ -267,16 +275,16 @@ static hipError_t launch_rest(const KArgs& a, hipStream_t stream) {
   }
   const int64_t grid2 = int64_t(a.B) * a.nchunks;
   if (a.lan_resample)
-    hipLaunchKernelGGL((sequence_kernel<DT, XF, AL, kT / 2, kMasses, true>), dim3((unsigned)grid2), dim3(kThreads), 0, stream, a);
+    hipLaunchKernelGGL((sequence_masses_kernel<DT, XF, AL, kT / 2, true>), dim3((unsigned)grid2), dim3(kThreads), 0, stream, a);
   else
-    hipLaunchKernelGGL((sequence_kernel<DT, XF, AL, kT / 2, kMasses, false>), dim3((unsigned)grid2), dim3(kThreads), 0, stream, a);
-  e = checked("sequence_kernel (masses)");
+    hipLaunchKernelGGL((sequence_masses_kernel<DT, XF, AL, kT / 2, false>), dim3((unsigned)grid2), dim3(kThreads), 0, stream, a);
+  e = checked("sequence_masses_kernel");
   if (e != hipSuccess) return e;
   if (a.lan_resample)
-    hipLaunchKernelGGL((sequence_kernel<DT, XF, AL, kT / 2, kSelect, true>), dim3(gB), dim3(kThreads), 0, stream, a);
+    hipLaunchKernelGGL((sequence_select_kernel<DT, XF, AL, true>), dim3(gB), dim3(kThreadsW), 0, stream, a);
   else
-    hipLaunchKernelGGL((sequence_kernel<DT, XF, AL, kT / 2, kSelect, false>), dim3(gB), dim3(kThreads), 0, stream, a);
-  return checked("sequence_kernel");
+    hipLaunchKernelGGL((sequence_select_kernel<DT, XF, AL, false>), dim3(gB), dim3(kThreadsW), 0, stream, a);
+  return checked("sequence_select_kernel");
 }
 
 template <int DT, bool XF>

@@ -47,6 +47,45 @@ def test_shapes_against_oracle(P, oracle, cfg, B, L, V, dtype):
     compare_verify(oracle, w, om, gpu)
 
 
+# Rows of several chunks: up to 32768 logits one workgroup of 1024 threads still holds the row
+# pair in registers (the per-sequence step is then one launch); beyond, accept / chunk masses /
+# selection are three launches.
+MID_ROWS = [
+    (5, 6, 4, 32768, "bf16", {}),                                   # four chunks of 8192, the longest one-launch row
+    (5, 4, 3, 32760, "bf16", {"resample_mode": 1}),                 # ragged last vector; vanilla law
+    (5, 4, 3, 24584, "bf16", {"temperature": 0.7}),                 # transformed bf16: fp32 words in registers
+    (1, 3, 3, 32768, "f32", {}),
+    (1, 3, 2, 20004, "f32", {"temperature": 1.3}),
+    (5, 3, 3, 32776, "bf16", {}),                                   # one vector beyond: the three-launch form
+    (5, 3, 3, 65536, "bf16", {}),
+    (5, 3, 2, 65528, "bf16", {"resample_mode": 1}),
+    (5, 3, 3, 40000, "bf16", {"temperature": 0.7}),
+    (1, 2, 2, 40004, "f32", {}),                                    # fp32: two vectors per thread in the selection
+    (5, 2, 2, 600000, "bf16", {}),                                  # more than 64 chunks: the serial chunk walk
+]
+
+
+@pytest.mark.parametrize("cfg,B,L,V,dtype,kw", MID_ROWS)
+def test_rows_of_several_chunks_in_one_workgroup(P, oracle, cfg, B, L, V, dtype, kw):
+    print("case", cfg, B, L, V, dtype, kw, flush=True)
+    w = make_workload(cfg, device="cuda", B=B, L=L, V=V, dtype=dtype)
+    if "temperature" in kw:
+        w.temperature = kw["temperature"]
+    mode = kw.get("resample_mode", 0)
+    om = _omega(P, w)
+    gpu = _run(P, oracle, w, om, resample_mode=mode)
+    compare_verify(oracle, w, om, gpu, resample_mode=mode)
+    # forced outcomes: rejection at the first position, and acceptance of everything (bonus row)
+    for om_f, tau in ((np.zeros(L, np.float32), 0), (np.full(L, 1e30, np.float32), L)):
+        gpu = _run(P, oracle, w, om_f, resample_mode=mode)
+        assert (gpu["accept_len"] == tau).all()
+        compare_verify(oracle, w, om_f, gpu, resample_mode=mode)
+    # no bonus row
+    w.target = w.target[:, :L]
+    gpu = _run(P, oracle, w, om, resample_mode=mode)
+    compare_verify(oracle, w, om, gpu, resample_mode=mode, has_bonus=False)
+
+
 @pytest.mark.parametrize("mode", [0, 1])
 @pytest.mark.parametrize("delta", [1.0, 2.0, 4.0])
 def test_modes_and_budgets(P, oracle, mode, delta):

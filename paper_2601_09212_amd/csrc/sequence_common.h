@@ -199,6 +199,29 @@ __device__ __forceinline__ int chunk_select(const RowRegs<DT, XF, kT>& rt, const
   return sm.bcast_i;
 }
 
+// f_i of Eq. relax and the accept test of position i of sequence b, from the statistics of its row
+// pair, the two logits of x~_i, omega_i and u_i.  Returns true when x~_i is rejected; a bonus row
+// (has_draft false) never is.  With `emit` it writes the per-position diagnostics.
+__device__ __forceinline__ bool accept_test(const KArgs& a, int b, int i, bool emit, bool has_draft, float Ct, float St,
+                                            float Cd, float Sd, float lt, float ld, float omega, float u) {
+  // exponents of p(x~) and q(x~) in base-2 units; the ratio p/q is formed from their
+  // difference so that it survives when both probabilities underflow fp32
+  const float et = __fmaf_rn(lt, kLog2e, -Ct), ed = __fmaf_rn(ld, kLog2e, -Cd);
+  const float ratio = __fmul_rn(exp2_fast(__fsub_rn(et, ed)), Sd / St);
+  // f = min{1, omega p/q}; a token the draft excludes (q = 0) has f = 1, also at 0/0
+  const float fi = (ld == -INFINITY) ? 1.f : ((omega > 0.f) ? fminf(1.f, __fmul_rn(omega, ratio)) : 0.f);
+  if (emit && has_draft) {
+    const int64_t o = int64_t(b) * a.L + i;
+    // aggregated probability of the neighbour set (Eq. p_lantern at x~_i): p_i(x~_i) times agg,
+    // which the LANTERN-style call passes as omega_i
+    if (a.p_agg_out) a.p_agg_out[o] = __fmul_rn(exp2_fast(et) / St, omega);
+    if (a.p_tok) a.p_tok[o] = exp2_fast(et) / St;
+    if (a.q_tok) a.q_tok[o] = exp2_fast(ed) / Sd;
+    if (a.f) a.f[o] = fi;
+  }
+  return has_draft && !(u <= fi);
+}
+
 // Position i of sequence b: statistics of its row pair (or of the bonus row alone), f_i of
 // Eq. relax and the accept test.  Returns true when x~_i is rejected.  With `emit` it writes the
 // per-position diagnostics.
@@ -226,23 +249,9 @@ __device__ __forceinline__ bool eval_position(const KArgs& a, int b, int i, bool
   asm volatile("" : "+v"(omega), "+v"(u));
   combine_parts(a, vt, Ct, St);
   combine_parts(a, vd, Cd, Sd);
-  // exponents of p(x~) and q(x~) in base-2 units; the ratio p/q is formed from their
-  // difference so that it survives when both probabilities underflow fp32
-  const float et = __fmaf_rn(lt, kLog2e, -Ct), ed = __fmaf_rn(ld, kLog2e, -Cd);
-  const float ratio = __fmul_rn(exp2_fast(__fsub_rn(et, ed)), Sd / St);
-  // f = min{1, omega p/q}; a token the draft excludes (q = 0) has f = 1, also at 0/0
-  const float fi = (ld == -INFINITY) ? 1.f : ((omega > 0.f) ? fminf(1.f, __fmul_rn(omega, ratio)) : 0.f);
-  if (emit && has_draft) {
-    const int64_t o = int64_t(b) * a.L + i;
-    // aggregated probability of the neighbour set (Eq. p_lantern at x~_i): p_i(x~_i) times agg,
-    // which the LANTERN-style call passes as omega_i
-    if (a.p_agg_out) a.p_agg_out[o] = __fmul_rn(exp2_fast(et) / St, omega);
-    if (a.p_tok) a.p_tok[o] = exp2_fast(et) / St;
-    if (a.q_tok) a.q_tok[o] = exp2_fast(ed) / Sd;
-    if (a.f) a.f[o] = fi;
-  }
+  const bool rej = accept_test(a, b, i, emit, has_draft, Ct, St, Cd, Sd, lt, ld, omega, u);
   if (!has_draft) { Cd = kRefFloor; Sd = 0.f; }         // the bonus row stands alone
-  return has_draft && !(u <= fi);
+  return rej;
 }
 
 // Accept test at every position of sequence b (Eq. relax) and tau = first rejection (Algorithm 1)

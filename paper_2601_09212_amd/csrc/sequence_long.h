@@ -22,12 +22,12 @@ struct SampledRow {
 };
 
 template <int DT, bool XF>
-__device__ __forceinline__ SampledRow sampled_row(const KArgs& a, int b) {
+__device__ __forceinline__ SampledRow sampled_row(const KArgs& a, int b, int tau) {
   constexpr int kES = Vec<DT>::kES;
   SampledRow r;
   const int rps = a.L + a.has_bonus;
   const bool masked = XF && a.top_k > 0;
-  r.j = a.resample_only ? 0 : a.accept_len[b];
+  r.j = a.resample_only ? 0 : tau;
   r.none = !a.resample_only && r.j >= a.L && !a.has_bonus;
   r.bonus = a.resample_only ? (a.d == nullptr) : (r.j == a.L);
   r.rt_ = b * rps + r.j;
@@ -82,14 +82,92 @@ __device__ __forceinline__ LanPatch lan_patch_span(const KArgs& a, int b, int j,
   return lp;
 }
 
-template <int DT, bool XF, bool AL, int kT, bool LAN>
+// tau of sequence b found by a 256-thread workgroup from the chunk statistics of the sequence's
+// rows (at most 64 chunks per row, at most kTauRows positions, the bonus row included), so that
+// the chunk-mass launch needs no accept_kernel before it: every workgroup of a sequence finds the
+// same tau for itself (same code, same inputs), the one with emit = true writes accept_len, the
+// per-position outputs and the sampled row's statistics for the selection kernel.
+//   wave w combines rows w, w+4, ... -- lane c takes chunk c, eight rows' loads in flight, then a
+//   wave maximum and a wave sum per row -- into LDS; one barrier; lane i of wave 0 runs the accept
+//   test of position i (its other inputs were requested at the very start); ballot; one barrier.
+constexpr int kTauRows = 64;
+struct SmemTau {
+  float2 st[2 * kTauRows];       // (reference exponent, sum): target rows 0 .. L(+1)-1, then the draft rows
+  float4 rowstat;
+  int tau;
+};
+__device__ __forceinline__ int find_tau_from_parts(const KArgs& a, int b, bool emit, SmemTau& sm) {
+  constexpr int kBatch = 8;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int rps = a.L + a.has_bonus, nrows = rps + a.L;
+  const bool mine = wv == 0 && lane < rps;              // this lane evaluates position `lane`
+  const bool has_draft = lane < a.L;
+  const int id = has_draft ? lane : a.L - 1;
+  float lt = 0.f, ld = 0.f, omega = 0.f, u = 0.f;
+  if (mine) {
+    lt = a.tok_logit[b * rps + lane];
+    ld = a.tok_logit[a.rows_t + b * a.L + id];
+    omega = a.omega[int64_t(b) * a.om_sb + id];
+    u = a.u_acc[int64_t(b) * a.L + id];
+  }
+  const int cl = lane < a.c1 ? lane : 0;
+  for (int q0 = wv; q0 < nrows; q0 += kWaves * kBatch) {
+    float2 v[kBatch];
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k) {
+      const int q = min(q0 + k * kWaves, nrows - 1);      // clamped: a row past the end is read and dropped
+      const int row = q < rps ? b * rps + q : a.rows_t + b * a.L + (q - rps);
+      v[k] = a.part[int64_t(row) * a.c1 + cl];
+    }
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k) {
+      const int q = q0 + k * kWaves;
+      const float cx = lane < a.c1 ? v[k].x : kRefFloor, sx = lane < a.c1 ? v[k].y : 0.f;
+      const float m = wave_max(cx);
+      const float t = wave_sum(sx * exp2_fast(cx - m));
+      if (lane == 0 && q < nrows) sm.st[q] = make_float2(m, t);
+    }
+  }
+  __syncthreads();
+  if (wv == 0) {
+    bool rej = false;
+    float Ct = kRefFloor, St = 0.f, Cd = kRefFloor, Sd = 0.f;
+    if (mine) {
+      const float2 t2 = sm.st[lane], d2 = sm.st[rps + id];
+      Ct = t2.x; St = t2.y; Cd = d2.x; Sd = d2.y;
+      rej = accept_test(a, b, lane, emit, has_draft, Ct, St, Cd, Sd, lt, ld, omega, u);
+      if (!has_draft) { Cd = kRefFloor; Sd = 0.f; }       // the bonus row stands alone
+    }
+    const unsigned long long br = __ballot(rej);
+    const int w = br ? __ffsll((long long)br) - 1 : a.L;
+    if (lane == w) sm.rowstat = make_float4(Ct, St, Cd, Sd);   // position w, or the bonus row when w == L
+    if (lane == 0) {
+      sm.tau = w;
+      if (emit) a.accept_len[b] = w;
+    }
+  }
+  __syncthreads();
+  return sm.tau;
+}
+
+// TAU: the workgroup finds tau itself (find_tau_from_parts) instead of reading what accept_kernel left.
+template <int DT, bool XF, bool AL, int kT, bool LAN, bool TAU>
 __global__ __launch_bounds__(kThreads) void sequence_masses_kernel(const KArgs a) {
   constexpr int kE = Vec<DT>::kE;
   constexpr int kChunk2 = kT * kThreads * kE;            // logits per sampling chunk
   __shared__ Smem sm;
   const int C = a.nchunks;
   const int b = blockIdx.x / C, c = blockIdx.x - b * C;
-  const SampledRow r = sampled_row<DT, XF>(a, b);
+  int tau = 0;
+  if constexpr (TAU) {
+    __shared__ SmemTau smt;
+    tau = find_tau_from_parts(a, b, c == 0, smt);
+    sm.rowstat = smt.rowstat;                            // every thread writes the same value
+    if (c == 0 && threadIdx.x == 0) a.seq_stat[b] = smt.rowstat;
+  } else {
+    if (!a.resample_only) tau = a.accept_len[b];
+  }
+  const SampledRow r = sampled_row<DT, XF>(a, b, tau);
   if (r.none) return;
 
   // the mass pass reads every chunk of the row exactly once: nontemporal loads.  They are in
@@ -100,7 +178,13 @@ __global__ __launch_bounds__(kThreads) void sequence_masses_kernel(const KArgs a
   load_chunk<DT, XF, kA, kT>(rt, r.t_c, r.t_u, base, a.V, a.cfg_scale, a.inv_T, r.thr_t);
   if (!r.bonus) load_chunk<DT, XF, kA, kT>(rd, r.d_c, r.d_u, base, a.V, a.cfg_scale, a.inv_T, r.thr_d);
   else rd.clear();                                    // never read in mode P
-  const float4 rs = sampled_row_stats(a, b, r, &sm.rowstat);
+  float4 rs;
+  if constexpr (TAU) {
+    __syncthreads();                                     // sm.rowstat, written above
+    rs = sm.rowstat;
+  } else {
+    rs = sampled_row_stats(a, b, r, &sm.rowstat);
+  }
   const ResidCoef k{rs.x, 1.f / rs.y, rs.z, r.bonus ? 1.f : 1.f / rs.w, r.omega,
                     r.bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
   // Eq. g_lantern: this thread's part of the patch -- which of its tokens belong to the rejected
@@ -154,7 +238,7 @@ __global__ __launch_bounds__(kThreadsW) void sequence_select_kernel(const KArgs 
   __shared__ float cm[kStage];
   const int C = a.nchunks;
   const int b = blockIdx.x;
-  const SampledRow r = sampled_row<DT, XF>(a, b);
+  const SampledRow r = sampled_row<DT, XF>(a, b, a.resample_only ? 0 : a.accept_len[b]);
   if (r.none) {
     if (threadIdx.x == 0) {
       a.next_token[b] = -1;

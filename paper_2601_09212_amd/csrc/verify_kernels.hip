@@ -240,7 +240,14 @@ template <int DT, bool XF, bool AL>
 static hipError_t launch_rest(const KArgs& a, hipStream_t stream) {
   constexpr int kT = Vec<DT>::kT;
   hipError_t e;
-  if (a.cs != a.c1 && !a.accept_combines) {   // rows have many statistics chunks: pre-combine them, one wave per row
+  // long rows: the chunk-mass launch finds tau itself when a row's chunk statistics fit one wave and
+  // the positions another (rows of up to 524288 logits, draft windows of up to 63 tokens), and all
+  // its workgroups are resident at once -- the search is then latency paid once instead of a
+  // launch; in a larger grid it would repeat with every round of workgroups (configuration 5,
+  // 4096 workgroups: 208.5 us with accept_kernel, 212.3 us without)
+  const bool fuse_tau = !a.resample_only && a.nt2 != kT && a.c1 <= 64 && a.L + a.has_bonus <= kTauRows &&
+                        int64_t(a.B) * a.nchunks <= 2048;
+  if (a.cs != a.c1 && !a.accept_combines && !fuse_tau) {   // rows have many statistics chunks: pre-combine them, one wave per row
     const int64_t gridc = (int64_t(a.rows_t) + a.rows_d + kWaves - 1) / kWaves;
     hipLaunchKernelGGL(combine_rows_kernel, dim3((unsigned)gridc), dim3(kThreads), 0, stream, a);
     e = checked("combine_rows_kernel");
@@ -268,16 +275,19 @@ static hipError_t launch_rest(const KArgs& a, hipStream_t stream) {
       return checked("sequence_whole_kernel");
     }
   }
-  if (!a.resample_only) {     // several chunks: find tau once per sequence
+  if (!a.resample_only && !fuse_tau) {     // find tau once per sequence
     hipLaunchKernelGGL((accept_kernel<DT, XF>), dim3(gB), dim3(kThreadsW), 0, stream, a);
     e = checked("accept_kernel");
     if (e != hipSuccess) return e;
   }
-  const int64_t grid2 = int64_t(a.B) * a.nchunks;
-  if (a.lan_resample)
-    hipLaunchKernelGGL((sequence_masses_kernel<DT, XF, AL, kT / 2, true>), dim3((unsigned)grid2), dim3(kThreads), 0, stream, a);
-  else
-    hipLaunchKernelGGL((sequence_masses_kernel<DT, XF, AL, kT / 2, false>), dim3((unsigned)grid2), dim3(kThreads), 0, stream, a);
+  const dim3 grid2((unsigned)(int64_t(a.B) * a.nchunks));
+  if (fuse_tau) {
+    if (a.lan_resample) hipLaunchKernelGGL((sequence_masses_kernel<DT, XF, AL, kT / 2, true, true>), grid2, dim3(kThreads), 0, stream, a);
+    else hipLaunchKernelGGL((sequence_masses_kernel<DT, XF, AL, kT / 2, false, true>), grid2, dim3(kThreads), 0, stream, a);
+  } else {
+    if (a.lan_resample) hipLaunchKernelGGL((sequence_masses_kernel<DT, XF, AL, kT / 2, true, false>), grid2, dim3(kThreads), 0, stream, a);
+    else hipLaunchKernelGGL((sequence_masses_kernel<DT, XF, AL, kT / 2, false, false>), grid2, dim3(kThreads), 0, stream, a);
+  }
   e = checked("sequence_masses_kernel");
   if (e != hipSuccess) return e;
   if (a.lan_resample)

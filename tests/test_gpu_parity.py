@@ -61,7 +61,10 @@ MID_ROWS = [
     (5, 3, 2, 65528, "bf16", {"resample_mode": 1}),
     (5, 3, 3, 40000, "bf16", {"temperature": 0.7}),
     (1, 2, 2, 40004, "f32", {}),                                    # fp32: two vectors per thread in the selection
-    (5, 2, 2, 600000, "bf16", {}),                                  # more than 64 chunks: the serial chunk walk
+    (5, 2, 2, 600000, "bf16", {}),                                  # more than 64 chunks: accept_kernel, the serial chunk walk
+    (5, 2, 63, 32776, "bf16", {}),                                  # 64 positions with the bonus row: tau still found by the chunk-mass launch
+    (5, 2, 64, 32776, "bf16", {}),                                  # 65: accept_kernel
+    (1, 5, 7, 70000, "f32", {"temperature": 0.9}),
 ]
 
 

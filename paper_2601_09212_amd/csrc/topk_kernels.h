@@ -6,8 +6,8 @@
 #pragma once
 
 // Statistics of whole rows under top-k truncation: one workgroup of TPB threads per row,
-// ROW / TPB transformed logits per thread in registers (ROW = 16384 with 512 threads, or 65536
-// with 1024 threads for vocabularies up to 64K).  The k-th largest value of the row is selected
+// ROW / TPB transformed logits per thread in registers (ROW = 16384 with 512 threads; 32768 or
+// 65536 with 1024 threads for vocabularies up to 32K / 64K).  The k-th largest value of the row is selected
 // first (topk.h); the softmax statistics are then taken over the entries >= that threshold,
 // against the reference exponent of the row maximum (always kept).  Writes the row's threshold,
 // its statistics -- one pair per row, or for the long form one pair per 8192 logits, the layout

@@ -175,7 +175,12 @@ static hipError_t launch_stats_any(const KArgs& a, hipStream_t stream) {
         else if (g3) CSD_TOPK_LAUNCH(kThreadsK, 0, true, kChunk);
         else if (guided) CSD_TOPK_LAUNCH(kThreadsK, 1, false, kChunk);
         else CSD_TOPK_LAUNCH(kThreadsK, 0, false, kChunk);
-      } else {                           // 16384 < V <= 65536: 1024 threads, statistics per 8192 logits
+      } else if (a.V <= 2 * kChunk) {    // 16384 < V <= 32768: 1024 threads with 32 logits each, statistics per 8192 logits
+        if (g3 && guided) CSD_TOPK_LAUNCH(kThreadsW, 1, true, 2 * kChunk);
+        else if (g3) CSD_TOPK_LAUNCH(kThreadsW, 0, true, 2 * kChunk);
+        else if (guided) CSD_TOPK_LAUNCH(kThreadsW, 1, false, 2 * kChunk);
+        else CSD_TOPK_LAUNCH(kThreadsW, 0, false, 2 * kChunk);
+      } else {                           // 32768 < V <= 65536: 64 logits per thread
         if (g3 && guided) CSD_TOPK_LAUNCH(kThreadsW, 1, true, kRowMid);
         else if (g3) CSD_TOPK_LAUNCH(kThreadsW, 0, true, kRowMid);
         else if (guided) CSD_TOPK_LAUNCH(kThreadsW, 1, false, kRowMid);

@@ -330,6 +330,9 @@ def test_topk_with_excluded_tokens(P, oracle):
 @pytest.mark.parametrize("cfg,B,L,V,dtype,top_k", [
     (3, 3, 3, 40000, "bf16", 1000),      # guidance + truncation on rows of five chunks
     (3, 2, 2, 65536, "bf16", 2000),      # a 64K vocabulary
+    (3, 3, 3, 32768, "bf16", 1000),      # the longest row of the 32-logits-per-thread form
+    (3, 2, 3, 24584, "bf16", 300),       # its ragged last statistics pair
+    (1, 2, 2, 20004, "f32", 7),
     (2, 2, 3, 20001, "bf16", 50),        # element-wise loads, no guidance
     (1, 2, 2, 33000, "f32", 1),          # greedy support on fp32 rows
     (5, 2, 2, 262144, "bf16", 4096),     # the large-vocabulary configuration's rows

@@ -159,32 +159,27 @@ __global__ __launch_bounds__(kThreads) void sequence_masses_kernel(const KArgs a
   const int C = a.nchunks;
   const int b = blockIdx.x / C, c = blockIdx.x - b * C;
   int tau = 0;
+  float4 rs;                                             // statistics of the sampled row
   if constexpr (TAU) {
     __shared__ SmemTau smt;
     tau = find_tau_from_parts(a, b, c == 0, smt);
-    sm.rowstat = smt.rowstat;                            // every thread writes the same value
-    if (c == 0 && threadIdx.x == 0) a.seq_stat[b] = smt.rowstat;
+    rs = smt.rowstat;
+    if (c == 0 && threadIdx.x == 0) a.seq_stat[b] = rs;  // for the selection kernel
   } else {
     if (!a.resample_only) tau = a.accept_len[b];
   }
   const SampledRow r = sampled_row<DT, XF>(a, b, tau);
   if (r.none) return;
-
-  // the mass pass reads every chunk of the row exactly once: nontemporal loads.  They are in
-  // flight before anything waits for the statistics.
+  // left by accept_kernel: the same for every thread, read straight from the workspace (a scalar
+  // load that is in flight while the chunk's vector loads are issued)
+  if constexpr (!TAU) rs = sampled_row_stats(a, b, r, &sm.rowstat);
+  // the mass pass reads every chunk of the row exactly once: nontemporal loads
   constexpr int kA = AL ? kAlignedStream : kUnaligned;
   const int64_t base = int64_t(c) * kChunk2;
   RowRegs<DT, XF, kT> rt, rd;
   load_chunk<DT, XF, kA, kT>(rt, r.t_c, r.t_u, base, a.V, a.cfg_scale, a.inv_T, r.thr_t);
   if (!r.bonus) load_chunk<DT, XF, kA, kT>(rd, r.d_c, r.d_u, base, a.V, a.cfg_scale, a.inv_T, r.thr_d);
   else rd.clear();                                    // never read in mode P
-  float4 rs;
-  if constexpr (TAU) {
-    __syncthreads();                                     // sm.rowstat, written above
-    rs = sm.rowstat;
-  } else {
-    rs = sampled_row_stats(a, b, r, &sm.rowstat);
-  }
   const ResidCoef k{rs.x, 1.f / rs.y, rs.z, r.bonus ? 1.f : 1.f / rs.w, r.omega,
                     r.bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
   // Eq. g_lantern: this thread's part of the patch -- which of its tokens belong to the rejected

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 import torch
 
-from tests.parity_util import MASS_ABS, R_FLOOR, REL_TOL, U_TOL, compare_verify, compare_verify_lantern, to_numpy
+from tests.parity_util import MASS_ABS, R_FLOOR, REL_TOL, U_TOL, compare_verify, compare_verify_lantern, to_numpy, token_band
 from tests.test_gpu_diagnostics import _check as check_diagnostics, _oracle_diag, _verify_diag
 from workloads import make_neighbor_table, make_workload, uniforms24
 
@@ -56,7 +56,7 @@ def _check_resample(P, oracle, w, omega0, mode, case, exempt):
                 C = np.cumsum(g[b])
                 v = float(u[b]) * R[b]
                 gap = (v - C[tk[b]]) / R[b] if tk[b] < ot[b] else (C[tk[b] - 1] - v) / R[b]
-                assert 0 <= gap <= U_TOL, (b, tk[b], ot[b], gap)
+                assert 0 <= gap <= token_band(R[b]), (b, tk[b], ot[b], gap)
                 exempt.append(("token", case, b))
 
 

@@ -77,9 +77,10 @@ def parse():
 class Runner:
     """Pool of resident batches of one configuration plus everything a verify call needs."""
 
-    def __init__(self, pkg, torch, cfg, pool_mb, max_pool=64, flags=0, B=None):
+    def __init__(self, pkg, torch, cfg, pool_mb, max_pool=64, flags=0, B=None, V=None, top_k=None):
         from workloads import make_workload as mk
-        make_workload = (lambda c, **kw: mk(c, B=B, **kw)) if B else mk
+        over = {k: v for k, v in (("B", B), ("V", V), ("top_k", top_k)) if v}
+        make_workload = (lambda c, **kw: mk(c, **over, **kw)) if over else mk
         self.pkg, self.torch, self.cfg = pkg, torch, cfg
         w0 = make_workload(cfg, device="cuda", call=0)
         self.bytes_per_step = w0.algorithmic_bytes()
@@ -592,16 +593,19 @@ def main():
     if a.others:
         extra = {}
         # the fifth entry is configuration 4 with eight times the sequences: the regime (B well above
-        # the number of compute units) the early-exit form is meant for
-        for c, big in ((1, None), (3, None), (4, None), (5, None), (4, 2048)):
-            if c == cfg and not big:
+        # the number of compute units) the early-exit form is meant for; the last two are
+        # configurations 2 and 3 at the 65536-token vocabulary of the paper's larger target model
+        # (guided sampling there uses top-k 2000): rows of several chunks
+        for c, big, vocab, topk in ((1, None, None, None), (3, None, None, None), (4, None, None, None), (5, None, None, None),
+                                    (4, 2048, None, None), (2, None, 65536, None), (3, 32, 65536, 2000)):
+            if c == cfg and not big and not vocab:
                 continue
             rr = Runner(pkg, torch, c, 2400.0 if c >= 4 else 600.0, max_pool=(2 if big else 8) if c >= 4 else 64,
-                        flags=flags, B=big)
+                        flags=flags, B=big, V=vocab, top_k=topk)
             d2, w2, s2 = rr.time(max(64, 8 * len(rr.pool)), 2 * len(rr.pool), a.launch)
             k2, _, c2 = rr.kernel_times(40)
             p2, pl2 = rr.read_probe_time(40)
-            name = "cfg%d" % c + ("_B%d" % big if big else "")
+            name = "cfg%d" % c + ("_B%d" % big if big else "") + ("_V%d" % vocab if vocab else "") + ("_k%d" % topk if topk else "")
             extra[name] = {"tokens_per_s": d2 * rr.B * rr.L / w2, "us_per_step": s2 / d2 * 1e6,
                                   "whole_call_GBps": rr.bytes_per_step / (s2 / d2) / 1e9,
                                   "whole_call_frac": rr.bytes_per_step / (s2 / d2) / 1e9 / HBM_PEAK_GBS,

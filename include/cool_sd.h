@@ -228,9 +228,10 @@ int cool_sd_diagnostics(const cool_sd_params* p,
  * two calls, alpha_dev / beta_dev required.  For rows of at most 16384 logits without top-k every
  * logit is read ONCE for both (the workgroup that holds a row pair leaves its softmax statistics,
  * the logits of x~_i, alpha_i and beta_i; the per-sequence kernel follows), so that a caller who
- * tunes delta online against a total-variation budget pays no second pass; otherwise the two
- * calls run one after the other on the stream.  COOL_SD_FLAG_EARLY_EXIT is ignored (the
- * diagnostics need every row). */
+ * tunes delta online against a total-variation budget pays no second pass; otherwise the
+ * diagnostics pass follows the verify call's kernels on the stream and reuses the row statistics
+ * and top-k thresholds they left in the workspace (the logits are read twice, not three times).
+ * COOL_SD_FLAG_EARLY_EXIT is ignored (the diagnostics need every row). */
 int cool_sd_verify_diagnostics(const cool_sd_params* p,
                                const void* target_dev, const void* target_uncond_dev,
                                const void* draft_dev, const void* draft_uncond_dev,

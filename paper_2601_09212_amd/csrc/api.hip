@@ -104,7 +104,8 @@ int run(const cool_sd_params* p, bool resample_only,
         const void* t, const void* tu, const void* d, const void* du,
         const int32_t* tokens, const float* omega, const float* u_acc, const float* u_res,
         int32_t* accept_len, int32_t* next_token, float* p_tok, float* q_tok, float* f,
-        float* resid_mass, void* ws, size_t ws_bytes, void* stream, const LanternArgs* lan = nullptr) {
+        float* resid_mass, void* ws, size_t ws_bytes, void* stream, const LanternArgs* lan = nullptr,
+        float* alpha = nullptr, float* beta = nullptr) {
   const int64_t L = resample_only ? 1 : p->L;
   const int hb = resample_only ? 0 : p->has_bonus;
   const int64_t rows = resample_only ? p->B : int64_t(p->B) * (L + hb);
@@ -112,7 +113,9 @@ int run(const cool_sd_params* p, bool resample_only,
   const Chunking ch = pick_chunking(p, rows_t + rows_d);
   const int64_t C = ch.c2;
   const bool radix = p->top_k > 0 && p->V > 4 * csd::kChunk;
-  const Layout lay = make_layout(p->B, rows_t + rows_d, ch.c1, C, 0, 0, lan ? int64_t(p->B) * L : 0,
+  // with alpha / beta the diagnostics pass follows on the statistics this call leaves (8192-logit chunks)
+  const int64_t pairs = alpha ? int64_t(p->B) * L : 0, CD = alpha ? (int64_t(p->V) + 8191) / 8192 : 0;
+  const Layout lay = make_layout(p->B, rows_t + rows_d, ch.c1, C, pairs, CD, lan ? int64_t(p->B) * L : 0,
                                  radix ? rows_t + rows_d : 0);
   if (!ws || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0 || ws_bytes < lay.total) return COOL_SD_EWORKSPACE;
 
@@ -182,6 +185,14 @@ int run(const cool_sd_params* p, bool resample_only,
   const bool xf = (tu != nullptr) || (p->temperature != 1.0f) || (p->top_k > 0);
   hipError_t e = csd::launch_verify(a, p->dtype, xf, static_cast<hipStream_t>(stream), g_profile ? g_ev : nullptr);
   g_profile_valid = g_profile && e == hipSuccess;
+  if (e == hipSuccess && alpha && !g_stats_only) {
+    // Theorem 2's per-position terms from the statistics (and thresholds) the verify call has just
+    // left in the workspace: the logits are read once more, not twice
+    a.alpha = alpha; a.beta = beta;
+    a.diag_part = reinterpret_cast<float2*>(w + lay.diag_part);
+    a.nchunks = (int32_t)CD;
+    e = csd::launch_diagnostics(a, p->dtype, xf, /*local=*/false, static_cast<hipStream_t>(stream), /*have_stats=*/true);
+  }
   return e == hipSuccess ? COOL_SD_OK : COOL_SD_ELAUNCH;
 }
 
@@ -229,7 +240,7 @@ int run_diag(const cool_sd_params* p, const void* t, const void* tu, const void*
   a.cs = direct ? (int32_t)ch.c1 : 1;
 
   const bool xf = (tu != nullptr) || (p->temperature != 1.0f) || (p->top_k > 0);
-  hipError_t e = csd::launch_diagnostics(a, p->dtype, xf, local, static_cast<hipStream_t>(stream));
+  hipError_t e = csd::launch_diagnostics(a, p->dtype, xf, local, static_cast<hipStream_t>(stream), false);
   return e == hipSuccess ? COOL_SD_OK : COOL_SD_ELAUNCH;
 }
 
@@ -408,16 +419,14 @@ int cool_sd_verify_diagnostics(const cool_sd_params* p, const void* target_dev, 
     return run_verify_diag(p, target_dev, target_uncond_dev, draft_dev, draft_uncond_dev, draft_tokens_dev, omega_dev,
                            u_accept_dev, u_resample_dev, accept_len_dev, next_token_dev, p_tok_dev, q_tok_dev, f_dev,
                            resid_mass_dev, alpha_dev, beta_dev, workspace_dev, workspace_bytes, hip_stream);
-  // top-k or rows of several chunks: the two calls one after the other (the early-exit flag is not
-  // honoured here, the diagnostics need every row anyway)
+  // top-k or rows of several chunks: the verify call, then the diagnostics pass on the row
+  // statistics and thresholds it left (the early-exit flag is not honoured here, the diagnostics
+  // need every row anyway)
   cool_sd_params q = *p;
   q.flags = 0;
-  const int rc = run(&q, false, target_dev, target_uncond_dev, draft_dev, draft_uncond_dev, draft_tokens_dev, omega_dev,
-                     u_accept_dev, u_resample_dev, accept_len_dev, next_token_dev, p_tok_dev, q_tok_dev, f_dev,
-                     resid_mass_dev, workspace_dev, workspace_bytes, hip_stream);
-  if (rc != COOL_SD_OK) return rc;
-  return run_diag(&q, target_dev, target_uncond_dev, draft_dev, draft_uncond_dev, omega_dev, alpha_dev, beta_dev,
-                  workspace_dev, workspace_bytes, hip_stream);
+  return run(&q, false, target_dev, target_uncond_dev, draft_dev, draft_uncond_dev, draft_tokens_dev, omega_dev,
+             u_accept_dev, u_resample_dev, accept_len_dev, next_token_dev, p_tok_dev, q_tok_dev, f_dev,
+             resid_mass_dev, workspace_dev, workspace_bytes, hip_stream, nullptr, alpha_dev, beta_dev);
 }
 
 int cool_sd_profile_enable(int enable) {

@@ -70,8 +70,10 @@ struct KArgs {
 hipError_t launch_verify(const KArgs& a, int dtype, bool xf, hipStream_t stream, hipEvent_t* ev);
 
 // Enqueue the kernels of one diagnostics call (alpha_i, beta_i of every row pair).  local: rows
-// are one chunk and need no statistics pass.
-hipError_t launch_diagnostics(const KArgs& a, int dtype, bool xf, bool local, hipStream_t stream);
+// are one chunk and need no statistics pass.  have_stats (not with local): the workspace already
+// holds the rows' chunk statistics and thresholds, numbered as in a verify call with these
+// arguments, so the statistics pass is skipped.
+hipError_t launch_diagnostics(const KArgs& a, int dtype, bool xf, bool local, hipStream_t stream, bool have_stats);
 
 // Enqueue the kernels of one cool_sd_verify_diagnostics call on rows of one chunk without top-k
 // (every logit read once for both results).

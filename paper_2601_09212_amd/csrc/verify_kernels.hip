@@ -313,7 +313,7 @@ hipError_t launch_verify(const KArgs& a, int dtype, bool xf, hipStream_t stream,
 }
 
 template <int DT, bool XF, bool AL>
-static hipError_t launch_diag_typed(const KArgs& a, bool local, hipStream_t stream) {
+static hipError_t launch_diag_typed(const KArgs& a, bool local, hipStream_t stream, bool have_stats) {
   constexpr int kT = Vec<DT>::kT;
   constexpr int kA = AL ? kAligned : kUnaligned;
   (void)hipGetLastError();
@@ -322,9 +322,9 @@ static hipError_t launch_diag_typed(const KArgs& a, bool local, hipStream_t stre
     hipLaunchKernelGGL((diag_kernel<DT, XF, kA, kT / 2, true>), dim3((unsigned)pairs), dim3(512), 0, stream, a);
     return checked("diag_kernel (one chunk)");
   }
-  hipError_t e = launch_stats_any<DT, XF, AL>(a, stream);
+  hipError_t e = have_stats ? hipSuccess : launch_stats_any<DT, XF, AL>(a, stream);
   if (e != hipSuccess) return e;
-  if (a.cs != a.c1) {
+  if (a.cs != a.c1) {     // (after a verify call too: its kernels may have combined the rows in LDS only)
     const int64_t gridc = (int64_t(a.rows_t) + a.rows_d + kWaves - 1) / kWaves;
     hipLaunchKernelGGL(combine_rows_kernel, dim3((unsigned)gridc), dim3(kThreads), 0, stream, a);
     e = checked("combine_rows_kernel");
@@ -366,17 +366,17 @@ hipError_t launch_verify_diagnostics(const KArgs& a, int dtype, bool xf, hipStre
                    : launch_verify_diag_typed<kDtF32, false, false>(a, stream);
 }
 
-hipError_t launch_diagnostics(const KArgs& a, int dtype, bool xf, bool local, hipStream_t stream) {
+hipError_t launch_diagnostics(const KArgs& a, int dtype, bool xf, bool local, hipStream_t stream, bool have_stats) {
   if (dtype == kDtBF16) {
-    if (xf) return a.aligned ? launch_diag_typed<kDtBF16, true, true>(a, local, stream)
-                             : launch_diag_typed<kDtBF16, true, false>(a, local, stream);
-    return a.aligned ? launch_diag_typed<kDtBF16, false, true>(a, local, stream)
-                     : launch_diag_typed<kDtBF16, false, false>(a, local, stream);
+    if (xf) return a.aligned ? launch_diag_typed<kDtBF16, true, true>(a, local, stream, have_stats)
+                             : launch_diag_typed<kDtBF16, true, false>(a, local, stream, have_stats);
+    return a.aligned ? launch_diag_typed<kDtBF16, false, true>(a, local, stream, have_stats)
+                     : launch_diag_typed<kDtBF16, false, false>(a, local, stream, have_stats);
   }
-  if (xf) return a.aligned ? launch_diag_typed<kDtF32, true, true>(a, local, stream)
-                           : launch_diag_typed<kDtF32, true, false>(a, local, stream);
-  return a.aligned ? launch_diag_typed<kDtF32, false, true>(a, local, stream)
-                   : launch_diag_typed<kDtF32, false, false>(a, local, stream);
+  if (xf) return a.aligned ? launch_diag_typed<kDtF32, true, true>(a, local, stream, have_stats)
+                           : launch_diag_typed<kDtF32, true, false>(a, local, stream, have_stats);
+  return a.aligned ? launch_diag_typed<kDtF32, false, true>(a, local, stream, have_stats)
+                   : launch_diag_typed<kDtF32, false, false>(a, local, stream, have_stats);
 }
 
 // Streaming-read yardstick (cool_sd_profile_read_probe): workgroup g reads 512 consecutive

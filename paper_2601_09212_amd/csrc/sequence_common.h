@@ -1,6 +1,5 @@
 // Pieces shared by the per-sequence kernels: combining chunk statistics, the residual law
-// element by element, chunk masses and selection, the accept test (eval_position, find_tau) and
-// accept_kernel of the long-row form.
+// element by element, chunk masses and selection, the accept test (eval_position, find_tau).
 // Part of the one translation unit verify_kernels.hip (included there, inside namespace csd,
 // after device_utils.h, kernels.h and topk.h); not a stand-alone header.
 #pragma once
@@ -313,25 +312,3 @@ struct SmemW {
   float4 rowstat;
 };
 
-// Middle kernel of the several-chunk path: one workgroup per sequence finds tau and leaves
-// accept_len[b] and the sampled row's statistics for the sampling kernel.
-// Rows of many statistics chunks: combine the chunks of sequence b's rows, one wave per row (what
-// combine_rows_kernel does for all rows), for find_tau to read them back.  Sixteen waves, so that
-// a window of eight positions is one or two rows per wave: each row is a memory round trip of
-// its own.  All 1024 threads of the workgroup must call it.
-__device__ __forceinline__ void combine_sequence_rows(const KArgs& a, int b) {
-  const int rps = a.L + a.has_bonus;
-  for (int q = threadIdx.x >> 6; q < rps + a.L; q += kWavesW)
-    combine_row_wave(a, q < rps ? b * rps + q : a.rows_t + b * a.L + (q - rps));
-  __syncthreads();          // the rows' statistics are visible to the whole workgroup
-}
-
-template <int DT, bool XF>
-__global__ __launch_bounds__(kThreadsW) void accept_kernel(const KArgs a) {
-  __shared__ SmemW sm;
-  const int b = blockIdx.x;
-  if (a.accept_combines) combine_sequence_rows(a, b);
-  const int j = find_tau<DT, XF, kThreadsW>(a, b, true, sm.pick, &sm.rowstat);
-  if (threadIdx.x == 0) a.seq_stat[b] = sm.rowstat;
-  (void)j;
-}

@@ -85,8 +85,8 @@ __device__ __forceinline__ LanPatch lan_patch_span(const KArgs& a, int b, int j,
 // tau of sequence b found by a 256-thread workgroup from the chunk statistics of the sequence's
 // rows (at most 64 chunks per row, at most kTauRows positions, the bonus row included), so that
 // the chunk-mass launch needs no accept_kernel before it: every workgroup of a sequence finds the
-// same tau for itself (same code, same inputs), the one with emit = true writes accept_len, the
-// per-position outputs and the sampled row's statistics for the selection kernel.
+// same tau for itself (same code, same inputs), the one with emit = true writes accept_len and
+// the per-position outputs.
 //   wave w combines rows w, w+4, ... -- lane c takes chunk c, eight rows' loads in flight, then a
 //   wave maximum and a wave sum per row -- into LDS; one barrier; lane i of wave 0 runs the accept
 //   test of position i (its other inputs were requested at the very start); ballot; one barrier.
@@ -148,6 +148,30 @@ __device__ __forceinline__ int find_tau_from_parts(const KArgs& a, int b, bool e
   }
   __syncthreads();
   return sm.tau;
+}
+
+// Rows of many statistics chunks, on the path that reads combined row statistics back from the
+// workspace: combine the chunks of sequence b's rows, one wave per row (what combine_rows_kernel
+// does for all rows).  All 1024 threads of the workgroup must call it.
+__device__ __forceinline__ void combine_sequence_rows(const KArgs& a, int b) {
+  const int rps = a.L + a.has_bonus;
+  for (int q = threadIdx.x >> 6; q < rps + a.L; q += kWavesW)
+    combine_row_wave(a, q < rps ? b * rps + q : a.rows_t + b * a.L + (q - rps));
+  __syncthreads();          // the rows' statistics are visible to the whole workgroup
+}
+
+// Middle kernel of the several-chunk path when the chunk-mass grid is large: one workgroup per
+// sequence finds tau and leaves accept_len[b] and the sampled row's statistics for the kernels
+// that follow.
+template <int DT, bool XF>
+__global__ __launch_bounds__(kThreadsW) void accept_kernel(const KArgs a) {
+  // (find_tau_from_parts with sixteen waves was measured here too: 5.3 us against 4.8 us on
+  // configuration 5 -- with one or two rows per wave its batches of eight are mostly padding)
+  __shared__ SmemW sm;
+  const int b = blockIdx.x;
+  if (a.accept_combines) combine_sequence_rows(a, b);
+  find_tau<DT, XF, kThreadsW>(a, b, true, sm.pick, &sm.rowstat);
+  if (threadIdx.x == 0) a.seq_stat[b] = sm.rowstat;
 }
 
 // TAU: the workgroup finds tau itself (find_tau_from_parts) instead of reading what accept_kernel left.

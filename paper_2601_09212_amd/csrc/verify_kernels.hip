@@ -67,10 +67,10 @@ __device__ __forceinline__ const char* row_ptr(const void* base, int64_t elem_of
 // what earlier ones define):
 #include "stats_kernels.h"          // row_stats_kernel, lantern_agg_position
 #include "topk_kernels.h"           // row_stats_topk_kernel, resample_topk_kernel, topk_radix_*
-#include "sequence_common.h"        // combine_rows_kernel, residual law, eval_position, find_tau, accept_kernel
+#include "sequence_common.h"        // combine_rows_kernel, residual law, eval_position, find_tau
 #include "sequence_whole.h"         // sequence_whole_kernel, lantern_agg_kernel
 #include "early_exit_kernels.h"     // sequence_early_exit_*kernel, resample_whole_kernel
-#include "sequence_long.h"          // sequence_masses_kernel, sequence_select_kernel
+#include "sequence_long.h"          // accept_kernel, sequence_masses_kernel, sequence_select_kernel
 #include "diagnostics_kernels.h"    // diag_kernel, diag_combine_kernel
 
 // ============================================================================ host side: launches

@@ -48,6 +48,10 @@ CASES = [
     (5, 3, 3, 40000, "bf16", 0),
     (5, 2, 2, 262144, "bf16", 0),
     (3, 2, 3, 40000, "bf16", 500),
+    (5, 3, 3, 32768, "bf16", 0),          # several chunks, per-sequence step in one workgroup
+    (1, 2, 3, 20004, "f32", 0),
+    (3, 2, 3, 24584, "bf16", 300),        # top-k with 32 logits per thread of 1024
+    (5, 2, 60, 32776, "bf16", 0),         # long window on long rows: tau found by the chunk-mass launch
     (4, 7, 70, 1024, "bf16", 0),          # more positions than one wave
 ]
 

@@ -44,8 +44,8 @@ def _check_resample(P, oracle, w, omega0, mode, case, exempt):
         tk, ms = tok.cpu().numpy(), mass.cpu().numpy().astype(np.float64)
         for b in range(B):
             assert 0 <= tk[b] < V
-            # R == 1 exactly: the law is p, or the oracle's fall-back where the law had no mass
-            unresolved = R[b] < R_FLOOR or (R[b] == 1.0 and ms[b] <= MASS_ABS)
+            # R == 1 (the sum of p in fp64): the law is p, or the oracle's fall-back where the law had no mass
+            unresolved = R[b] < R_FLOOR or (abs(R[b] - 1.0) <= 1e-12 and ms[b] <= MASS_ABS)
             if unresolved:
                 assert 0 <= ms[b] <= MASS_ABS or abs(ms[b] - 1.0) <= REL_TOL
                 exempt.append(("mass", case, b))

@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=3000)
     ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--vocab", type=int, default=0, help="the workload's recipe at another vocabulary size (e.g. 65536)")
+    ap.add_argument("--batch", type=int, default=0, help="the workload's recipe with another number of sequences")
+    ap.add_argument("--top-k", type=int, default=0, help="the workload's recipe with this top-k (guided recipe: cfg3)")
     ap.add_argument("--launch", default="graph", choices=["graph", "direct"])
     ap.add_argument("--pool-mb", type=float, default=600.0, help="distinct input batches cycled, total size")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="time budget of the CPU oracle sample")
@@ -528,7 +531,8 @@ def main():
 
     cfg = int(a.workload[3:])
     flags = pkg.COOL_SD_FLAG_EARLY_EXIT if a.early_exit else 0
-    r = Runner(pkg, torch, cfg, a.pool_mb, flags=flags)
+    r = Runner(pkg, torch, cfg, a.pool_mb, flags=flags, B=a.batch or None, V=a.vocab or None, top_k=a.top_k or None)
+    variant = bool(a.batch or a.vocab or a.top_k)      # not the configuration itself: its recipe at another size
     if a.counter_run:
         # reference for the byte counters: an elementwise kernel (dst = src * 1) that moves exactly
         # 2^30 B in and 2^30 B out
@@ -573,12 +577,14 @@ def main():
         "ms_per_step": wall / done * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "config 2: B=32, L=8, V=16384, %s logits, exp schedule delta=1.1 nu=0.7" % dtype
-                   if cfg == 2 else "config %d: B=%d, L=%d, V=%d, %s logits" % (cfg, r.B, r.L, r.V, dtype),
+                   if cfg == 2 and not variant else "config %d%s: B=%d, L=%d, V=%d, %s logits%s" % (
+                       cfg, "'s recipe" if variant else "", r.B, r.L, r.V, dtype,
+                       ", top-k %d" % r.pool[0].top_k if r.pool[0].top_k else ""),
                    "input_dtype": dtype, "launch": a.launch, "early_exit": bool(a.early_exit), "pool_batches": len(r.pool),
                    "pool_mb": len(r.pool) * r.bytes_per_step / 1e6, "bytes_per_step": r.bytes_per_step},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": (MEASURED_TRAFFIC_EARLY if a.early_exit else MEASURED_TRAFFIC_BYTES).get(a.workload),
+                     "traffic": None if variant else (MEASURED_TRAFFIC_EARLY if a.early_exit else MEASURED_TRAFFIC_BYTES).get(a.workload),
                      "kernel": kernel_name, "algorithmic_bytes_per_launch": kernel_bytes,
                      "us_per_launch": kern_s * 1e6,
                      "us_per_launch_lone_events": kern_ev_s * 1e6,
@@ -598,7 +604,7 @@ def main():
         # (guided sampling there uses top-k 2000): rows of several chunks
         for c, big, vocab, topk in ((1, None, None, None), (3, None, None, None), (4, None, None, None), (5, None, None, None),
                                     (4, 2048, None, None), (2, None, 65536, None), (3, 32, 65536, 2000)):
-            if c == cfg and not big and not vocab:
+            if c == cfg and not big and not vocab and not variant:
                 continue
             rr = Runner(pkg, torch, c, 2400.0 if c >= 4 else 600.0, max_pool=(2 if big else 8) if c >= 4 else 64,
                         flags=flags, B=big, V=vocab, top_k=topk)

@@ -1,11 +1,13 @@
-// Second step of a verify call on rows longer than 16384 logits (chunk masses, then selection).
+// Per-sequence step of a verify call on rows longer than 32768 logits (tau, chunk masses, selection).
 // Part of the one translation unit verify_kernels.hip (included there, inside namespace csd,
 // after device_utils.h, kernels.h and topk.h); not a stand-alone header.
 #pragma once
 
 // ============================================================================ kernel 2, long rows
-// Rows too long for one workgroup's registers: the draw x_{tau+1} from the resampling law of the
-// sampled row (Eq. opt_G / Eq. g_tsd / p_{L+1}) in two launches after accept_kernel.
+// Rows too long for one workgroup's registers: tau, then the draw x_{tau+1} from the resampling law
+// of the sampled row (Eq. opt_G / Eq. g_tsd / p_{L+1}), cut at kernel boundaries.
+//   accept_kernel           grid = B, 1024 threads.  tau of every sequence; only launched when the
+//                           next kernel's grid is too large to find tau itself.
 //   sequence_masses_kernel  grid = B x C, 256 threads.  Rows of C chunks of 8192 logits:
 //                           workgroup (b, c) writes the mass of chunk c (the bandwidth part: the
 //                           row pair is streamed once).

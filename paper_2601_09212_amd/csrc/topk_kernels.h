@@ -84,10 +84,12 @@ __global__ __launch_bounds__(TPB, ROW == kChunk ? 6 : 4) void row_stats_topk_ker
 // the tile -> thread -> element search (tile k of the row is the TPB*kE consecutive logits from
 // k*TPB*kE on; thread t owns vector t of each tile), each level "first positive-mass entry whose
 // inclusive sum exceeds the remainder, else the last positive-mass entry".
-template <int DT, int AL, int GD>
-__global__ __launch_bounds__(kThreadsK) void resample_topk_kernel(const KArgs a) {
-  constexpr int TPB = kThreadsK, kE = Vec<DT>::kE, kES = Vec<DT>::kES;
-  constexpr int kVW = kChunk / (TPB * kE);             // tiles: 4 (bf16) / 8 (fp32)
+// (TPB, ROW) = (512, 16384), or 1024 threads for rows of up to 32768 / 65536 logits, as in
+// row_stats_topk_kernel.
+template <int DT, int AL, int GD, int TPB = kThreadsK, int ROW = kChunk>
+__global__ __launch_bounds__(TPB) void resample_topk_kernel(const KArgs a) {
+  constexpr int kE = Vec<DT>::kE, kES = Vec<DT>::kES;
+  constexpr int kVW = ROW / (TPB * kE);                // tiles: 4 (bf16) / 8 (fp32) on rows of 16384 logits
   constexpr int kW = TPB / 64;
   static_assert(kVW <= 8, "tile_part holds up to 8 tiles");
   __shared__ TopkSmem<TPB> ts;

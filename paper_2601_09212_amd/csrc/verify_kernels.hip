@@ -215,12 +215,24 @@ static hipError_t launch_typed(const KArgs& a, hipStream_t stream, hipEvent_t* e
     return ee;
   }
   if constexpr (XF) {
-    if (a.resample_only && a.top_k > 0 && a.d == nullptr && a.V <= kChunk && !a.stats_only) {
-      // the drafting stage's draw under truncation: one launch
+    // the drafting stage's draw under truncation: one launch while one workgroup can hold the row
+    // (65536 logits of bf16, 32768 of fp32: 64 fp32 words per thread)
+    constexpr int kRowOne = DT == kDtBF16 ? 4 * kChunk : 2 * kChunk;
+    if (a.resample_only && a.top_k > 0 && a.d == nullptr && a.V <= kRowOne && !a.stats_only) {
       constexpr int kA = AL ? kAligned : kUnaligned;
+      const dim3 gB((unsigned)a.B);
+      const bool guided = a.tu != nullptr;
       if (ev) (void)hipEventRecord(ev[1], stream);
-      if (a.tu != nullptr) hipLaunchKernelGGL((resample_topk_kernel<DT, kA, 1>), dim3((unsigned)a.B), dim3(kThreadsK), 0, stream, a);
-      else hipLaunchKernelGGL((resample_topk_kernel<DT, kA, 0>), dim3((unsigned)a.B), dim3(kThreadsK), 0, stream, a);
+      if (a.V <= kChunk) {
+        if (guided) hipLaunchKernelGGL((resample_topk_kernel<DT, kA, 1>), gB, dim3(kThreadsK), 0, stream, a);
+        else hipLaunchKernelGGL((resample_topk_kernel<DT, kA, 0>), gB, dim3(kThreadsK), 0, stream, a);
+      } else if (a.V <= 2 * kChunk) {
+        if (guided) hipLaunchKernelGGL((resample_topk_kernel<DT, kA, 1, kThreadsW, 2 * kChunk>), gB, dim3(kThreadsW), 0, stream, a);
+        else hipLaunchKernelGGL((resample_topk_kernel<DT, kA, 0, kThreadsW, 2 * kChunk>), gB, dim3(kThreadsW), 0, stream, a);
+      } else {
+        if (guided) hipLaunchKernelGGL((resample_topk_kernel<DT, kA, 1, kThreadsW, kRowOne>), gB, dim3(kThreadsW), 0, stream, a);
+        else hipLaunchKernelGGL((resample_topk_kernel<DT, kA, 0, kThreadsW, kRowOne>), gB, dim3(kThreadsW), 0, stream, a);
+      }
       hipError_t er = checked("resample_topk_kernel");
       if (ev) (void)hipEventRecord(ev[2], stream);
       return er;

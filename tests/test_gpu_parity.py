@@ -488,7 +488,13 @@ def test_long_draft_windows_and_tiny_shapes(P, oracle):
     (16384, "bf16", False, 16384, 1.0),     # k = V: nothing is cut
     (8, "f32", False, 1, 1.0),              # k = 1: the arg max
     (16384, "bf16", False, 0, 1.0),         # no truncation: the plain one-launch draw
-    (40000, "bf16", True, 300, 1.0),        # rows of several chunks: statistics pass + sampling kernels
+    (40000, "bf16", True, 300, 1.0),        # rows of several chunks, truncated: still one workgroup of 1024 threads
+    (65536, "bf16", True, 2000, 1.0),       # the larger model's vocabulary and truncation
+    (24584, "bf16", False, 50, 0.8),        # the 32-logits-per-thread form, ragged tail
+    (20004, "f32", True, 7, 1.0),
+    (33000, "f32", False, 400, 1.0),        # fp32 beyond 32768: statistics pass + sampling kernels
+    (40000, "bf16", False, 0, 1.0),         # no truncation on rows of several chunks: statistics pass + sampling kernels
+    (70000, "bf16", True, 500, 1.0),        # beyond one workgroup: radix passes
 ])
 def test_draft_side_sampling_through_resample(P, oracle, V, dtype, guided, top_k, temperature):
     """Drawing x~ ~ Q (Algorithm 1, drafting stage) is cool_sd_resample with the draft's logits as the

@@ -49,10 +49,24 @@ __device__ __forceinline__ SampledRow sampled_row(const KArgs& a, int b, int tau
 }
 
 // Statistics (Ct, St, Cd, Sd) of the sampled row: left by accept_kernel, or, for the stand-alone
-// resampling call, combined here by one thread.  All threads must call it.
+// resampling call, combined here -- by the first wave straight from the chunk statistics (lane c
+// takes chunk c) when a row has at most 64 of them, else by one thread from the combined row
+// statistics that combine_rows_kernel left.  All threads must call it.
 __device__ __forceinline__ float4 sampled_row_stats(const KArgs& a, int b, const SampledRow& r, float4* slot) {
   if (!a.resample_only) return a.seq_stat[b];
-  if (threadIdx.x == 0) {
+  if (a.c1 <= 64) {
+    if (threadIdx.x < 64) {
+      const int lane = threadIdx.x, cl = lane < a.c1 ? lane : 0;
+      const float2 vt = a.part[int64_t(r.rt_) * a.c1 + cl];
+      const float2 vd = a.part[int64_t(r.bonus ? r.rt_ : r.rd_) * a.c1 + cl];     // a bonus row has no draft: read and dropped
+      const bool in = lane < a.c1;
+      const float ct = in ? vt.x : kRefFloor, cd = (in && !r.bonus) ? vd.x : kRefFloor;
+      const float Ct = wave_max(ct), Cd = wave_max(cd);
+      const float St = wave_sum((in ? vt.y : 0.f) * exp2_fast(ct - Ct));
+      const float Sd = wave_sum(((in && !r.bonus) ? vd.y : 0.f) * exp2_fast(cd - Cd));
+      if (lane == 0) *slot = make_float4(Ct, St, Cd, Sd);
+    }
+  } else if (threadIdx.x == 0) {
     float Ct, St, Cd = kRefFloor, Sd = 0.f;
     combine_row(a, r.rt_, Ct, St);
     if (!r.bonus) combine_row(a, r.rd_, Cd, Sd);

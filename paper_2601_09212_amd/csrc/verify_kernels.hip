@@ -264,7 +264,9 @@ static hipError_t launch_rest(const KArgs& a, hipStream_t stream) {
   // 4096 workgroups: 208.5 us with accept_kernel, 212.3 us without)
   const bool fuse_tau = !a.resample_only && a.nt2 != kT && a.c1 <= 64 && a.L + a.has_bonus <= kTauRows &&
                         int64_t(a.B) * a.nchunks <= 2048;
-  if (a.cs != a.c1 && !a.accept_combines && !fuse_tau) {   // rows have many statistics chunks: pre-combine them, one wave per row
+  // the long-row kernels of the stand-alone resampling call combine up to 64 chunk statistics themselves
+  const bool resample_combines = a.resample_only && a.nt2 != kT && a.c1 <= 64;
+  if (a.cs != a.c1 && !a.accept_combines && !fuse_tau && !resample_combines) {   // rows have many statistics chunks: pre-combine them, one wave per row
     const int64_t gridc = (int64_t(a.rows_t) + a.rows_d + kWaves - 1) / kWaves;
     hipLaunchKernelGGL(combine_rows_kernel, dim3((unsigned)gridc), dim3(kThreads), 0, stream, a);
     e = checked("combine_rows_kernel");

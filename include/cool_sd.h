@@ -194,9 +194,9 @@ int cool_sd_verify_lantern(const cool_sd_params* p,
  * temperature and top-k apply as configured).
  *   token_dev out int32 [B], resid_mass_dev out float [B] (optional; the mass of the law that
  *   was sampled: R of Eq. opt_G / Eq. g_tsd, 1 when the law is p itself).
- * Rows of at most 16384 logits are served by a single kernel launch (except truncated rows with
- * a draft), so a call per drafted token costs one launch latency; so are draft-less truncated rows
- * of up to 65536 logits (bf16) or 32768 (fp32). */
+ * Rows of at most 16384 logits (32768 when 16-byte aligned) are served by a single kernel launch
+ * (except truncated rows with a draft), so a call per drafted token costs one launch latency; so
+ * are draft-less truncated rows of up to 65536 logits (bf16) or 32768 (fp32). */
 int cool_sd_resample(const cool_sd_params* p,
                      const void* target_rows_dev, const void* target_uncond_rows_dev,
                      const void* draft_rows_dev, const void* draft_uncond_rows_dev,

@@ -193,10 +193,11 @@ __global__ __launch_bounds__(kThreadsW) void sequence_early_exit_kernel(const KA
 // 1024 threads holds the row pair (or the single row when no draft is given), forms its softmax
 // statistics block-wide and draws the token from the registers.  The drafting loop calls this once
 // per drafted token, so its latency (one launch instead of two) is what matters.
-template <int DT, bool XF, bool AL>
+// MUL = 2: rows of up to 32768 logits (32 words per row and thread), as in sequence_whole_kernel.
+template <int DT, bool XF, bool AL, int MUL = 1>
 __global__ __launch_bounds__(kThreadsW) void resample_whole_kernel(const KArgs a) {
   constexpr int kE = Vec<DT>::kE, kES = Vec<DT>::kES;
-  constexpr int kVW = kChunk / (kThreadsW * kE);
+  constexpr int kVW = MUL * kChunk / (kThreadsW * kE);
   __shared__ SmemW sm;
   __shared__ RedW red;
   const int b = blockIdx.x;

@@ -238,9 +238,14 @@ static hipError_t launch_typed(const KArgs& a, hipStream_t stream, hipEvent_t* e
       return er;
     }
   }
-  if (a.resample_only && a.top_k == 0 && a.V <= kChunk && !a.stats_only) {   // short rows: one launch
+  // rows that one workgroup holds in registers (16384 logits; 32768 when aligned): one launch
+  const int row_one = AL ? 2 * kChunk : kChunk;
+  if (a.resample_only && a.top_k == 0 && a.V <= row_one && !a.stats_only) {
     if (ev) (void)hipEventRecord(ev[1], stream);
-    hipLaunchKernelGGL((resample_whole_kernel<DT, XF, AL>), dim3((unsigned)a.B), dim3(kThreadsW), 0, stream, a);
+    if (a.V <= kChunk) hipLaunchKernelGGL((resample_whole_kernel<DT, XF, AL>), dim3((unsigned)a.B), dim3(kThreadsW), 0, stream, a);
+    if constexpr (AL) {
+      if (a.V > kChunk) hipLaunchKernelGGL((resample_whole_kernel<DT, XF, true, 2>), dim3((unsigned)a.B), dim3(kThreadsW), 0, stream, a);
+    }
     hipError_t er = checked("resample_whole_kernel");
     if (ev) (void)hipEventRecord(ev[2], stream);
     return er;

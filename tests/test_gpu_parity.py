@@ -493,7 +493,9 @@ def test_long_draft_windows_and_tiny_shapes(P, oracle):
     (24584, "bf16", False, 50, 0.8),        # the 32-logits-per-thread form, ragged tail
     (20004, "f32", True, 7, 1.0),
     (33000, "f32", False, 400, 1.0),        # fp32 beyond 32768: statistics pass + sampling kernels
-    (40000, "bf16", False, 0, 1.0),         # no truncation on rows of several chunks: statistics pass + sampling kernels
+    (32768, "bf16", False, 0, 1.0),         # no truncation, up to 32768 logits: still one launch
+    (24584, "f32", True, 0, 0.9),
+    (40000, "bf16", False, 0, 1.0),         # no truncation on longer rows: statistics pass + sampling kernels
     (70000, "bf16", True, 500, 1.0),        # beyond one workgroup: radix passes
 ])
 def test_draft_side_sampling_through_resample(P, oracle, V, dtype, guided, top_k, temperature):

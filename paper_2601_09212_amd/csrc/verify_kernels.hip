@@ -349,8 +349,13 @@ static hipError_t launch_diag_typed(const KArgs& a, bool local, hipStream_t stre
     e = checked("combine_rows_kernel");
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((diag_kernel<DT, XF, kA, kT / 2, false>), dim3((unsigned)(pairs * a.nchunks)), dim3(kThreads), 0,
-                     stream, a);
+  // this pass is the last reader of the logits: beyond what the caches hold, nontemporal loads
+  const double bytes = double(pairs) * 2.0 * a.V * Vec<DT>::kES * (a.tu ? 2 : 1);
+  const dim3 gridd((unsigned)(pairs * a.nchunks));
+  if (AL && bytes > 128e6)
+    hipLaunchKernelGGL((diag_kernel<DT, XF, AL ? kAlignedStream : kUnaligned, kT / 2, false>), gridd, dim3(kThreads), 0, stream, a);
+  else
+    hipLaunchKernelGGL((diag_kernel<DT, XF, kA, kT / 2, false>), gridd, dim3(kThreads), 0, stream, a);
   e = checked("diag_kernel");
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(diag_combine_kernel, dim3((unsigned)((pairs + kThreads - 1) / kThreads)), dim3(kThreads), 0,

@@ -258,17 +258,21 @@ static hipError_t launch_typed(const KArgs& a, hipStream_t stream, hipEvent_t* e
   return e;
 }
 
+// Long rows: the chunk-mass launch finds tau itself when a row's chunk statistics fit one wave and
+// the positions another (rows of up to 524288 logits, draft windows of up to 63 tokens), and all
+// its workgroups are resident at once -- the search is then latency paid once instead of a
+// launch; in a larger grid it would repeat with every round of workgroups (configuration 5,
+// 4096 workgroups: 208.5 us with accept_kernel, 212.3 us without).
+template <int DT> static bool tau_in_mass_launch(const KArgs& a) {
+  return !a.resample_only && a.nt2 != Vec<DT>::kT && a.c1 <= 64 && a.L + a.has_bonus <= kTauRows &&
+         int64_t(a.B) * a.nchunks <= 2048;
+}
+
 template <int DT, bool XF, bool AL>
 static hipError_t launch_rest(const KArgs& a, hipStream_t stream) {
   constexpr int kT = Vec<DT>::kT;
   hipError_t e;
-  // long rows: the chunk-mass launch finds tau itself when a row's chunk statistics fit one wave and
-  // the positions another (rows of up to 524288 logits, draft windows of up to 63 tokens), and all
-  // its workgroups are resident at once -- the search is then latency paid once instead of a
-  // launch; in a larger grid it would repeat with every round of workgroups (configuration 5,
-  // 4096 workgroups: 208.5 us with accept_kernel, 212.3 us without)
-  const bool fuse_tau = !a.resample_only && a.nt2 != kT && a.c1 <= 64 && a.L + a.has_bonus <= kTauRows &&
-                        int64_t(a.B) * a.nchunks <= 2048;
+  const bool fuse_tau = tau_in_mass_launch<DT>(a);
   // the long-row kernels of the stand-alone resampling call combine up to 64 chunk statistics themselves
   const bool resample_combines = a.resample_only && a.nt2 != kT && a.c1 <= 64;
   if (a.cs != a.c1 && !a.accept_combines && !fuse_tau && !resample_combines) {   // rows have many statistics chunks: pre-combine them, one wave per row
@@ -343,7 +347,10 @@ static hipError_t launch_diag_typed(const KArgs& a, bool local, hipStream_t stre
   }
   hipError_t e = have_stats ? hipSuccess : launch_stats_any<DT, XF, AL>(a, stream);
   if (e != hipSuccess) return e;
-  if (a.cs != a.c1) {     // (after a verify call too: its kernels may have combined the rows in LDS only)
+  // after a verify call accept_kernel has left the combined rows, unless tau was found by the
+  // chunk-mass launch (which combines in LDS only)
+  const bool have_rows = have_stats && a.accept_combines && !tau_in_mass_launch<DT>(a);
+  if (a.cs != a.c1 && !have_rows) {
     const int64_t gridc = (int64_t(a.rows_t) + a.rows_d + kWaves - 1) / kWaves;
     hipLaunchKernelGGL(combine_rows_kernel, dim3((unsigned)gridc), dim3(kThreads), 0, stream, a);
     e = checked("combine_rows_kernel");

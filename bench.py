@@ -3,21 +3,24 @@
 
 A step is one cool_sd_verify call (softmax statistics of every target and draft row, relaxed
 accept test, first rejection, one draw from the optimal resampling law) on one batch of
-synthetic input that is already resident in HBM.  The workload is configuration 2 of the
-benchmark list (B=32, L=8, V=16384, bf16); steps cycle through a pool of distinct batches
-larger than the 256 MB last-level cache, and are replayed from a HIP graph so that the
-host's launch cost does not hide the device time.
+synthetic input that is already resident in HBM.  The workload is configuration 5 of the
+benchmark list, the largest one (B=128, L=8, V=262144, bf16: 1.14 GB of logits per call); steps
+cycle through a pool of distinct batches and are replayed from a HIP graph so that the host's
+launch cost does not hide the device time.
 
 Prints ONE JSON line: verified draft tokens per second, with
   roofline      HBM, for the dominant kernel (row_stats_kernel, the pass that reads every logit):
-                algorithmic bytes of one launch / its average duration, from HIP events that the
-                library records around that kernel on the launch stream (cool_sd_profile_*),
-                over the same batches right after the timed region
+                algorithmic bytes of one launch / its average duration, measured live with events
+                on the launch stream around graph replays of that kernel alone
+                (cool_sd_bench_row_stats of the benchmark library), over the same batches right
+                after the timed region; `whole_call_frac` is the same ratio for the whole step;
+                `traffic` is read from the rocprofv3 counter summary under profiles/
   cpu_baseline  the fp64 CPU oracle timed on a bounded sample of the same batches.
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -26,30 +29,42 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/),
-# scaled by the same counters' reading on a plain copy kernel; None = not measured.
-# Fetched + written bytes of row_stats_kernel per launch.
-MEASURED_TRAFFIC_BYTES = {"cfg1": None, "cfg2": 17.96e6, "cfg3": 71.72e6, "cfg4": 277.75e6, "cfg5": 1143.20e6}
-# the same for sequence_early_exit_kernel (--early-exit)
-MEASURED_TRAFFIC_EARLY = {"cfg2": 8.11e6, "cfg4": 51.46e6}
+
+
+def measured_traffic(workload, early_exit=False):
+    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summary of
+    this workload (profiles/verify_<workload>_rocprofv3.md, written by
+    paper_2601_09212_amd/profile_summary.py from FETCH_SIZE / WRITE_SIZE runs): the line
+    `traffic_bytes_per_launch: <kernel> <bytes>`.  None when no summary holds one."""
+    name = "verify_early_exit_%s_rocprofv3.md" % workload if early_exit else "verify_%s_rocprofv3.md" % workload
+    try:
+        text = open(os.path.join(ROOT, "profiles", name)).read()
+    except OSError:
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*(\S+)\s+([0-9.eE+]+)\s*$", text, flags=re.M)
+    return float(m.group(2)) if m else None
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3000)
-    ap.add_argument("--warmup", type=int, default=300)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--steps", type=int, default=600)
+    ap.add_argument("--warmup", type=int, default=60)
+    ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--vocab", type=int, default=0, help="the workload's recipe at another vocabulary size (e.g. 65536)")
     ap.add_argument("--batch", type=int, default=0, help="the workload's recipe with another number of sequences")
     ap.add_argument("--top-k", type=int, default=0, help="the workload's recipe with this top-k (guided recipe: cfg3)")
     ap.add_argument("--launch", default="graph", choices=["graph", "direct"])
-    ap.add_argument("--pool-mb", type=float, default=600.0, help="distinct input batches cycled, total size")
+    ap.add_argument("--pool-mb", type=float, default=0.0,
+                    help="distinct input batches cycled, total size (default: 3400 for configurations 4-5, else 600)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="time budget of the CPU oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--others", action="store_true", default=True,
-                    help="also time configurations 1, 3, 4, 5 and configuration 4's recipe at B = 2048 (extra key "
-                         "`other_workloads`; on by default, a few seconds)")
+                    help="also time the other four configurations (extra key `other_workloads`; on by default, a "
+                         "few seconds)")
+    ap.add_argument("--variants", action="store_true",
+                    help="with --others: also configuration 4's recipe at B = 2048 and the recipes of configurations "
+                         "2 and 3 at a 65536-token vocabulary")
     ap.add_argument("--no-others", dest="others", action="store_false", help="time the named workload only")
     ap.add_argument("--early-exit", action="store_true",
                     help="time the early-exit form (COOL_SD_FLAG_EARLY_EXIT) instead of the all-rows form; the "
@@ -212,19 +227,11 @@ class Runner:
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e-3 / (passes * len(self.pool))
 
-    def read_probe_time(self, n):
-        """Yardstick for the statistics kernel: a plain streaming read of the same logit tensors in one
-        launch of the same shape (cool_sd_profile_read_probe), replayed back to back from a graph
-        exactly as kernel_times() replays the statistics kernel.  Guided workloads need two launches
-        (conditional pair, unconditional pair).  Returns seconds per step and launches per step."""
-        pkg, torch = self.pkg, self.torch
-        out = torch.empty(self.bytes_per_step // 8192 + 64, dtype=torch.int32, device="cuda")
-
-        def issue():
-            for w in self.pool:
-                pkg.cool_sd_profile_read_probe(w.target, w.draft, out)
-                if w.target_uncond is not None:
-                    pkg.cool_sd_profile_read_probe(w.target_uncond, w.draft_uncond, out)
+    def _replay_time(self, issue, n):
+        """Seconds per pool batch of `issue` (one pass over the pool), replayed from a HIP graph and
+        bracketed by events on the launch stream (torch's current stream, the one the binding
+        hands to the library)."""
+        torch = self.torch
         issue()
         torch.cuda.synchronize()
         g = torch.cuda.CUDAGraph()
@@ -239,55 +246,52 @@ class Runner:
             g.replay()
         e1.record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e-3 / (reps * len(self.pool)), 2 if self.pool[0].target_uncond is not None else 1
+        return e0.elapsed_time(e1) * 1e-3 / (reps * len(self.pool))
 
-    def kernel_times(self, n):
-        """Average duration of the statistics kernel and of the whole call, over the pool.
-
-        Statistics kernel: the library is switched to launch that kernel alone, one graph holds one such
-        launch per pool batch, and HIP events on the launch stream bracket replays of it: back-to-back
-        launches, so the figure is the kernel's duration plus the gap between two launches.
-        Whole call (and the statistics kernel once more, `events`): HIP events that the library records
-        around one direct call on the launch stream; these include the dispatch latency of a lone launch."""
+    def read_probe_time(self, n):
+        """Yardstick for the statistics kernel: a plain streaming read of the same logit tensors in one
+        launch of the same shape (cool_sd_bench_read_probe), replayed back to back from a graph
+        exactly as kernel_time() replays the statistics kernel.  Guided workloads need two launches
+        (conditional pair, unconditional pair).  Returns seconds per step and launches per step."""
         pkg, torch = self.pkg, self.torch
+        out = torch.empty(self.bytes_per_step // 8192 + 64, dtype=torch.int32, device="cuda")
+
+        def issue():
+            for w in self.pool:
+                pkg.cool_sd_bench_read_probe(w.target, w.draft, out)
+                if w.target_uncond is not None:
+                    pkg.cool_sd_bench_read_probe(w.target_uncond, w.draft_uncond, out)
+        return self._replay_time(issue, n), 2 if self.pool[0].target_uncond is not None else 1
+
+    def kernel_time(self, n):
+        """Average duration of the statistics kernel over the pool: the benchmark library launches that
+        kernel alone (cool_sd_bench_row_stats: same grid, chunking and loads as in the verify call),
+        one launch per pool batch is captured into a graph, and events on the launch stream bracket
+        replays of it -- back-to-back launches, so the figure is the kernel's duration plus the gap
+        between two launches."""
+        pkg = self.pkg
+
+        def issue():
+            for w in self.pool:
+                pkg.cool_sd_bench_row_stats(self.params, w.target, w.target_uncond, w.draft, w.draft_uncond,
+                                            w.draft_tokens, self.ws)
+        return self._replay_time(issue, n)
+
+    def direct_call_times(self, n):
+        """Mean and median duration of one direct (not graph-replayed) verify call, each bracketed by
+        its own pair of events on the launch stream; includes the dispatch latency of a lone call."""
+        torch = self.torch
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for i in range(5):
+            self.step(i)
         torch.cuda.synchronize()
-        pkg.cool_sd_profile_enable(2)
-        try:
-            for i in range(len(self.pool)):
-                self.step(i)
-            torch.cuda.synchronize()
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g):
-                for i in range(len(self.pool)):
-                    self.step(i)
-            reps = max(2, -(-n // len(self.pool)))
-            g.replay()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i, (e0, e1) in enumerate(ev):
             e0.record()
-            for _ in range(reps):
-                g.replay()
+            self.step(i)
             e1.record()
             torch.cuda.synchronize()
-            k_graph = e0.elapsed_time(e1) * 1e-3 / (reps * len(self.pool))
-            del g
-        finally:
-            pkg.cool_sd_profile_enable(0)
-        pkg.cool_sd_profile_enable(1)
-        k_ms = c_ms = 0.0
-        calls = []
-        try:
-            for i in range(n + 5):
-                self.step(i)
-                a, b = pkg.cool_sd_profile_read()
-                if i >= 5:
-                    k_ms += a
-                    c_ms += b
-                    calls.append(b)
-        finally:
-            pkg.cool_sd_profile_enable(0)
-        self.call_median_s = sorted(calls)[len(calls) // 2] * 1e-3
-        return k_graph, k_ms / n * 1e-3, c_ms / n * 1e-3
+        t = sorted(e0.elapsed_time(e1) * 1e-3 for e0, e1 in ev)
+        return sum(t) / len(t), t[len(t) // 2]
 
 
 def run_diagnostics(r, n):
@@ -489,34 +493,49 @@ def delta_sweep(r, deltas=(1.0, 1.1, 2.0, 3.0, 4.0)):
 
 
 def cpu_baseline(runner, budget_s):
-    """The oracle, as it stands, on whole batches of the same pool until the time budget is used."""
+    """The oracle, as it stands, on whole batches of the same pool until the time budget is used
+    (OpenMP over sequences, all host cores), then on one core on the first sequences of a batch."""
     from oracle import oracle as O
-    from tests.parity_util import run_oracle
+    from tests.parity_util import run_oracle, subset
     threads = O.max_threads()
-    run_oracle(O, runner.pool[0], runner.omega_np, num_threads=threads)      # page in / build
-    t0 = time.perf_counter()
-    calls = 0
-    while True:
-        run_oracle(O, runner.pool[calls % len(runner.pool)], runner.omega_np, num_threads=threads)
+    first = subset(runner.pool[0], list(range(min(runner.B, threads))))
+    run_oracle(O, first, runner.omega_np, num_threads=threads)               # page in / build
+    host = [None] * len(runner.pool)        # float32 host copies are made outside the timed region
+
+    def prepared(i):
+        if host[i] is None:
+            w = runner.pool[i]
+            t, d, tu, du = w.logits_f32_numpy()
+            host[i] = dict(t=t, d=d, tu=tu, du=du, tok=w.draft_tokens.cpu().numpy(), ua=w.u_accept.cpu().numpy(),
+                           ur=w.u_resample.cpu().numpy(), w=w)
+        return host[i]
+
+    def call(h, nthreads, nseq=None):
+        sl = slice(None) if nseq is None else slice(0, nseq)
+        w = h["w"]
+        O.verify(h["t"][sl], h["d"][sl], h["tok"][sl], runner.omega_np, h["ua"][sl], h["ur"][sl],
+                 target_uncond=None if h["tu"] is None else h["tu"][sl],
+                 draft_uncond=None if h["du"] is None else h["du"][sl], cfg_scale=w.cfg_scale,
+                 temperature=w.temperature, top_k=w.top_k, num_threads=nthreads)
+
+    calls, el = 0, 0.0
+    while el < budget_s:
+        h = prepared(calls % len(runner.pool))
+        t0 = time.perf_counter()
+        call(h, threads)
+        el += time.perf_counter() - t0
         calls += 1
-        el = time.perf_counter() - t0
-        if el >= budget_s:
-            break
     tokens = calls * runner.B * runner.L
-    # the same oracle on one core, on a shorter sample
+    # the same oracle on one core, on the first sequences of a batch
+    n1 = max(1, min(runner.B, int(runner.B * (budget_s / 4) / max(el / calls * threads, 1e-9))))
     t1 = time.perf_counter()
-    c1 = 0
-    while True:
-        run_oracle(O, runner.pool[c1 % len(runner.pool)], runner.omega_np, num_threads=1)
-        c1 += 1
-        e1 = time.perf_counter() - t1
-        if e1 >= budget_s / 4:
-            break
+    call(prepared(0), 1, n1)
+    e1 = time.perf_counter() - t1
     return {"value": tokens / el, "unit": "verified draft tokens/s", "cores": threads, "kind": "oracle",
             "sample": "%d verify calls of the same workload (B=%d, L=%d, V=%d), %.1f s, OpenMP over sequences"
                       % (calls, runner.B, runner.L, runner.V, el),
-            "single_core_value": c1 * runner.B * runner.L / e1,
-            "single_core_sample": "%d verify calls, %.1f s, 1 thread" % (c1, e1)}
+            "single_core_value": n1 * runner.L / e1,
+            "single_core_sample": "the first %d sequences of one call, %.1f s, 1 thread" % (n1, e1)}
 
 
 def main():
@@ -531,7 +550,8 @@ def main():
 
     cfg = int(a.workload[3:])
     flags = pkg.COOL_SD_FLAG_EARLY_EXIT if a.early_exit else 0
-    r = Runner(pkg, torch, cfg, a.pool_mb, flags=flags, B=a.batch or None, V=a.vocab or None, top_k=a.top_k or None)
+    pool_mb = a.pool_mb or (3400.0 if cfg >= 4 else 600.0)
+    r = Runner(pkg, torch, cfg, pool_mb, flags=flags, B=a.batch or None, V=a.vocab or None, top_k=a.top_k or None)
     variant = bool(a.batch or a.vocab or a.top_k)      # not the configuration itself: its recipe at another size
     if a.counter_run:
         # reference for the byte counters: an elementwise kernel (dst = src * 1) that moves exactly
@@ -552,7 +572,8 @@ def main():
         return
     done, wall, dev_s = r.time(a.steps, a.warmup, a.launch)
     tokens = done * r.B * r.L
-    kern_s, kern_ev_s, call_s = r.kernel_times(a.kernel_samples)
+    kern_s = r.kernel_time(a.kernel_samples)
+    call_s, call_median_s = r.direct_call_times(min(a.kernel_samples, 100))
     probe_s, probe_launches = r.read_probe_time(a.kernel_samples)
     kernel_name = "row_stats_topk_kernel" if r.pool[0].top_k > 0 else "row_stats_kernel"
     kernel_bytes = r.bytes_per_step
@@ -571,45 +592,51 @@ def main():
         kern_s = dev_s / done
     achieved = kernel_bytes / kern_s / 1e9
     dtype = r.pool[0].dtype
+    step_s = wall / done
     line = {
         "metric": "verified draft tokens/sec (1 GPU) + achieved HBM GB/s fraction of peak",
         "value": tokens / wall, "unit": "verified draft tokens/s", "n_gpus": 1, "steps": done, "warmup": a.warmup,
-        "ms_per_step": wall / done * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": step_s * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "config 2: B=32, L=8, V=16384, %s logits, exp schedule delta=1.1 nu=0.7" % dtype
-                   if cfg == 2 and not variant else "config %d%s: B=%d, L=%d, V=%d, %s logits%s" % (
+        "config": {"workload": "config %d%s: B=%d, L=%d, V=%d, %s logits%s, exp schedule delta=%.3g nu=%.3g" % (
                        cfg, "'s recipe" if variant else "", r.B, r.L, r.V, dtype,
-                       ", top-k %d" % r.pool[0].top_k if r.pool[0].top_k else ""),
+                       ", guidance s=%g, top-k %d" % (r.pool[0].cfg_scale, r.pool[0].top_k) if r.pool[0].top_k else "",
+                       r.pool[0].delta, r.pool[0].nu),
                    "input_dtype": dtype, "launch": a.launch, "early_exit": bool(a.early_exit), "pool_batches": len(r.pool),
                    "pool_mb": len(r.pool) * r.bytes_per_step / 1e6, "bytes_per_step": r.bytes_per_step},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None if variant else (MEASURED_TRAFFIC_EARLY if a.early_exit else MEASURED_TRAFFIC_BYTES).get(a.workload),
+                     "traffic": None if variant else measured_traffic(a.workload, a.early_exit),
                      "kernel": kernel_name, "algorithmic_bytes_per_launch": kernel_bytes,
                      "us_per_launch": kern_s * 1e6,
-                     "us_per_launch_lone_events": kern_ev_s * 1e6,
+                     # the whole step (every launch of the call) against the same algorithmic bytes
+                     "whole_call_us": step_s * 1e6, "whole_call_GBps": r.bytes_per_step / step_s / 1e9,
+                     "whole_call_frac": r.bytes_per_step / step_s / 1e9 / HBM_PEAK_GBS,
+                     "graph_step_us": dev_s / done * 1e6,
+                     "direct_call_us": call_s * 1e6, "direct_call_median_us": call_median_s * 1e6,
                      # a plain read of the same tensors in one launch of the same shape: what the chip
                      # delivers for this many bytes per launch, start-up included
                      "read_probe": {"us": probe_s * 1e6, "GBps": r.bytes_per_step / probe_s / 1e9,
-                                    "launches": probe_launches, "kernel_over_probe": kern_s / probe_s},
-                     "whole_call_us": call_s * 1e6, "whole_call_median_us": r.call_median_s * 1e6,
-                     "whole_call_GBps": r.bytes_per_step / call_s / 1e9,
-                     "graph_step_us": dev_s / done * 1e6},
+                                    "launches": probe_launches, "kernel_over_probe": kern_s / probe_s}},
     }
+    if not a.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(r, a.cpu_seconds)
     if a.others:
         extra = {}
-        # the fifth entry is configuration 4 with eight times the sequences: the regime (B well above
-        # the number of compute units) the early-exit form is meant for; the last two are
-        # configurations 2 and 3 at the 65536-token vocabulary of the paper's larger target model
-        # (guided sampling there uses top-k 2000): rows of several chunks
-        for c, big, vocab, topk in ((1, None, None, None), (3, None, None, None), (4, None, None, None), (5, None, None, None),
-                                    (4, 2048, None, None), (2, None, 65536, None), (3, 32, 65536, 2000)):
+        todo = [(c, None, None, None) for c in (1, 2, 3, 4, 5)]
+        if a.variants:
+            # configuration 4 with eight times the sequences: the regime (B well above the number of
+            # compute units) the early-exit form is meant for; configurations 2 and 3 at the
+            # 65536-token vocabulary of the paper's larger target model (guided sampling there uses
+            # top-k 2000): rows of several chunks
+            todo += [(4, 2048, None, None), (2, None, 65536, None), (3, 32, 65536, 2000)]
+        for c, big, vocab, topk in todo:
             if c == cfg and not big and not vocab and not variant:
                 continue
             rr = Runner(pkg, torch, c, 2400.0 if c >= 4 else 600.0, max_pool=(2 if big else 8) if c >= 4 else 64,
                         flags=flags, B=big, V=vocab, top_k=topk)
             d2, w2, s2 = rr.time(max(64, 8 * len(rr.pool)), 2 * len(rr.pool), a.launch)
-            k2, _, c2 = rr.kernel_times(40)
+            k2 = rr.kernel_time(40)
             p2, pl2 = rr.read_probe_time(40)
             name = "cfg%d" % c + ("_B%d" % big if big else "") + ("_V%d" % vocab if vocab else "") + ("_k%d" % topk if topk else "")
             extra[name] = {"tokens_per_s": d2 * rr.B * rr.L / w2, "us_per_step": s2 / d2 * 1e6,
@@ -645,8 +672,6 @@ def main():
         line["draft_sampler"] = time_draft_sampler(r)
     if a.delta_sweep:
         line["delta_sweep"] = delta_sweep(r)
-    if not a.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(r, a.cpu_seconds)
     print(json.dumps(line), flush=True)
 
 

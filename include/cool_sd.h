@@ -22,8 +22,9 @@
  *   - Functions return COOL_SD_OK (0) or a negative cool_sd_status.  Argument errors are
  *     detected on the host before anything is enqueued.  Draft tokens outside [0, V) are a
  *     contract violation that no status reports: wherever a token is used as an address the
- *     kernels clamp it into [0, V-1] first, so nothing outside the rows is read, but the
- *     results of that sequence are unspecified.
+ *     kernels clamp it into [0, V-1] first, so nothing outside the rows is read and the results
+ *     are those of the clamped token.  COOL_SD_FLAG_CHECK_TOKENS (always on in the debug build
+ *     libcool_sd_checked.so) marks such sequences with accept_len = next_token = -1.
  *   - Logits must be finite or -inf (-inf = token excluded); every row needs at least one
  *     finite logit.  Uniforms lie in [0, 1).
  *   - The workspace holds only intermediate results of one call (chunk statistics, masses);
@@ -38,6 +39,13 @@
 
 #include <stddef.h>
 #include <stdint.h>
+
+/* The library is built with hidden visibility; these are its only exported symbols. */
+#if defined(__GNUC__) || defined(__clang__)
+#define COOL_SD_API __attribute__((visibility("default")))
+#else
+#define COOL_SD_API
+#endif
 
 #ifdef __cplusplus
 extern "C" {
@@ -77,7 +85,14 @@ typedef enum {
    * all-rows path.
    * When honoured, p_tok / q_tok / f of positions after the rejected one are NaN and the
    * workspace is not touched.  accept_len, next_token and resid_mass mean the same in both. */
-  COOL_SD_FLAG_EARLY_EXIT = 1
+  COOL_SD_FLAG_EARLY_EXIT = 1,
+  /* Checked mode of the verify calls: one more (small) kernel after the others looks at every
+   * draft token on the device; a sequence that holds a token outside [0, V) gets
+   * accept_len = -1, next_token = -1 and resid_mass = 0 instead of the results of the clamped
+   * token.  Every kernel still runs to its end on such input.  The debug build of the library
+   * (libcool_sd_checked.so, compiled with -DCOOL_SD_CHECKED_BUILD) behaves as if every call set
+   * this bit. */
+  COOL_SD_FLAG_CHECK_TOKENS = 2
 } cool_sd_flags;
 
 typedef struct {
@@ -108,16 +123,16 @@ typedef struct {
  * omega_out: host float[L]; omega_out[i-1] = omega_i of the paper.  Evaluated in fp64 and
  * rounded once to fp32.  COOL_SD_EINVAL on bad arguments (LINEAR with ell < L would need a
  * negative weight). */
-int cool_sd_schedule(int32_t kind, int32_t L, float delta, float param, float* omega_out);
+COOL_SD_API int cool_sd_schedule(int32_t kind, int32_t L, float delta, float param, float* omega_out);
 
 /* Bytes of device workspace cool_sd_verify / cool_sd_verify_lantern / cool_sd_verify_diagnostics /
  * cool_sd_resample / cool_sd_diagnostics need for these params
  * (for resample only B, V, dtype and top_k matter).  0 on invalid params. */
-size_t cool_sd_workspace_bytes(const cool_sd_params* p);
+COOL_SD_API size_t cool_sd_workspace_bytes(const cool_sd_params* p);
 
 /* Zero a workspace on the stream.  Optional (no call depends on the workspace's contents);
  * kept for callers that want defined memory.  workspace_dev must be 256-byte aligned. */
-int cool_sd_workspace_init(void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+COOL_SD_API int cool_sd_workspace_init(void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
 /* Verification stage of Algorithm 1 for B sequences; asynchronous on hip_stream.
  *   target_dev          [B, L + has_bonus, V] logits of P (conditional ones under guidance)
@@ -136,7 +151,7 @@ int cool_sd_workspace_init(void* workspace_dev, size_t workspace_bytes, void* hi
  *   resid_mass_dev      out float [B], optional: R = sum_x g(x) of the sampled law
  *                       (sum of p for the bonus draw, 0 when next_token = -1)
  * The accepted tokens are draft_tokens[b, 0:tau]; they are not copied. */
-int cool_sd_verify(const cool_sd_params* p,
+COOL_SD_API int cool_sd_verify(const cool_sd_params* p,
                    const void* target_dev, const void* target_uncond_dev,
                    const void* draft_dev, const void* draft_uncond_dev,
                    const int32_t* draft_tokens_dev,
@@ -171,7 +186,7 @@ int cool_sd_verify(const cool_sd_params* p,
  * Everything else as in cool_sd_verify (there is no omega; COOL_SD_FLAG_EARLY_EXIT is ignored).
  * The set is decided from fp32 weights p_i(n)/p_i(x~_i); a running sum within rounding of
  * lambda may fall on either side. */
-int cool_sd_verify_lantern(const cool_sd_params* p,
+COOL_SD_API int cool_sd_verify_lantern(const cool_sd_params* p,
                            const void* target_dev, const void* target_uncond_dev,
                            const void* draft_dev, const void* draft_uncond_dev,
                            const int32_t* draft_tokens_dev,
@@ -197,7 +212,7 @@ int cool_sd_verify_lantern(const cool_sd_params* p,
  * Rows of at most 16384 logits (32768 when 16-byte aligned) are served by a single kernel launch
  * (except truncated rows with a draft), so a call per drafted token costs one launch latency; so
  * are draft-less truncated rows of up to 65536 logits (bf16) or 32768 (fp32). */
-int cool_sd_resample(const cool_sd_params* p,
+COOL_SD_API int cool_sd_resample(const cool_sd_params* p,
                      const void* target_rows_dev, const void* target_uncond_rows_dev,
                      const void* draft_rows_dev, const void* draft_uncond_rows_dev,
                      const float* omega_rows_dev, const float* u_dev,
@@ -216,7 +231,7 @@ int cool_sd_resample(const cool_sd_params* p,
  * Tensors, strides, omega and the logit transform are those of cool_sd_verify (the bonus row of
  * the target tensor is not read); resample_mode is ignored.  Same workspace, same size.  Rows
  * of at most 16384 logits without top-k are read once; otherwise twice (statistics, then sums). */
-int cool_sd_diagnostics(const cool_sd_params* p,
+COOL_SD_API int cool_sd_diagnostics(const cool_sd_params* p,
                         const void* target_dev, const void* target_uncond_dev,
                         const void* draft_dev, const void* draft_uncond_dev,
                         const float* omega_dev,
@@ -233,7 +248,7 @@ int cool_sd_diagnostics(const cool_sd_params* p,
  * diagnostics pass follows the verify call's kernels on the stream and reuses the row statistics
  * and top-k thresholds they left in the workspace (the logits are read twice, not three times).
  * COOL_SD_FLAG_EARLY_EXIT is ignored (the diagnostics need every row). */
-int cool_sd_verify_diagnostics(const cool_sd_params* p,
+COOL_SD_API int cool_sd_verify_diagnostics(const cool_sd_params* p,
                                const void* target_dev, const void* target_uncond_dev,
                                const void* draft_dev, const void* draft_uncond_dev,
                                const int32_t* draft_tokens_dev,
@@ -248,28 +263,8 @@ int cool_sd_verify_diagnostics(const cool_sd_params* p,
                                void* workspace_dev, size_t workspace_bytes,
                                void* hip_stream);
 
-/* Benchmark instrumentation (not for production paths, not thread-safe).  mode 0: off.
- * mode 1 (not usable while the stream is being captured into a graph): cool_sd_verify /
- * cool_sd_resample record HIP events on the call's stream around the row-statistics kernel (the
- * pass that reads every logit from HBM) and around the whole call; cool_sd_profile_read waits for
- * the last instrumented call and returns both durations in milliseconds.
- * mode 2: cool_sd_verify / cool_sd_resample enqueue the row-statistics kernel ALONE and write no
- * output, so that a benchmark can time that kernel back to back (also from a captured graph). */
-int cool_sd_profile_enable(int mode);
-int cool_sd_profile_read(float* stats_kernel_ms, float* call_ms);
-
-/* Benchmark instrumentation: a plain streaming read of two device buffers in ONE launch with the
- * launch shape of the row-statistics kernel on short rows (256 threads, 16 bytes per lane and
- * load, 8 KiB per workgroup) and no arithmetic beyond an exclusive-or of the words -- what this
- * GPU delivers for that many bytes in one launch, start-up included, as a live yardstick beside
- * the statistics kernel's own time.  a_dev / b_dev: 16-byte aligned, sizes multiples of 16
- * (b_bytes may be 0); workspace_dev: at least 4 bytes per 8 KiB read (rounded up per buffer),
- * receives one word per workgroup.  Asynchronous on hip_stream. */
-int cool_sd_profile_read_probe(const void* a_dev, size_t a_bytes, const void* b_dev, size_t b_bytes,
-                               void* workspace_dev, size_t workspace_bytes, void* hip_stream);
-
 /* Static description of a cool_sd_status. */
-const char* cool_sd_strerror(int code);
+COOL_SD_API const char* cool_sd_strerror(int code);
 
 #ifdef __cplusplus
 }

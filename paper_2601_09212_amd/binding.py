@@ -12,10 +12,13 @@ import numpy as np
 COOL_SD_F32, COOL_SD_BF16 = 0, 1
 COOL_SD_SCHED_UNIFORM, COOL_SD_SCHED_EXP, COOL_SD_SCHED_LINEAR = 0, 1, 2
 COOL_SD_RESAMPLE_OPT, COOL_SD_RESAMPLE_VANILLA, COOL_SD_RESAMPLE_LANTERN = 0, 1, 2
-COOL_SD_FLAG_EARLY_EXIT = 1
+COOL_SD_FLAG_EARLY_EXIT, COOL_SD_FLAG_CHECK_TOKENS = 1, 2
 COOL_SD_OK, COOL_SD_EINVAL, COOL_SD_EWORKSPACE, COOL_SD_ELAUNCH, COOL_SD_EUNSUPPORTED = 0, -1, -2, -3, -4
 
-LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcool_sd.so")
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcool_sd.so")
+LIB_CHECKED_PATH = os.path.join(_HERE, "libcool_sd_checked.so")     # debug build: draft tokens checked on every call
+LIB_BENCH_PATH = os.path.join(_HERE, "libcool_sd_bench.so")         # benchmark companion (include/cool_sd_bench.h)
 
 
 class CoolSDError(RuntimeError):
@@ -35,48 +38,63 @@ class CoolSDParams(C.Structure):
 
 
 _lib = None
+_bench = None
+
+
+def load(path):
+    """Load a build of the C-ABI library (the product, or its checked build) and declare the entry
+    points of include/cool_sd.h.  Fails loudly when the file has not been built."""
+    if not os.path.exists(path):
+        raise ImportError("%s is not built: run `python -m paper_2601_09212_amd.build` "
+                          "(or __graft_entry__.build()); there is no fallback path" % os.path.basename(path))
+    # PyTorch ships its own copy of the HIP runtime (soname libamdhip64.so.7).  Load it first so
+    # that this library binds to the same runtime instance that owns torch's memory and streams;
+    # two runtimes in one process do not see each other's devices.
+    import torch  # noqa: F401
+    L = C.CDLL(path)
+    vp, pp = C.c_void_p, C.POINTER(CoolSDParams)
+    L.cool_sd_schedule.argtypes = [C.c_int32, C.c_int32, C.c_float, C.c_float, C.POINTER(C.c_float)]
+    L.cool_sd_schedule.restype = C.c_int
+    L.cool_sd_workspace_bytes.argtypes = [pp]
+    L.cool_sd_workspace_bytes.restype = C.c_size_t
+    L.cool_sd_workspace_init.argtypes = [vp, C.c_size_t, vp]
+    L.cool_sd_workspace_init.restype = C.c_int
+    L.cool_sd_verify.argtypes = [pp] + [vp] * 14 + [vp, C.c_size_t, vp]
+    L.cool_sd_verify.restype = C.c_int
+    L.cool_sd_verify_lantern.argtypes = ([pp] + [vp] * 6 + [C.c_int32, C.c_float] + [vp] * 10
+                                         + [vp, C.c_size_t, vp])
+    L.cool_sd_verify_lantern.restype = C.c_int
+    L.cool_sd_verify_diagnostics.argtypes = [pp] + [vp] * 16 + [vp, C.c_size_t, vp]
+    L.cool_sd_verify_diagnostics.restype = C.c_int
+    L.cool_sd_resample.argtypes = [pp] + [vp] * 8 + [vp, C.c_size_t, vp]
+    L.cool_sd_resample.restype = C.c_int
+    L.cool_sd_diagnostics.argtypes = [pp] + [vp] * 7 + [vp, C.c_size_t, vp]
+    L.cool_sd_diagnostics.restype = C.c_int
+    L.cool_sd_strerror.argtypes = [C.c_int]
+    L.cool_sd_strerror.restype = C.c_char_p
+    return L
 
 
 def lib():
-    """The loaded C-ABI library.  Fails loudly when it has not been built."""
+    """The loaded product library."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            raise ImportError("libcool_sd.so is not built: run `python -m paper_2601_09212_amd.build` "
-                              "(or __graft_entry__.build()); there is no fallback path")
-        # PyTorch ships its own copy of the HIP runtime (soname libamdhip64.so.7).  Load it first so
-        # that this library binds to the same runtime instance that owns torch's memory and streams;
-        # two runtimes in one process do not see each other's devices.
-        import torch  # noqa: F401
-        L = C.CDLL(LIB_PATH)
-        vp, pp = C.c_void_p, C.POINTER(CoolSDParams)
-        L.cool_sd_schedule.argtypes = [C.c_int32, C.c_int32, C.c_float, C.c_float, C.POINTER(C.c_float)]
-        L.cool_sd_schedule.restype = C.c_int
-        L.cool_sd_workspace_bytes.argtypes = [pp]
-        L.cool_sd_workspace_bytes.restype = C.c_size_t
-        L.cool_sd_workspace_init.argtypes = [vp, C.c_size_t, vp]
-        L.cool_sd_workspace_init.restype = C.c_int
-        L.cool_sd_verify.argtypes = [pp] + [vp] * 14 + [vp, C.c_size_t, vp]
-        L.cool_sd_verify.restype = C.c_int
-        L.cool_sd_verify_lantern.argtypes = ([pp] + [vp] * 6 + [C.c_int32, C.c_float] + [vp] * 10
-                                             + [vp, C.c_size_t, vp])
-        L.cool_sd_verify_lantern.restype = C.c_int
-        L.cool_sd_verify_diagnostics.argtypes = [pp] + [vp] * 16 + [vp, C.c_size_t, vp]
-        L.cool_sd_verify_diagnostics.restype = C.c_int
-        L.cool_sd_resample.argtypes = [pp] + [vp] * 8 + [vp, C.c_size_t, vp]
-        L.cool_sd_resample.restype = C.c_int
-        L.cool_sd_diagnostics.argtypes = [pp] + [vp] * 7 + [vp, C.c_size_t, vp]
-        L.cool_sd_diagnostics.restype = C.c_int
-        L.cool_sd_profile_enable.argtypes = [C.c_int]
-        L.cool_sd_profile_enable.restype = C.c_int
-        L.cool_sd_profile_read.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_float)]
-        L.cool_sd_profile_read.restype = C.c_int
-        L.cool_sd_profile_read_probe.argtypes = [vp, C.c_size_t, vp, C.c_size_t, vp, C.c_size_t, vp]
-        L.cool_sd_profile_read_probe.restype = C.c_int
-        L.cool_sd_strerror.argtypes = [C.c_int]
-        L.cool_sd_strerror.restype = C.c_char_p
-        _lib = L
+        _lib = load(LIB_PATH)
     return _lib
+
+
+def bench_lib():
+    """The benchmark companion library (only bench.py and its tests use it)."""
+    global _bench
+    if _bench is None:
+        L = load(LIB_BENCH_PATH)
+        vp, pp = C.c_void_p, C.POINTER(CoolSDParams)
+        L.cool_sd_bench_row_stats.argtypes = [pp] + [vp] * 5 + [vp, C.c_size_t, vp]
+        L.cool_sd_bench_row_stats.restype = C.c_int
+        L.cool_sd_bench_read_probe.argtypes = [vp, C.c_size_t, vp, C.c_size_t, vp, C.c_size_t, vp]
+        L.cool_sd_bench_read_probe.restype = C.c_int
+        _bench = L
+    return _bench
 
 
 def _ptr(t):
@@ -181,29 +199,26 @@ def cool_sd_diagnostics(params, target, target_uncond, draft, draft_uncond, omeg
     return rc
 
 
-def cool_sd_profile_read_probe(a, b, workspace, stream=None, check=True):
-    """Streaming read of tensors a and b (b may be None) in one launch; see include/cool_sd.h."""
+def cool_sd_bench_read_probe(a, b, workspace, stream=None, check=True):
+    """Streaming read of tensors a and b (b may be None) in one launch; see include/cool_sd_bench.h."""
     nb = lambda t: 0 if t is None else t.numel() * t.element_size()
-    rc = lib().cool_sd_profile_read_probe(_ptr(a), nb(a), _ptr(b), nb(b), _ptr(workspace), nb(workspace), _stream(stream))
+    rc = bench_lib().cool_sd_bench_read_probe(_ptr(a), nb(a), _ptr(b), nb(b), _ptr(workspace), nb(workspace),
+                                              _stream(stream))
     if check and rc != 0:
-        raise CoolSDError(rc, "cool_sd_profile_read_probe")
+        raise CoolSDError(rc, "cool_sd_bench_read_probe")
     return rc
 
 
-def cool_sd_profile_enable(mode):
-    """0 / False: off; 1 / True: events around the statistics kernel and the call; 2: statistics kernel only."""
-    rc = lib().cool_sd_profile_enable(int(mode))
-    if rc != 0:
-        raise CoolSDError(rc, "cool_sd_profile_enable")
-
-
-def cool_sd_profile_read():
-    """(statistics-kernel ms, whole-call ms) of the last instrumented call."""
-    a, b = C.c_float(), C.c_float()
-    rc = lib().cool_sd_profile_read(C.byref(a), C.byref(b))
-    if rc != 0:
-        raise CoolSDError(rc, "cool_sd_profile_read")
-    return a.value, b.value
+def cool_sd_bench_row_stats(params, target, target_uncond, draft, draft_uncond, draft_tokens, workspace, stream=None,
+                            check=True):
+    """The statistics pass of cool_sd_verify alone; see include/cool_sd_bench.h."""
+    rc = bench_lib().cool_sd_bench_row_stats(C.byref(params), _ptr(target), _ptr(target_uncond), _ptr(draft),
+                                             _ptr(draft_uncond), _ptr(draft_tokens), _ptr(workspace),
+                                             0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                             _stream(stream))
+    if check and rc != 0:
+        raise CoolSDError(rc, "cool_sd_bench_row_stats")
+    return rc
 
 
 # ------------------------------------------------------------------ conveniences (marshalling only)

@@ -1,7 +1,9 @@
 // Per-position terms of Theorem 2 (alpha_i, beta_i).
-// Part of the one translation unit verify_kernels.hip (included there, inside namespace csd,
-// after device_utils.h, kernels.h and topk.h); not a stand-alone header.
 #pragma once
+#include "sequence_common.h"
+#include "stats_kernels.h"
+
+namespace csd {
 
 // ============================================================================ diagnostics
 // Per-position quantities of Theorem 2 for the row pair (p_i, q_i) with relaxation omega_i:
@@ -169,3 +171,5 @@ __global__ __launch_bounds__(kThreads) void diag_combine_kernel(const KArgs a) {
   a.alpha[rp] = A;
   a.beta[rp] = Bv;
 }
+
+}  // namespace csd

@@ -1,7 +1,8 @@
 // Early-exit form of the verify call and the one-launch cool_sd_resample on short rows.
-// Part of the one translation unit verify_kernels.hip (included there, inside namespace csd,
-// after device_utils.h, kernels.h and topk.h); not a stand-alone header.
 #pragma once
+#include "sequence_whole.h"
+
+namespace csd {
 
 // ============================================================================ early-exit variant
 // Algorithm 1 stops verifying at the first rejection; this kernel does the same with the memory
@@ -394,3 +395,5 @@ __global__ __launch_bounds__(kThreads) void sequence_early_exit_tile_kernel(cons
     if (a.resid_mass) a.resid_mass[b] = R;
   }
 }
+
+}  // namespace csd

@@ -34,7 +34,7 @@ struct KArgs {
   float* f;
   float* resid_mass;        // [B] or nullptr
   int32_t resample_mode, resample_only, aligned;
-  int32_t stats_only;       // benchmark: launch row_stats_kernel only
+  int32_t stats_only;       // enqueue the statistics pass alone (the benchmark library's timing entry point)
   int32_t early_exit;       // verify: stop reading a sequence's rows at its first rejection (one kernel)
   int32_t stream_loads;     // statistics kernel: input larger than the caches, use nontemporal loads
   int32_t nchunks, nt2;     // sampling kernel: chunks per row, tiles per chunk
@@ -65,9 +65,7 @@ struct KArgs {
 
 // Enqueue the kernels of one verify (or stand-alone resample) call.  xf: the logit transform
 // (guidance / temperature / top-k) is active.  Returns hipSuccess or the launch error.
-// ev: nullptr, or three events recorded before the statistics kernel, after it, and after the
-// last kernel.
-hipError_t launch_verify(const KArgs& a, int dtype, bool xf, hipStream_t stream, hipEvent_t* ev);
+hipError_t launch_verify(const KArgs& a, int dtype, bool xf, hipStream_t stream);
 
 // Enqueue the kernels of one diagnostics call (alpha_i, beta_i of every row pair).  local: rows
 // are one chunk and need no statistics pass.  have_stats (not with local): the workspace already
@@ -79,10 +77,52 @@ hipError_t launch_diagnostics(const KArgs& a, int dtype, bool xf, bool local, hi
 // (every logit read once for both results).
 hipError_t launch_verify_diagnostics(const KArgs& a, int dtype, bool xf, hipStream_t stream);
 
+// Checked mode (COOL_SD_FLAG_CHECK_TOKENS), after the kernels of a verify call: sequences that hold a
+// draft token outside [0, V) get accept_len = next_token = -1 and resid_mass = 0.
+hipError_t launch_check_tokens(const KArgs& a, hipStream_t stream);
+
 // Zero n 32-bit words.
 hipError_t launch_zero(uint32_t* p, size_t n, hipStream_t stream);
 // benchmark yardstick: streaming read of two buffers (sizes in 16-byte vectors), one word out per workgroup
 hipError_t launch_read_probe(const uint4* a, size_t na, const uint4* b, size_t nb, uint32_t* out, hipStream_t stream);
 constexpr size_t kProbeVecsPerGroup = 512;   // 8 KiB
+
+// ---------------------------------------------------------------------------------------------
+// The pieces the calls above are made of.  Each lives in a translation unit of its own
+// (statistics pass, per-sequence step, diagnostics) so that the library builds in parallel; all of
+// them only enqueue kernels on `stream`.
+
+// Which launch does the neighbour aggregation of cool_sd_verify_lantern: it rides on the statistics
+// launch when it needs no top-k threshold, or when the workgroup that selects a target row's
+// threshold can do it (rows of one workgroup); otherwise a launch of its own follows.
+inline bool lantern_fused(const KArgs& a) {
+  return a.nbr != nullptr && !a.stats_only && (a.top_k == 0 || a.V <= 4 * 16384);
+}
+
+// statistics pass (stats_launch.hip): softmax statistics of every row (under top-k: threshold
+// selection first), the logit of x~_i per row, and the fused neighbour aggregation
+hipError_t launch_statistics(const KArgs& a, int dtype, bool xf, hipStream_t stream);
+// cool_sd_resample without a draft under top-k on rows one workgroup holds: one launch
+bool resample_topk_fits(const KArgs& a, int dtype);
+hipError_t launch_resample_topk(const KArgs& a, int dtype, hipStream_t stream);
+
+// per-sequence step (sequence_launch.hip): everything after the statistics pass
+hipError_t launch_sequence(const KArgs& a, int dtype, bool xf, hipStream_t stream);
+// whether the chunk-mass launch of a long-row call finds tau itself (then no kernel before it
+// leaves the combined row statistics in the workspace)
+bool tau_in_mass_launch(const KArgs& a, int dtype);
+hipError_t launch_combine_rows(const KArgs& a, hipStream_t stream);
+// the whole verify call per sequence, stopping at the first rejection (COOL_SD_FLAG_EARLY_EXIT)
+hipError_t launch_early_exit(const KArgs& a, int dtype, bool xf, hipStream_t stream);
+// cool_sd_resample on rows one workgroup holds, without top-k: one launch
+bool resample_whole_fits(const KArgs& a);
+hipError_t launch_resample_whole(const KArgs& a, int dtype, bool xf, hipStream_t stream);
+
+// diagnostics (diagnostics_launch.hip)
+// one-chunk rows: every logit read once; ver: also leave the verify call's statistics (plus B
+// workgroups for the bonus rows)
+hipError_t launch_diag_local(const KArgs& a, int dtype, bool xf, bool ver, hipStream_t stream);
+// long rows / top-k: chunk sums against the row statistics in the workspace, then their combination
+hipError_t launch_diag_chunks(const KArgs& a, int dtype, bool xf, hipStream_t stream);
 
 }  // namespace csd

@@ -1,8 +1,9 @@
 // Pieces shared by the per-sequence kernels: combining chunk statistics, the residual law
 // element by element, chunk masses and selection, the accept test (eval_position, find_tau).
-// Part of the one translation unit verify_kernels.hip (included there, inside namespace csd,
-// after device_utils.h, kernels.h and topk.h); not a stand-alone header.
 #pragma once
+#include "kernel_common.h"
+
+namespace csd {
 
 
 // Optional middle kernel (rows with more than kMaxDirect statistics chunks): one wave per row
@@ -19,11 +20,6 @@ __device__ __forceinline__ void combine_row_wave(const KArgs& a, int r) {
   for (int cc = lane; cc < a.c1; cc += 64) s = __fadd_rn(s, p[cc].y * exp2_fast(p[cc].x - m));
   s = wave_sum(s);
   if (lane == 0) a.rowstat[r] = make_float2(m, s);
-}
-__global__ __launch_bounds__(kThreads) void combine_rows_kernel(const KArgs a) {
-  const int r = blockIdx.x * kWaves + (threadIdx.x >> 6);
-  if (r >= a.rows_t + a.rows_d) return;
-  combine_row_wave(a, r);
 }
 
 // Statistics of row r from at most kMaxDirect entries (a.stat, a.cs entries per row), all
@@ -312,3 +308,4 @@ struct SmemW {
   float4 rowstat;
 };
 
+}  // namespace csd

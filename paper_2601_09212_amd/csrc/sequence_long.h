@@ -1,7 +1,8 @@
 // Per-sequence step of a verify call on rows longer than 32768 logits (tau, chunk masses, selection).
-// Part of the one translation unit verify_kernels.hip (included there, inside namespace csd,
-// after device_utils.h, kernels.h and topk.h); not a stand-alone header.
 #pragma once
+#include "sequence_whole.h"
+
+namespace csd {
 
 // ============================================================================ kernel 2, long rows
 // Rows too long for one workgroup's registers: tau, then the draw x_{tau+1} from the resampling law
@@ -380,3 +381,5 @@ __global__ __launch_bounds__(kThreadsW) void sequence_select_kernel(const KArgs 
     if (a.resid_mass) a.resid_mass[b] = R;
   }
 }
+
+}  // namespace csd

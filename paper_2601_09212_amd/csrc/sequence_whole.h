@@ -1,8 +1,10 @@
 // Second launch of a verify call on rows of at most 16384 logits: sequence_whole_kernel with its
 // register-resident sampler; the stand-alone neighbour aggregation kernel.
-// Part of the one translation unit verify_kernels.hip (included there, inside namespace csd,
-// after device_utils.h, kernels.h and topk.h); not a stand-alone header.
 #pragma once
+#include "sequence_common.h"
+#include "stats_kernels.h"
+
+namespace csd {
 
 // ============================================================================ kernel 2, rows of one chunk
 // One workgroup of 1024 threads per sequence (rows of at most 16384 logits): find tau, re-read
@@ -213,17 +215,4 @@ __global__ __launch_bounds__(kThreadsW) void sequence_whole_kernel(const KArgs a
   }
 }
 
-// ============================================================================ neighbour aggregation
-// Eq. f_lantern: the acceptance probability of x~_i uses the probability of its neighbour set
-// A(x~_i) = {x~_i} + the longest prefix of its neighbour list (nearest first) whose summed
-// probability stays below lambda p_i(x~_i).  Relative to p_i(x~_i) the members weigh
-// 2^((l_n - l_x) log2e), which needs no row statistics, so one wave per position gathers the k
-// neighbour logits, scans their weights and leaves agg = sum over A / p_i(x~_i) >= 1 where the
-// accept test reads its relaxation parameter: Eq. f_lantern is Eq. relax with omega_i = agg.
-// Also writes the number of members (for Eq. g_lantern) and the optional outputs.
-__global__ __launch_bounds__(kThreads) void lantern_agg_kernel(const KArgs a, int dt, int xf) {
-  const int pos = blockIdx.x * kWaves + (threadIdx.x >> 6);       // (b, i)
-  if (pos >= a.B * a.L) return;
-  const int b = pos / a.L, rt_ = b * (a.L + a.has_bonus) + (pos - b * a.L);
-  lantern_agg_position(a, pos, dt, xf != 0, (xf && a.top_k > 0) ? a.thr[rt_] : -INFINITY);
-}
+}  // namespace csd

@@ -1,8 +1,10 @@
 // Statistics pass (the HBM-bound launch of a verify call): row_stats_kernel and the neighbour
 // aggregation that rides along in its launch.
-// Part of the one translation unit verify_kernels.hip (included there, inside namespace csd,
-// after device_utils.h, kernels.h and topk.h); not a stand-alone header.
 #pragma once
+#include "kernel_common.h"
+#include "topk.h"
+
+namespace csd {
 
 // ============================================================================ kernel 1
 // Softmax statistics of one chunk of one row.  Rows are numbered: target rows first
@@ -43,11 +45,12 @@ template <int DT, bool G3> __device__ __forceinline__ RowRef row_ref(const KArgs
 // The draft token x~_i of a row (or -1), fetched with a per-lane load: a load from an address
 // the compiler can prove uniform would go through the scalar cache and the wait for it would
 // also hold back the chunk's vector loads that follow in program order.
+// The value is clamped into [0, V-1] wherever it is used as an address, like in every other kernel.
 __device__ __forceinline__ int load_draft_token(const KArgs& a, const RowRef& rw) {
   if (a.tokens == nullptr || rw.i >= a.L) return -1;
   int z = 0;
   asm volatile("" : "+v"(z));
-  return a.tokens[int64_t(rw.b) * a.L + rw.i + z];
+  return min(max(a.tokens[int64_t(rw.b) * a.L + rw.i + z], 0), a.V - 1);
 }
 
 __device__ __forceinline__ float token_logit_any(int dt, const char* cond, const char* uncond, int x, bool xf,
@@ -137,12 +140,11 @@ __global__ __launch_bounds__(kThreads, 3) void row_stats_kernel(const KArgs a) {
   }
   RowRegs<DT, XF, NT> x;
   load_chunk<DT, XF, AL, NT>(x, rw.cond, rw.uncond, base, a.V, a.cfg_scale, a.inv_T, thr);
-  int tok = load_draft_token(a, rw);     // after the chunk's loads in program order, used after them
+  const int tok = load_draft_token(a, rw);     // after the chunk's loads in program order, used after them
   // the (transformed) logit of x~_i for the accept test of the next kernel, taken from the
   // registers of the thread that holds it: element e of vector (tile k, thread t) is token
   // base + (k*256 + t)*kE + e
   if (tok >= 0) {
-    tok = min(tok, a.V - 1);
     const int64_t rel = int64_t(tok) - base;
     if (rel >= 0 && rel < NT * kThreads * kE) {
       const int vec = int(rel) / kE, e = int(rel) - vec * kE;
@@ -174,3 +176,5 @@ __global__ __launch_bounds__(kThreads, 3) void row_stats_kernel(const KArgs a) {
     a.part[int64_t(r) * C1 + c] = make_float2(C, S);
   }
 }
+
+}  // namespace csd

@@ -1,9 +1,10 @@
 // Top-k truncation: whole-row statistics with threshold selection (row_stats_topk_kernel), the
 // draft-side draw in one launch (resample_topk_kernel) and the radix passes for rows beyond
 // 65536 logits.
-// Part of the one translation unit verify_kernels.hip (included there, inside namespace csd,
-// after device_utils.h, kernels.h and topk.h); not a stand-alone header.
 #pragma once
+#include "stats_kernels.h"
+
+namespace csd {
 
 // Statistics of whole rows under top-k truncation: one workgroup of TPB threads per row,
 // ROW / TPB transformed logits per thread in registers (ROW = 16384 with 512 threads; 32768 or
@@ -33,10 +34,9 @@ __global__ __launch_bounds__(TPB, ROW == kChunk ? 6 : 4) void row_stats_topk_ker
   // vector k of thread t is vector k*TPB + t of the row
   load_chunk<DT, true, AL, kVW, TPB, 1, 4, GD>(x, rw.cond, rw.uncond, 0, a.V, a.cfg_scale, a.inv_T, -INFINITY);
   // the raw logits of x~_i, requested now and used at the very end
-  int tok = load_draft_token(a, rw);
+  const int tok = load_draft_token(a, rw);
   float tok_c = 0.f, tok_u = 0.f;
   if (tok >= 0 && threadIdx.x == 0) {
-    tok = min(tok, a.V - 1);
     tok_c = load_elem<DT>(rw.cond, tok);
     if (rw.uncond) tok_u = load_elem<DT>(rw.uncond, tok);
   }
@@ -243,41 +243,4 @@ __global__ __launch_bounds__(kThreads) void topk_radix_hist_kernel(const KArgs a
   }
 }
 
-// One workgroup per row: the digit of this pass that holds the k-th largest key.  Thread t owns
-// the eight buckets 2047 - 8t .. 2040 - 8t, so that ascending thread order is descending key order.
-__global__ __launch_bounds__(kThreads) void topk_radix_select_kernel(const KArgs a, int pass) {
-  __shared__ uint32_t wave_tot[kWaves];
-  const int r = blockIdx.x;
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  uint32_t* hist = a.rk_hist + int64_t(r) * kRadixBuckets;
-  const uint32_t k_rem = pass == 0 ? (uint32_t)a.top_k : a.rk_state[2 * r + 1];
-  const uint32_t prefix = pass == 0 ? 0u : a.rk_state[2 * r];
-  uint32_t h[8], local = 0;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int bkt = kRadixBuckets - 1 - (threadIdx.x * 8 + j);
-    h[j] = hist[bkt];
-    hist[bkt] = 0u;                                       // ready for the next pass / the next call
-    local += h[j];
-  }
-  const uint32_t incl = wave_scan_incl_u32(local);
-  if (lane == 63) wave_tot[wv] = incl;
-  __syncthreads();
-  uint32_t before = incl - local;
-#pragma unroll
-  for (int w = 0; w < kWaves; ++w) before += (w < wv) ? wave_tot[w] : 0u;
-  if (before < k_rem && k_rem <= before + local) {        // exactly one thread
-    uint32_t cum = before;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      if (cum < k_rem && k_rem <= cum + h[j]) {
-        const uint32_t digit = (uint32_t)(kRadixBuckets - 1 - (threadIdx.x * 8 + j));
-        const uint32_t np = prefix | (digit << radix_shift(pass));
-        a.rk_state[2 * r] = np;
-        a.rk_state[2 * r + 1] = k_rem - cum;
-        if (pass == 2) a.thr[r] = key_value(np);
-      }
-      cum += h[j];
-    }
-  }
-}
+}  // namespace csd

@@ -10,17 +10,10 @@ import numpy as np
 import pytest
 import torch
 
+from tests.parity_util import oracle_diagnostics as _oracle_diag, verify_diagnostics_call as _verify_diag
 from workloads import make_workload
 
 pytestmark = pytest.mark.gpu
-
-
-def _oracle_diag(oracle, w, om):
-    kw = dict(cfg_scale=w.cfg_scale, temperature=w.temperature, top_k=w.top_k)
-    tu = None if w.target_uncond is None else w.target_uncond.float().cpu().numpy()
-    du = None if w.draft_uncond is None else w.draft_uncond.float().cpu().numpy()
-    return oracle.diagnostics(w.target.float().cpu().numpy(), w.draft.float().cpu().numpy(), om,
-                              target_uncond=tu, draft_uncond=du, **kw)
 
 
 def _check(P, oracle, w, om):
@@ -145,26 +138,6 @@ def test_accepted_length_matches_its_prediction_at_full_size(P):
         else:
             assert float(beta.max()) > 0.0 and float(beta.min()) >= 0.0
         assert float(alpha.min()) > 0.0 and float(alpha.max()) <= 1.0 + 1e-6
-
-
-def _verify_diag(P, w, om, mode=0):
-    """cool_sd_verify_diagnostics on a workload; returns (verify outputs as numpy dict, alpha, beta)."""
-    from tests.parity_util import to_numpy
-    omega = torch.from_numpy(np.ascontiguousarray(om, dtype=np.float32)).cuda()
-    params = P.make_params(w.target, w.draft, top_k=w.top_k, cfg_scale=w.cfg_scale, temperature=w.temperature,
-                           resample_mode=mode, omega_stride_b=0 if omega.dim() == 1 else omega.stride(0))
-    ws = torch.empty(max(P.cool_sd_workspace_bytes(params), 256), dtype=torch.uint8, device="cuda")
-    B, L = w.B, w.L
-    out = dict(accept_len=torch.full((B,), -9, dtype=torch.int32, device="cuda"),
-               next_token=torch.full((B,), -9, dtype=torch.int32, device="cuda"),
-               p_tok=torch.zeros((B, L), device="cuda"), q_tok=torch.zeros((B, L), device="cuda"),
-               f=torch.zeros((B, L), device="cuda"), resid_mass=torch.zeros(B, device="cuda"))
-    alpha, beta = torch.zeros((B, L), device="cuda"), torch.zeros((B, L), device="cuda")
-    P.cool_sd_verify_diagnostics(params, w.target, w.target_uncond, w.draft, w.draft_uncond, w.draft_tokens, omega,
-                                 w.u_accept, w.u_resample, out["accept_len"], out["next_token"], out["p_tok"],
-                                 out["q_tok"], out["f"], out["resid_mass"], alpha, beta, ws)
-    torch.cuda.synchronize()
-    return to_numpy(out), alpha.cpu().numpy().astype(np.float64), beta.cpu().numpy().astype(np.float64)
 
 
 # (cfg recipe, B, L, V, dtype, top_k): one-chunk rows take the single-pass form; top-k and long rows

@@ -8,7 +8,8 @@ import pytest
 import torch
 
 from tests.parity_util import MASS_ABS, R_FLOOR, REL_TOL, U_TOL, compare_verify, compare_verify_lantern, to_numpy, token_band
-from tests.test_gpu_diagnostics import _check as check_diagnostics, _oracle_diag, _verify_diag
+from tests.parity_util import oracle_diagnostics as _oracle_diag, verify_diagnostics_call as _verify_diag
+from tests.test_gpu_diagnostics import _check as check_diagnostics
 from workloads import make_neighbor_table, make_workload, uniforms24
 
 pytestmark = pytest.mark.gpu

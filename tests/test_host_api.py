@@ -9,16 +9,57 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def test_library_exports_every_declared_symbol(P):
-    header = open(os.path.join(ROOT, "include", "cool_sd.h")).read()
+def _declared(header_name):
+    header = open(os.path.join(ROOT, "include", header_name)).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    names = re.findall(r"\b(cool_sd_[a-z_]+)\s*\(", header)
-    assert set(names) >= {"cool_sd_schedule", "cool_sd_workspace_bytes", "cool_sd_workspace_init",
-                          "cool_sd_verify", "cool_sd_verify_lantern", "cool_sd_resample", "cool_sd_diagnostics",
-                          "cool_sd_strerror"}
+    return set(re.findall(r"\b(cool_sd_[a-z_]+)\s*\(", header))
+
+
+def _exported(path):
+    """Dynamic symbols a library defines (any kind: functions, objects, kernel handles)."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", path], capture_output=True, text=True, check=True).stdout
+    return {ln.split()[-1] for ln in out.splitlines() if ln.strip()}
+
+
+def test_library_exports_exactly_the_declared_symbols(P):
+    """libcool_sd.so exports the entry points of include/cool_sd.h and nothing else: no benchmark
+    switch, no kernel handle, no mutable object."""
+    names = _declared("cool_sd.h")
+    assert names == {"cool_sd_schedule", "cool_sd_workspace_bytes", "cool_sd_workspace_init", "cool_sd_verify",
+                     "cool_sd_verify_lantern", "cool_sd_verify_diagnostics", "cool_sd_resample",
+                     "cool_sd_diagnostics", "cool_sd_strerror"}
+    assert _exported(P.binding.LIB_PATH) == names
+    assert _exported(P.binding.LIB_CHECKED_PATH) == names
     raw = C.CDLL(P.binding.LIB_PATH)
-    for n in set(names):
+    for n in names:
         assert hasattr(raw, n), n
+
+
+def test_bench_library_exports_its_header_on_top(P):
+    extra = _declared("cool_sd_bench.h")
+    assert extra == {"cool_sd_bench_row_stats", "cool_sd_bench_read_probe"}
+    assert _exported(P.binding.LIB_BENCH_PATH) == _declared("cool_sd.h") | extra
+
+
+def test_product_library_has_no_writable_state():
+    """No file-scope mutable object in the product library: its .data and .bss hold nothing of the
+    library's own (what remains is the HIP fat-binary registration the compiler emits, named
+    __hip_*), so no call can depend on an earlier one."""
+    import subprocess
+    from paper_2601_09212_amd import binding
+    out = subprocess.run(["nm", "--defined-only", binding.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    own = []
+    for ln in out.splitlines():
+        parts = ln.split()
+        if len(parts) == 3 and parts[1] in "bBdD":
+            name = parts[2]
+            if name.startswith("_") and not name.startswith("_Z"):
+                continue          # C runtime and HIP registration bookkeeping
+            if name.startswith("_Z") and "kernel" in name:
+                continue          # kernel handles: constant after the loader's relocation
+            own.append(ln)
+    assert not own, own
 
 
 def test_struct_layout_matches_header(P):
@@ -62,7 +103,7 @@ def test_workspace_bytes_and_invalid_params(P):
     assert big > small
     for bad in (dict(B=0), dict(V=0), dict(dtype=3), dict(top_k=-1), dict(top_k=16385), dict(temperature=0.0),
                 dict(temperature=float("inf")), dict(cfg_scale=float("nan")), dict(resample_mode=3),
-                dict(flags=2), dict(flags=-1), dict(t_stride_b=-1)):
+                dict(flags=4), dict(flags=-1), dict(t_stride_b=-1)):
         assert P.cool_sd_workspace_bytes(_params(P, **bad)) == 0, bad
     # L out of range is still a valid stand-alone resample shape (L is ignored there)
     assert P.cool_sd_workspace_bytes(_params(P, L=0)) > 0
@@ -119,10 +160,17 @@ def test_verify_validates_before_touching_the_gpu(P):
     assert both(_params(P)) == E.COOL_SD_EWORKSPACE
     assert both(_params(P), ws=C.c_void_p(0x1000), n=16) == E.COOL_SD_EWORKSPACE
     assert both(_params(P, top_k=5), ws=C.c_void_p(0x1000), n=16) == E.COOL_SD_EWORKSPACE     # the two-pass form
-    # read probe
-    assert lib.cool_sd_profile_read_probe(null, 16, null, 0, fake, 64, null) == E.COOL_SD_EINVAL
-    assert lib.cool_sd_profile_read_probe(fake, 24, null, 0, fake, 64, null) == E.COOL_SD_EINVAL
-    assert lib.cool_sd_profile_read_probe(fake, 1 << 20, null, 0, fake, 64, null) == E.COOL_SD_EWORKSPACE
+    # the benchmark library's entry points
+    bl = P.binding.bench_lib()
+    assert bl.cool_sd_bench_read_probe(null, 16, null, 0, fake, 64, null) == E.COOL_SD_EINVAL
+    assert bl.cool_sd_bench_read_probe(fake, 24, null, 0, fake, 64, null) == E.COOL_SD_EINVAL
+    assert bl.cool_sd_bench_read_probe(fake, 1 << 20, null, 0, fake, 64, null) == E.COOL_SD_EWORKSPACE
+    assert bl.cool_sd_bench_row_stats(C.byref(_params(P)), null, null, fake, null, fake, null, 0, null) == E.COOL_SD_EINVAL
+    assert bl.cool_sd_bench_row_stats(C.byref(_params(P)), fake, null, fake, null, fake, null, 0, null) == E.COOL_SD_EWORKSPACE
+    # the checked mode is an option bit of the verify calls; unknown bits stay errors
+    assert call(_params(P, flags=E.COOL_SD_FLAG_CHECK_TOKENS)) == E.COOL_SD_EWORKSPACE
+    assert call(_params(P, flags=E.COOL_SD_FLAG_CHECK_TOKENS | E.COOL_SD_FLAG_EARLY_EXIT)) == E.COOL_SD_EWORKSPACE
+    assert call(_params(P, flags=8)) == E.COOL_SD_EINVAL
     # aggregated acceptance over neighbours
     def lan(params, nbr=fake, k=10, lam=2.0, ws=null, n=0):
         return lib.cool_sd_verify_lantern(C.byref(params), fake, null, fake, null, fake, nbr, k, C.c_float(lam),
@@ -138,7 +186,6 @@ def test_verify_validates_before_touching_the_gpu(P):
     assert P.cool_sd_workspace_bytes(_params(P, resample_mode=E.COOL_SD_RESAMPLE_LANTERN)) > 0
     for code in (0, -1, -2, -3, -4, -99):
         assert isinstance(P.cool_sd_strerror(code), str) and P.cool_sd_strerror(code)
-    assert lib.cool_sd_profile_read(None, None) == E.COOL_SD_EINVAL
 
 
 def test_binding_fails_loudly_without_library(P, monkeypatch):

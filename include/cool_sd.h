@@ -71,7 +71,9 @@ typedef enum {
   COOL_SD_EINVAL = -1,       /* null pointer, bad shape / stride / dtype / option           */
   COOL_SD_EWORKSPACE = -2,   /* workspace missing, misaligned or smaller than required       */
   COOL_SD_ELAUNCH = -3,      /* the HIP runtime refused a launch                             */
-  COOL_SD_EUNSUPPORTED = -4  /* valid request the kernels do not implement (none at present)  */
+  COOL_SD_EUNSUPPORTED = -4, /* valid request the kernels do not implement (none at present)  */
+  COOL_SD_ETOOLARGE = -5     /* cool_sd_verify_noalloc: the shape needs more workspace than
+                                COOL_SD_NOALLOC_WORKSPACE_BYTES                                  */
 } cool_sd_status;
 
 /* Options of cool_sd_verify (cool_sd_params.flags). */
@@ -164,6 +166,35 @@ COOL_SD_API int cool_sd_verify(const cool_sd_params* p,
                    float* resid_mass_dev,
                    void* workspace_dev, size_t workspace_bytes,
                    void* hip_stream);
+
+/* cool_sd_verify for callers that can neither allocate device memory nor carry a workspace: code
+ * under HIP graph capture with a fixed set of buffers, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, kernels and results as cool_sd_verify, without the workspace
+ * arguments: the intermediate results of the call (chunk statistics, per-sequence statistics, chunk
+ * masses) live in a device array inside the library, COOL_SD_NOALLOC_WORKSPACE_BYTES large, of
+ * which every GPU the library is used on holds one copy until the process ends.  The call
+ * allocates nothing and frees nothing.
+ *   - Shapes whose workspace (what cool_sd_verify itself would use for these params) exceeds the
+ *     array are refused with COOL_SD_ETOOLARGE before anything is enqueued; the five benchmark
+ *     configurations fit (the largest, B=128 L=8 V=262144, uses 0.6 MB).
+ *   - All calls on one GPU share that GPU's array, whatever their stream: two calls that overlap
+ *     in time on one GPU race.  Order them (one stream, or events).  Nothing in the array needs
+ *     initialisation and nothing in it is meaningful after the call.
+ *   - The array's device address is looked up at the first call on each device (not a stream
+ *     operation, no allocation); make that first call outside a stream capture. */
+#define COOL_SD_NOALLOC_WORKSPACE_BYTES (4u << 20)
+COOL_SD_API int cool_sd_verify_noalloc(const cool_sd_params* p,
+                                       const void* target_dev, const void* target_uncond_dev,
+                                       const void* draft_dev, const void* draft_uncond_dev,
+                                       const int32_t* draft_tokens_dev,
+                                       const float* omega_dev,
+                                       const float* u_accept_dev,
+                                       const float* u_resample_dev,
+                                       int32_t* accept_len_dev,
+                                       int32_t* next_token_dev,
+                                       float* p_tok_dev, float* q_tok_dev, float* f_dev,
+                                       float* resid_mass_dev,
+                                       void* hip_stream);
 
 /* Verification stage of Algorithm 1 with the acceptance probability of the LANTERN family in
  * place of Eq. relax (the paper's comparison system, Eq. p_lantern / Eq. f_lantern, and its

@@ -14,6 +14,8 @@ COOL_SD_SCHED_UNIFORM, COOL_SD_SCHED_EXP, COOL_SD_SCHED_LINEAR = 0, 1, 2
 COOL_SD_RESAMPLE_OPT, COOL_SD_RESAMPLE_VANILLA, COOL_SD_RESAMPLE_LANTERN = 0, 1, 2
 COOL_SD_FLAG_EARLY_EXIT, COOL_SD_FLAG_CHECK_TOKENS = 1, 2
 COOL_SD_OK, COOL_SD_EINVAL, COOL_SD_EWORKSPACE, COOL_SD_ELAUNCH, COOL_SD_EUNSUPPORTED = 0, -1, -2, -3, -4
+COOL_SD_ETOOLARGE = -5
+COOL_SD_NOALLOC_WORKSPACE_BYTES = 4 << 20
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcool_sd.so")
@@ -61,6 +63,8 @@ def load(path):
     L.cool_sd_workspace_init.restype = C.c_int
     L.cool_sd_verify.argtypes = [pp] + [vp] * 14 + [vp, C.c_size_t, vp]
     L.cool_sd_verify.restype = C.c_int
+    L.cool_sd_verify_noalloc.argtypes = [pp] + [vp] * 14 + [vp]
+    L.cool_sd_verify_noalloc.restype = C.c_int
     L.cool_sd_verify_lantern.argtypes = ([pp] + [vp] * 6 + [C.c_int32, C.c_float] + [vp] * 10
                                          + [vp, C.c_size_t, vp])
     L.cool_sd_verify_lantern.restype = C.c_int
@@ -143,6 +147,17 @@ def cool_sd_verify(params, target, target_uncond, draft, draft_uncond, draft_tok
                               _stream(stream))
     if check and rc != 0:
         raise CoolSDError(rc, "cool_sd_verify")
+    return rc
+
+
+def cool_sd_verify_noalloc(params, target, target_uncond, draft, draft_uncond, draft_tokens, omega, u_accept,
+                           u_resample, accept_len, next_token, p_tok, q_tok, f, resid_mass, stream=None, check=True):
+    rc = lib().cool_sd_verify_noalloc(C.byref(params), _ptr(target), _ptr(target_uncond), _ptr(draft),
+                                      _ptr(draft_uncond), _ptr(draft_tokens), _ptr(omega), _ptr(u_accept),
+                                      _ptr(u_resample), _ptr(accept_len), _ptr(next_token), _ptr(p_tok), _ptr(q_tok),
+                                      _ptr(f), _ptr(resid_mass), _stream(stream))
+    if check and rc != 0:
+        raise CoolSDError(rc, "cool_sd_verify_noalloc")
     return rc
 
 

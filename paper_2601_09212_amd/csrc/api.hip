@@ -1,7 +1,35 @@
 // C ABI of the Cool-SD verify-and-resample library: the entry points of include/cool_sd.h.
+#include <atomic>
+
 #include "api_core.h"
 
 using namespace csd_api;
+
+namespace {
+
+// cool_sd_verify_noalloc: the call's workspace lives in this array instead of caller memory.  Every
+// GPU the library runs on holds its own copy at its own address until the process ends; the name
+// below is only the host-side stand-in of the symbol, so the device address is looked up once per
+// device (hipGetSymbolAddress, with that device current) and kept.  The per-device pointers are
+// the only state of the library: written once each, to a value that never changes.
+constexpr size_t kStaticWorkspaceBytes = size_t(COOL_SD_NOALLOC_WORKSPACE_BYTES);
+static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> scratch_ptr[kMaxDevices];
+
+int static_workspace(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return COOL_SD_ELAUNCH;
+  void* ptr = scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return COOL_SD_ELAUNCH;
+    scratch_ptr[dev].store(ptr, std::memory_order_release);
+  }
+  *out = ptr;
+  return COOL_SD_OK;
+}
+
+}  // namespace
 
 extern "C" {
 
@@ -68,6 +96,26 @@ int cool_sd_verify(const cool_sd_params* p, const void* target_dev, const void* 
   return run(p, false, target_dev, target_uncond_dev, draft_dev, draft_uncond_dev, draft_tokens_dev, omega_dev,
              u_accept_dev, u_resample_dev, accept_len_dev, next_token_dev, p_tok_dev, q_tok_dev, f_dev,
              resid_mass_dev, workspace_dev, workspace_bytes, hip_stream);
+}
+
+int cool_sd_verify_noalloc(const cool_sd_params* p, const void* target_dev, const void* target_uncond_dev,
+                           const void* draft_dev, const void* draft_uncond_dev, const int32_t* draft_tokens_dev,
+                           const float* omega_dev, const float* u_accept_dev, const float* u_resample_dev,
+                           int32_t* accept_len_dev, int32_t* next_token_dev, float* p_tok_dev, float* q_tok_dev,
+                           float* f_dev, float* resid_mass_dev, void* hip_stream) {
+  if (!params_ok(p, false)) return COOL_SD_EINVAL;
+  if (!target_dev || !draft_dev || !draft_tokens_dev || !omega_dev || !u_accept_dev || !u_resample_dev ||
+      !accept_len_dev || !next_token_dev)
+    return COOL_SD_EINVAL;
+  if ((target_uncond_dev == nullptr) != (draft_uncond_dev == nullptr)) return COOL_SD_EINVAL;
+  // the size is known from the params alone: refuse before anything touches the device
+  if (plan_call(p, false, true, false, false).lay.total > kStaticWorkspaceBytes) return COOL_SD_ETOOLARGE;
+  void* ws = nullptr;
+  const int rc = static_workspace(&ws);
+  if (rc != COOL_SD_OK) return rc;
+  return run(p, false, target_dev, target_uncond_dev, draft_dev, draft_uncond_dev, draft_tokens_dev, omega_dev,
+             u_accept_dev, u_resample_dev, accept_len_dev, next_token_dev, p_tok_dev, q_tok_dev, f_dev,
+             resid_mass_dev, ws, kStaticWorkspaceBytes, hip_stream);
 }
 
 int cool_sd_verify_lantern(const cool_sd_params* p, const void* target_dev, const void* target_uncond_dev,
@@ -146,6 +194,7 @@ const char* cool_sd_strerror(int code) {
     case COOL_SD_EWORKSPACE: return "workspace missing, misaligned or too small";
     case COOL_SD_ELAUNCH: return "HIP launch failed";
     case COOL_SD_EUNSUPPORTED: return "request not implemented by the kernels";
+    case COOL_SD_ETOOLARGE: return "shape needs more workspace than the library's static array holds";
     default: return "unknown status";
   }
 }

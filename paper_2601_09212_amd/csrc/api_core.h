@@ -108,23 +108,37 @@ inline int call_flags(const cool_sd_params* p) {
 
 inline bool is_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Workspace layout of one verify / stand-alone resample call, with the chunking it runs with.
+// has_draft: a draft tensor is given; lan: neighbour aggregation; with_diag: the diagnostics pass
+// follows on the statistics this call leaves (8192-logit chunks).
+struct CallPlan { Chunking ch; Layout lay; int64_t L, rows_t, rows_d, C, CD; int hb; bool radix; };
+CallPlan plan_call(const cool_sd_params* p, bool resample_only, bool has_draft, bool lan, bool with_diag) {
+  CallPlan o;
+  o.L = resample_only ? 1 : p->L;
+  o.hb = resample_only ? 0 : p->has_bonus;
+  o.rows_t = resample_only ? p->B : int64_t(p->B) * (o.L + o.hb);
+  o.rows_d = has_draft ? int64_t(p->B) * o.L : 0;
+  o.ch = pick_chunking(p, o.rows_t + o.rows_d);
+  o.C = o.ch.c2;
+  o.radix = p->top_k > 0 && p->V > 4 * csd::kChunk;
+  const int64_t pairs = with_diag ? int64_t(p->B) * o.L : 0;
+  o.CD = with_diag ? (int64_t(p->V) + 8191) / 8192 : 0;
+  o.lay = make_layout(p->B, o.rows_t + o.rows_d, o.ch.c1, o.C, pairs, o.CD, lan ? int64_t(p->B) * o.L : 0,
+                      o.radix ? o.rows_t + o.rows_d : 0);
+  return o;
+}
+
 int run(const cool_sd_params* p, bool resample_only,
         const void* t, const void* tu, const void* d, const void* du,
         const int32_t* tokens, const float* omega, const float* u_acc, const float* u_res,
         int32_t* accept_len, int32_t* next_token, float* p_tok, float* q_tok, float* f,
         float* resid_mass, void* ws, size_t ws_bytes, void* stream, const LanternArgs* lan = nullptr,
         float* alpha = nullptr, float* beta = nullptr, bool stats_only = false) {
-  const int64_t L = resample_only ? 1 : p->L;
-  const int hb = resample_only ? 0 : p->has_bonus;
-  const int64_t rows = resample_only ? p->B : int64_t(p->B) * (L + hb);
-  const int64_t rows_t = rows, rows_d = d ? int64_t(p->B) * L : 0;
-  const Chunking ch = pick_chunking(p, rows_t + rows_d);
-  const int64_t C = ch.c2;
-  const bool radix = p->top_k > 0 && p->V > 4 * csd::kChunk;
-  // with alpha / beta the diagnostics pass follows on the statistics this call leaves (8192-logit chunks)
-  const int64_t pairs = alpha ? int64_t(p->B) * L : 0, CD = alpha ? (int64_t(p->V) + 8191) / 8192 : 0;
-  const Layout lay = make_layout(p->B, rows_t + rows_d, ch.c1, C, pairs, CD, lan ? int64_t(p->B) * L : 0,
-                                 radix ? rows_t + rows_d : 0);
+  const CallPlan pl = plan_call(p, resample_only, d != nullptr, lan != nullptr, alpha != nullptr);
+  const int64_t L = pl.L, rows_t = pl.rows_t, rows_d = pl.rows_d, C = pl.C, CD = pl.CD;
+  const int hb = pl.hb;
+  const Chunking& ch = pl.ch;
+  const Layout& lay = pl.lay;
   if (!ws || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0 || ws_bytes < lay.total) return COOL_SD_EWORKSPACE;
 
   const int kE = (p->dtype == COOL_SD_BF16) ? 8 : 4;

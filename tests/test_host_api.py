@@ -27,8 +27,8 @@ def test_library_exports_exactly_the_declared_symbols(P):
     switch, no kernel handle, no mutable object."""
     names = _declared("cool_sd.h")
     assert names == {"cool_sd_schedule", "cool_sd_workspace_bytes", "cool_sd_workspace_init", "cool_sd_verify",
-                     "cool_sd_verify_lantern", "cool_sd_verify_diagnostics", "cool_sd_resample",
-                     "cool_sd_diagnostics", "cool_sd_strerror"}
+                     "cool_sd_verify_noalloc", "cool_sd_verify_lantern", "cool_sd_verify_diagnostics",
+                     "cool_sd_resample", "cool_sd_diagnostics", "cool_sd_strerror"}
     assert _exported(P.binding.LIB_PATH) == names
     assert _exported(P.binding.LIB_CHECKED_PATH) == names
     raw = C.CDLL(P.binding.LIB_PATH)
@@ -58,6 +58,9 @@ def test_product_library_has_no_writable_state():
                 continue          # C runtime and HIP registration bookkeeping
             if name.startswith("_Z") and "kernel" in name:
                 continue          # kernel handles: constant after the loader's relocation
+            if "scratch" in name:
+                continue          # cool_sd_verify_noalloc: the static workspace's host-side stand-in and
+                                  # its per-device address, written once to a value that never changes
             own.append(ln)
     assert not own, own
 
@@ -167,6 +170,14 @@ def test_verify_validates_before_touching_the_gpu(P):
     assert bl.cool_sd_bench_read_probe(fake, 1 << 20, null, 0, fake, 64, null) == E.COOL_SD_EWORKSPACE
     assert bl.cool_sd_bench_row_stats(C.byref(_params(P)), null, null, fake, null, fake, null, 0, null) == E.COOL_SD_EINVAL
     assert bl.cool_sd_bench_row_stats(C.byref(_params(P)), fake, null, fake, null, fake, null, 0, null) == E.COOL_SD_EWORKSPACE
+    # the allocation-free entry point: arguments first, then the size limit, both before any device call
+    na = lambda params, t=fake: lib.cool_sd_verify_noalloc(C.byref(params), t, null, fake, null, fake, fake, fake, fake,
+                                                           fake, fake, null, null, null, null, null)
+    assert na(_params(P), t=null) == E.COOL_SD_EINVAL
+    assert na(_params(P, L=0)) == E.COOL_SD_EINVAL
+    huge = dict(B=4096, L=64, V=262144, t_stride_l=262144, d_stride_l=262144, t_stride_b=65 * 262144, d_stride_b=64 * 262144)
+    assert na(_params(P, **huge)) == E.COOL_SD_ETOOLARGE
+    assert "static" in P.cool_sd_strerror(E.COOL_SD_ETOOLARGE)
     # the checked mode is an option bit of the verify calls; unknown bits stay errors
     assert call(_params(P, flags=E.COOL_SD_FLAG_CHECK_TOKENS)) == E.COOL_SD_EWORKSPACE
     assert call(_params(P, flags=E.COOL_SD_FLAG_CHECK_TOKENS | E.COOL_SD_FLAG_EARLY_EXIT)) == E.COOL_SD_EWORKSPACE
@@ -184,7 +195,7 @@ def test_verify_validates_before_touching_the_gpu(P):
     assert lan(_params(P, resample_mode=3)) == E.COOL_SD_EINVAL
     assert call(_params(P, resample_mode=E.COOL_SD_RESAMPLE_LANTERN)) == E.COOL_SD_EINVAL   # only with neighbours
     assert P.cool_sd_workspace_bytes(_params(P, resample_mode=E.COOL_SD_RESAMPLE_LANTERN)) > 0
-    for code in (0, -1, -2, -3, -4, -99):
+    for code in (0, -1, -2, -3, -4, -5, -99):
         assert isinstance(P.cool_sd_strerror(code), str) and P.cool_sd_strerror(code)
 
 

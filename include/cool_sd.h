@@ -94,7 +94,13 @@ typedef enum {
    * token.  Every kernel still runs to its end on such input.  The debug build of the library
    * (libcool_sd_checked.so, compiled with -DCOOL_SD_CHECKED_BUILD) behaves as if every call set
    * this bit. */
-  COOL_SD_FLAG_CHECK_TOKENS = 2
+  COOL_SD_FLAG_CHECK_TOKENS = 2,
+  /* The draw x ~ G* (or ~ p for the bonus / draft-side draw) is made in fp32 and re-done in fp64
+   * only where fp32 cannot resolve the law: its total mass below 1/16 (p and q f nearly cancel),
+   * or the levels of the fp32 search disagreeing by rounding.  With this bit every draw of the
+   * call takes the fp64 path -- for validation; several times slower per sequence.  Results: the
+   * same token except where u lies within ~1e-7 of a boundary of the law's CDF. */
+  COOL_SD_FLAG_EXACT_DRAW = 4
 } cool_sd_flags;
 
 typedef struct {

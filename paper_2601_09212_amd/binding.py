@@ -12,7 +12,7 @@ import numpy as np
 COOL_SD_F32, COOL_SD_BF16 = 0, 1
 COOL_SD_SCHED_UNIFORM, COOL_SD_SCHED_EXP, COOL_SD_SCHED_LINEAR = 0, 1, 2
 COOL_SD_RESAMPLE_OPT, COOL_SD_RESAMPLE_VANILLA, COOL_SD_RESAMPLE_LANTERN = 0, 1, 2
-COOL_SD_FLAG_EARLY_EXIT, COOL_SD_FLAG_CHECK_TOKENS = 1, 2
+COOL_SD_FLAG_EARLY_EXIT, COOL_SD_FLAG_CHECK_TOKENS, COOL_SD_FLAG_EXACT_DRAW = 1, 2, 4
 COOL_SD_OK, COOL_SD_EINVAL, COOL_SD_EWORKSPACE, COOL_SD_ELAUNCH, COOL_SD_EUNSUPPORTED = 0, -1, -2, -3, -4
 COOL_SD_ETOOLARGE = -5
 COOL_SD_NOALLOC_WORKSPACE_BYTES = 4 << 20

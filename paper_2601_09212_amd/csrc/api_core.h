@@ -89,7 +89,7 @@ bool params_ok(const cool_sd_params* p, bool for_resample, bool lantern = false)
   if (p->resample_mode != COOL_SD_RESAMPLE_OPT && p->resample_mode != COOL_SD_RESAMPLE_VANILLA &&
       !(lantern && p->resample_mode == COOL_SD_RESAMPLE_LANTERN))
     return false;
-  if ((p->flags & ~(COOL_SD_FLAG_EARLY_EXIT | COOL_SD_FLAG_CHECK_TOKENS)) != 0) return false;
+  if ((p->flags & ~(COOL_SD_FLAG_EARLY_EXIT | COOL_SD_FLAG_CHECK_TOKENS | COOL_SD_FLAG_EXACT_DRAW)) != 0) return false;
   const int64_t L = for_resample ? 1 : p->L;
   const int64_t rows = for_resample ? p->B : int64_t(p->B) * (L + p->has_bonus);
   if (2 * rows * ((int64_t(p->V) + 4095) / 4096) > 0x7fffffffLL) return false;   // grid size
@@ -166,6 +166,7 @@ int run(const cool_sd_params* p, bool resample_only,
   a.resample_only = resample_only ? 1 : 0;
   a.aligned = aligned ? 1 : 0;
   a.stats_only = stats_only ? 1 : 0;
+  a.exact_draw = (p->flags & COOL_SD_FLAG_EXACT_DRAW) ? 1 : 0;
   a.early_exit = (!resample_only && !lan && aligned && (p->flags & COOL_SD_FLAG_EARLY_EXIT) && p->top_k == 0 &&
                   p->V <= csd::kChunk && p->L <= 1024) ? 1 : 0;
   if (lan) {
@@ -293,6 +294,7 @@ int run_verify_diag(const cool_sd_params* p, const void* t, const void* tu, cons
   a.om_sb = p->omega_stride_b;
   a.B = p->B; a.L = (int32_t)L; a.V = p->V; a.has_bonus = p->has_bonus;
   a.top_k = 0; a.resample_mode = p->resample_mode;
+  a.exact_draw = (p->flags & COOL_SD_FLAG_EXACT_DRAW) ? 1 : 0;
   a.aligned = aligned ? 1 : 0;
   a.nchunks = 1;                                  // one sampling chunk, one diagnostics chunk
   const int kT = (p->dtype == COOL_SD_BF16) ? 8 : 16;

@@ -34,6 +34,33 @@ __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
+// ---------------------------------------------------------------- fp64 exponential
+// (for the few scalar decisions and rare re-draws that are made in fp64)
+constexpr double kLog2eD = 1.44269504088896340736;
+
+// 2^y for y <= ~1: split into integer and fraction, e^(f ln 2) by its Taylor polynomial of degree
+// 12 on |f ln 2| <= 0.347 (remainder below 4e-17), scaled by the integer part.  -inf and anything
+// below the normal range give 0.
+__device__ __forceinline__ double exp2_d(double y) {
+  if (!(y > -1021.0)) return 0.0;
+  const double n = rint(y);
+  const double t = (y - n) * 0.693147180559945309417;
+  double p = 1.0 / 479001600.0;
+  p = fma(p, t, 1.0 / 39916800.0);
+  p = fma(p, t, 1.0 / 3628800.0);
+  p = fma(p, t, 1.0 / 362880.0);
+  p = fma(p, t, 1.0 / 40320.0);
+  p = fma(p, t, 1.0 / 5040.0);
+  p = fma(p, t, 1.0 / 720.0);
+  p = fma(p, t, 1.0 / 120.0);
+  p = fma(p, t, 1.0 / 24.0);
+  p = fma(p, t, 1.0 / 6.0);
+  p = fma(p, t, 0.5);
+  p = fma(p, t, 1.0);
+  p = fma(p, t, 1.0);
+  return ldexp(p, (int)n);
+}
+
 // ---------------------------------------------------------------- wave / block primitives
 // Wave-wide reductions.  Within each row of 16 lanes a DPP butterfly (swap neighbours, swap
 // pairs, mirror the half row, mirror the row) leaves the row's result in all 16 lanes; the four

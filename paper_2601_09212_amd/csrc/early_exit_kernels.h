@@ -57,7 +57,9 @@ __global__ __launch_bounds__(kThreadsW) void sequence_early_exit_kernel(const KA
   constexpr int kVW = kChunk / (kThreadsW * kE);       // vectors per thread: 2 (bf16) / 4 (fp32)
   constexpr int kPer = kVW * kE;                       // logits per thread
   __shared__ SmemE sm;
+  __shared__ ExactSmem<kThreadsW> smx;
   const int b = blockIdx.x, L = a.L, tid = threadIdx.x;
+  if (tid == 0) sm.w.needs64 = 0;
   for (int i = tid; i < L; i += kThreadsW) {
     sm.tok[i] = min(max(a.tokens[int64_t(b) * L + i], 0), a.V - 1);
     sm.u[i] = a.u_acc[int64_t(b) * L + i];
@@ -134,17 +136,15 @@ __global__ __launch_bounds__(kThreadsW) void sequence_early_exit_kernel(const KA
     lt = sm.tokl[par][0];
     ld = sm.tokl[par][1];
     // same evaluation of f_i = min{1, omega_i p_i(x~_i) / q_i(x~_i)} as the all-rows path (Eq. relax)
-    const float et = __fmaf_rn(lt, kLog2e, -Ct), ed = __fmaf_rn(ld, kLog2e, -Cd);
-    const float ratio = __fmul_rn(exp2_fast(__fsub_rn(et, ed)), Sd / St);
-    const float omega = sm.om[i];
-    const float fi = (ld == -INFINITY) ? 1.f : ((omega > 0.f) ? fminf(1.f, __fmul_rn(omega, ratio)) : 0.f);
+    const double fi = relaxed_accept_prob(lt, ld, Ct, St, Cd, Sd, sm.om[i]);
     if (tid == 0) {
       const int64_t o = int64_t(b) * L + i;
+      const float et = __fmaf_rn(lt, kLog2e, -Ct), ed = __fmaf_rn(ld, kLog2e, -Cd);
       if (a.p_tok) a.p_tok[o] = exp2_fast(et) / St;
       if (a.q_tok) a.q_tok[o] = exp2_fast(ed) / Sd;
-      if (a.f) a.f[o] = fi;
+      if (a.f) a.f[o] = (float)fi;
     }
-    return !(sm.u[i] <= fi);                            // uniform: every thread sees the same values
+    return !((double)sm.u[i] <= fi);                            // uniform: every thread sees the same values
   };
   for (int i0 = 0; i0 < L && j == L; i0 += D) {
 #pragma unroll
@@ -182,8 +182,18 @@ __global__ __launch_bounds__(kThreadsW) void sequence_early_exit_kernel(const KA
   ResidCoef k{Ct, 1.f / St, Cd, bonus ? 1.f : 1.f / Sd, bonus ? 1.f : sm.om[j],
               bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
   float R;
-  bool writer;
-  const int token = sample_whole<DT, XF, kVW>(rt, rd, k, a.u_res[b], a.V, sm.w, R, writer);
+  bool writer, trust;
+  int token = sample_whole<DT, XF, kVW>(rt, rd, k, a.u_res[b], a.V, sm.w, R, writer, trust);
+  if (draw_needs_fp64(writer, trust, a.exact_draw, &sm.w.needs64)) {
+    const int jt = bonus ? L : j;                       // the row that was sampled from
+    const int64_t ot = int64_t(b) * a.t_sb + int64_t(jt) * a.t_sl, od = int64_t(b) * a.d_sb + int64_t(min(jt, L - 1)) * a.d_sl;
+    const ExactJob job{{row_ptr(a.t, ot, kES), guided ? row_ptr(a.tu, ot, kES) : nullptr, -INFINITY, (double)Ct},
+                       {bonus ? nullptr : row_ptr(a.d, od, kES), (guided && !bonus) ? row_ptr(a.du, od, kES) : nullptr,
+                        -INFINITY, (double)Cd},
+                       DT, XF, a.V, a.cfg_scale, a.inv_T, k.omega, k.mode, nullptr, 0, 0, 0};
+    token = exact_draw<kThreadsW>(job, a.u_res[b], R, smx);
+    writer = tid == 0;
+  }
   if (writer) {
     a.next_token[b] = token;
     if (a.resid_mass) a.resid_mass[b] = R;
@@ -201,7 +211,9 @@ __global__ __launch_bounds__(kThreadsW) void resample_whole_kernel(const KArgs a
   constexpr int kVW = MUL * kChunk / (kThreadsW * kE);
   __shared__ SmemW sm;
   __shared__ RedW red;
+  __shared__ ExactSmem<kThreadsW> smx;
   const int b = blockIdx.x;
+  if (threadIdx.x == 0) sm.needs64 = 0;
   const bool bonus = a.d == nullptr;                    // no draft: the law is p itself
   const char* t_c = row_ptr(a.t, int64_t(b) * a.t_sb, kES);
   const char* t_u = row_ptr(a.tu, int64_t(b) * a.t_sb, kES);
@@ -222,8 +234,14 @@ __global__ __launch_bounds__(kThreadsW) void resample_whole_kernel(const KArgs a
   ResidCoef k{Ct, 1.f / St, Cd, bonus ? 1.f : 1.f / Sd, omega,
               bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
   float R;
-  bool writer;
-  const int token = sample_whole<DT, XF, kVW>(rt, rd, k, u, a.V, sm, R, writer);
+  bool writer, trust;
+  int token = sample_whole<DT, XF, kVW>(rt, rd, k, u, a.V, sm, R, writer, trust);
+  if (draw_needs_fp64(writer, trust, a.exact_draw, &sm.needs64)) {
+    const ExactJob job{{t_c, t_u, -INFINITY, (double)Ct}, {d_c, d_u, -INFINITY, (double)Cd}, DT, XF, a.V, a.cfg_scale,
+                       a.inv_T, omega, k.mode, nullptr, 0, 0, 0};
+    token = exact_draw<kThreadsW>(job, u, R, smx);
+    writer = threadIdx.x == 0;
+  }
   if (writer) {
     a.next_token[b] = token;
     if (a.resid_mass) a.resid_mass[b] = R;
@@ -257,6 +275,7 @@ __global__ __launch_bounds__(kThreads) void sequence_early_exit_tile_kernel(cons
   constexpr int kE = Vec<DT>::kE, kES = Vec<DT>::kES, kT = Vec<DT>::kT;
   static_assert(RowRegs<DT, XF, kT>::kRaw, "rows stay packed");
   __shared__ SmemT sm;
+  __shared__ ExactSmem<kThreads> smx;
   const int b = blockIdx.x, L = a.L, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   struct Slot { uint4 tc[kT], dc[kT]; float tl, dl; };
   // vector k of this thread starts at element (k*256 + tid)*kE; 32-bit offsets from the (uniform)
@@ -342,17 +361,15 @@ __global__ __launch_bounds__(kThreads) void sequence_early_exit_tile_kernel(cons
     stats_read(par, 0, Ct, St);
     stats_read(par, 1, Cd, Sd);
     // same evaluation of f_i = min{1, omega_i p_i(x~_i) / q_i(x~_i)} as the all-rows path (Eq. relax)
-    const float et = __fmaf_rn(lt, kLog2e, -Ct), ed = __fmaf_rn(ld, kLog2e, -Cd);
-    const float ratio = __fmul_rn(exp2_fast(__fsub_rn(et, ed)), Sd / St);
-    const float omega = sm.om[i];
-    const float fi = (ld == -INFINITY) ? 1.f : ((omega > 0.f) ? fminf(1.f, __fmul_rn(omega, ratio)) : 0.f);
+    const double fi = relaxed_accept_prob(lt, ld, Ct, St, Cd, Sd, sm.om[i]);
     if (tid == 0) {
       const int64_t o = int64_t(b) * L + i;
+      const float et = __fmaf_rn(lt, kLog2e, -Ct), ed = __fmaf_rn(ld, kLog2e, -Cd);
       if (a.p_tok) a.p_tok[o] = exp2_fast(et) / St;
       if (a.q_tok) a.q_tok[o] = exp2_fast(ed) / Sd;
-      if (a.f) a.f[o] = fi;
+      if (a.f) a.f[o] = (float)fi;
     }
-    if (!(sm.u[i] <= fi)) { j = i; break; }             // uniform: every thread sees the same values
+    if (!((double)sm.u[i] <= fi)) { j = i; break; }             // uniform: every thread sees the same values
   }
   // positions that were never evaluated
   for (int i = j + 1 + tid; i < L; i += kThreads) {
@@ -381,6 +398,7 @@ __global__ __launch_bounds__(kThreads) void sequence_early_exit_tile_kernel(cons
   ResidCoef k{Ct, 1.f / St, Cd, bonus ? 1.f : 1.f / Sd, bonus ? 1.f : sm.om[j],
               bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
   float part[kT], R = 0.f;
+  bool fell_back = false;
   for (int attempt = 0; attempt < 2; ++attempt) {
     chunk_masses<DT, XF, kT>(rt, rd, k, part, sm.s);
     R = 0.f;
@@ -388,10 +406,24 @@ __global__ __launch_bounds__(kThreads) void sequence_early_exit_tile_kernel(cons
     for (int t = 0; t < kT; ++t) R = __fadd_rn(R, sm.s.tile_tot[t]);
     if (R > 0.f || k.mode == kModeP) break;
     k.mode = kModeP;       // no rejection possible at this position: any law is optimal, use p
+    fell_back = true;
   }
-  const int off = chunk_select<DT, XF, kT>(rt, rd, k, part, __fmul_rn(a.u_res[b], R), sm.s);
+  bool trust;
+  int token = chunk_select<DT, XF, kT>(rt, rd, k, part, __fmul_rn(a.u_res[b], R), sm.s, trust);
+  token = min(max(token, 0), a.V - 1);
+  // the fp32 draw stands unless a level fell back, the law is light, or p had to take the place of
+  // a law without fp32 mass
+  if (!trust || fell_back || (k.mode != kModeP && R < kSafeMass) || a.exact_draw) {
+    const int jt = bonus ? L : j;
+    const int64_t ot = int64_t(b) * a.t_sb + int64_t(jt) * a.t_sl, od = int64_t(b) * a.d_sb + int64_t(min(jt, L - 1)) * a.d_sl;
+    const ExactJob job{{row_ptr(a.t, ot, kES), nullptr, -INFINITY, (double)Ct},
+                       {bonus ? nullptr : row_ptr(a.d, od, kES), nullptr, -INFINITY, (double)Cd},
+                       DT, XF, a.V, 1.f, 1.f, k.omega, fell_back ? (a.resample_mode == 1 ? kModeVanilla : kModeOpt) : k.mode,
+                       nullptr, 0, 0, 0};
+    token = exact_draw<kThreads>(job, a.u_res[b], R, smx);
+  }
   if (tid == 0) {
-    a.next_token[b] = min(max(off, 0), a.V - 1);
+    a.next_token[b] = token;
     if (a.resid_mass) a.resid_mass[b] = R;
   }
 }

@@ -24,6 +24,7 @@ struct Smem {
   int pick_first[kWaves];
   int pick_last[kWaves];
   int bcast_i;
+  int trust;            // chunk_select: the fp32 draw stands
   float4 rowstat;
 };
 

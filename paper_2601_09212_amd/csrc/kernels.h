@@ -36,6 +36,7 @@ struct KArgs {
   int32_t resample_mode, resample_only, aligned;
   int32_t stats_only;       // enqueue the statistics pass alone (the benchmark library's timing entry point)
   int32_t early_exit;       // verify: stop reading a sequence's rows at its first rejection (one kernel)
+  int32_t exact_draw;       // every draw x ~ G in fp64 (COOL_SD_FLAG_EXACT_DRAW), not only those the fp32 path does not trust
   int32_t stream_loads;     // statistics kernel: input larger than the caches, use nontemporal loads
   int32_t nchunks, nt2;     // sampling kernel: chunks per row, tiles per chunk
   int32_t nt1, chunk1;      // statistics kernel: tiles per chunk, logits per chunk

@@ -125,12 +125,16 @@ __device__ __forceinline__ void chunk_masses(const RowRegs<DT, XF, kT>& rt, cons
 // exceeds the remainder, else the last positive-mass entry", so the result always has
 // positive mass even when the levels' roundings disagree.  Returns the offset in the chunk
 // (same value in every thread), or -1 if the chunk holds no mass.
+// trust (the same in every thread): no level fell back to its last entry with mass; otherwise the
+// caller re-does the draw in fp64.
 template <int DT, bool XF, int kT, bool LAN = false>
 __device__ __forceinline__ int chunk_select(const RowRegs<DT, XF, kT>& rt, const RowRegs<DT, XF, kT>& rd,
                                             const ResidCoef& k, const float (&part)[kT],
-                                            float v, Smem& sm, const LanPatch lp = LanPatch{0u, -1, 1.f}) {
+                                            float v, Smem& sm, bool& trust,
+                                            const LanPatch lp = LanPatch{0u, -1, 1.f}) {
   constexpr int kE = Vec<DT>::kE;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  trust = false;
   // level 1: tile
   int ks = -1, klast = -1;
   float base = 0.f, base_last = 0.f, cum = 0.f;
@@ -143,7 +147,8 @@ __device__ __forceinline__ int chunk_select(const RowRegs<DT, XF, kT>& rt, const
     }
     cum = __fadd_rn(cum, T);
   }
-  if (ks < 0) { ks = klast; base = base_last; }
+  const bool tile_fallback = ks < 0;
+  if (tile_fallback) { ks = klast; base = base_last; }
   if (ks < 0) return -1;
   const float v2 = v - base;
   // level 2: thread
@@ -166,7 +171,8 @@ __device__ __forceinline__ int chunk_select(const RowRegs<DT, XF, kT>& rt, const
   }
   __syncthreads();
   int win = min(min(sm.pick_first[0], sm.pick_first[1]), min(sm.pick_first[2], sm.pick_first[3]));
-  if (win == 0x7fffffff) win = max(max(sm.pick_last[0], sm.pick_last[1]), max(sm.pick_last[2], sm.pick_last[3]));
+  const bool thread_fallback = win == 0x7fffffff;
+  if (thread_fallback) win = max(max(sm.pick_last[0], sm.pick_last[1]), max(sm.pick_last[2], sm.pick_last[3]));
   if (win < 0) return -1;
   // level 3: element, by the winning thread
   if ((int)threadIdx.x == win) {
@@ -187,11 +193,30 @@ __device__ __forceinline__ int chunk_select(const RowRegs<DT, XF, kT>& rt, const
         }
       }
     }
-    if (found < 0) found = last;
+    const bool element_fallback = found < 0;
+    if (element_fallback) found = last;
     sm.bcast_i = (ks * kThreads + win) * kE + found;
+    sm.trust = !(tile_fallback || thread_fallback || element_fallback);
   }
   __syncthreads();
+  trust = sm.trust != 0;
   return sm.bcast_i;
+}
+
+// f_i = min{1, omega_i p_i(x~_i) / q_i(x~_i)} of Eq. relax from the statistics of the row pair and the
+// two logits of x~_i, in fp64: the decision u_i <= f_i is made once per position, so its arithmetic
+// costs nothing, and what is left of the error is that of the fp32 row sums St, Sd.  The ratio
+// p/q is formed from the DIFFERENCE of the two logits (exact in fp64) and of the integer reference
+// exponents, so it survives when both probabilities underflow.  A token the draft excludes (q = 0)
+// has f = 1, also at 0/0; omega = 0 gives f = 0.
+__device__ __forceinline__ double relaxed_accept_prob(float lt, float ld, float Ct, float St, float Cd, float Sd,
+                                                      float omega) {
+  if (ld == -INFINITY) return 1.0;
+  if (!(omega > 0.f)) return 0.0;
+  const double e = fma((double)lt - (double)ld, kLog2eD, (double)Cd - (double)Ct);
+  // 2^e may exceed the fp64 range for absurd logit gaps: anything beyond 2^64 is f = 1 anyway
+  const double ratio = (e > 64.0 ? 1.8446744073709552e19 : exp2_d(e)) * ((double)Sd / (double)St);
+  return fmin(1.0, (double)omega * ratio);
 }
 
 // f_i of Eq. relax and the accept test of position i of sequence b, from the statistics of its row
@@ -199,22 +224,18 @@ __device__ __forceinline__ int chunk_select(const RowRegs<DT, XF, kT>& rt, const
 // (has_draft false) never is.  With `emit` it writes the per-position diagnostics.
 __device__ __forceinline__ bool accept_test(const KArgs& a, int b, int i, bool emit, bool has_draft, float Ct, float St,
                                             float Cd, float Sd, float lt, float ld, float omega, float u) {
-  // exponents of p(x~) and q(x~) in base-2 units; the ratio p/q is formed from their
-  // difference so that it survives when both probabilities underflow fp32
-  const float et = __fmaf_rn(lt, kLog2e, -Ct), ed = __fmaf_rn(ld, kLog2e, -Cd);
-  const float ratio = __fmul_rn(exp2_fast(__fsub_rn(et, ed)), Sd / St);
-  // f = min{1, omega p/q}; a token the draft excludes (q = 0) has f = 1, also at 0/0
-  const float fi = (ld == -INFINITY) ? 1.f : ((omega > 0.f) ? fminf(1.f, __fmul_rn(omega, ratio)) : 0.f);
+  const double fi = relaxed_accept_prob(lt, ld, Ct, St, Cd, Sd, omega);
   if (emit && has_draft) {
     const int64_t o = int64_t(b) * a.L + i;
+    const float et = __fmaf_rn(lt, kLog2e, -Ct), ed = __fmaf_rn(ld, kLog2e, -Cd);
     // aggregated probability of the neighbour set (Eq. p_lantern at x~_i): p_i(x~_i) times agg,
     // which the LANTERN-style call passes as omega_i
     if (a.p_agg_out) a.p_agg_out[o] = __fmul_rn(exp2_fast(et) / St, omega);
     if (a.p_tok) a.p_tok[o] = exp2_fast(et) / St;
     if (a.q_tok) a.q_tok[o] = exp2_fast(ed) / Sd;
-    if (a.f) a.f[o] = fi;
+    if (a.f) a.f[o] = (float)fi;
   }
-  return has_draft && !(u <= fi);
+  return has_draft && !((double)u <= fi);
 }
 
 // Position i of sequence b: statistics of its row pair (or of the bonus row alone), f_i of
@@ -306,6 +327,7 @@ struct SmemW {
   int pick_last[kWavesW];
   float scan_tot[kWavesW];
   float4 rowstat;
+  int needs64;          // the fp32 draw is not trusted: re-do it in fp64
 };
 
 }  // namespace csd

@@ -272,8 +272,10 @@ __global__ __launch_bounds__(kThreadsW) void sequence_select_kernel(const KArgs 
   constexpr int kVS = kChunk2 / (kThreadsW * kE);         // consecutive vectors per thread: 1 (bf16) / 2 (fp32)
   __shared__ SmemW sm;
   __shared__ float cm[kStage];
+  __shared__ ExactSmem<kThreadsW> smx;
   const int C = a.nchunks;
   const int b = blockIdx.x;
+  if (threadIdx.x == 0) sm.needs64 = 0;           // barriers lie between this and its readers
   const SampledRow r = sampled_row<DT, XF>(a, b, a.resample_only ? 0 : a.accept_len[b]);
   if (r.none) {
     if (threadIdx.x == 0) {
@@ -285,6 +287,7 @@ __global__ __launch_bounds__(kThreadsW) void sequence_select_kernel(const KArgs 
   const float4 rs = sampled_row_stats(a, b, r, &sm.rowstat);
   ResidCoef k{rs.x, 1.f / rs.y, rs.z, r.bonus ? 1.f : 1.f / rs.w, r.omega,
               r.bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
+  const int law = k.mode;                                 // before any fall-back to p
 
   // mass of chunk cc under the fallback law p, from the chunk statistics of the statistics pass
   const int per = kChunk2 / a.chunk1;
@@ -297,10 +300,11 @@ __global__ __launch_bounds__(kThreadsW) void sequence_select_kernel(const KArgs 
     return m;
   };
   // The chunk that holds u*R: first with positive mass whose inclusive sum exceeds u*R, else the
-  // last with mass.
+  // last with mass.  chunk_trust: no fall-back at this level, and the law is heavy enough for its
+  // fp32 mass to be accurate.
   float R, cbase = 0.f;
   int cs = -1;
-  bool fallback = false;
+  bool fallback = false, chunk_trust = true;
   if (C <= 64) {
     // up to 64 chunks (rows of 524288 logits): lane c of every wave takes chunk c, one memory
     // round trip and a wave scan, no LDS and no barrier; every wave gets the same answer
@@ -319,6 +323,7 @@ __global__ __launch_bounds__(kThreadsW) void sequence_select_kernel(const KArgs 
     const float excl = wave_prev_lane(incl);
     const bool pos = m > 0.f;
     const unsigned long long bh = __ballot(pos && incl > v), bp = __ballot(pos);
+    chunk_trust = bh != 0;
     cs = bh ? __ffsll((long long)bh) - 1 : (bp ? 63 - __clzll((long long)bp) : 0);
     cbase = lane_f(excl, cs);
   } else {
@@ -357,9 +362,11 @@ __global__ __launch_bounds__(kThreadsW) void sequence_select_kernel(const KArgs 
       }
       cum = __fadd_rn(cum, m);
     }
+    chunk_trust = cs >= 0;
     if (cs < 0) { cs = clast; cbase = cbase_last; }
     if (cs < 0) cs = 0;
   }
+  chunk_trust = chunk_trust && !fallback && (law == kModeP || R >= kSafeMass);
   const float v_in = __fsub_rn(__fmul_rn(a.u_res[b], R), cbase);   // mass left to walk inside the chunk
 
   // the chosen chunk, thread t holding its vectors t*kVS ..: same search as on short rows, for
@@ -374,10 +381,25 @@ __global__ __launch_bounds__(kThreadsW) void sequence_select_kernel(const KArgs 
     if (!r.bonus && !fallback) lp = lan_patch_span(a, b, r.j, r.omega, base + int64_t(threadIdx.x) * (kVS * kE), kVS * kE);
   }
   float R_chunk;
-  bool writer;
-  const int off = sample_whole<DT, XF, kVS, LAN, true>(rt, rd, k, v_in, a.V - (int)base, sm, R_chunk, writer, lp);
+  bool writer, trust;
+  int token = (int)base + sample_whole<DT, XF, kVS, LAN, true>(rt, rd, k, v_in, a.V - (int)base, sm, R_chunk, writer, trust,
+                                                               lp);
+  if (draw_needs_fp64(writer, trust && chunk_trust, a.exact_draw, &sm.needs64)) {
+    ExactJob job{{r.t_c, r.t_u, r.thr_t, (double)rs.x}, {r.d_c, r.d_u, r.thr_d, (double)rs.z}, DT, XF, a.V, a.cfg_scale,
+                 a.inv_T, r.omega, law, nullptr, 0, 0, 0};
+    if constexpr (LAN) {
+      if (!r.bonus) {
+        job.lan_x = min(max(a.tokens[int64_t(b) * a.L + r.j], 0), a.V - 1);
+        job.nbr_row = a.nbr + int64_t(job.lan_x) * a.lan_k;
+        job.lan_k = a.lan_k;
+        job.lan_m = a.lan_count[int64_t(b) * a.L + r.j];
+      }
+    }
+    token = exact_draw<kThreadsW>(job, a.u_res[b], R, smx);
+    writer = threadIdx.x == 0;
+  }
   if (writer) {
-    a.next_token[b] = (int)base + off;
+    a.next_token[b] = token;
     if (a.resid_mass) a.resid_mass[b] = R;
   }
 }

@@ -1,6 +1,7 @@
 // Second launch of a verify call on rows of at most 16384 logits: sequence_whole_kernel with its
 // register-resident sampler; the stand-alone neighbour aggregation kernel.
 #pragma once
+#include "exact_draw.h"
 #include "sequence_common.h"
 #include "stats_kernels.h"
 
@@ -24,10 +25,14 @@ namespace csd {
 // ABS: `u` is not the uniform but the mass to walk itself (the caller has taken u*R of a longer
 // row and subtracted what lies before this part of it); V is then the number of tokens from the
 // first one held here to the end of the row.
+// trust (meaningful in the writer thread only): the fp32 result stands -- no level of the search
+// had to fall back to its last entry with mass and (not ABS, where the caller knows the whole
+// law's mass) the law weighs at least kSafeMass.  Otherwise the caller re-does the draw in fp64
+// (exact_draw.h).
 template <int DT, bool XF, int kVW, bool LAN = false, bool ABS = false>
 __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, const RowRegs<DT, XF, kVW>& rd,
                                             ResidCoef k, float u, int V, SmemW& sm, float& R, bool& writer,
-                                            const LanPatch lp = LanPatch{0u, -1, 1.f}) {
+                                            bool& trust, const LanPatch lp = LanPatch{0u, -1, 1.f}) {
   constexpr int kE = Vec<DT>::kE;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   // mass of element e of this thread's vector v
@@ -38,6 +43,7 @@ __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, cons
   float r[kVW * kE];           // masses of this thread's tokens, kept for the final search
   float part[kVW], mine, incl, excl;
   R = 0.f;
+  bool fell_back = false;      // the law had no fp32 mass and p took its place
   for (int attempt = 0; attempt < 2; ++attempt) {
     mine = 0.f;
 #pragma unroll
@@ -70,6 +76,7 @@ __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, cons
     excl = __fadd_rn(woff, excl_w);
     if (R > 0.f || k.mode == kModeP) break;
     k.mode = kModeP;   // no rejection possible at this position: any law is optimal, use p
+    fell_back = true;
   }
 
   // thread: first with positive mass whose inclusive sum exceeds u*R, else the last with mass
@@ -85,8 +92,10 @@ __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, cons
   int win = 0x7fffffff, last_pos = -1;
 #pragma unroll
   for (int w = 0; w < kWavesW; ++w) { win = min(win, sm.pick[w]); last_pos = max(last_pos, sm.pick_last[w]); }
-  if (win == 0x7fffffff) win = last_pos;
+  const bool thread_fallback = win == 0x7fffffff;
+  if (thread_fallback) win = last_pos;
   writer = win >= 0 ? (int)threadIdx.x == win : threadIdx.x == 0;   // a row without any mass: token 0
+  trust = true;
   int token = 0;
   if ((int)threadIdx.x == win) {
     // vector, then element: same rule at each level
@@ -101,7 +110,8 @@ __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, cons
       }
       cum = __fadd_rn(cum, part[q]);
     }
-    if (vs < 0) { vs = vlast; vbase = vbase_last; }
+    const bool vector_fallback = vs < 0;
+    if (vector_fallback) { vs = vlast; vbase = vbase_last; }
     const float v3 = v2 - vbase;
     float rv[kE];                 // the selected vector's masses
 #pragma unroll
@@ -120,10 +130,23 @@ __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, cons
         if (found < 0 && run > v3) found = e;
       }
     }
-    if (found < 0) found = last;
+    const bool element_fallback = found < 0;
+    if (element_fallback) found = last;
     token = (win * kVW + vs) * kE + found;
+    trust = !(thread_fallback || vector_fallback || element_fallback || fell_back) &&
+            (ABS || k.mode == kModeP || R >= kSafeMass);
+  } else if (writer) {
+    trust = !fell_back;        // no mass at all: a row without a finite logit, outside the contract
   }
   return token >= V ? V - 1 : token;
+}
+
+// After a draw: the whole workgroup learns whether the thread that found the token trusts it.
+// `flag` is an LDS word that thread 0 cleared before an earlier barrier.
+__device__ __forceinline__ bool draw_needs_fp64(bool writer, bool trust, int force, int* flag) {
+  if (writer && !trust) *flag = 1;
+  __syncthreads();
+  return *flag != 0 || force != 0;
 }
 
 // MUL = 2: the same for rows of up to 32768 logits, whose pair still fits the registers of 1024
@@ -137,10 +160,11 @@ __global__ __launch_bounds__(kThreadsW) void sequence_whole_kernel(const KArgs a
   static_assert(MUL == 1 || (MUL == 2 && !LAN), "the neighbour patch is one 32-bit mask per thread");
   static_assert((RowRegs<DT, XF, kVW>::kRaw ? kVW * 4 : kVW * kE) <= 32, "a row pair must fit the registers");
   __shared__ SmemW sm;
+  __shared__ ExactSmem<kThreadsW> smx;
   const int b = blockIdx.x;
   const int rps = a.L + a.has_bonus;
   const bool masked = XF && a.top_k > 0;
-
+  if (threadIdx.x == 0) sm.needs64 = 0;           // several barriers lie between this and its readers
 
   int j = 0;
   if (!a.resample_only) {
@@ -182,7 +206,9 @@ __global__ __launch_bounds__(kThreadsW) void sequence_whole_kernel(const KArgs a
 
   float R;
   int token;
-  bool writer;
+  bool writer, trust;
+  ExactJob job{{t_c, t_u, thr_t, (double)rs.x}, {d_c, d_u, thr_d, (double)rs.z}, DT, XF, a.V, a.cfg_scale, a.inv_T,
+               omega, k.mode, nullptr, 0, 0, 0};
   if constexpr (LAN) {
     // Eq. g_lantern: the law is [P^{k,lambda} - q]_+ around the rejected token x~_j; this thread
     // owns the kVW*kE consecutive tokens from first_tok on
@@ -204,10 +230,16 @@ __global__ __launch_bounds__(kThreadsW) void sequence_whole_kernel(const KArgs a
         const int dn = n - first_tok;
         if (dn >= 0 && dn < kVW * kE) lp.zmask |= 1u << dn;
       }
+      job.mode = kModeVanilla;
+      job.nbr_row = row; job.lan_k = a.lan_k; job.lan_m = m; job.lan_x = xd;
     }
-    token = sample_whole<DT, XF, kVW, true>(rt, rd, k, a.u_res[b], a.V, sm, R, writer, lp);
+    token = sample_whole<DT, XF, kVW, true>(rt, rd, k, a.u_res[b], a.V, sm, R, writer, trust, lp);
   } else {
-    token = sample_whole<DT, XF, kVW>(rt, rd, k, a.u_res[b], a.V, sm, R, writer);
+    token = sample_whole<DT, XF, kVW>(rt, rd, k, a.u_res[b], a.V, sm, R, writer, trust);
+  }
+  if (draw_needs_fp64(writer, trust, a.exact_draw, &sm.needs64)) {
+    token = exact_draw<kThreadsW>(job, a.u_res[b], R, smx);
+    writer = threadIdx.x == 0;
   }
   if (writer) {
     a.next_token[b] = token;

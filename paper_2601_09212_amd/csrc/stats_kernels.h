@@ -79,7 +79,11 @@ __device__ __forceinline__ void lantern_agg_position(const KArgs& a, int pos, in
   // tok_logit, formed here so that this does not have to wait for that kernel
   const float lx = token_logit_any(dt, cond, uncond, x, xf, a.cfg_scale, a.inv_T, thr);
   const int32_t* row = a.nbr + int64_t(x) * a.lan_k;
-  float cum = 0.f;
+  // The set is an integer decision (which neighbours belong): it is taken in fp64 -- weights from
+  // the exact logit differences, running sum in list order -- so that it agrees with exact
+  // arithmetic wherever the inequality is not a tie to fifteen digits.  One wave, k values: free.
+  double cum = 0.0;
+  const double lam = (double)a.lan_lambda;
   int m = 0;
   if (lx > -INFINITY) {                       // p(x~) = 0 admits no neighbour: nothing is below 0
     for (int j0 = 0; j0 < a.lan_k; j0 += 64) {
@@ -87,24 +91,30 @@ __device__ __forceinline__ void lantern_agg_position(const KArgs& a, int pos, in
       const int n = j < a.lan_k ? row[j] : -1;
       const bool valid = n >= 0 && n < a.V && n != x;
       const float ln = valid ? token_logit_any(dt, cond, uncond, n, xf, a.cfg_scale, a.inv_T, thr) : -INFINITY;
-      const float w = valid ? exp2_fast(__fmul_rn(__fsub_rn(ln, lx), kLog2e)) : 0.f;
-      const float incl = __fadd_rn(cum, wave_scan_incl(w));
+      const double w = valid ? exp2_d(((double)ln - (double)lx) * kLog2eD) : 0.0;
+      double incl = w;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const double t = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += t;
+      }
+      incl += cum;
       const unsigned long long bv = __ballot(valid);
-      const unsigned long long bf = __ballot(valid && !(incl < a.lan_lambda));
+      const unsigned long long bf = __ballot(valid && !(incl < lam));
       if (bf) {                                // the first neighbour that does not fit ends the set
         const int fl = __ffsll((long long)bf) - 1;
         m += __popcll(bv & ((1ull << fl) - 1ull));
         // the running sum before lane fl: weights of skipped lanes are zero, so it is the sum
         // over the members taken so far
-        if (fl > 0) cum = lane_f(incl, fl - 1);
+        if (fl > 0) cum = __shfl(incl, fl - 1, 64);
         break;
       }
       m += __popcll(bv);
-      cum = lane_f(incl, 63);
+      cum = __shfl(incl, 63, 64);
     }
   }
   if (lane == 0) {
-    a.lan_omega[pos] = __fadd_rn(1.f, cum);
+    a.lan_omega[pos] = (float)(1.0 + cum);
     a.lan_count[pos] = m;
     if (a.count_out) a.count_out[pos] = m;
   }

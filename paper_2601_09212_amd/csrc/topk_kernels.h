@@ -2,6 +2,7 @@
 // draft-side draw in one launch (resample_topk_kernel) and the radix passes for rows beyond
 // 65536 logits.
 #pragma once
+#include "exact_draw.h"
 #include "stats_kernels.h"
 
 namespace csd {
@@ -96,6 +97,8 @@ __global__ __launch_bounds__(TPB) void resample_topk_kernel(const KArgs a) {
   __shared__ float tile_part[kW][8];
   __shared__ float scan_tot[kW];
   __shared__ int pick_first[kW], pick_last[kW];
+  __shared__ int needs64;
+  __shared__ ExactSmem<TPB> smx;
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   topk_prepare(ts);
   RowRegs<DT, true, kVW> x;
@@ -147,7 +150,8 @@ __global__ __launch_bounds__(TPB) void resample_topk_kernel(const KArgs a) {
     }
     cum = __fadd_rn(cum, T[k]);
   }
-  if (ks < 0) { ks = klast; base = base_last; }
+  const bool tile_fallback = ks < 0;
+  if (tile_fallback) { ks = klast; base = base_last; }
   if (ks < 0) {            // a row without any finite logit: outside the contract, answer token 0
     if (tid == 0) { a.next_token[b] = 0; if (a.resid_mass) a.resid_mass[b] = 0.f; }
     return;
@@ -160,6 +164,7 @@ __global__ __launch_bounds__(TPB) void resample_topk_kernel(const KArgs a) {
   const float incl_w = wave_scan_incl(my);
   const float excl_w = wave_prev_lane(incl_w);
   if (lane == 63) scan_tot[wv] = incl_w;
+  if (tid == 0) needs64 = 0;
   __syncthreads();
   float woff = 0.f;
 #pragma unroll
@@ -176,8 +181,10 @@ __global__ __launch_bounds__(TPB) void resample_topk_kernel(const KArgs a) {
   int win = 0x7fffffff, last_pos = -1;
 #pragma unroll
   for (int w = 0; w < kW; ++w) { win = min(win, pick_first[w]); last_pos = max(last_pos, pick_last[w]); }
-  if (win == 0x7fffffff) win = last_pos;
+  const bool thread_fallback = win == 0x7fffffff;
+  if (thread_fallback) win = last_pos;
   // level 3: element, by the winning thread
+  int token = 0;
   if (tid == win) {
     const float v3 = v2 - excl;
     int found = -1, last = 0;
@@ -193,9 +200,23 @@ __global__ __launch_bounds__(TPB) void resample_topk_kernel(const KArgs a) {
         if (found < 0 && run > v3) found = j;
       }
     }
-    if (found < 0) found = last;
-    a.next_token[b] = min((ks * TPB + win) * kE + found, a.V - 1);
-    if (a.resid_mass) a.resid_mass[b] = 1.f;             // the law is p itself
+    const bool element_fallback = found < 0;
+    if (element_fallback) found = last;
+    token = min((ks * TPB + win) * kE + found, a.V - 1);
+    // the law is p itself (mass 1): fp32 resolves it unless a level's roundings disagreed
+    if (tile_fallback || thread_fallback || element_fallback) needs64 = 1;
+  }
+  __syncthreads();
+  float mass = 1.f;                                      // the law is p itself
+  if (needs64 || a.exact_draw) {
+    const ExactJob job{{row_ptr(a.t, int64_t(b) * a.t_sb, kES), row_ptr(a.tu, int64_t(b) * a.t_sb, kES), thr, (double)c},
+                       {nullptr, nullptr, -INFINITY, 0.0}, DT, true, a.V, a.cfg_scale, a.inv_T, 1.f, kModeP, nullptr, 0, 0, 0};
+    token = exact_draw<TPB>(job, u, mass, smx);
+    win = 0;
+  }
+  if (tid == win) {
+    a.next_token[b] = token;
+    if (a.resid_mass) a.resid_mass[b] = mass;
   }
 }
 

@@ -201,25 +201,37 @@ def test_resample_entry_point(P, oracle):
             ot, om_, g = oracle.resample(t.float().cpu().numpy(), d.float().cpu().numpy(), om.cpu().numpy(),
                                          u.cpu().numpy(), resample_mode=mode, want_g=True)
             np.testing.assert_allclose(mass.cpu().numpy(), om_, rtol=1e-5)
-            for b in range(6):
-                if tok[b].item() != ot[b]:
-                    C = np.cumsum(g[b]); v = float(u[b]) * om_[b]; k = tok[b].item()
-                    gap = (v - C[k]) / om_[b] if k < ot[b] else (C[k - 1] - v) / om_[b]
-                    assert g[b][k] > 0 and 0 <= gap <= token_band(om_[b])
+            _tokens_match_or_sit_on_a_boundary(tok.cpu().numpy(), ot, g, om_, u.cpu().numpy())
         # bonus draw: draft absent
         tok = torch.full((6,), -7, dtype=torch.int32, device="cuda")
         P.cool_sd_resample(params, t, None, None, None, None, u, tok, None, ws)
         torch.cuda.synchronize()
-        ot, _ = oracle.resample(t.float().cpu().numpy(), None, None, u.cpu().numpy())
-        assert (tok.cpu().numpy() == ot).sum() >= 5
+        ot, om_, g = oracle.resample(t.float().cpu().numpy(), None, None, u.cpu().numpy(), want_g=True)
+        _tokens_match_or_sit_on_a_boundary(tok.cpu().numpy(), ot, g, om_, u.cpu().numpy())
+
+
+def _tokens_match_or_sit_on_a_boundary(tok, ot, g, R, u):
+    """Every token equals the oracle's, or has mass and its uniform lies within 1e-6 (in units of
+    u) of the boundary of the oracle's CDF between the two tokens.  Returns the number of such cases."""
+    n = 0
+    for b in range(len(tok)):
+        k = int(tok[b])
+        assert 0 <= k < g[b].shape[0] and g[b][k] > 0, (b, k)
+        if k != ot[b]:
+            C = np.cumsum(g[b])
+            v = float(u[b]) * R[b]
+            gap = (v - C[k]) / R[b] if k < ot[b] else (C[k - 1] - v) / R[b]
+            assert 0 <= gap <= token_band(R[b]), (b, k, int(ot[b]), gap)
+            n += 1
+    return n
 
 
 def test_resample_where_the_law_has_no_mass(P, oracle):
     """p and q that coincide (here: both one-hot on the same token after top-1 truncation, from
     different logits) leave [p - q]_+ without mass: any law is optimal there, the oracle falls
-    back to p (mass 1).  fp32 may see one ulp of dust instead of an exact zero; either way the
-    token must be the one token that has probability, and the reported mass is 1 or that dust."""
-    from tests.parity_util import MASS_ABS
+    back to p (mass 1).  The token must be the one token that has probability, and the reported
+    mass is 1 (the fall-back) or rounding residue far below anything fp64 resolves."""
+    from tests.parity_util import R_FLOOR
     B, V = 64, 2
     g = torch.Generator(device="cuda").manual_seed(3)
     t = torch.randn((B, V), generator=g, device="cuda") * 3
@@ -241,42 +253,40 @@ def test_resample_where_the_law_has_no_mass(P, oracle):
         np.testing.assert_array_equal(ot, t.argmax(1).cpu().numpy())
         m = mass.cpu().numpy()
         same = same_top.cpu().numpy()
-        assert ((np.abs(m[same] - 1.0) <= 1e-5) | ((m[same] >= 0) & (m[same] <= MASS_ABS))).all()
+        assert ((np.abs(m[same] - 1.0) <= 1e-5) | ((m[same] >= 0) & (m[same] <= 10 * R_FLOOR))).all()
         np.testing.assert_allclose(m[~same], om_[~same], rtol=1e-5)     # disjoint supports: mass 1
 
 
 def test_resample_from_a_small_residual_of_peaked_rows(P, oracle):
-    """Guided rows at temperature 0.5 are so peaked that p and q nearly cancel: R = 1.9e-3 here, the
-    cumulative masses carry ~4e-8 of absolute fp32 error, and the uniform of this case falls 2.3e-5
-    (in units of u) from a boundary of the oracle's CDF -- inside what fp32 probabilities resolve
-    (token_band), outside the 1e-6 that holds for R near 1.  Found by a randomised sweep."""
+    """Guided rows at temperature 0.5 are so peaked that p and q nearly cancel: R = 1.9e-3 here.  fp32
+    probabilities cannot resolve such a law (cumulative masses off by ~4e-8, which is 2e-5 in units of
+    u), so the library draws it in fp64: mass within 1e-5 relative, token the oracle's unless u lies
+    within 1e-6 of a boundary.  Found by a randomised sweep of the fp32-only version."""
     V = 8200
     w = make_workload(3, device="cuda", B=1, L=5, V=V, dtype="bf16", seed=5000 + 41 * 1000 + 136, top_k=0)
     om = P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, 5, 20.0, 0.7)
-    u = uniforms24(torch.Generator(device="cuda").manual_seed(136), (1,), "cuda")
     torch.manual_seed(201)
     m = torch.rand(V, device="cuda") < 0.3               # tokens the draft excludes
     m[201 % V] = False
     d = w.draft[:, 0].clone(); du = w.draft_uncond[:, 0].clone()
     d[..., m] = float("-inf"); du[..., m] = float("-inf")
     t = w.target[:, 0].contiguous(); tu = w.target_uncond[:, 0].contiguous()
+    # the same row pair under 64 uniforms: the one of the original case, and more across the CDF
+    B = 64
+    t, tu, d, du = (x.expand(B, V).contiguous() for x in (t, tu, d, du))
+    u = uniforms24(torch.Generator(device="cuda").manual_seed(136), (B,), "cuda")
     params = P.make_params(t.unsqueeze(1), d.unsqueeze(1), has_bonus=0, cfg_scale=w.cfg_scale, temperature=0.5)
     ws = torch.empty(max(P.cool_sd_workspace_bytes(params), 256), dtype=torch.uint8, device="cuda")
-    omr = torch.full((1,), float(om[0]), device="cuda")
-    tok = torch.full((1,), -7, dtype=torch.int32, device="cuda"); mass = torch.zeros(1, device="cuda")
+    omr = torch.full((B,), float(om[0]), device="cuda")
+    tok = torch.full((B,), -7, dtype=torch.int32, device="cuda"); mass = torch.zeros(B, device="cuda")
     P.cool_sd_resample(params, t, tu, d, du, omr, u, tok, mass, ws)
     torch.cuda.synchronize()
     ot, R, g = oracle.resample(t.float().cpu().numpy(), d.float().cpu().numpy(), omr.cpu().numpy(), u.cpu().numpy(),
                                target_uncond=tu.float().cpu().numpy(), draft_uncond=du.float().cpu().numpy(),
                                cfg_scale=w.cfg_scale, temperature=0.5, want_g=True)
     assert 1e-4 < R[0] < 1e-2                            # the regime this test is about
-    assert abs(mass.item() - R[0]) <= 1e-5 * R[0] + 1e-6
-    k = tok.item()
-    assert 0 <= k < V and g[0][k] > 0
-    if k != ot[0]:
-        C = np.cumsum(g[0]); v = float(u[0]) * R[0]
-        gap = (v - C[k]) / R[0] if k < ot[0] else (C[k - 1] - v) / R[0]
-        assert 0 <= gap <= token_band(R[0]), gap
+    np.testing.assert_allclose(mass.cpu().numpy(), R, rtol=1e-5)
+    assert _tokens_match_or_sit_on_a_boundary(tok.cpu().numpy(), ot, g, R, u.cpu().numpy()) <= 1
 
 
 def test_repeat_calls_share_workspace_and_are_deterministic(P, oracle):
@@ -412,7 +422,8 @@ def test_full_size_configurations(P, oracle, cfg, n_check):
     else:
         idx = np.sort(np.random.default_rng(cfg).choice(w.B, n_check, replace=False))
         st = compare_verify(oracle, subset(w, idx), om, {k: v[idx] for k, v in gpu.items()})
-    print("exemptions", st, flush=True)
+    # every exemption counted here lies inside the 1e-6 band (compare_verify asserts it); none is expected
+    print("exemptions (uniform within 1e-6 of its threshold)", st, flush=True)
     assert st["tau_exempt"] + st["token_exempt"] <= 2
     # acceptance statistics are those of speculative decoding, not degenerate
     if w.B >= 32:
@@ -524,16 +535,10 @@ def test_draft_side_sampling_through_resample(P, oracle, V, dtype, guided, top_k
                                  target_uncond=None if du is None else du.float().cpu().numpy(), cfg_scale=scale,
                                  temperature=temperature, top_k=top_k, want_g=True)
     np.testing.assert_allclose(mass.cpu().numpy(), om_, rtol=1e-5)
-    t = tok.cpu().numpy()
     for b in range(B):
-        assert 0 <= t[b] < V and g[b][t[b]] > 0
         if top_k:
             assert (g[b] > 0).sum() >= min(top_k, V)
-        if t[b] != ot[b]:
-            C = np.cumsum(g[b]); v = float(u[b]) * om_[b]
-            gap = (v - C[t[b]]) / om_[b] if t[b] < ot[b] else (C[t[b] - 1] - v) / om_[b]
-            assert 0 <= gap <= token_band(om_[b])
-    assert (t == ot).sum() >= B - 1
+    _tokens_match_or_sit_on_a_boundary(tok.cpu().numpy(), ot, g, om_, u.cpu().numpy())
 
 
 def test_random_shapes_and_options(P, oracle):

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 import torch
 
-from tests.parity_util import MASS_ABS, R_FLOOR, REL_TOL, U_TOL, compare_verify, compare_verify_lantern, to_numpy, token_band
+from tests.parity_util import R_FLOOR, REL_TOL, U_TOL, compare_verify, compare_verify_lantern, to_numpy, token_band
 from tests.parity_util import oracle_diagnostics as _oracle_diag, verify_diagnostics_call as _verify_diag
 from tests.test_gpu_diagnostics import _check as check_diagnostics
 from workloads import make_neighbor_table, make_workload, uniforms24
@@ -46,12 +46,12 @@ def _check_resample(P, oracle, w, omega0, mode, case, exempt):
         for b in range(B):
             assert 0 <= tk[b] < V
             # R == 1 (the sum of p in fp64): the law is p, or the oracle's fall-back where the law had no mass
-            unresolved = R[b] < R_FLOOR or (abs(R[b] - 1.0) <= 1e-12 and ms[b] <= MASS_ABS)
+            unresolved = R[b] < R_FLOOR or (abs(R[b] - 1.0) <= 1e-12 and ms[b] <= 10 * R_FLOOR)
             if unresolved:
-                assert 0 <= ms[b] <= MASS_ABS or abs(ms[b] - 1.0) <= REL_TOL
+                assert 0 <= ms[b] <= 10 * R_FLOOR or abs(ms[b] - 1.0) <= REL_TOL
                 exempt.append(("mass", case, b))
                 continue
-            assert abs(ms[b] - R[b]) <= REL_TOL * R[b] + MASS_ABS
+            assert abs(ms[b] - R[b]) <= REL_TOL * R[b], (b, ms[b], R[b])
             assert g[b][tk[b]] > 0
             if tk[b] != ot[b]:
                 C = np.cumsum(g[b])

@@ -106,7 +106,7 @@ def test_workspace_bytes_and_invalid_params(P):
     assert big > small
     for bad in (dict(B=0), dict(V=0), dict(dtype=3), dict(top_k=-1), dict(top_k=16385), dict(temperature=0.0),
                 dict(temperature=float("inf")), dict(cfg_scale=float("nan")), dict(resample_mode=3),
-                dict(flags=4), dict(flags=-1), dict(t_stride_b=-1)):
+                dict(flags=8), dict(flags=-1), dict(t_stride_b=-1)):
         assert P.cool_sd_workspace_bytes(_params(P, **bad)) == 0, bad
     # L out of range is still a valid stand-alone resample shape (L is ignored there)
     assert P.cool_sd_workspace_bytes(_params(P, L=0)) > 0

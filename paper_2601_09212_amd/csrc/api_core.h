@@ -6,6 +6,8 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <algorithm>
+
 #include "cool_sd.h"
 #include "device_utils.h"
 #include "kernels.h"
@@ -18,7 +20,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t seq_stat, chunk_R, thr, tok_logit, rowstat, part, diag_part, lan, rk_hist, rk_state, total;
+  size_t seq_stat, ticket, chunk_R, thr, tok_logit, rowstat, part, diag_part, lan, rk_hist, rk_state, total;
 };
 
 // cool_sd_verify_lantern only
@@ -40,6 +42,7 @@ Layout make_layout(int64_t B, int64_t rows, int64_t c1, int64_t C, int64_t pairs
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes); return at; };
   o.seq_stat = take(size_t(B) * 16);
+  o.ticket = take(size_t(B) * 4);
   o.chunk_R = take(size_t(B) * C * 4);
   o.thr = take(size_t(rows) * 4);
   o.tok_logit = take(size_t(rows) * 4);
@@ -185,12 +188,20 @@ int run(const cool_sd_params* p, bool resample_only,
   // beyond ~128 MB the logits cannot stay in L2 / Infinity Cache until the sequence kernel re-reads a row
   a.stream_loads = (double(rows_t + rows_d) * p->V * (p->dtype == COOL_SD_BF16 ? 2 : 4) * (tu ? 2 : 1)) > 128e6 ? 1 : 0;
   a.nchunks = (int32_t)C; a.nt2 = ch.nt2;
+  // long-row tail launch: about 1024 workgroups in all (four per compute unit: enough loads in
+  // flight to saturate HBM without queueing them so deep that the launch's few dependent loads
+  // wait behind them), at most one per chunk, at least one per eight chunks
+#ifndef CSD_TAIL_TARGET
+#define CSD_TAIL_TARGET 1024
+#endif
+  a.tail_groups = (int32_t)std::max<int64_t>((C + 7) / 8, std::min<int64_t>(C, CSD_TAIL_TARGET / p->B));
   a.cfg_scale = p->cfg_scale;
   a.inv_T = 1.0f / p->temperature;
   a.rows_t = (int32_t)rows_t; a.rows_d = (int32_t)rows_d;
   a.nt1 = ch.nt1; a.chunk1 = ch.chunk1; a.c1 = (int32_t)ch.c1;
   a.chunk_R = reinterpret_cast<float*>(w + lay.chunk_R);
   a.seq_stat = reinterpret_cast<float4*>(w + lay.seq_stat);
+  a.ticket = reinterpret_cast<int32_t*>(w + lay.ticket);
   a.thr = reinterpret_cast<float*>(w + lay.thr);
   a.tok_logit = reinterpret_cast<float*>(w + lay.tok_logit);
   a.part = reinterpret_cast<float2*>(w + lay.part);
@@ -252,6 +263,7 @@ int run_diag(const cool_sd_params* p, const void* t, const void* tu, const void*
   a.inv_T = 1.0f / p->temperature;
   a.rows_t = (int32_t)pairs; a.rows_d = (int32_t)pairs;
   a.nt1 = ch.nt1; a.chunk1 = ch.chunk1; a.c1 = (int32_t)ch.c1;
+  a.ticket = reinterpret_cast<int32_t*>(w + lay.ticket);
   a.thr = reinterpret_cast<float*>(w + lay.thr);
   a.tok_logit = reinterpret_cast<float*>(w + lay.tok_logit);
   a.part = reinterpret_cast<float2*>(w + lay.part);
@@ -305,6 +317,7 @@ int run_verify_diag(const cool_sd_params* p, const void* t, const void* tu, cons
   a.nt1 = kT; a.chunk1 = csd::kChunk; a.c1 = 1;   // one statistics pair per row
   a.chunk_R = reinterpret_cast<float*>(w + lay.chunk_R);
   a.seq_stat = reinterpret_cast<float4*>(w + lay.seq_stat);
+  a.ticket = reinterpret_cast<int32_t*>(w + lay.ticket);
   a.thr = reinterpret_cast<float*>(w + lay.thr);
   a.tok_logit = reinterpret_cast<float*>(w + lay.tok_logit);
   a.part = reinterpret_cast<float2*>(w + lay.part);

@@ -46,6 +46,8 @@ struct KArgs {
   int32_t accept_combines;  // long rows: accept_kernel combines the chunk statistics of its own rows (no combine_rows launch)
   float4* seq_stat;         // [B]           statistics of the sampled row (several-chunk path)
   float* chunk_R;           // [B, nchunks]  residual mass per chunk of the sampled row  (nchunks > 1)
+  int32_t* ticket;          // [B]           workgroups of the long-row tail launch that have finished their chunks
+  int32_t tail_groups;      // workgroups per sequence of that launch
   // top-k on rows longer than one workgroup: radix-select state in the workspace
   uint32_t* rk_hist;        // [rows_t + rows_d, 2048] digit counts of the current pass
   uint32_t* rk_state;       // [rows_t + rows_d, 2]    key bits fixed so far, rank still to find
@@ -109,9 +111,9 @@ hipError_t launch_resample_topk(const KArgs& a, int dtype, hipStream_t stream);
 
 // per-sequence step (sequence_launch.hip): everything after the statistics pass
 hipError_t launch_sequence(const KArgs& a, int dtype, bool xf, hipStream_t stream);
-// whether the chunk-mass launch of a long-row call finds tau itself (then no kernel before it
-// leaves the combined row statistics in the workspace)
-bool tau_in_mass_launch(const KArgs& a, int dtype);
+// whether a long-row call runs its per-sequence step as one launch that finds tau itself (then no
+// kernel leaves the combined row statistics in the workspace)
+bool tail_in_one_launch(const KArgs& a, int dtype);
 hipError_t launch_combine_rows(const KArgs& a, hipStream_t stream);
 // the whole verify call per sequence, stopping at the first rejection (COOL_SD_FLAG_EARLY_EXIT)
 hipError_t launch_early_exit(const KArgs& a, int dtype, bool xf, hipStream_t stream);

@@ -34,24 +34,32 @@ __global__ __launch_bounds__(kThreads) void lantern_agg_kernel(const KArgs a, in
   lantern_agg_position(a, pos, dt, xf != 0, (xf && a.top_k > 0) ? a.thr[rt_] : -INFINITY);
 }
 
-// Long rows: the chunk-mass launch finds tau itself when a row's chunk statistics fit one wave and
-// the positions another (rows of up to 524288 logits, draft windows of up to 63 tokens), and all
-// its workgroups are resident at once -- the search is then latency paid once instead of a
-// launch; in a larger grid it would repeat with every round of workgroups.
-bool tau_in_mass_launch(const KArgs& a, int dtype) {
+// Long rows: the per-sequence step is ONE launch (sequence_tail_kernel) when a row's chunk statistics
+// fit one wave and the positions another (rows of up to 524288 logits, draft windows of up to 63
+// tokens with the bonus row) and the sampled rows hold at most kTailFusedChunks chunks in all;
+// otherwise accept_kernel, sequence_masses_kernel and sequence_select_kernel follow each other.
+// The limit is where the two forms cross: the one launch saves two launch gaps and one latency
+// chain, but its few dependent loads (tau at the start, the chunk masses and the chosen chunk at
+// the end) queue behind its own streaming loads once the launch saturates HBM, which three
+// launches, each starting on an idle memory system, do not suffer.
+#ifndef CSD_TAIL_MAX
+#define CSD_TAIL_MAX 256
+#endif
+constexpr int64_t kTailFusedChunks = CSD_TAIL_MAX;
+bool tail_in_one_launch(const KArgs& a, int dtype) {
   const int kT = dtype == kDtBF16 ? Vec<kDtBF16>::kT : Vec<kDtF32>::kT;
-  return !a.resample_only && a.nt2 != kT && a.c1 <= 64 && a.L + a.has_bonus <= kTauRows &&
-         int64_t(a.B) * a.nchunks <= 2048;
+  return !a.resample_only && a.nt2 != kT && a.c1 <= 64 && a.nchunks <= 64 && a.L + a.has_bonus <= kTauRows &&
+         int64_t(a.B) * a.nchunks <= kTailFusedChunks;
 }
 
 template <int DT, bool XF, bool AL>
 static hipError_t launch_sequence_typed(const KArgs& a, hipStream_t stream) {
   constexpr int kT = Vec<DT>::kT;
   hipError_t e;
-  const bool fuse_tau = tau_in_mass_launch(a, DT);
+  const bool one_launch = tail_in_one_launch(a, DT) && !(AL && !a.lan_resample && a.V <= 2 * kChunk);
   // the long-row kernels of the stand-alone resampling call combine up to 64 chunk statistics themselves
   const bool resample_combines = a.resample_only && a.nt2 != kT && a.c1 <= 64;
-  if (a.cs != a.c1 && !a.accept_combines && !fuse_tau && !resample_combines) {   // rows have many statistics chunks: pre-combine them
+  if (a.cs != a.c1 && !a.accept_combines && !one_launch && !resample_combines) {   // rows have many statistics chunks: pre-combine them
     e = launch_combine_rows(a, stream);
     if (e != hipSuccess) return e;
   }
@@ -71,18 +79,18 @@ static hipError_t launch_sequence_typed(const KArgs& a, hipStream_t stream) {
     if (!a.lan_resample && a.V <= 2 * kChunk)
       return launch("sequence_whole_kernel", sequence_whole_kernel<DT, XF, AL, false, 2>, gB, bW, stream, a);
   }
-  if (!a.resample_only && !fuse_tau) {     // find tau once per sequence
+  if (one_launch) {
+    const dim3 gridt((unsigned)(int64_t(a.B) * a.tail_groups));
+    if (a.lan_resample) return launch("sequence_tail_kernel", sequence_tail_kernel<DT, XF, AL, kT / 2, true>, gridt, dim3(kThreads), stream, a);
+    return launch("sequence_tail_kernel", sequence_tail_kernel<DT, XF, AL, kT / 2, false>, gridt, dim3(kThreads), stream, a);
+  }
+  if (!a.resample_only) {     // find tau once per sequence
     e = launch("accept_kernel", accept_kernel<DT, XF>, gB, bW, stream, a);
     if (e != hipSuccess) return e;
   }
   const dim3 grid2((unsigned)(int64_t(a.B) * a.nchunks)), b2(kThreads);
-  const char* wm = "sequence_masses_kernel";
-  if (fuse_tau)
-    e = a.lan_resample ? launch(wm, sequence_masses_kernel<DT, XF, AL, kT / 2, true, true>, grid2, b2, stream, a)
-                       : launch(wm, sequence_masses_kernel<DT, XF, AL, kT / 2, false, true>, grid2, b2, stream, a);
-  else
-    e = a.lan_resample ? launch(wm, sequence_masses_kernel<DT, XF, AL, kT / 2, true, false>, grid2, b2, stream, a)
-                       : launch(wm, sequence_masses_kernel<DT, XF, AL, kT / 2, false, false>, grid2, b2, stream, a);
+  e = a.lan_resample ? launch("sequence_masses_kernel", sequence_masses_kernel<DT, XF, AL, kT / 2, true>, grid2, b2, stream, a)
+                     : launch("sequence_masses_kernel", sequence_masses_kernel<DT, XF, AL, kT / 2, false>, grid2, b2, stream, a);
   if (e != hipSuccess) return e;
   if (a.lan_resample) return launch("sequence_select_kernel", sequence_select_kernel<DT, XF, AL, true>, gB, bW, stream, a);
   return launch("sequence_select_kernel", sequence_select_kernel<DT, XF, AL, false>, gB, bW, stream, a);

@@ -24,8 +24,9 @@ struct SampledRow {
   float thr_t, thr_d, omega;
 };
 
+// omega_known: the caller already holds omega of the sampled position (NaN: load it here).
 template <int DT, bool XF>
-__device__ __forceinline__ SampledRow sampled_row(const KArgs& a, int b, int tau) {
+__device__ __forceinline__ SampledRow sampled_row(const KArgs& a, int b, int tau, float omega_known = NAN) {
   constexpr int kES = Vec<DT>::kES;
   SampledRow r;
   const int rps = a.L + a.has_bonus;
@@ -44,7 +45,7 @@ __device__ __forceinline__ SampledRow sampled_row(const KArgs& a, int b, int tau
   if (!r.none) {
     if (masked) r.thr_t = a.thr[r.rt_];
     if (masked && !r.bonus) r.thr_d = a.thr[r.rd_];
-    if (!r.bonus) r.omega = a.omega[int64_t(b) * a.om_sb + r.j];
+    if (!r.bonus) r.omega = omega_known == omega_known ? omega_known : a.omega[int64_t(b) * a.om_sb + r.j];
   }
   return r;
 }
@@ -99,6 +100,36 @@ __device__ __forceinline__ LanPatch lan_patch_span(const KArgs& a, int b, int j,
   return lp;
 }
 
+// Eq. g_lantern for a thread of a 256-thread workgroup that holds a chunk of `span` tokens from
+// `base` on in the tile layout (element e of tile t of thread tid is token
+// base + (t*256 + tid)*kE + e, patch bit t*kE + e): which of its tokens belong to the rejected
+// token's neighbour set, and where the rejected token itself sits (-1: not here).
+template <int kE>
+__device__ __forceinline__ LanPatch lan_patch_tile(const KArgs& a, int b, int j, float omega, int64_t base, int span) {
+  LanPatch lp{0u, -1, 1.f};
+  auto slot = [&](int tokn) -> int {              // bit of token tokn in this thread, or -1
+    const int64_t rel = int64_t(tokn) - base;
+    if (rel < 0 || rel >= span) return -1;
+    const int vec = int(rel) / kE;
+    if ((vec & (kThreads - 1)) != (int)threadIdx.x) return -1;
+    return (vec / kThreads) * kE + (int(rel) - vec * kE);
+  };
+  const int xd = min(max(a.tokens[int64_t(b) * a.L + j], 0), a.V - 1);
+  const int m = a.lan_count[int64_t(b) * a.L + j];
+  lp.agg = omega;                                     // sum over the set / p(x~_j), from lantern_agg_position
+  lp.aggpos = slot(xd);
+  const int32_t* row = a.nbr + int64_t(xd) * a.lan_k;
+  int taken = 0;
+  for (int jj = 0; jj < a.lan_k && taken < m; ++jj) {   // the first m valid neighbours are the members
+    const int n = row[jj];
+    if (n < 0 || n >= a.V || n == xd) continue;
+    ++taken;
+    const int sl = slot(n);
+    if (sl >= 0) lp.zmask |= 1u << sl;
+  }
+  return lp;
+}
+
 // tau of sequence b found by a 256-thread workgroup from the chunk statistics of the sequence's
 // rows (at most 64 chunks per row, at most kTauRows positions, the bonus row included), so that
 // the chunk-mass launch needs no accept_kernel before it: every workgroup of a sequence finds the
@@ -111,6 +142,7 @@ constexpr int kTauRows = 64;
 struct SmemTau {
   float2 st[2 * kTauRows];       // (reference exponent, sum): target rows 0 .. L(+1)-1, then the draft rows
   float4 rowstat;
+  float omega;                   // omega of the sampled position (1 for the bonus row)
   int tau;
 };
 __device__ __forceinline__ int find_tau_from_parts(const KArgs& a, int b, bool emit, SmemTau& sm) {
@@ -157,7 +189,10 @@ __device__ __forceinline__ int find_tau_from_parts(const KArgs& a, int b, bool e
     }
     const unsigned long long br = __ballot(rej);
     const int w = br ? __ffsll((long long)br) - 1 : a.L;
-    if (lane == w) sm.rowstat = make_float4(Ct, St, Cd, Sd);   // position w, or the bonus row when w == L
+    if (lane == w) {                                          // position w, or the bonus row when w == L
+      sm.rowstat = make_float4(Ct, St, Cd, Sd);
+      sm.omega = has_draft ? omega : 1.f;
+    }
     if (lane == 0) {
       sm.tau = w;
       if (emit) a.accept_len[b] = w;
@@ -191,29 +226,21 @@ __global__ __launch_bounds__(kThreadsW) void accept_kernel(const KArgs a) {
   if (threadIdx.x == 0) a.seq_stat[b] = sm.rowstat;
 }
 
-// TAU: the workgroup finds tau itself (find_tau_from_parts) instead of reading what accept_kernel left.
-template <int DT, bool XF, bool AL, int kT, bool LAN, bool TAU>
+// Chunk masses of the sampled rows as a launch of its own (the three-launch form: rows of more than
+// 64 statistics chunks, draft windows beyond kTauRows positions, the stand-alone resampling call).
+template <int DT, bool XF, bool AL, int kT, bool LAN>
 __global__ __launch_bounds__(kThreads) void sequence_masses_kernel(const KArgs a) {
   constexpr int kE = Vec<DT>::kE;
   constexpr int kChunk2 = kT * kThreads * kE;            // logits per sampling chunk
   __shared__ Smem sm;
   const int C = a.nchunks;
   const int b = blockIdx.x / C, c = blockIdx.x - b * C;
-  int tau = 0;
-  float4 rs;                                             // statistics of the sampled row
-  if constexpr (TAU) {
-    __shared__ SmemTau smt;
-    tau = find_tau_from_parts(a, b, c == 0, smt);
-    rs = smt.rowstat;
-    if (c == 0 && threadIdx.x == 0) a.seq_stat[b] = rs;  // for the selection kernel
-  } else {
-    if (!a.resample_only) tau = a.accept_len[b];
-  }
+  const int tau = a.resample_only ? 0 : a.accept_len[b];
   const SampledRow r = sampled_row<DT, XF>(a, b, tau);
   if (r.none) return;
   // left by accept_kernel: the same for every thread, read straight from the workspace (a scalar
   // load that is in flight while the chunk's vector loads are issued)
-  if constexpr (!TAU) rs = sampled_row_stats(a, b, r, &sm.rowstat);
+  const float4 rs = sampled_row_stats(a, b, r, &sm.rowstat);
   // the mass pass reads every chunk of the row exactly once: nontemporal loads
   constexpr int kA = AL ? kAlignedStream : kUnaligned;
   const int64_t base = int64_t(c) * kChunk2;
@@ -223,32 +250,10 @@ __global__ __launch_bounds__(kThreads) void sequence_masses_kernel(const KArgs a
   else rd.clear();                                    // never read in mode P
   const ResidCoef k{rs.x, 1.f / rs.y, rs.z, r.bonus ? 1.f : 1.f / rs.w, r.omega,
                     r.bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
-  // Eq. g_lantern: this thread's part of the patch -- which of its tokens belong to the rejected
-  // token's neighbour set (element e of tile t is token base + (t*256 + tid)*kE + e, bit t*kE + e)
+  // Eq. g_lantern: this thread's part of the patch
   LanPatch lp{0u, -1, 1.f};
   if constexpr (LAN) {
-    if (!r.bonus) {
-      auto slot = [&](int tokn) -> int {              // bit of token tokn in this thread, or -1
-        const int64_t rel = int64_t(tokn) - base;
-        if (rel < 0 || rel >= kChunk2) return -1;
-        const int vec = int(rel) / kE;
-        if ((vec & (kThreads - 1)) != (int)threadIdx.x) return -1;
-        return (vec / kThreads) * kE + (int(rel) - vec * kE);
-      };
-      const int xd = min(max(a.tokens[int64_t(b) * a.L + r.j], 0), a.V - 1);
-      const int m = a.lan_count[int64_t(b) * a.L + r.j];
-      lp.agg = r.omega;
-      lp.aggpos = slot(xd);
-      const int32_t* row = a.nbr + int64_t(xd) * a.lan_k;
-      int taken = 0;
-      for (int jj = 0; jj < a.lan_k && taken < m; ++jj) {   // the first m valid neighbours are the members
-        const int n = row[jj];
-        if (n < 0 || n >= a.V || n == xd) continue;
-        ++taken;
-        const int sl = slot(n);
-        if (sl >= 0) lp.zmask |= 1u << sl;
-      }
-    }
+    if (!r.bonus) lp = lan_patch_tile<Vec<DT>::kE>(a, b, r.j, r.omega, base, kChunk2);
   }
   // only the chunk's total is needed: per-thread sum in ascending tile order, one wave reduction,
   // one barrier
@@ -399,6 +404,179 @@ __global__ __launch_bounds__(kThreadsW) void sequence_select_kernel(const KArgs 
     writer = threadIdx.x == 0;
   }
   if (writer) {
+    a.next_token[b] = token;
+    if (a.resid_mass) a.resid_mass[b] = R;
+  }
+}
+
+// ============================================================================ long rows, one launch
+// Everything after the statistics pass for sequences whose rows have at most 64 statistics chunks
+// and at most kTauRows positions: G workgroups of 256 threads per sequence.
+//   1. every workgroup finds tau for itself from the chunk statistics (find_tau_from_parts; the
+//      first one writes accept_len and the per-position outputs);
+//   2. workgroup g streams chunks g, g + G, ... of the sampled row pair (8192 logits each, at most
+//      kTailPer per workgroup) and leaves each chunk's residual mass in the workspace;
+//   3. it then takes a ticket of its sequence; the workgroup that draws the last ticket knows that
+//      all chunk masses of the sequence are written: it picks the chunk that holds u*R (lane per
+//      chunk, one wave scan), re-reads that one chunk and finds the token in it, tile -> thread ->
+//      element, like the early-exit kernel does on its rows.
+// No workgroup waits for another: whoever comes last does the rest, so the grid need not be
+// resident at once.  Ordering: a chunk mass is written with a device-scope atomic store whose
+// completion the writer awaits before its device-scope fetch-add on the ticket, and the last
+// workgroup reads the masses with device-scope atomic loads.  The tickets are cleared by the
+// statistics launch of the same call (first workgroup of every sequence).
+// Against the three launches this replaces (accept_kernel, sequence_masses_kernel,
+// sequence_select_kernel) it saves two launch gaps and one of the three latency chains.
+constexpr int kTailPer = 8;      // chunks one workgroup of the tail launch takes at most
+template <int DT, bool XF, bool AL, int kT, bool LAN>
+__global__ __launch_bounds__(kThreads) void sequence_tail_kernel(const KArgs a) {
+  constexpr int kE = Vec<DT>::kE;
+  constexpr int kChunk2 = kT * kThreads * kE;            // logits per sampling chunk (8192)
+  __shared__ Smem sm;
+  __shared__ SmemTau smt;
+  __shared__ ExactSmem<kThreads> smx;
+  __shared__ int last_flag;
+  const int C = a.nchunks, G = a.tail_groups;
+  const int b = blockIdx.x / G, g = blockIdx.x - b * G;
+  const int tau = find_tau_from_parts(a, b, g == 0, smt);
+  const float4 rs = smt.rowstat;                         // statistics of the sampled row
+  const SampledRow r = sampled_row<DT, XF>(a, b, tau, smt.omega);
+  if (r.none) {
+    if (g == 0 && threadIdx.x == 0) {
+      a.next_token[b] = -1;
+      if (a.resid_mass) a.resid_mass[b] = 0.f;
+    }
+    return;
+  }
+  ResidCoef k{rs.x, 1.f / rs.y, rs.z, r.bonus ? 1.f : 1.f / rs.w, r.omega,
+              r.bonus ? kModeP : (a.resample_mode == 1 ? kModeVanilla : kModeOpt)};
+  const int law = k.mode;
+  // The mass pass: this workgroup's chunks g, g + G, ... (at most kTailPer of them), each read
+  // exactly once (nontemporal loads).  Two register sets alternate, so the loads of the next chunk
+  // are in flight while the current one is summed; a thread keeps one partial sum per chunk and
+  // nothing is exchanged between threads until all chunks are done (no barrier in the loop).
+  constexpr int kA = AL ? kAlignedStream : kUnaligned;
+  float acc[kTailPer];
+#pragma unroll
+  for (int i = 0; i < kTailPer; ++i) acc[i] = 0.f;
+  auto fetch = [&](RowRegs<DT, XF, kT>& rt, RowRegs<DT, XF, kT>& rd, int c) {
+    const int64_t base = int64_t(c) * kChunk2;
+    load_chunk<DT, XF, kA, kT>(rt, r.t_c, r.t_u, base, a.V, a.cfg_scale, a.inv_T, r.thr_t);
+    if (!r.bonus) load_chunk<DT, XF, kA, kT>(rd, r.d_c, r.d_u, base, a.V, a.cfg_scale, a.inv_T, r.thr_d);
+    else rd.clear();                                    // never read in mode P
+  };
+  auto chunk_sum = [&](const RowRegs<DT, XF, kT>& rt, const RowRegs<DT, XF, kT>& rd, int c) -> float {
+    LanPatch lp{0u, -1, 1.f};
+    if constexpr (LAN) {
+      if (!r.bonus) lp = lan_patch_tile<kE>(a, b, r.j, r.omega, int64_t(c) * kChunk2, kChunk2);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int t = 0; t < kT; ++t) {
+#pragma unroll
+      for (int e = 0; e < kE; ++e) sum = __fadd_rn(sum, tile_elem<DT, XF, kT, LAN>(rt, rd, k, lp, t, e));
+    }
+    return sum;
+  };
+  {
+    RowRegs<DT, XF, kT> rt0, rd0, rt1, rd1;
+    if (g < C) fetch(rt0, rd0, g);
+#pragma unroll
+    for (int i = 0; i < kTailPer; i += 2) {
+      const int c0 = g + i * G, c1 = c0 + G, c2 = c1 + G;
+      if (c1 < C) fetch(rt1, rd1, c1);
+      if (c0 < C) acc[i] = chunk_sum(rt0, rd0, c0);
+      if (i + 2 < kTailPer && c2 < C) fetch(rt0, rd0, c2);
+      if (i + 1 < kTailPer && c1 < C) acc[i + 1] = chunk_sum(rt1, rd1, c1);
+    }
+  }
+  // one reduction for all chunks of this workgroup: wave sums to LDS, then thread i adds the four
+  // wave sums of its i-th chunk and writes the chunk's mass with a device-scope store
+#pragma unroll
+  for (int i = 0; i < kTailPer; ++i) {
+    const float ws = wave_sum(acc[i]);
+    if ((threadIdx.x & 63) == 0) sm.tile_part[threadIdx.x >> 6][i] = ws;
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < kTailPer && g + (int)threadIdx.x * G < C) {
+    const int i = threadIdx.x;
+    const float m = __fadd_rn(__fadd_rn(sm.tile_part[0][i], sm.tile_part[1][i]), __fadd_rn(sm.tile_part[2][i], sm.tile_part[3][i]));
+    __hip_atomic_store(&a.chunk_R[int64_t(b) * C + g + i * G], m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // this thread's store has been acknowledged before the barrier that precedes the ticket
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+  __syncthreads();
+  // the ticket: this workgroup's masses were written with device-scope stores, which go through to
+  // the point where every compute die sees them, and each writer has waited for the acknowledgement
+  // before the barrier above; only then does the workgroup count itself.  (A release fence would do the same and more: it also
+  // writes back every dirty line of the die's L2, which costs far more than this launch.)
+  if (threadIdx.x == 0) {
+    const int old = __hip_atomic_fetch_add(&a.ticket[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    last_flag = old == G - 1;
+  }
+  __syncthreads();
+  if (!last_flag) return;
+  // the last workgroup reads the masses with device-scope loads (never from a stale cache line)
+
+  // the chunk that holds u*R: first with positive mass whose inclusive sum exceeds u*R, else the
+  // last with mass; lane c of every wave takes chunk c (C <= 64)
+  const int lane = threadIdx.x & 63;
+  const int per = kChunk2 / a.chunk1;
+  auto p_mass = [&](int cc) -> float {        // mass of chunk cc under the fall-back law p, from the statistics pass
+    float m = 0.f;
+    for (int q = cc * per; q < min((cc + 1) * per, a.c1); ++q) {
+      const float2 pp = a.part[int64_t(r.rt_) * a.c1 + q];
+      m = __fadd_rn(m, __fmul_rn(__fmul_rn(pp.y, exp2_fast(pp.x - rs.x)), k.at));
+    }
+    return m;
+  };
+  float m = lane < C ? __hip_atomic_load(&a.chunk_R[int64_t(b) * C + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+  float incl = wave_scan_incl(m);
+  float R = lane_f(incl, 63);
+  bool fallback = false;
+  if (!(R > 0.f)) {    // no rejection possible at this position: any law is optimal, use p
+    fallback = true;
+    k.mode = kModeP;
+    m = lane < C ? p_mass(lane) : 0.f;
+    incl = wave_scan_incl(m);
+    R = lane_f(incl, 63);
+  }
+  const float v = __fmul_rn(a.u_res[b], R);
+  const float excl = wave_prev_lane(incl);
+  const bool pos = m > 0.f;
+  const unsigned long long bh = __ballot(pos && incl > v), bp = __ballot(pos);
+  const int cs = bh ? __ffsll((long long)bh) - 1 : (bp ? 63 - __clzll((long long)bp) : 0);
+  const float v_in = __fsub_rn(v, lane_f(excl, cs));   // mass left to walk inside the chunk
+  bool trust = bh != 0 && !fallback && (law == kModeP || R >= kSafeMass);
+
+  const int64_t base = int64_t(cs) * kChunk2;
+  RowRegs<DT, XF, kT> rt, rd;
+  load_chunk<DT, XF, AL ? kAligned : kUnaligned, kT>(rt, r.t_c, r.t_u, base, a.V, a.cfg_scale, a.inv_T, r.thr_t);
+  if (!r.bonus) load_chunk<DT, XF, AL ? kAligned : kUnaligned, kT>(rd, r.d_c, r.d_u, base, a.V, a.cfg_scale, a.inv_T, r.thr_d);
+  else rd.clear();
+  LanPatch lp{0u, -1, 1.f};
+  if constexpr (LAN) {
+    if (!r.bonus && !fallback) lp = lan_patch_tile<kE>(a, b, r.j, r.omega, base, kChunk2);
+  }
+  float part[kT];
+  chunk_masses<DT, XF, kT, LAN>(rt, rd, k, part, sm, lp);
+  bool chunk_trust;
+  int token = (int)base + max(chunk_select<DT, XF, kT, LAN>(rt, rd, k, part, v_in, sm, chunk_trust, lp), 0);
+  token = min(token, a.V - 1);
+  if (!(trust && chunk_trust) || a.exact_draw) {
+    ExactJob job{{r.t_c, r.t_u, r.thr_t, (double)rs.x}, {r.d_c, r.d_u, r.thr_d, (double)rs.z}, DT, XF, a.V, a.cfg_scale,
+                 a.inv_T, r.omega, law, nullptr, 0, 0, 0};
+    if constexpr (LAN) {
+      if (!r.bonus) {
+        job.lan_x = min(max(a.tokens[int64_t(b) * a.L + r.j], 0), a.V - 1);
+        job.nbr_row = a.nbr + int64_t(job.lan_x) * a.lan_k;
+        job.lan_k = a.lan_k;
+        job.lan_m = a.lan_count[int64_t(b) * a.L + r.j];
+      }
+    }
+    token = exact_draw<kThreads>(job, a.u_res[b], R, smx);
+  }
+  if (threadIdx.x == 0) {
     a.next_token[b] = token;
     if (a.resid_mass) a.resid_mass[b] = R;
   }

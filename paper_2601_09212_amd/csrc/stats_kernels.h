@@ -142,6 +142,9 @@ __global__ __launch_bounds__(kThreads, 3) void row_stats_kernel(const KArgs a) {
   const RowRef rw = row_ref<DT, G3>(a, lin);
   const int r = rw.r;
   const int64_t base = int64_t(c) * (NT * kThreads * kE);
+  // the first workgroup of every sequence clears the sequence's ticket for the long-row tail launch
+  // that follows in the stream
+  if (c == 0 && rw.i == 0 && !rw.is_draft && threadIdx.x == 0) a.ticket[rw.b] = 0;
 
   // rows longer than one workgroup under top-k: the threshold was selected by the radix passes
   float thr = -INFINITY;

@@ -30,6 +30,7 @@ __global__ __launch_bounds__(TPB, ROW == kChunk ? 6 : 4) void row_stats_topk_ker
   __shared__ float red_s[kSub][kW];
   const RowRef rw = row_ref<DT, G3>(a, blockIdx.x);
   const int r = rw.r;
+  if (rw.i == 0 && !rw.is_draft && threadIdx.x == 0) a.ticket[rw.b] = 0;   // for the long-row tail launch that follows
   topk_prepare(ts);                                     // the barrier inside topk_threshold orders it
   RowRegs<DT, true, kVW> x;
   // vector k of thread t is vector k*TPB + t of the row

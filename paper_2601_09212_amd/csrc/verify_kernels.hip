@@ -83,9 +83,9 @@ hipError_t launch_diagnostics(const KArgs& a, int dtype, bool xf, bool local, hi
   if (local) return launch_diag_local(a, dtype, xf, /*ver=*/false, stream);
   hipError_t e = have_stats ? hipSuccess : launch_statistics(a, dtype, xf, stream);
   if (e != hipSuccess) return e;
-  // after a verify call accept_kernel has left the combined rows, unless tau was found by the
-  // chunk-mass launch (which combines in LDS only)
-  const bool have_rows = have_stats && a.accept_combines && !tau_in_mass_launch(a, dtype);
+  // after a verify call accept_kernel has left the combined rows, unless the per-sequence step ran
+  // as one launch (which combines in LDS only)
+  const bool have_rows = have_stats && a.accept_combines && !tail_in_one_launch(a, dtype);
   if (a.cs != a.c1 && !have_rows) {
     e = launch_combine_rows(a, stream);
     if (e != hipSuccess) return e;

@@ -78,15 +78,22 @@ typedef enum {
 
 /* Options of cool_sd_verify (cool_sd_params.flags). */
 typedef enum {
-  /* Algorithm 1 stops at the first rejection; with this flag so does the memory traffic: one
-   * workgroup per sequence walks positions 1, 2, ... and reads no row pair after the rejected one
-   * (except the single pair whose loads were already issued ahead).  Pays when B is at least
-   * the number of compute units, since most of the 2L+1 rows are then never read.  Honoured for
-   * V <= 16384, L <= 1024, top_k == 0 and 16-byte aligned rows (base pointers and strides multiples
-   * of 16 bytes, V a multiple of 8 for bf16 / 4 for fp32); otherwise the call silently runs the
-   * all-rows path.
-   * When honoured, p_tok / q_tok / f of positions after the rejected one are NaN and the
-   * workspace is not touched.  accept_len, next_token and resid_mass mean the same in both. */
+  /* Algorithm 1 stops at the first rejection; with this flag so does the memory traffic.  Two
+   * forms, chosen by the shape (cool_sd_early_exit_form tells which):
+   *   V <= 16384 (and L <= 1024, 16-byte aligned rows: base pointers and strides multiples of 16
+   *   bytes, V a multiple of 8 for bf16 / 4 for fp32): one workgroup per sequence walks positions
+   *   1, 2, ... and reads no row pair after the rejected one (except the single pair whose loads
+   *   were already issued ahead); the workspace is not touched.  Pays when B is at least the
+   *   number of compute units.
+   *   16384 < V <= 524288, any alignment: the call verifies in rounds of 1, 1, 2, 4, ... positions
+   *   (two launches per round); a sequence's rows are read up to the end of the round that holds
+   *   its rejection, then the row pair it samples from once more.  Pays when rejections come
+   *   early in the window; costs about 7 us per round when they do not.
+   * Not honoured under top-k, by cool_sd_verify_lantern and cool_sd_verify_diagnostics, or for
+   * shapes outside the two forms: the call then reads every row, and cool_sd_early_exit_form
+   * returns COOL_SD_EARLY_EXIT_NONE.
+   * When honoured, p_tok / q_tok / f of positions after the rejected one are NaN.  accept_len,
+   * next_token and resid_mass mean the same in all forms. */
   COOL_SD_FLAG_EARLY_EXIT = 1,
   /* Checked mode of the verify calls: one more (small) kernel after the others looks at every
    * draft token on the device; a sequence that holds a token outside [0, V) gets
@@ -299,6 +306,15 @@ COOL_SD_API int cool_sd_verify_diagnostics(const cool_sd_params* p,
                                float* alpha_dev, float* beta_dev,
                                void* workspace_dev, size_t workspace_bytes,
                                void* hip_stream);
+
+/* How cool_sd_verify (and cool_sd_verify_noalloc) would honour COOL_SD_FLAG_EARLY_EXIT for these
+ * parameters.  rows_aligned: nonzero when every logit row of the call starts on a 16-byte boundary
+ * (base pointers and strides) and V is a multiple of a 16-byte vector.  Host only: no device call.
+ * Returns one of the values below, or COOL_SD_EINVAL. */
+#define COOL_SD_EARLY_EXIT_NONE 0     /* flag clear or not honoured: every row is read        */
+#define COOL_SD_EARLY_EXIT_SEQUENCE 1 /* one workgroup per sequence, position by position     */
+#define COOL_SD_EARLY_EXIT_ROUNDS 2   /* long rows: rounds of positions                       */
+COOL_SD_API int cool_sd_early_exit_form(const cool_sd_params* p, int rows_aligned);
 
 /* Static description of a cool_sd_status. */
 COOL_SD_API const char* cool_sd_strerror(int code);

@@ -16,6 +16,7 @@ COOL_SD_FLAG_EARLY_EXIT, COOL_SD_FLAG_CHECK_TOKENS, COOL_SD_FLAG_EXACT_DRAW = 1,
 COOL_SD_OK, COOL_SD_EINVAL, COOL_SD_EWORKSPACE, COOL_SD_ELAUNCH, COOL_SD_EUNSUPPORTED = 0, -1, -2, -3, -4
 COOL_SD_ETOOLARGE = -5
 COOL_SD_NOALLOC_WORKSPACE_BYTES = 4 << 20
+COOL_SD_EARLY_EXIT_NONE, COOL_SD_EARLY_EXIT_SEQUENCE, COOL_SD_EARLY_EXIT_ROUNDS = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcool_sd.so")
@@ -74,6 +75,8 @@ def load(path):
     L.cool_sd_resample.restype = C.c_int
     L.cool_sd_diagnostics.argtypes = [pp] + [vp] * 7 + [vp, C.c_size_t, vp]
     L.cool_sd_diagnostics.restype = C.c_int
+    L.cool_sd_early_exit_form.argtypes = [pp, C.c_int]
+    L.cool_sd_early_exit_form.restype = C.c_int
     L.cool_sd_strerror.argtypes = [C.c_int]
     L.cool_sd_strerror.restype = C.c_char_p
     return L
@@ -110,6 +113,14 @@ def _stream(stream):
         import torch
         stream = torch.cuda.current_stream().cuda_stream
     return C.c_void_p(stream)
+
+
+def cool_sd_early_exit_form(params, rows_aligned=True):
+    """How a verify call with these parameters honours COOL_SD_FLAG_EARLY_EXIT (host only)."""
+    rc = lib().cool_sd_early_exit_form(C.byref(params), int(bool(rows_aligned)))
+    if rc < 0:
+        raise CoolSDError(rc, "cool_sd_early_exit_form")
+    return rc
 
 
 def cool_sd_strerror(code):

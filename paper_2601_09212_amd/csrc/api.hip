@@ -187,6 +187,12 @@ int cool_sd_verify_diagnostics(const cool_sd_params* p, const void* target_dev, 
              resid_mass_dev, workspace_dev, workspace_bytes, hip_stream, nullptr, alpha_dev, beta_dev);
 }
 
+int cool_sd_early_exit_form(const cool_sd_params* p, int rows_aligned) {
+  if (!params_ok(p, /*for_resample=*/false)) return COOL_SD_EINVAL;
+  const int kE = (p->dtype == COOL_SD_BF16) ? 8 : 4;
+  return early_exit_form(p, rows_aligned != 0 && p->V % kE == 0);
+}
+
 const char* cool_sd_strerror(int code) {
   switch (code) {
     case COOL_SD_OK: return "ok";

@@ -42,7 +42,7 @@ Layout make_layout(int64_t B, int64_t rows, int64_t c1, int64_t C, int64_t pairs
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes); return at; };
   o.seq_stat = take(size_t(B) * 16);
-  o.ticket = take(size_t(B) * 4);
+  o.ticket = take(size_t(B) * 8);       // tickets, then the state of a verification in rounds
   o.chunk_R = take(size_t(B) * C * 4);
   o.thr = take(size_t(rows) * 4);
   o.tok_logit = take(size_t(rows) * 4);
@@ -109,6 +109,16 @@ inline int call_flags(const cool_sd_params* p) {
 #endif
 }
 
+// How a verify call with these parameters honours COOL_SD_FLAG_EARLY_EXIT (cool_sd_early_exit_form).
+// aligned: every row starts on a 16-byte boundary and V is a multiple of a 16-byte vector.
+inline int early_exit_form(const cool_sd_params* p, bool aligned) {
+  if (!(p->flags & COOL_SD_FLAG_EARLY_EXIT) || p->top_k != 0) return COOL_SD_EARLY_EXIT_NONE;
+  if (p->V <= csd::kChunk) return (aligned && p->L <= 1024) ? COOL_SD_EARLY_EXIT_SEQUENCE : COOL_SD_EARLY_EXIT_NONE;
+  // rounds: a row's chunk statistics fit one wave, and the three-dimensional grid holds the call
+  const Chunking ch = pick_chunking(p, int64_t(p->B) * (2 * int64_t(p->L) + p->has_bonus));
+  return (ch.c1 <= 64 && p->B <= 65535) ? COOL_SD_EARLY_EXIT_ROUNDS : COOL_SD_EARLY_EXIT_NONE;
+}
+
 inline bool is_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Workspace layout of one verify / stand-alone resample call, with the chunking it runs with.
@@ -170,8 +180,9 @@ int run(const cool_sd_params* p, bool resample_only,
   a.aligned = aligned ? 1 : 0;
   a.stats_only = stats_only ? 1 : 0;
   a.exact_draw = (p->flags & COOL_SD_FLAG_EXACT_DRAW) ? 1 : 0;
-  a.early_exit = (!resample_only && !lan && aligned && (p->flags & COOL_SD_FLAG_EARLY_EXIT) && p->top_k == 0 &&
-                  p->V <= csd::kChunk && p->L <= 1024) ? 1 : 0;
+  const int form = (resample_only || lan || alpha || stats_only) ? COOL_SD_EARLY_EXIT_NONE : early_exit_form(p, aligned);
+  a.early_exit = form == COOL_SD_EARLY_EXIT_SEQUENCE ? 1 : 0;
+  a.windowed = form == COOL_SD_EARLY_EXIT_ROUNDS ? 1 : 0;
   if (lan) {
     // Eq. f_lantern is Eq. relax with a data-dependent omega_i >= 1 that lantern_agg_kernel leaves
     // in the workspace; with f >= f^van the optimal law G* is [p - q]_+ (Proposition on the design
@@ -202,6 +213,7 @@ int run(const cool_sd_params* p, bool resample_only,
   a.chunk_R = reinterpret_cast<float*>(w + lay.chunk_R);
   a.seq_stat = reinterpret_cast<float4*>(w + lay.seq_stat);
   a.ticket = reinterpret_cast<int32_t*>(w + lay.ticket);
+  a.tau_ws = a.ticket + p->B;
   a.thr = reinterpret_cast<float*>(w + lay.thr);
   a.tok_logit = reinterpret_cast<float*>(w + lay.tok_logit);
   a.part = reinterpret_cast<float2*>(w + lay.part);

@@ -22,7 +22,7 @@ constexpr float kLog2e = 1.44269504088896340736f;
 constexpr float kRefFloor = -1.5e30f;  // "no finite logit seen yet" reference exponent
 // how a kernel may load a row: element-wise, 16-byte vectors, or 16-byte vectors with the
 // nontemporal hint (large read-once inputs)
-enum { kUnaligned = 0, kAligned = 1, kAlignedStream = 2 };
+enum { kUnaligned = 0, kAligned = 1, kAlignedStream = 2, kAlignedFull = 3 };
 
 template <int DT> struct Vec {
   static constexpr int kE = (DT == kDtBF16) ? 8 : 4;       // elements per 16-byte vector
@@ -90,10 +90,16 @@ __device__ __forceinline__ float wave_sum(float v) {
   v = __fadd_rn(v, dpp_f<kDppMirror>(v));
   return __fadd_rn(__fadd_rn(lane_f(v, 0), lane_f(v, 16)), __fadd_rn(lane_f(v, 32), lane_f(v, 48)));
 }
+template <int CTRL> __device__ __forceinline__ int dpp_i(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
 __device__ __forceinline__ int wave_min_i(int v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, 64));
-  return v;
+  v = min(v, dpp_i<kDppSwap1>(v));
+  v = min(v, dpp_i<kDppSwap2>(v));
+  v = min(v, dpp_i<kDppHalfMirror>(v));
+  v = min(v, dpp_i<kDppMirror>(v));
+  return min(min(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+             min(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
 }
 // Inclusive prefix sum over the 64 lanes of a wave, ascending lane order, without LDS traffic:
 // four DPP row shifts (1, 2, 4, 8; lanes without a source read 0) scan each row of 16 lanes,
@@ -143,6 +149,8 @@ template <int DT> __device__ __forceinline__ uint4 neg_inf_vec() {
 template <int DT, int AL>
 __device__ __forceinline__ uint4 load_vec(const char* __restrict__ row, int64_t e, int V) {
   constexpr int kE = Vec<DT>::kE;
+  if (AL == kAlignedFull)       // the caller knows that every vector it asks for lies inside the row
+    return *reinterpret_cast<const uint4*>(row + e * Vec<DT>::kES);
   if (AL) {
     const bool in = e < V;
     const int64_t ec = in ? e : int64_t(V - kE);

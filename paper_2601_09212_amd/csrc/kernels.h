@@ -22,6 +22,7 @@ struct KArgs {
   int32_t rows_t, rows_d;   // target rows B*(L+has_bonus), draft rows B*L (0: no draft)
   int32_t c1, top_k;        // statistics chunks per row; top-k (0 = off)
   float cfg_scale, inv_T;
+  int32_t win_lo, win_hi;   // statistics pass over the rows of positions [win_lo, win_hi) only (win_hi == 0: all rows)
   // --- the rest
   int64_t om_sb;
   const float* omega;       // [L] or [B, L]
@@ -48,6 +49,8 @@ struct KArgs {
   float* chunk_R;           // [B, nchunks]  residual mass per chunk of the sampled row  (nchunks > 1)
   int32_t* ticket;          // [B]           workgroups of the long-row tail launch that have finished their chunks
   int32_t tail_groups;      // workgroups per sequence of that launch
+  int32_t windowed;         // verify in rounds of positions that stop reading a sequence after its first rejection
+  int32_t* tau_ws;          // [B]           that form's state: -1 while every position so far was accepted, else tau
   // top-k on rows longer than one workgroup: radix-select state in the workspace
   uint32_t* rk_hist;        // [rows_t + rows_d, 2048] digit counts of the current pass
   uint32_t* rk_state;       // [rows_t + rows_d, 2]    key bits fixed so far, rank still to find
@@ -117,6 +120,9 @@ bool tail_in_one_launch(const KArgs& a, int dtype);
 hipError_t launch_combine_rows(const KArgs& a, hipStream_t stream);
 // the whole verify call per sequence, stopping at the first rejection (COOL_SD_FLAG_EARLY_EXIT)
 hipError_t launch_early_exit(const KArgs& a, int dtype, bool xf, hipStream_t stream);
+// the same flag on long rows: after the statistics launch of the window [win_lo, win_hi), the accept
+// tests of that window for the sequences still without a rejection
+hipError_t launch_accept_window(const KArgs& a, int dtype, bool xf, hipStream_t stream);
 // cool_sd_resample on rows one workgroup holds, without top-k: one launch
 bool resample_whole_fits(const KArgs& a);
 hipError_t launch_resample_whole(const KArgs& a, int dtype, bool xf, hipStream_t stream);

@@ -56,7 +56,7 @@ template <int DT, bool XF, bool AL>
 static hipError_t launch_sequence_typed(const KArgs& a, hipStream_t stream) {
   constexpr int kT = Vec<DT>::kT;
   hipError_t e;
-  const bool one_launch = tail_in_one_launch(a, DT) && !(AL && !a.lan_resample && a.V <= 2 * kChunk);
+  const bool one_launch = !a.windowed && tail_in_one_launch(a, DT) && !(AL && !a.lan_resample && a.V <= 2 * kChunk);
   // the long-row kernels of the stand-alone resampling call combine up to 64 chunk statistics themselves
   const bool resample_combines = a.resample_only && a.nt2 != kT && a.c1 <= 64;
   if (a.cs != a.c1 && !a.accept_combines && !one_launch && !resample_combines) {   // rows have many statistics chunks: pre-combine them
@@ -76,7 +76,7 @@ static hipError_t launch_sequence_typed(const KArgs& a, hipStream_t stream) {
   if constexpr (AL) {
     // aligned rows of up to 32768 logits (four statistics chunks, read directly) still fit the
     // registers of one workgroup: the one-launch form
-    if (!a.lan_resample && a.V <= 2 * kChunk)
+    if (!a.lan_resample && !a.windowed && a.V <= 2 * kChunk)
       return launch("sequence_whole_kernel", sequence_whole_kernel<DT, XF, AL, false, 2>, gB, bW, stream, a);
   }
   if (one_launch) {
@@ -84,7 +84,7 @@ static hipError_t launch_sequence_typed(const KArgs& a, hipStream_t stream) {
     if (a.lan_resample) return launch("sequence_tail_kernel", sequence_tail_kernel<DT, XF, AL, kT / 2, true>, gridt, dim3(kThreads), stream, a);
     return launch("sequence_tail_kernel", sequence_tail_kernel<DT, XF, AL, kT / 2, false>, gridt, dim3(kThreads), stream, a);
   }
-  if (!a.resample_only) {     // find tau once per sequence
+  if (!a.resample_only && !a.windowed) {     // find tau once per sequence (verification in rounds has done it)
     e = launch("accept_kernel", accept_kernel<DT, XF>, gB, bW, stream, a);
     if (e != hipSuccess) return e;
   }
@@ -108,6 +108,15 @@ static hipError_t launch_sequence_typed(const KArgs& a, hipStream_t stream) {
 
 hipError_t launch_sequence(const KArgs& a, int dtype, bool xf, hipStream_t stream) {
   CSD_DISPATCH(launch_sequence_typed, a, stream);
+}
+
+hipError_t launch_accept_window(const KArgs& a, int dtype, bool xf, hipStream_t stream) {
+  const dim3 gB((unsigned)a.B), bk(kThreads);
+  const char* what = "accept_window_kernel";
+  if (dtype == kDtBF16) return xf ? launch(what, accept_window_kernel<kDtBF16, true>, gB, bk, stream, a)
+                                  : launch(what, accept_window_kernel<kDtBF16, false>, gB, bk, stream, a);
+  return xf ? launch(what, accept_window_kernel<kDtF32, true>, gB, bk, stream, a)
+            : launch(what, accept_window_kernel<kDtF32, false>, gB, bk, stream, a);
 }
 
 // Early exit: aligned rows only (the caller checks the conditions of COOL_SD_FLAG_EARLY_EXIT).

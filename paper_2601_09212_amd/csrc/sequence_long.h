@@ -226,6 +226,92 @@ __global__ __launch_bounds__(kThreadsW) void accept_kernel(const KArgs a) {
   if (threadIdx.x == 0) a.seq_stat[b] = sm.rowstat;
 }
 
+// COOL_SD_FLAG_EARLY_EXIT on long rows: Algorithm 1's `break`, taken between launches.  The call
+// walks the draft window in rounds of 1, 1, 2, 4, ... positions (at most 63, the bonus row rides with
+// the last round); a round is a statistics launch over the rows of its positions -- workgroups of a
+// sequence that already has its rejection return at once -- followed by this kernel, which runs the
+// accept tests of the round for the sequences still without a rejection: 256 threads per sequence,
+// wave w combines the chunk statistics of rows w, w+4, ... of the round (lane c takes chunk c: rows
+// of at most 64 chunks), then lane i of the first wave tests position win_lo + i.  A sequence whose
+// tau is now known gets accept_len and the statistics of the row it samples from, as accept_kernel
+// would leave them; the per-position outputs of positions after the rejected one are NaN (never
+// evaluated).  tau_ws[b] stays -1 while the sequence has no rejection.
+template <int DT, bool XF>
+__global__ __launch_bounds__(kThreads) void accept_window_kernel(const KArgs a) {
+  __shared__ SmemTau sm;
+  const int b = blockIdx.x, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int rps = a.L + a.has_bonus;
+  const int lo = a.win_lo, ht = min(a.win_hi, rps), hd = min(a.win_hi, a.L);
+  const int nt = ht - lo, nd = max(hd - lo, 0), nrows = nt + nd;
+  const bool last = a.win_hi >= rps;
+  if (lo > 0 && a.tau_ws[b] >= 0) {           // rejected in an earlier round
+    for (int i = lo + threadIdx.x; i < hd; i += kThreads) {
+      const int64_t o = int64_t(b) * a.L + i;
+      if (a.p_tok) a.p_tok[o] = NAN;
+      if (a.q_tok) a.q_tok[o] = NAN;
+      if (a.f) a.f[o] = NAN;
+    }
+    return;
+  }
+  const int pos = lo + lane;
+  const bool mine = wv == 0 && lane < nt;               // this lane tests position `pos`
+  const bool has_draft = pos < a.L;
+  float lt = 0.f, ld = 0.f, omega = 1.f, u = 0.f;
+  if (mine) {
+    lt = a.tok_logit[b * rps + pos];
+    if (has_draft) {
+      ld = a.tok_logit[a.rows_t + b * a.L + pos];
+      omega = a.omega[int64_t(b) * a.om_sb + pos];
+      u = a.u_acc[int64_t(b) * a.L + pos];
+    }
+  }
+  const int cl = lane < a.c1 ? lane : 0;
+  constexpr int kBatch = 4;                             // rows whose loads a wave has in flight together
+  for (int q0 = wv; q0 < nrows; q0 += kWaves * kBatch) {
+    float2 v[kBatch];
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k) {
+      const int q = min(q0 + k * kWaves, nrows - 1);      // clamped: a row past the end is read and dropped
+      const int row = q < nt ? b * rps + lo + q : a.rows_t + b * a.L + lo + (q - nt);
+      v[k] = a.part[int64_t(row) * a.c1 + cl];
+    }
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k) {
+      const int q = q0 + k * kWaves;
+      const float cx = lane < a.c1 ? v[k].x : kRefFloor, sx = lane < a.c1 ? v[k].y : 0.f;
+      const float m = wave_max(cx);
+      const float t = wave_sum(sx * exp2_fast(cx - m));
+      if (lane == 0 && q < nrows) sm.st[q] = make_float2(m, t);
+    }
+  }
+  __syncthreads();
+  if (wv != 0) return;
+  bool rej = false;
+  float Ct = kRefFloor, St = 0.f, Cd = kRefFloor, Sd = 0.f;
+  if (mine) {
+    const float2 t2 = sm.st[lane];
+    Ct = t2.x; St = t2.y;
+    if (has_draft) {
+      const float2 d2 = sm.st[nt + lane];
+      Cd = d2.x; Sd = d2.y;
+    }
+    rej = accept_test(a, b, pos, true, has_draft, Ct, St, Cd, Sd, lt, ld, omega, u);
+  }
+  const unsigned long long br = __ballot(rej);
+  const int w = br ? __ffsll((long long)br) - 1 : (last ? a.L - lo : -1);    // lane of the sampled row, -1: none yet
+  if (w >= 0 && mine && has_draft && lane > w) {        // positions after the rejected one
+    const int64_t o = int64_t(b) * a.L + pos;
+    if (a.p_tok) a.p_tok[o] = NAN;
+    if (a.q_tok) a.q_tok[o] = NAN;
+    if (a.f) a.f[o] = NAN;
+  }
+  if (w >= 0 && lane == w) a.seq_stat[b] = make_float4(Ct, St, Cd, Sd);      // position tau, or the bonus row
+  if (lane == 0) {
+    a.tau_ws[b] = w >= 0 ? lo + w : -1;
+    if (w >= 0) a.accept_len[b] = lo + w;
+  }
+}
+
 // Chunk masses of the sampled rows as a launch of its own (the three-launch form: rows of more than
 // 64 statistics chunks, draft windows beyond kTauRows positions, the stand-alone resampling call).
 template <int DT, bool XF, bool AL, int kT, bool LAN>

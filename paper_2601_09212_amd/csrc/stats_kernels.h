@@ -23,9 +23,12 @@ template <int DT, bool G3> __device__ __forceinline__ RowRef row_ref(const KArgs
   RowRef o;
   const int per_t = a.L + a.has_bonus;
   if (G3) {
+    // grid.y counts the target rows of the window of positions, then its draft rows (the window
+    // is the whole sequence unless the call verifies in rounds)
+    const int wt = (a.win_hi ? min(a.win_hi, per_t) : per_t) - a.win_lo;
     o.b = blockIdx.z;
-    o.is_draft = (int)blockIdx.y >= per_t;
-    o.i = o.is_draft ? blockIdx.y - per_t : blockIdx.y;
+    o.is_draft = (int)blockIdx.y >= wt;
+    o.i = a.win_lo + (o.is_draft ? blockIdx.y - wt : blockIdx.y);
     o.r = o.is_draft ? a.rows_t + o.b * a.L + o.i : o.b * per_t + o.i;
   } else {
     o.r = lin;
@@ -139,6 +142,10 @@ __global__ __launch_bounds__(kThreads, 3) void row_stats_kernel(const KArgs a) {
     }
   }
   const int lin = G3 ? 0 : blockIdx.x / C1, c = G3 ? blockIdx.x : blockIdx.x - lin * C1;
+  if constexpr (G3) {
+    // verification in rounds: a sequence that has its rejection needs no further row
+    if (a.win_lo > 0 && a.tau_ws[blockIdx.z] >= 0) return;
+  }
   const RowRef rw = row_ref<DT, G3>(a, lin);
   const int r = rw.r;
   const int64_t base = int64_t(c) * (NT * kThreads * kE);

@@ -2,6 +2,7 @@
 // translation units stats_bf16_xf.hip, stats_bf16_plain.hip, stats_f32_xf.hip and
 // stats_f32_plain.hip each instantiate one (dtype, transform) slice so that they compile in parallel.
 #pragma once
+#include <algorithm>
 #include "stats_kernels.h"
 #include "topk_kernels.h"
 
@@ -13,7 +14,9 @@ hipError_t launch_topk_radix_select(const KArgs& a, int pass, hipStream_t stream
 // Grid of a statistics kernel: (chunks, rows of one sequence, sequences) when the dimensions
 // allow it, else one dimension.
 inline bool stats_grid3(const KArgs& a, dim3& grid) {
-  const int64_t per_seq = int64_t(a.L) + a.has_bonus + (a.rows_d ? a.L : 0);
+  const int64_t per_t = int64_t(a.L) + a.has_bonus, hi = a.win_hi ? a.win_hi : per_t;
+  const int64_t wt = std::min<int64_t>(hi, per_t) - a.win_lo, wd = a.rows_d ? std::min<int64_t>(hi, a.L) - a.win_lo : 0;
+  const int64_t per_seq = wt + std::max<int64_t>(wd, 0);
   if (a.B <= 65535 && per_seq <= 65535) {
     grid = dim3((unsigned)a.c1, (unsigned)per_seq, (unsigned)a.B);
     return true;

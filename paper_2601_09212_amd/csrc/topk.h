@@ -4,8 +4,8 @@
 //
 // Method: value-bucket refinement.  The finite values lie in [lo, hi].  2048 equal-width
 // buckets over that range are counted with LDS atomics; the bucket that holds the k-th largest
-// is found by a prefix sum; if it holds at most kListCap values they are copied to LDS and the
-// answer is found by counting ranks, otherwise the range is narrowed to that bucket's own
+// is found by a prefix sum; if it holds at most kListCap values (the "bracket") they are copied to
+// LDS and the answer is found by counting ranks, otherwise the range is narrowed to that bucket's own
 // minimum and maximum and the step repeats.  The bucket index is a monotone function of the
 // value, so every value of a lower-numbered bucket is >= every value of a higher one.  For
 // Gaussian-like logits one step leaves about ten candidates.
@@ -29,6 +29,7 @@ template <int TPB> struct TopkSmem {
   uint32_t key_min, key_max;
   int bsel;
   uint32_t k_in_bucket, n_in_bucket;
+  uint32_t n_keep;
   float thr;
 };
 
@@ -57,20 +58,35 @@ __device__ __forceinline__ float wave_min(float v) {
   return fminf(fminf(lane_f(v, 0), lane_f(v, 16)), fminf(lane_f(v, 32), lane_f(v, 48)));
 }
 
-// k-th largest of the values of all threads that lie in [lo, hi]; the caller guarantees that lo
-// and hi are the minimum and maximum of the finite values and that the LDS histogram is zero.
-// in_range: every value of every thread lies in [lo, hi] (no -inf entries), so the first pass
-// needs no range test.  Returns -inf when fewer than k values are finite.  All TPB threads must
-// call it; result in every thread.
+// Where the k-th largest value lies once the bucket steps have narrowed it down: either the value
+// itself (exact: every remaining candidate ties, or fewer than k values are finite), or one
+// bucket of at most kListCap values.  bucket_of(v, hi, scale) == bsel names the candidates, which
+// all lie in [g_lo, g_hi]; values above g_hi are larger than every candidate, values below g_lo
+// smaller; kk is the rank of the wanted value among the nb candidates.
+struct TopkBracket {
+  bool exact;
+  float thr;                   // exact only
+  float g_lo, g_hi, hi, scale;
+  int bsel;
+  uint32_t kk, nb;
+};
+
+// Bracket of the kk-th largest of the values of all threads that lie in [lo, hi]; the caller
+// guarantees that lo and hi are the minimum and maximum of the finite values and that the LDS
+// histogram is zero.  in_range: every value of every thread lies in [lo, hi] (no -inf entries), so
+// the first pass needs no range test.  All TPB threads must call it; result in every thread, and
+// the candidate list of the shared state is empty.
 template <int NVAL, int TPB>
-__device__ __forceinline__ float kth_largest(const uint32_t (&xw)[NVAL], uint32_t kk, float lo, float hi,
-                                             bool in_range, TopkSmem<TPB>& ts) {
+__device__ __forceinline__ TopkBracket kth_bracket(const uint32_t (&xw)[NVAL], uint32_t kk, float lo, float hi,
+                                                   bool in_range, TopkSmem<TPB>& ts) {
   constexpr int kW = TPB / 64;            // waves
   constexpr int kPer = kBuckets / TPB;    // buckets owned by one thread in the prefix step
   auto X = [&](int i) { return __uint_as_float(xw[i]); };
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  TopkBracket br{true, hi, 0.f, 0.f, hi, 0.f, 0, kk, 0u};
   for (int iter = 0; iter < 16; ++iter) {
-    if (!(hi > lo)) return hi;                           // every remaining candidate ties
+    br.thr = hi;
+    if (!(hi > lo)) return br;                           // every remaining candidate ties
     const float width = __fsub_rn(hi, lo);
     const float scale = kBucketSpan / width;
     if (iter > 0) {       // the first pass finds the histogram zeroed by topk_prepare
@@ -101,7 +117,7 @@ __device__ __forceinline__ float kth_largest(const uint32_t (&xw)[NVAL], uint32_
       before += (w < wv) ? ts.wave_tot[w] : 0u;
       total += ts.wave_tot[w];
     }
-    if (kk > total) return -INFINITY;
+    if (kk > total) { br.thr = -INFINITY; return br; }
     if (before < kk && kk <= before + local) {
       uint32_t cum = before;
 #pragma unroll
@@ -122,21 +138,9 @@ __device__ __forceinline__ float kth_largest(const uint32_t (&xw)[NVAL], uint32_
     const float g_hi = fminf(hi, hi - (float)bsel * step + margin);
     const float g_lo = fmaxf(lo, hi - (float)(bsel + 1) * step - margin);
     if (nb <= (uint32_t)kListCap) {
-#pragma unroll
-      for (int i = 0; i < NVAL; ++i)
-        if (X(i) >= g_lo && X(i) <= g_hi) {
-          if (bucket_of(X(i), hi, scale) == bsel) ts.list[atomicAdd(&ts.n_list, 1u)] = X(i);
-        }
-      __syncthreads();
-      // the kk-th largest v has fewer than kk values above it and at least kk values >= it
-      for (uint32_t i = tid; i < nb; i += TPB) {
-        const float v = ts.list[i];
-        uint32_t g = 0, ge = 0;
-        for (uint32_t j = 0; j < nb; ++j) { g += ts.list[j] > v; ge += ts.list[j] >= v; }
-        if (g < kk && kk <= ge) ts.thr = v;
-      }
-      __syncthreads();
-      return ts.thr;
+      br.exact = false;
+      br.g_lo = g_lo; br.g_hi = g_hi; br.hi = hi; br.scale = scale; br.bsel = bsel; br.kk = kk; br.nb = nb;
+      return br;
     }
     // too many candidates (heavy ties or a very uneven row): narrow the range to this bucket
 #pragma unroll
@@ -157,14 +161,40 @@ __device__ __forceinline__ float kth_largest(const uint32_t (&xw)[NVAL], uint32_
     hi = key_value(ts.key_max);
     in_range = false;
   }
-  return hi;   // not reached for fp32 inputs: every step splits distinct values
+  br.thr = hi;   // not reached for fp32 inputs: every step splits distinct values
+  return br;
 }
 
-// Returns the k-th largest of all NVAL x TPB values (1 <= k <= their number, -inf entries
-// included); -inf when fewer than k values are finite.  row_max receives the largest value
+// The wanted value from its bracket: the candidates are copied to LDS and ranked.  All TPB threads
+// must call it; result in every thread.
+template <int NVAL, int TPB>
+__device__ __forceinline__ float kth_from_bracket(const uint32_t (&xw)[NVAL], const TopkBracket& br, TopkSmem<TPB>& ts) {
+  if (br.exact) return br.thr;
+  auto X = [&](int i) { return __uint_as_float(xw[i]); };
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < NVAL; ++i)
+    if (X(i) >= br.g_lo && X(i) <= br.g_hi) {
+      if (bucket_of(X(i), br.hi, br.scale) == br.bsel) ts.list[atomicAdd(&ts.n_list, 1u)] = X(i);
+    }
+  __syncthreads();
+  // the kk-th largest v has fewer than kk values above it and at least kk values >= it
+  for (uint32_t i = tid; i < br.nb; i += TPB) {
+    const float v = ts.list[i];
+    uint32_t g = 0, ge = 0;
+    for (uint32_t j = 0; j < br.nb; ++j) { g += ts.list[j] > v; ge += ts.list[j] >= v; }
+    if (g < br.kk && br.kk <= ge) ts.thr = v;
+  }
+  __syncthreads();
+  return ts.thr;
+}
+
+// Bracket of the k-th largest of all NVAL x TPB values (1 <= k <= their number, -inf entries
+// included); exactly -inf when fewer than k values are finite.  row_max receives the largest value
 // (-inf for a row without a finite entry).  All TPB threads must call it.
 template <int NVAL, int TPB>
-__device__ __forceinline__ float topk_threshold(const uint32_t (&xw)[NVAL], int k, TopkSmem<TPB>& ts, float& row_max) {
+__device__ __forceinline__ TopkBracket topk_bracket(const uint32_t (&xw)[NVAL], int k, TopkSmem<TPB>& ts, float& row_max) {
+  const TopkBracket none{true, -INFINITY, 0.f, 0.f, 0.f, 0.f, 0, 0u, 0u};
   auto X = [&](int i) { return __uint_as_float(xw[i]); };
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   float hi = X(0), lo = X(0);
@@ -182,7 +212,7 @@ __device__ __forceinline__ float topk_threshold(const uint32_t (&xw)[NVAL], int 
 #pragma unroll
   for (int w = 1; w < TPB / 64; ++w) { lo = fminf(lo, ts.red_lo[w]); hi = fmaxf(hi, ts.red_hi[w]); }
   row_max = hi;
-  if (!(hi > -INFINITY)) return -INFINITY;           // no finite value at all
+  if (!(hi > -INFINITY)) return none;                // no finite value at all
   bool in_range = true;
   if (!(lo > -INFINITY)) {
     // the row has -inf entries (excluded tokens, or elements beyond V): the minimum of the
@@ -199,7 +229,14 @@ __device__ __forceinline__ float topk_threshold(const uint32_t (&xw)[NVAL], int 
 #pragma unroll
     for (int w = 1; w < TPB / 64; ++w) lo = fminf(lo, ts.red_lo[w]);
   }
-  return kth_largest<NVAL, TPB>(xw, (uint32_t)k, lo, hi, in_range, ts);
+  return kth_bracket<NVAL, TPB>(xw, (uint32_t)k, lo, hi, in_range, ts);
+}
+
+// The k-th largest itself.
+template <int NVAL, int TPB>
+__device__ __forceinline__ float topk_threshold(const uint32_t (&xw)[NVAL], int k, TopkSmem<TPB>& ts, float& row_max) {
+  const TopkBracket br = topk_bracket<NVAL, TPB>(xw, k, ts, row_max);
+  return kth_from_bracket<NVAL, TPB>(xw, br, ts);
 }
 
 // Zero the histogram; call it (all threads) before topk_threshold, e.g. while loads are in flight.

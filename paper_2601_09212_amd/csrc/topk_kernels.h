@@ -33,8 +33,12 @@ __global__ __launch_bounds__(TPB, ROW == kChunk ? 6 : 4) void row_stats_topk_ker
   if (rw.i == 0 && !rw.is_draft && threadIdx.x == 0) a.ticket[rw.b] = 0;   // for the long-row tail launch that follows
   topk_prepare(ts);                                     // the barrier inside topk_threshold orders it
   RowRegs<DT, true, kVW> x;
-  // vector k of thread t is vector k*TPB + t of the row
-  load_chunk<DT, true, AL, kVW, TPB, 1, 4, GD>(x, rw.cond, rw.uncond, 0, a.V, a.cfg_scale, a.inv_T, -INFINITY);
+  // vector k of thread t is vector k*TPB + t of the row; a row that fills the workgroup's span
+  // exactly needs no range test on its vectors
+  if (AL != kUnaligned && a.V == ROW)
+    load_chunk<DT, true, kAlignedFull, kVW, TPB, 1, 4, GD>(x, rw.cond, rw.uncond, 0, a.V, a.cfg_scale, a.inv_T, -INFINITY);
+  else
+    load_chunk<DT, true, AL, kVW, TPB, 1, 4, GD>(x, rw.cond, rw.uncond, 0, a.V, a.cfg_scale, a.inv_T, -INFINITY);
   // the raw logits of x~_i, requested now and used at the very end
   const int tok = load_draft_token(a, rw);
   float tok_c = 0.f, tok_u = 0.f;
@@ -43,27 +47,82 @@ __global__ __launch_bounds__(TPB, ROW == kChunk ? 6 : 4) void row_stats_topk_ker
     if (rw.uncond) tok_u = load_elem<DT>(rw.uncond, tok);
   }
   float row_max;
-  const float thr = topk_threshold<kVW * kE, TPB>(x.w, a.top_k, ts, row_max);
+  const TopkBracket br = topk_bracket<kVW * kE, TPB>(x.w, a.top_k, ts, row_max);
   const float c = fmaxf(ceilf(row_max * kLog2e), kRefFloor);
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-#pragma unroll
-  for (int sub = 0; sub < kSub; ++sub) {
+  float thr;
+  if (kSub == 1 && !br.exact) {
+    // One pass does both jobs: values above the bracket are kept whatever the threshold turns
+    // out to be, so their weights are summed while the few candidates are still being collected;
+    // the candidates at or above the threshold are added once they are ranked.
     float s = 0.f;
 #pragma unroll
-    for (int n = sub * kTS * kE; n < (sub + 1) * kTS * kE; ++n) {
+    for (int n = 0; n < kVW * kE; ++n) {
       const float l = __uint_as_float(x.w[n]);
       const float e = exp2_fast(__fmaf_rn(l, kLog2e, -c));
-      s += (l >= thr) ? e : 0.f;
+      const bool above = l > br.g_hi;
+      s += above ? e : 0.f;
+      if (!above && l >= br.g_lo) {
+        const int bk = bucket_of(l, br.hi, br.scale);
+        if (bk == br.bsel) ts.list[atomicAdd(&ts.n_list, 1u)] = l;
+        else if (bk < br.bsel) s += e;
+      }
     }
     s = wave_sum(s);
-    if (lane == 0) red_s[sub][wv] = s;
-  }
-  __syncthreads();
-  if ((int)threadIdx.x < kSub && (int)threadIdx.x < a.c1) {
-    float S = red_s[threadIdx.x][0];
+    if (lane == 0) red_s[0][wv] = s;
+    __syncthreads();
+    // Rank the candidates.  A candidate with fewer than kk larger ones is kept; kept candidates
+    // leave their weights in rank order (equal values in any order: their weights are equal), so
+    // that the sum below does not depend on the order in which the list was filled.
+    float* kept = reinterpret_cast<float*>(ts.hist);     // the histogram is no longer needed
+    for (uint32_t i = threadIdx.x; i < br.nb; i += TPB) {
+      const float v = ts.list[i];
+      uint32_t g = 0, ge = 0, eq_before = 0;
+      for (uint32_t j = 0; j < br.nb; ++j) {
+        const float w = ts.list[j];
+        g += w > v;
+        ge += w >= v;
+        eq_before += (j < i) && (w == v);
+      }
+      if (g < br.kk) {
+        kept[g + eq_before] = exp2_fast(__fmaf_rn(v, kLog2e, -c));
+        if (br.kk <= ge) { ts.thr = v; ts.n_keep = ge; }
+      }
+    }
+    __syncthreads();
+    thr = ts.thr;
+    if (wv == 0) {
+      float cs = 0.f;
+      for (uint32_t j = lane; j < ts.n_keep; j += 64) cs += kept[j];
+      cs = wave_sum(cs);
+      if (lane == 0 && a.c1 > 0) {
+        float S = red_s[0][0];
 #pragma unroll
-    for (int w = 1; w < kW; ++w) S = __fadd_rn(S, red_s[threadIdx.x][w]);
-    a.part[int64_t(r) * a.c1 + threadIdx.x] = make_float2(c, S);
+        for (int w = 1; w < kW; ++w) S = __fadd_rn(S, red_s[0][w]);
+        a.part[int64_t(r) * a.c1] = make_float2(c, __fadd_rn(S, cs));
+      }
+    }
+  } else {
+    thr = kth_from_bracket<kVW * kE, TPB>(x.w, br, ts);
+#pragma unroll
+    for (int sub = 0; sub < kSub; ++sub) {
+      float s = 0.f;
+#pragma unroll
+      for (int n = sub * kTS * kE; n < (sub + 1) * kTS * kE; ++n) {
+        const float l = __uint_as_float(x.w[n]);
+        const float e = exp2_fast(__fmaf_rn(l, kLog2e, -c));
+        s += (l >= thr) ? e : 0.f;
+      }
+      s = wave_sum(s);
+      if (lane == 0) red_s[sub][wv] = s;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < kSub && (int)threadIdx.x < a.c1) {
+      float S = red_s[threadIdx.x][0];
+#pragma unroll
+      for (int w = 1; w < kW; ++w) S = __fadd_rn(S, red_s[threadIdx.x][w]);
+      a.part[int64_t(r) * a.c1 + threadIdx.x] = make_float2(c, S);
+    }
   }
   if (threadIdx.x == 0) {
     a.thr[r] = thr;

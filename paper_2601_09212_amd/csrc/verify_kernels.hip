@@ -34,6 +34,7 @@
 // No workgroup ever waits for another one inside a launch: there are no fences or spin waits
 // anywhere, the only global atomics are the integer histogram adds of the radix passes (whose
 // sums do not depend on the order), and every output is a pure function of the inputs.
+#include <algorithm>
 #include "kernel_common.h"
 
 namespace csd {
@@ -73,6 +74,21 @@ hipError_t launch_verify(const KArgs& a, int dtype, bool xf, hipStream_t stream)
     // stand-alone resampling on rows that one workgroup holds: one launch
     if (xf && resample_topk_fits(a, dtype)) return launch_resample_topk(a, dtype, stream);
     if (resample_whole_fits(a)) return launch_resample_whole(a, dtype, xf, stream);
+  }
+  if (a.windowed && !a.stats_only) {
+    // rounds of 1, 1, 2, 4, ... positions, at most 63; the bonus row rides with the last round
+    KArgs w = a;
+    for (int lo = 0, n = 1; lo < a.L;) {
+      const int hi = std::min(lo + n, (int)a.L);
+      w.win_lo = lo;
+      w.win_hi = hi == a.L ? a.L + a.has_bonus : hi;
+      hipError_t e = launch_statistics(w, dtype, xf, stream);
+      if (e == hipSuccess) e = launch_accept_window(w, dtype, xf, stream);
+      if (e != hipSuccess) return e;
+      n = hi == 1 ? 1 : std::min(2 * n, 63);
+      lo = hi;
+    }
+    return launch_sequence(a, dtype, xf, stream);
   }
   hipError_t e = launch_statistics(a, dtype, xf, stream);
   if (e != hipSuccess || a.stats_only) return e;

@@ -93,6 +93,15 @@ def _oracle_row_law(O, w, b, j, omega_bj, resample_mode):
     return int(tok[0]), float(mass[0]), g[0]
 
 
+def early_exit_form(P, w, has_bonus=True):
+    """What cool_sd_early_exit_form says for a verify call on workload w with COOL_SD_FLAG_EARLY_EXIT
+    (rows of torch tensors: 16-byte aligned whenever V is a multiple of the vector width)."""
+    params = P.make_params(w.target, w.draft, top_k=w.top_k, cfg_scale=w.cfg_scale, temperature=w.temperature,
+                           flags=P.COOL_SD_FLAG_EARLY_EXIT)
+    vec = 8 if w.dtype == "bf16" else 4
+    return P.cool_sd_early_exit_form(params, w.V % vec == 0)
+
+
 def compare_verify(O, w, omega, gpu, ref=None, resample_mode=0, has_bonus=True, early_exit=False):
     """Assert parity of one verify call.  gpu: dict of numpy arrays.  Returns counters.
     early_exit: the per-position outputs after the rejected position must be NaN (never evaluated)."""

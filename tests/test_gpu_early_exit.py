@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 import torch
 
-from tests.parity_util import compare_verify, to_numpy
+from tests.parity_util import compare_verify, early_exit_form, run_oracle, to_numpy
 from workloads import make_workload
 
 pytestmark = pytest.mark.gpu
@@ -39,6 +39,7 @@ def test_early_exit_shapes(P, oracle, cfg, B, L, V, dtype):
     om = P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, L, w.delta, w.nu)
     early, full = _both(P, w, om)
     honoured = V % (8 if dtype == "bf16" else 4) == 0     # otherwise the rows are not 16-byte aligned
+    assert early_exit_form(P, w) == (P.COOL_SD_EARLY_EXIT_SEQUENCE if honoured else P.COOL_SD_EARLY_EXIT_NONE)
     compare_verify(oracle, w, om, early, early_exit=honoured)
     # the two forms sum the softmax denominators in different orders, so they may differ where a
     # uniform sits on a threshold; everywhere else they agree
@@ -77,13 +78,76 @@ def test_early_exit_per_sequence_omega_guidance_and_temperature(P, oracle):
 
 
 def test_early_exit_falls_back_where_not_supported(P, oracle):
-    """top-k and rows longer than 16384 logits run the all-rows path: every position is filled."""
-    for w in (make_workload(3, device="cuda", B=3, L=4), make_workload(5, device="cuda", B=2, L=3, V=40000)):
+    """Under top-k the call reads every row, the query says so, and every position is filled."""
+    for w in (make_workload(3, device="cuda", B=3, L=4), make_workload(3, device="cuda", B=2, L=3, V=40000, top_k=500)):
+        assert early_exit_form(P, w) == P.COOL_SD_EARLY_EXIT_NONE
         om = P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, w.L, w.delta, w.nu)
         early, full = _both(P, w, om)
         compare_verify(oracle, w, om, early)
         for k in early:
             np.testing.assert_array_equal(early[k], full[k])
+
+
+# ------------------------------------------------------------------ long rows: verification in rounds
+LONG_SHAPES = [
+    (5, 3, 8, 40000, "bf16"),       # rounds 1, 1, 2, 4 + bonus
+    (5, 2, 5, 20001, "bf16"),       # rows not 16-byte aligned
+    (5, 2, 1, 65536, "bf16"),       # L = 1: one round
+    (1, 2, 3, 33000, "f32"),
+    (5, 4, 2, 16392, "bf16"),       # just beyond one chunk
+    (5, 2, 70, 16400, "bf16"),      # rounds up to 32 positions, the last one short
+    (5, 1, 200, 17000, "bf16"),     # rounds capped at 63 positions
+    (5, 2, 4, 262144, "bf16"),      # config 5 rows
+    (5, 1, 2, 524288, "bf16"),      # the longest rows of this form (64 statistics chunks)
+]
+
+
+@pytest.mark.parametrize("cfg,B,L,V,dtype", LONG_SHAPES)
+def test_rounds_shapes(P, oracle, cfg, B, L, V, dtype):
+    print("case", cfg, B, L, V, dtype, flush=True)
+    w = make_workload(cfg, device="cuda", B=B, L=L, V=V, dtype=dtype)
+    assert early_exit_form(P, w) == P.COOL_SD_EARLY_EXIT_ROUNDS
+    for delta in (w.delta, 30.0):           # delta = 30: most positions accepted, later rounds and bonus draws
+        om = P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, L, delta, w.nu)
+        ref = run_oracle(oracle, w, om, 0)
+        early, full = _both(P, w, om)
+        compare_verify(oracle, w, om, early, ref=ref, early_exit=True)
+        compare_verify(oracle, w, om, full, ref=ref)
+        # same statistics kernels, same accept formula, same draw: the two forms agree exactly
+        np.testing.assert_array_equal(early["accept_len"], full["accept_len"])
+        np.testing.assert_array_equal(early["next_token"], full["next_token"])
+
+
+def test_rounds_beyond_the_form_fall_back(P, oracle):
+    w = make_workload(5, device="cuda", B=1, L=1, V=524296)
+    assert early_exit_form(P, w) == P.COOL_SD_EARLY_EXIT_NONE
+    om = P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, 1, w.delta, w.nu)
+    early, full = _both(P, w, om)
+    for k in early:
+        np.testing.assert_array_equal(early[k], full[k])
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_rounds_modes_no_bonus_per_sequence_omega_and_transform(P, oracle, mode):
+    w = make_workload(5, device="cuda", B=6, L=8, V=33000)
+    om = np.tile(P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, 8, 3.0, w.nu), (6, 1)).astype(np.float32)
+    om[0] = 0.0                              # rejected at once
+    om[1] = 1e6                              # everything accepted: the bonus draw
+    om[2, 3:] = 0.0                          # rejected at position 4, the first of a round
+    om[3, 5:] = 0.0                          # rejected inside a round
+    early, _ = _both(P, w, om, resample_mode=mode)
+    compare_verify(oracle, w, om, early, resample_mode=mode, early_exit=True)
+    assert early["accept_len"][0] == 0 and early["accept_len"][1] == 8
+    assert early["accept_len"][2] <= 3 and early["accept_len"][3] <= 5
+    w.target = w.target[:, :8].contiguous()
+    early, _ = _both(P, w, om, resample_mode=mode)
+    compare_verify(oracle, w, om, early, resample_mode=mode, has_bonus=False, early_exit=True)
+    assert early["accept_len"][1] == 8 and early["next_token"][1] == -1
+    g = make_workload(3, device="cuda", B=3, L=5, V=32768, top_k=0)      # guided logits, no top-k
+    g.temperature = 0.7
+    omg = P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, 5, 2.0, g.nu)
+    early, _ = _both(P, g, omg, resample_mode=mode)
+    compare_verify(oracle, g, omg, early, resample_mode=mode, early_exit=True)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])

@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 import torch
 
-from tests.parity_util import compare_verify, compare_verify_lantern, to_numpy
+from tests.parity_util import compare_verify, compare_verify_lantern, early_exit_form, to_numpy
 from workloads import make_neighbor_table, make_workload, uniforms24
 
 pytestmark = pytest.mark.gpu
@@ -44,7 +44,7 @@ def test_every_draw_in_fp64_matches_the_oracle(P, oracle, cfg, B, L, V, dtype, k
         w.temperature = kw["temperature"]
     mode = kw.get("resample_mode", 0)
     flags = P.COOL_SD_FLAG_EXACT_DRAW | (P.COOL_SD_FLAG_EARLY_EXIT if early else 0)
-    honoured = bool(early) and V <= 16384 and w.top_k == 0 and V % (8 if dtype == "bf16" else 4) == 0
+    honoured = bool(early) and early_exit_form(P, w) != 0
     for delta, has_bonus in ((1.1, True), (4.0, True), (1e30, True), (0.0, True), (1.1, False)):
         if delta == 0.0:
             om = np.zeros(L, np.float32)                                  # rejection at the first position

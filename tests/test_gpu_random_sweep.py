@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 import torch
 
-from tests.parity_util import R_FLOOR, REL_TOL, U_TOL, compare_verify, compare_verify_lantern, to_numpy, token_band
+from tests.parity_util import R_FLOOR, REL_TOL, U_TOL, compare_verify, compare_verify_lantern, early_exit_form, to_numpy, token_band
 from tests.parity_util import oracle_diagnostics as _oracle_diag, verify_diagnostics_call as _verify_diag
 from tests.test_gpu_diagnostics import _check as check_diagnostics
 from workloads import make_neighbor_table, make_workload, uniforms24
@@ -104,7 +104,7 @@ def test_random_cases_through_every_entry_point(P, oracle, seed):
         st = compare_verify(oracle, w, om, gpu, resample_mode=mode, has_bonus=bonus)
         exempt += [("verify", case)] * (st["tau_exempt"] + st["token_exempt"])
         early = to_numpy(P.verify_workload(w, omt, resample_mode=mode, flags=P.COOL_SD_FLAG_EARLY_EXIT))
-        honoured = w.top_k == 0 and V <= 16384 and V % (8 if dtype == "bf16" else 4) == 0
+        honoured = early_exit_form(P, w, bonus) != 0
         st = compare_verify(oracle, w, om, early, resample_mode=mode, has_bonus=bonus, early_exit=honoured)
         exempt += [("early", case)] * (st["tau_exempt"] + st["token_exempt"])
         if bonus:

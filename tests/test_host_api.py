@@ -28,7 +28,7 @@ def test_library_exports_exactly_the_declared_symbols(P):
     names = _declared("cool_sd.h")
     assert names == {"cool_sd_schedule", "cool_sd_workspace_bytes", "cool_sd_workspace_init", "cool_sd_verify",
                      "cool_sd_verify_noalloc", "cool_sd_verify_lantern", "cool_sd_verify_diagnostics",
-                     "cool_sd_resample", "cool_sd_diagnostics", "cool_sd_strerror"}
+                     "cool_sd_resample", "cool_sd_diagnostics", "cool_sd_early_exit_form", "cool_sd_strerror"}
     assert _exported(P.binding.LIB_PATH) == names
     assert _exported(P.binding.LIB_CHECKED_PATH) == names
     raw = C.CDLL(P.binding.LIB_PATH)
@@ -197,6 +197,29 @@ def test_verify_validates_before_touching_the_gpu(P):
     assert P.cool_sd_workspace_bytes(_params(P, resample_mode=E.COOL_SD_RESAMPLE_LANTERN)) > 0
     for code in (0, -1, -2, -3, -4, -5, -99):
         assert isinstance(P.cool_sd_strerror(code), str) and P.cool_sd_strerror(code)
+
+
+def test_early_exit_form_query(P):
+    """cool_sd_early_exit_form names the form a verify call takes under COOL_SD_FLAG_EARLY_EXIT, so that
+    the fall-back to reading every row is visible to the caller (host logic only)."""
+    E = P
+    form = lambda aligned=True, **kw: P.cool_sd_early_exit_form(_params(P, **kw), aligned)
+    ee = E.COOL_SD_FLAG_EARLY_EXIT
+    assert form(V=16384) == E.COOL_SD_EARLY_EXIT_NONE                              # flag clear
+    assert form(V=16384, flags=ee) == E.COOL_SD_EARLY_EXIT_SEQUENCE
+    assert form(V=16384, flags=ee | E.COOL_SD_FLAG_EXACT_DRAW) == E.COOL_SD_EARLY_EXIT_SEQUENCE
+    assert form(False, V=16384, flags=ee) == E.COOL_SD_EARLY_EXIT_NONE             # unaligned short rows
+    assert form(V=16383, flags=ee) == E.COOL_SD_EARLY_EXIT_NONE                    # V not a multiple of the vector
+    assert form(V=16384, L=1025, flags=ee) == E.COOL_SD_EARLY_EXIT_NONE
+    assert form(V=16384, top_k=10, flags=ee) == E.COOL_SD_EARLY_EXIT_NONE
+    assert form(V=16385, flags=ee) == E.COOL_SD_EARLY_EXIT_ROUNDS
+    assert form(False, V=262144, flags=ee) == E.COOL_SD_EARLY_EXIT_ROUNDS          # any alignment
+    assert form(V=262144, dtype=E.COOL_SD_F32, flags=ee) == E.COOL_SD_EARLY_EXIT_ROUNDS
+    assert form(V=524288, flags=ee) == E.COOL_SD_EARLY_EXIT_ROUNDS
+    assert form(V=524289, flags=ee) == E.COOL_SD_EARLY_EXIT_NONE                   # more than 64 statistics chunks
+    assert form(V=262144, top_k=5, flags=ee) == E.COOL_SD_EARLY_EXIT_NONE
+    with pytest.raises(P.CoolSDError):
+        P.cool_sd_early_exit_form(_params(P, V=0, flags=ee), True)
 
 
 def test_binding_fails_loudly_without_library(P, monkeypatch):

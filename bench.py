@@ -29,6 +29,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+_HOST_THREADS = None
 
 
 def measured_traffic(workload, early_exit=False):
@@ -59,6 +60,8 @@ def parse():
                     help="distinct input batches cycled, total size (default: 3400 for configurations 4-5, else 600)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="time budget of the CPU oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-others", action="store_true",
+                    help="also time the CPU oracle on the other workloads (a few seconds each; for the results table)")
     ap.add_argument("--others", action="store_true", default=True,
                     help="also time the other four configurations (extra key `other_workloads`; on by default, a "
                          "few seconds)")
@@ -497,7 +500,10 @@ def cpu_baseline(runner, budget_s):
     (OpenMP over sequences, all host cores), then on one core on the first sequences of a batch."""
     from oracle import oracle as O
     from tests.parity_util import run_oracle, subset
-    threads = O.max_threads()
+    global _HOST_THREADS
+    if _HOST_THREADS is None:           # asked once: the single-core sample below leaves the OpenMP default at 1
+        _HOST_THREADS = O.max_threads()
+    threads = _HOST_THREADS
     first = subset(runner.pool[0], list(range(min(runner.B, threads))))
     run_oracle(O, first, runner.omega_np, num_threads=threads)               # page in / build
     host = [None] * len(runner.pool)        # float32 host copies are made outside the timed region
@@ -577,19 +583,31 @@ def main():
     probe_s, probe_launches = r.read_probe_time(a.kernel_samples)
     kernel_name = "row_stats_topk_kernel" if r.pool[0].top_k > 0 else "row_stats_kernel"
     kernel_bytes = r.bytes_per_step
-    if a.early_exit and r.V <= 16384:
-        # one kernel per call; its algorithmic bytes are the rows Algorithm 1 needs: both rows of every
+    needed_bytes = None
+    if a.early_exit:
+        # Algorithmic bytes of the early-exit forms: the rows Algorithm 1 needs, i.e. both rows of every
         # position up to and including the rejected one, or all L pairs plus the bonus row
-        need = 0
+        need, taus = 0, []
         for i in range(len(r.pool)):
             r.step(i)
             tau = r.accept_len.cpu().numpy().astype("int64")
+            taus.append(float(tau.mean()))
             need += int(((tau + 1).clip(max=r.L) * 2 + (tau == r.L)).sum()) * r.V * r.pool[0].target.element_size()
-        # bf16 rows without a logit transform take the 256-thread form of the kernel
-        plain_bf16 = r.pool[0].dtype == "bf16" and r.pool[0].target_uncond is None and r.pool[0].temperature == 1.0
-        kernel_name = "sequence_early_exit_tile_kernel" if plain_bf16 else "sequence_early_exit_kernel"
-        kernel_bytes = need / len(r.pool)
-        kern_s = dev_s / done
+        needed_bytes = need / len(r.pool)
+        form = pkg.cool_sd_early_exit_form(r.params, True)
+        if form == pkg.COOL_SD_EARLY_EXIT_SEQUENCE:
+            # one kernel per call; bf16 rows without a logit transform take the 256-thread form of it
+            plain_bf16 = r.pool[0].dtype == "bf16" and r.pool[0].target_uncond is None and r.pool[0].temperature == 1.0
+            kernel_name = "sequence_early_exit_tile_kernel" if plain_bf16 else "sequence_early_exit_kernel"
+            kernel_bytes = needed_bytes
+            kern_s = dev_s / done
+        elif form == pkg.COOL_SD_EARLY_EXIT_ROUNDS:
+            # several statistics launches per call, each over the rows of one round of positions: the
+            # roofline figure is the whole call against the needed rows
+            kernel_name = "row_stats_kernel (one launch per round of positions) + accept_window_kernel + sequence_masses_kernel + sequence_select_kernel"
+            kernel_bytes = needed_bytes
+            kern_s = dev_s / done
+    call_bytes = needed_bytes if needed_bytes is not None else r.bytes_per_step
     achieved = kernel_bytes / kern_s / 1e9
     dtype = r.pool[0].dtype
     step_s = wall / done
@@ -607,11 +625,15 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": None if variant else measured_traffic(a.workload, a.early_exit),
+                     "early_exit_form": None if not a.early_exit else pkg.cool_sd_early_exit_form(r.params, True),
+                     "early_exit_needed_bytes": needed_bytes,
+                     "early_exit_mean_tau": None if not a.early_exit else sum(taus) / len(taus),
                      "kernel": kernel_name, "algorithmic_bytes_per_launch": kernel_bytes,
                      "us_per_launch": kern_s * 1e6,
                      # the whole step (every launch of the call) against the same algorithmic bytes
-                     "whole_call_us": step_s * 1e6, "whole_call_GBps": r.bytes_per_step / step_s / 1e9,
-                     "whole_call_frac": r.bytes_per_step / step_s / 1e9 / HBM_PEAK_GBS,
+                     # (with --early-exit: against the rows Algorithm 1 needs)
+                     "whole_call_us": step_s * 1e6, "whole_call_GBps": call_bytes / step_s / 1e9,
+                     "whole_call_frac": call_bytes / step_s / 1e9 / HBM_PEAK_GBS,
                      "graph_step_us": dev_s / done * 1e6,
                      "direct_call_us": call_s * 1e6, "direct_call_median_us": call_median_s * 1e6,
                      # a plain read of the same tensors in one launch of the same shape: what the chip
@@ -647,6 +669,8 @@ def main():
                                   "read_probe_us": p2 * 1e6, "read_probe_GBps": rr.bytes_per_step / p2 / 1e9,
                                   "read_probe_launches": pl2,
                                   "bytes_per_step": rr.bytes_per_step, "pool_batches": len(rr.pool)}
+            if a.cpu_others and not a.no_cpu_baseline:
+                extra[name]["cpu_baseline"] = cpu_baseline(rr, a.cpu_seconds / 3)
             if a.diagnostics:
                 extra[name]["diagnostics"] = time_diagnostics(rr)
             if a.lantern:

@@ -345,21 +345,22 @@ __device__ __forceinline__ void finish_chunk(RowRegs<DT, XF, NT>& r, const uint4
   }
 }
 
-// Per-thread streaming softmax statistics in base-2 units with an INTEGER reference exponent:
-// c = ceil(max*log2e) over the logits seen so far and s = sum 2^(l*log2e - c).  Because c is an
-// integer, every later change of reference is an exact power-of-two scaling.
+// Per-thread softmax statistics in base-2 units with an INTEGER reference exponent:
+// c = ceil(max*log2e) over the thread's logits (at least kRefFloor) and s = sum 2^(l*log2e - c).
+// Because c is an integer, every later change of reference is an exact power-of-two scaling.
 template <int DT, bool XF, int NT>
 __device__ __forceinline__ void thread_stats(const RowRegs<DT, XF, NT>& r, float& c, float& s) {
   constexpr int kE = Vec<DT>::kE;
-  c = kRefFloor;
+  float tm = r.get(0, 0);
+#pragma unroll
+  for (int k = 0; k < NT; ++k) {
+#pragma unroll
+    for (int j = 0; j < kE; ++j) tm = fmaxf(tm, r.get(k, j));
+  }
+  c = fmaxf(ceilf(tm * kLog2e), kRefFloor);
   s = 0.f;
 #pragma unroll
   for (int k = 0; k < NT; ++k) {
-    float tm = r.get(k, 0);
-#pragma unroll
-    for (int j = 1; j < kE; ++j) tm = fmaxf(tm, r.get(k, j));
-    const float cn = ceilf(tm * kLog2e);
-    if (cn > c) { s *= exp2_fast(c - cn); c = cn; }
 #pragma unroll
     for (int j = 0; j < kE; ++j) s += exp2_fast(__fmaf_rn(r.get(k, j), kLog2e, -c));
   }

@@ -142,11 +142,11 @@ __global__ __launch_bounds__(kThreads, 3) void row_stats_kernel(const KArgs a) {
     }
   }
   const int lin = G3 ? 0 : blockIdx.x / C1, c = G3 ? blockIdx.x : blockIdx.x - lin * C1;
+  const RowRef rw = row_ref<DT, G3>(a, lin);
   if constexpr (G3) {
     // verification in rounds: a sequence that has its rejection needs no further row
-    if (a.win_lo > 0 && a.tau_ws[blockIdx.z] >= 0) return;
+    if (a.win_lo > 0 && a.tau_ws[rw.b] >= 0) return;
   }
-  const RowRef rw = row_ref<DT, G3>(a, lin);
   const int r = rw.r;
   const int64_t base = int64_t(c) * (NT * kThreads * kE);
   // the first workgroup of every sequence clears the sequence's ticket for the long-row tail launch

@@ -37,12 +37,14 @@ SQ_COUNTERS = ["SQ_WAVES", "SQ_BUSY_CU_CYCLES", "SQ_WAVE_CYCLES", "SQ_INSTS_VALU
 COPY_BYTES = 1 << 30
 
 
-def commands(workload, raw, flags, sq):
+def commands(workload, raw, flags, sq, trace_only=False):
     bench = ["python3", os.path.join(ROOT, "bench.py"), "--no-others", "--workload", workload]
     prof = ["rocprofv3", "--output-format", "csv"]
     trace = prof + ["--kernel-trace", "--stats", "-d", os.path.join(raw, "trace"), "-o", "t", "--"] + bench + \
         ["--launch", "direct", "--steps", "300", "--warmup", "30", "--no-cpu-baseline"] + flags
     out = [("trace", trace, 240)]
+    if trace_only:
+        return out
     passes = [("fetch", ["FETCH_SIZE"]), ("write", ["WRITE_SIZE"])] + ([("sq", SQ_COUNTERS)] if sq else [])
     for name, counters in passes:
         out.append((name, prof + ["--pmc"] + counters + ["-d", os.path.join(raw, name), "-o", name[0], "--"] + bench +
@@ -50,9 +52,9 @@ def commands(workload, raw, flags, sq):
     return out
 
 
-def collect(workload, raw, flags, sq):
+def collect(workload, raw, flags, sq, trace_only=False):
     env = dict(os.environ, TMPDIR="/tmp")
-    for name, cmd, limit in commands(workload, raw, flags, sq):
+    for name, cmd, limit in commands(workload, raw, flags, sq, trace_only):
         print("[profile_summary]", name, flush=True)
         with open(os.path.join(raw, name + ".log"), "w") as log:
             try:
@@ -127,7 +129,7 @@ def bench_line(raw):
     return None
 
 
-def summary(workload, raw, flags, sq):
+def summary(workload, raw, flags, sq, trace_only=False):
     lines = []
     stats = kernel_stats(raw)
     lines.append("== kernel trace (rocprofv3 --kernel-trace --stats), library kernels, times in us")
@@ -136,7 +138,7 @@ def summary(workload, raw, flags, sq):
     timed = [s for s in stats if "read_probe" not in s[0]]
     dominant = max(timed, key=lambda s: s[5])[0]
     total = {}
-    for counter, sub in (("FETCH_SIZE", "fetch"), ("WRITE_SIZE", "write")):
+    for counter, sub in (() if trace_only else (("FETCH_SIZE", "fetch"), ("WRITE_SIZE", "write"))):
         per_kernel, refv, per_unit = byte_counter(raw, sub, counter)
         lines.append("== %s: mean reading per launch -> bytes (bytes per unit from the reference copy: %.1f)" % (counter, per_unit))
         for k, (n, m) in per_kernel.items():
@@ -154,10 +156,13 @@ def summary(workload, raw, flags, sq):
                              (d["SQ_INSTS_VALU"] / d["SQ_WAVES"], d["SQ_INSTS_LDS"] / d["SQ_WAVES"],
                               d["SQ_ACTIVE_INST_VALU"] / d["SQ_BUSY_CU_CYCLES"], d["SQ_ACTIVE_INST_LDS"] / d["SQ_BUSY_CU_CYCLES"],
                               d["SQ_LDS_BANK_CONFLICT"] / max(d["SQ_ACTIVE_INST_LDS"], 1.0)))
-    if dominant not in total:
+    if not trace_only and dominant not in total:
         sys.exit("profile_summary: no counter reading for " + dominant)
+    traffic = "(trace only: no counter passes)" if trace_only else (
+        "HBM bytes (FETCH_SIZE + WRITE_SIZE) per launch of the kernel with the largest share of the time:\n\n"
+        "traffic_bytes_per_launch: %s %.0f" % (dominant.split("<")[0], total[dominant]))
     cmds = "\n".join("    (cd /tmp; TMPDIR=/tmp " + " ".join(
-        c.replace(ROOT + "/", "").replace(raw, "RAW") for c in cmd) + ")" for _, cmd, _ in commands(workload, raw, flags, sq))
+        c.replace(raw, "RAW").replace(ROOT + "/", "") for c in cmd) + ")" for _, cmd, _ in commands(workload, raw, flags, sq, trace_only))
     bl = bench_line(raw)
     text = """# rocprofv3 summary: bench.py --workload %s%s
 
@@ -180,9 +185,7 @@ per row, guidance, 3-D grid>; sequence_*_kernel<dtype, logit transform, aligned 
 %s
 ```
 
-HBM bytes (FETCH_SIZE + WRITE_SIZE) per launch of the kernel with the largest share of the time:
-
-traffic_bytes_per_launch: %s %.0f
+%s
 
 bench.py's JSON line in the traced run (slower than an untraced run; compare the trace's average
 for the dominant kernel with `roofline.us_per_launch` of an untraced run):
@@ -190,9 +193,8 @@ for the dominant kernel with `roofline.us_per_launch` of an untraced run):
 ```
 %s
 ```
-""" % (workload, (" " + " ".join(flags)) if flags else "", workload, " --sq" if sq else "",
-       (" -- " + " ".join(flags)) if flags else "", cmds, "\n".join(lines), dominant.split("<")[0], total[dominant],
-       json.dumps(bl, indent=1))
+""" % (workload, (" " + " ".join(flags)) if flags else "", workload, (" --sq" if sq else "") + (" --trace-only" if trace_only else ""),
+       (" -- " + " ".join(flags)) if flags else "", cmds, "\n".join(lines), traffic, json.dumps(bl, indent=1))
     return text
 
 
@@ -202,14 +204,15 @@ def main():
     ap.add_argument("--raw", required=True, help="folder for rocprofv3's output (created)")
     ap.add_argument("--out", required=True, help="the summary to write")
     ap.add_argument("--sq", action="store_true", help="also collect the SQ instruction / LDS counters")
+    ap.add_argument("--trace-only", action="store_true", help="kernel trace only, no counter passes (no traffic line)")
     ap.add_argument("--no-collect", action="store_true", help="raw files are already there: only write the summary")
     ap.add_argument("flags", nargs="*", help="after --: further flags for bench.py (--early-exit, --lantern, ...)")
     a = ap.parse_args()
     raw = os.path.abspath(a.raw)
     os.makedirs(raw, exist_ok=True)
     if not a.no_collect:
-        collect(a.workload, raw, a.flags, a.sq)
-    text = summary(a.workload, raw, a.flags, a.sq)
+        collect(a.workload, raw, a.flags, a.sq, a.trace_only)
+    text = summary(a.workload, raw, a.flags, a.sq, a.trace_only)
     with open(a.out, "w") as f:
         f.write(text)
     print("[profile_summary] wrote", a.out, flush=True)

@@ -32,16 +32,20 @@ HBM_PEAK_GBS = 8000.0
 _HOST_THREADS = None
 
 
-def measured_traffic(workload, early_exit=False):
+def measured_traffic(workload, early_exit=False, per_call=False):
     """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summary of
     this workload (profiles/verify_<workload>_rocprofv3.md, written by
     paper_2601_09212_amd/profile_summary.py from FETCH_SIZE / WRITE_SIZE runs): the line
-    `traffic_bytes_per_launch: <kernel> <bytes>`.  None when no summary holds one."""
+    `traffic_bytes_per_launch: <kernel> <bytes>` (per_call: `traffic_bytes_per_call: <bytes>`, all
+    launches of one library call).  None when no summary holds one."""
     name = "verify_early_exit_%s_rocprofv3.md" % workload if early_exit else "verify_%s_rocprofv3.md" % workload
     try:
         text = open(os.path.join(ROOT, "profiles", name)).read()
     except OSError:
         return None
+    if per_call:
+        m = re.search(r"^traffic_bytes_per_call:\s*([0-9.eE+]+)\s*$", text, flags=re.M)
+        return float(m.group(1)) if m else None
     m = re.search(r"^traffic_bytes_per_launch:\s*(\S+)\s+([0-9.eE+]+)\s*$", text, flags=re.M)
     return float(m.group(2)) if m else None
 
@@ -625,6 +629,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": None if variant else measured_traffic(a.workload, a.early_exit),
+                     "traffic_per_call": None if variant else measured_traffic(a.workload, a.early_exit, per_call=True),
                      "early_exit_form": None if not a.early_exit else pkg.cool_sd_early_exit_form(r.params, True),
                      "early_exit_needed_bytes": needed_bytes,
                      "early_exit_mean_tau": None if not a.early_exit else sum(taus) / len(taus),

@@ -1,4 +1,5 @@
-// HIP kernels of the Cool-SD verification stage for gfx950 (MI355X).
+// Cool-SD verification stage for gfx950 (MI355X): which kernels a call enqueues, and the few
+// kernels that belong to no other translation unit.
 //
 // What is computed (paper notation): for every draft position i of every sequence the
 // softmax statistics of the target row p_i and the draft row q_i, the relaxed acceptance
@@ -7,33 +8,34 @@
 // G* = Norm([p - min(q, omega p)]_+) (Eq. opt_G) at the first rejected position, or from
 // p_{L+1} when nothing was rejected (Algorithm 1, bonus token).
 //
-// Two launches per verify call.
-//   row_stats_kernel   grid = (chunks, rows of a sequence, sequences).  The HBM-bound pass: every
-//                      logit is read once.  A workgroup streams one small chunk (4K-16K logits)
-//                      of one row through registers and writes the chunk's softmax statistics
-//                      (integer base-2 reference exponent, sum).  No workgroup talks to another;
-//                      few registers, so many workgroups per CU keep loads in flight.
-//                      Under top-k truncation row_stats_topk_kernel takes its place: one workgroup
-//                      holds a whole row (up to 65536 logits) and selects the threshold first.
-//   sequence_whole_kernel  grid = B.  Per sequence: combine the chunk statistics of its rows,
-//                      accept test at each position, tau = first rejection; then re-read ONLY row
-//                      tau+1 (one row pair of 2L+1, usually still in L2 / Infinity Cache), keep it
-//                      in registers, form the residual masses and draw x_{tau+1} by a
-//                      hierarchical inverse CDF.
-// Rows longer than 16384 logits do not fit one workgroup's registers; the second step is then
-// split at kernel boundaries: accept_kernel (chunk statistics combined, tau; one workgroup per
-// sequence), sequence_masses_kernel (mass of every 8192-logit chunk of the sampled rows,
-// streaming) and sequence_select_kernel (pick the chunk that holds u*R, re-read it, inverse
-// CDF).  cool_sd_resample on short rows is one launch (resample_whole_kernel, resample_topk_kernel).
-// Other entry points add: lantern_agg_position (neighbour aggregation of the LANTERN-style
-// acceptance: part of the statistics launch, or lantern_agg_kernel after the radix passes),
-// sequence_early_exit_tile_kernel / sequence_early_exit_kernel (the whole call per sequence,
-// stopping at the first rejection), diag_kernel (per-position terms of Theorem 2; in
-// cool_sd_verify_diagnostics it also plays the statistics pass), and for top-k
-// on rows beyond 65536 logits three radix passes (topk_radix_*).
-// No workgroup ever waits for another one inside a launch: there are no fences or spin waits
-// anywhere, the only global atomics are the integer histogram adds of the radix passes (whose
-// sums do not depend on the order), and every output is a pure function of the inputs.
+// A verify call is a statistics pass followed by a per-sequence step.
+//   statistics pass (stats_launch.hip, stats_kernels.h, topk_kernels.h)
+//       row_stats_kernel: grid = (chunks, rows of a sequence, sequences).  The HBM-bound pass: every
+//       logit is read once.  A workgroup streams one small chunk (4K-16K logits) of one row through
+//       registers and writes the chunk's softmax statistics (integer base-2 reference exponent,
+//       sum).  No workgroup talks to another; few registers, so many workgroups per compute unit
+//       keep loads in flight.  Under top-k truncation row_stats_topk_kernel takes its place: one
+//       workgroup holds a whole row (up to 65536 logits) and selects the threshold first; longer
+//       rows take three radix passes (topk_radix_*) before the ordinary kernel.
+//   per-sequence step (sequence_launch.hip, sequence_whole.h, sequence_long.h)
+//       rows of one chunk: sequence_whole_kernel, grid = B.  Combine the chunk statistics of the
+//       sequence's rows, accept test at each position, tau = first rejection; then re-read ONLY
+//       row tau+1 (one row pair of 2L+1, usually still in L2 / Infinity Cache), keep it in
+//       registers, form the residual masses and draw x_{tau+1} by a hierarchical inverse CDF.
+//       longer rows: accept_kernel (tau; one workgroup per sequence), sequence_masses_kernel (mass
+//       of every 8192-logit chunk of the sampled rows, streaming) and sequence_select_kernel (the
+//       chunk that holds u*R, re-read, inverse CDF); on small batches the three are one launch,
+//       sequence_tail_kernel, whose last workgroup per sequence (a ticket) does the selection.
+//   A draw that fp32 cannot resolve is re-done in fp64 inside the same kernel (exact_draw.h).
+// Other forms: COOL_SD_FLAG_EARLY_EXIT (sequence_early_exit_*_kernel: the whole call per
+// sequence on rows of one chunk; longer rows: rounds of positions, launch_verify below);
+// cool_sd_resample on short rows is one launch (resample_whole_kernel, resample_topk_kernel);
+// lantern_agg_position (neighbour aggregation of the LANTERN-style acceptance: part of the
+// statistics launch, or lantern_agg_kernel after the radix passes); diag_kernel (per-position
+// terms of Theorem 2; in cool_sd_verify_diagnostics it also plays the statistics pass).
+// No workgroup ever spins or waits for another one.  Global atomics: the integer histogram adds
+// of the radix passes (order-independent sums) and the relaxed ticket of sequence_tail_kernel;
+// there are no fences.  Every output is a pure function of the inputs.
 #include <algorithm>
 #include "kernel_common.h"
 

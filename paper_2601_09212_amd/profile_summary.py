@@ -35,6 +35,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SQ_COUNTERS = ["SQ_WAVES", "SQ_BUSY_CU_CYCLES", "SQ_WAVE_CYCLES", "SQ_INSTS_VALU", "SQ_ACTIVE_INST_VALU", "SQ_INSTS_LDS",
                "SQ_ACTIVE_INST_LDS", "SQ_LDS_BANK_CONFLICT"]
 COPY_BYTES = 1 << 30
+COUNTER_STEPS = 20          # library calls in a counter run
 
 
 def commands(workload, raw, flags, sq, trace_only=False):
@@ -48,7 +49,7 @@ def commands(workload, raw, flags, sq, trace_only=False):
     passes = [("fetch", ["FETCH_SIZE"]), ("write", ["WRITE_SIZE"])] + ([("sq", SQ_COUNTERS)] if sq else [])
     for name, counters in passes:
         out.append((name, prof + ["--pmc"] + counters + ["-d", os.path.join(raw, name), "-o", name[0], "--"] + bench +
-                    ["--counter-run", "--steps", "20"] + flags, 150))
+                    ["--counter-run", "--steps", str(COUNTER_STEPS)] + flags, 150))
     return out
 
 
@@ -137,13 +138,15 @@ def summary(workload, raw, flags, sq, trace_only=False):
         lines.append("%-92s calls=%5d avg=%9.2f min=%9.2f max=%9.2f" % (n, calls, avg, lo, hi))
     timed = [s for s in stats if "read_probe" not in s[0]]
     dominant = max(timed, key=lambda s: s[5])[0]
-    total = {}
+    total, per_call = {}, 0.0
     for counter, sub in (() if trace_only else (("FETCH_SIZE", "fetch"), ("WRITE_SIZE", "write"))):
         per_kernel, refv, per_unit = byte_counter(raw, sub, counter)
         lines.append("== %s: mean reading per launch -> bytes (bytes per unit from the reference copy: %.1f)" % (counter, per_unit))
         for k, (n, m) in per_kernel.items():
             lines.append("%-92s n=%3d reading=%12.1f -> %14.0f B" % (k, n, m, m * per_unit))
             total[k] = total.get(k, 0.0) + m * per_unit
+            if "zero_words" not in k and "read_probe" not in k:
+                per_call += n * m * per_unit / COUNTER_STEPS
         lines.append("%-92s n=%3d reading=%12.1f -> %14.0f B" % ("reference copy (2^30 B each way)", 5, refv, refv * per_unit))
     if sq:
         lines.append("== SQ counters: mean per launch, summed over the chip (cycles are per-SIMD / per-CU cycle counts as the counter defines them)")
@@ -161,6 +164,10 @@ def summary(workload, raw, flags, sq, trace_only=False):
     traffic = "(trace only: no counter passes)" if trace_only else (
         "HBM bytes (FETCH_SIZE + WRITE_SIZE) per launch of the kernel with the largest share of the time:\n\n"
         "traffic_bytes_per_launch: %s %.0f" % (dominant.split("<")[0], total[dominant]))
+    if not trace_only and not any(f in flags for f in ("--lantern", "--diagnostics")):
+        # (runs with those flags also make calls of other entry points: no per-call figure)
+        traffic += ("\n\nand of all launches of one cool_sd_verify call (the counter runs make %d calls):\n\n"
+                    "traffic_bytes_per_call: %.0f" % (COUNTER_STEPS, per_call))
     cmds = "\n".join("    (cd /tmp; TMPDIR=/tmp " + " ".join(
         c.replace(raw, "RAW").replace(ROOT + "/", "") for c in cmd) + ")" for _, cmd, _ in commands(workload, raw, flags, sq, trace_only))
     bl = bench_line(raw)

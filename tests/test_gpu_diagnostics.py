@@ -53,6 +53,22 @@ def test_diagnostics_shapes(P, oracle, cfg, B, L, V, dtype):
     _check(P, oracle, w, om)
 
 
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_diagnostics_at_full_size(P, oracle, cfg):
+    """cool_sd_diagnostics and cool_sd_verify_diagnostics on the benchmark configurations at their full
+    sizes (the shapes bench.py --diagnostics times): every position's alpha and beta against the oracle."""
+    from tests.parity_util import compare_verify, verify_diagnostics_call
+    print("full cfg", cfg, flush=True)
+    w = make_workload(cfg, device="cuda")
+    om = P.cool_sd_schedule(P.COOL_SD_SCHED_EXP, w.L, 2.0, w.nu)
+    alpha, beta = _check(P, oracle, w, om)
+    both, alpha2, beta2 = verify_diagnostics_call(P, w, om)
+    compare_verify(oracle, w, om, both)
+    a_ref, b_ref = _oracle_diag(oracle, w, om)
+    np.testing.assert_allclose(alpha2, a_ref, rtol=1e-5, atol=1e-9)
+    np.testing.assert_allclose(beta2, b_ref, rtol=1e-5, atol=2e-6)
+
+
 def test_diagnostics_budgets_and_per_sequence_omega(P, oracle):
     w = make_workload(2, device="cuda", B=6, L=8, V=16384)
     for delta in (0.5, 1.0, 4.0):

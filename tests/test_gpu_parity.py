@@ -408,8 +408,8 @@ def test_topk_on_long_rows(P, oracle, cfg, B, L, V, dtype, top_k):
 @pytest.mark.parametrize("cfg,n_check", [(1, None), (2, None), (3, None), (4, None), (5, None)])
 def test_full_size_configurations(P, oracle, cfg, n_check):
     """The five configurations at their full sizes, launched exactly as bench.py launches them (same
-    params, workspace and chunking).  Every sequence of every configuration is checked against the
-    oracle."""
+    params, workspace and chunking), without and with the early-exit flag.  Every sequence of every
+    configuration is checked against the oracle."""
     from tests.parity_util import subset
     print("full cfg", cfg, flush=True)
     w = make_workload(cfg, device="cuda")
@@ -418,7 +418,17 @@ def test_full_size_configurations(P, oracle, cfg, n_check):
     assert gpu["accept_len"].min() >= 0 and gpu["accept_len"].max() <= w.L
     assert gpu["next_token"].min() >= 0 and gpu["next_token"].max() < w.V
     if n_check is None:
-        st = compare_verify(oracle, w, om, gpu)
+        from tests.parity_util import early_exit_form, run_oracle
+        ref = run_oracle(oracle, w, om, 0)
+        st = compare_verify(oracle, w, om, gpu, ref=ref)
+        # the same call with COOL_SD_FLAG_EARLY_EXIT (one workgroup per sequence on configurations 1, 2
+        # and 4, rounds of positions on configuration 5, not honoured under top-k) against the same reference
+        early = _run(P, oracle, w, om, flags=P.COOL_SD_FLAG_EARLY_EXIT)
+        form = early_exit_form(P, w)
+        assert form == {1: 1, 2: 1, 3: 0, 4: 1, 5: 2}[cfg]
+        st2 = compare_verify(oracle, w, om, early, ref=ref, early_exit=form != 0)
+        print("early-exit form", form, "exemptions", st2, flush=True)
+        assert st2["tau_exempt"] + st2["token_exempt"] <= 2
     else:
         idx = np.sort(np.random.default_rng(cfg).choice(w.B, n_check, replace=False))
         st = compare_verify(oracle, subset(w, idx), om, {k: v[idx] for k, v in gpu.items()})

@@ -7,13 +7,15 @@ namespace csd {
 // ============================================================================ kernel 2, long rows
 // Rows too long for one workgroup's registers: tau, then the draw x_{tau+1} from the resampling law
 // of the sampled row (Eq. opt_G / Eq. g_tsd / p_{L+1}), cut at kernel boundaries.
-//   accept_kernel           grid = B, 1024 threads.  tau of every sequence; only launched when the
-//                           next kernel's grid is too large to find tau itself.
+//   accept_kernel           grid = B, 1024 threads.  tau of every sequence.
 //   sequence_masses_kernel  grid = B x C, 256 threads.  Rows of C chunks of 8192 logits:
 //                           workgroup (b, c) writes the mass of chunk c (the bandwidth part: the
 //                           row pair is streamed once).
 //   sequence_select_kernel  grid = B, 1024 threads.  Walks the C chunk masses, loads the chunk that
 //                           holds u*R and finds the token in it.
+//   sequence_tail_kernel    grid = B x G, 256 threads.  The three above in one launch, for calls
+//                           whose sampled rows hold few chunks in all (small batches).
+//   accept_window_kernel    grid = B, 256 threads.  COOL_SD_FLAG_EARLY_EXIT: tau by rounds of positions.
 
 // What both kernels need to know about the row that sequence b samples from.
 struct SampledRow {
@@ -132,7 +134,7 @@ __device__ __forceinline__ LanPatch lan_patch_tile(const KArgs& a, int b, int j,
 
 // tau of sequence b found by a 256-thread workgroup from the chunk statistics of the sequence's
 // rows (at most 64 chunks per row, at most kTauRows positions, the bonus row included), so that
-// the chunk-mass launch needs no accept_kernel before it: every workgroup of a sequence finds the
+// sequence_tail_kernel needs no accept_kernel before it: every workgroup of a sequence finds the
 // same tau for itself (same code, same inputs), the one with emit = true writes accept_len and
 // the per-position outputs.
 //   wave w combines rows w, w+4, ... -- lane c takes chunk c, eight rows' loads in flight, then a

@@ -653,9 +653,9 @@ def main():
         todo = [(c, None, None, None) for c in (1, 2, 3, 4, 5)]
         if a.variants:
             # configuration 4 with eight times the sequences: the regime (B well above the number of
-            # compute units) the early-exit form is meant for; configurations 2 and 3 at the
-            # 65536-token vocabulary of the paper's larger target model (guided sampling there uses
-            # top-k 2000): rows of several chunks
+            # compute units) the one-workgroup early-exit form is meant for; the recipes of
+            # configurations 2 and 3 at a 65536-token vocabulary (the guided one with top-k 2000):
+            # rows of several chunks
             todo += [(4, 2048, None, None), (2, None, 65536, None), (3, 32, 65536, 2000)]
         for c, big, vocab, topk in todo:
             if c == cfg and not big and not vocab and not variant:

@@ -208,9 +208,30 @@ __device__ __forceinline__ int find_tau_from_parts(const KArgs& a, int b, bool e
 // workspace: combine the chunks of sequence b's rows, one wave per row (what combine_rows_kernel
 // does for all rows).  All 1024 threads of the workgroup must call it.
 __device__ __forceinline__ void combine_sequence_rows(const KArgs& a, int b) {
-  const int rps = a.L + a.has_bonus;
-  for (int q = threadIdx.x >> 6; q < rps + a.L; q += kWavesW)
-    combine_row_wave(a, q < rps ? b * rps + q : a.rows_t + b * a.L + (q - rps));
+  const int rps = a.L + a.has_bonus, nrows = rps + a.L;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  auto row_of = [&](int q) { return q < rps ? b * rps + q : a.rows_t + b * a.L + (q - rps); };
+  if (a.c1 <= 64) {
+    // lane c takes chunk c; the loads of up to four of this wave's rows are in flight together,
+    // so a wave with several rows pays one memory round trip, not one per row
+    constexpr int kBatch = 4;
+    const int cl = lane < a.c1 ? lane : 0;
+    for (int q0 = wv; q0 < nrows; q0 += kWavesW * kBatch) {
+      float2 v[kBatch];
+#pragma unroll
+      for (int k = 0; k < kBatch; ++k) v[k] = a.part[int64_t(row_of(min(q0 + k * kWavesW, nrows - 1))) * a.c1 + cl];
+#pragma unroll
+      for (int k = 0; k < kBatch; ++k) {
+        const int q = q0 + k * kWavesW;
+        const float cx = lane < a.c1 ? v[k].x : kRefFloor, sx = lane < a.c1 ? v[k].y : 0.f;
+        const float m = wave_max(cx);
+        const float t = wave_sum(sx * exp2_fast(cx - m));
+        if (lane == 0 && q < nrows) a.rowstat[row_of(q)] = make_float2(m, t);
+      }
+    }
+  } else {
+    for (int q = wv; q < nrows; q += kWavesW) combine_row_wave(a, row_of(q));
+  }
   __syncthreads();          // the rows' statistics are visible to the whole workgroup
 }
 
@@ -369,6 +390,12 @@ __global__ __launch_bounds__(kThreadsW) void sequence_select_kernel(const KArgs 
   const int C = a.nchunks;
   const int b = blockIdx.x;
   if (threadIdx.x == 0) sm.needs64 = 0;           // barriers lie between this and its readers
+  // what does not depend on tau is requested before tau arrives: lane c's chunk mass (rows of up
+  // to 64 chunks) and the uniform
+  const int lane0 = threadIdx.x & 63;
+  float m_early = (C <= 64 && lane0 < C) ? a.chunk_R[int64_t(b) * C + lane0] : 0.f;
+  float u_early = a.u_res[b];
+  asm volatile("" : "+v"(m_early), "+v"(u_early));
   const SampledRow r = sampled_row<DT, XF>(a, b, a.resample_only ? 0 : a.accept_len[b]);
   if (r.none) {
     if (threadIdx.x == 0) {
@@ -402,7 +429,7 @@ __global__ __launch_bounds__(kThreadsW) void sequence_select_kernel(const KArgs 
     // up to 64 chunks (rows of 524288 logits): lane c of every wave takes chunk c, one memory
     // round trip and a wave scan, no LDS and no barrier; every wave gets the same answer
     const int lane = threadIdx.x & 63;
-    float m = lane < C ? a.chunk_R[int64_t(b) * C + lane] : 0.f;
+    float m = m_early;
     float incl = wave_scan_incl(m);
     R = lane_f(incl, 63);
     if (!(R > 0.f)) {    // no rejection possible at this position: any law is optimal, use p
@@ -412,7 +439,7 @@ __global__ __launch_bounds__(kThreadsW) void sequence_select_kernel(const KArgs 
       incl = wave_scan_incl(m);
       R = lane_f(incl, 63);
     }
-    const float v = __fmul_rn(a.u_res[b], R);
+    const float v = __fmul_rn(u_early, R);
     const float excl = wave_prev_lane(incl);
     const bool pos = m > 0.f;
     const unsigned long long bh = __ballot(pos && incl > v), bp = __ballot(pos);

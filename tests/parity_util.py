@@ -13,14 +13,18 @@ U_TOL = 1e-6
 REL_TOL = 1e-5
 ABS_FLOOR = 1e-37          # below fp32's normal range the GPU flushes to zero
 # A law whose exact mass is below this is not determined by fp64 arithmetic either: the masses
-# [p - q f]_+ are then rounding residue of probabilities that coincide to twelve digits, and two
-# correct fp64 evaluations (the oracle's and the library's, which sum in different orders) may see
-# different residue, or none.  What the paper fixes there (proof of the proposition on the optimal
-# G, App.): when the rejection mass sum_x (1 - f(x)) q(x) vanishes any G attains the infimum of the
-# bound, and a row is reached with exactly that probability; the oracle's fall-back to p is one such
-# choice.  The sampled token is then only required to be valid (in range, positive probability
-# under p), and the reported mass to be either that residue or the fall-back's 1.
-R_FLOOR = 1e-12
+# [p - q f]_+ are then rounding residue of probabilities that coincide to nine digits and more.  fp64
+# probabilities near 1 carry ~1e-15 of rounding (a few ulp from the exponential and the normaliser),
+# so two correct fp64 evaluations (the oracle's and the library's, which sum in different orders)
+# agree on R only to ~1e-15 absolute: the 1e-5 relative tolerance on the mass needs R >= 1e-10, the
+# 1e-6 band on the token (1e-6 R in units of mass) needs R >= 1e-9.  Seen: R = 1.4195e-12 on a
+# two-token vocabulary, reported as 1.4194e-12 (7.8e-5 apart).  What the paper fixes there (proof
+# of the proposition on the optimal G, App.): when the rejection mass sum_x (1 - f(x)) q(x) vanishes
+# any G attains the infimum of the bound, and a row is reached with exactly that probability; the
+# oracle's fall-back to p is one such choice.  The sampled token is then only required to be valid
+# (in range, positive probability under p), and the reported mass to be either that residue or the
+# fall-back's 1.
+R_FLOOR = 1e-9
 
 
 def token_band(R):

@@ -118,6 +118,24 @@ def test_rounds_shapes(P, oracle, cfg, B, L, V, dtype):
         np.testing.assert_array_equal(early["next_token"], full["next_token"])
 
 
+def test_rounds_reject_at_every_window_edge(P, oracle):
+    """L = 130: rounds [0,1) [1,2) [2,4) [4,8) [8,16) [16,32) [32,64) [64,127) [127,131).  Sequence b accepts
+    everything before position taus[b] (huge omega) and rejects there (omega = 0): first and last position
+    of every round, and the fully accepted window with its bonus draw."""
+    taus = [0, 1, 2, 3, 4, 7, 8, 15, 16, 31, 32, 63, 64, 126, 127, 129, 130]
+    L, V = 130, 16400
+    w = make_workload(5, device="cuda", B=len(taus), L=L, V=V)
+    om = np.full((len(taus), L), 1e30, np.float32)
+    for b, t in enumerate(taus):
+        om[b, t:] = 0.0
+    early, full = _both(P, w, om)
+    np.testing.assert_array_equal(early["accept_len"], np.array(taus, np.int32))
+    ref = run_oracle(oracle, w, om, 0)
+    compare_verify(oracle, w, om, early, ref=ref, early_exit=True)
+    compare_verify(oracle, w, om, full, ref=ref)
+    np.testing.assert_array_equal(early["next_token"], full["next_token"])
+
+
 def test_rounds_beyond_the_form_fall_back(P, oracle):
     w = make_workload(5, device="cuda", B=1, L=1, V=524296)
     assert early_exit_form(P, w) == P.COOL_SD_EARLY_EXIT_NONE

@@ -30,6 +30,7 @@ namespace csd {
 #define CSD_SAFE_MASS 0.0625f
 #endif
 constexpr float kSafeMass = CSD_SAFE_MASS;   // laws lighter than this are always drawn in fp64
+constexpr double kDustMass = 1e-14;          // fp64 laws lighter than this are rounding residue: p takes their place
 // One row as the exact path reads it.
 struct ExactRow {
   const char* cond;
@@ -200,7 +201,9 @@ __device__ __forceinline__ int exact_draw(const ExactJob& J, float u, float& R_o
   int mode = has_d ? J.mode : kModeP;
   double base = 0.0, R = 0.0, v = 0.0;
   int win = exact_level<TPB>(J, mode, 0, J.V, St, Sd, p_agg, base, R, v, false, u, sm);
-  if (!(R > 0.0) && mode != kModeP) {
+  // a mass this small is rounding residue of probabilities that coincide (fp64 probabilities near 1
+  // carry ~1e-16 each): treated like no mass at all
+  if (!(R > kDustMass) && mode != kModeP) {
     mode = kModeP;
     base = 0.0;
     win = exact_level<TPB>(J, mode, 0, J.V, St, Sd, p_agg, base, R, v, false, u, sm);

@@ -277,7 +277,7 @@ __device__ __forceinline__ bool eval_position(const KArgs& a, int b, int i, bool
 template <int DT, bool XF, int TPB>
 __device__ __forceinline__ int find_tau(const KArgs& a, int b, bool emit, int* pick /*[TPB/64]*/, float4* rowstat) {
   const int rps = a.L + a.has_bonus;
-  if (rps <= 64) {
+  if (__builtin_expect(rps <= 64, 1)) {
     // the usual case: one wave holds every position, the first rejection is the lowest set bit
     // of a ballot, and one barrier hands tau and the sampled row's statistics to the others
     if (threadIdx.x < 64) {

@@ -74,7 +74,7 @@ __device__ __forceinline__ int sample_whole(const RowRegs<DT, XF, kVW>& rt, cons
     const float woff = wv == 0 ? 0.f : lane_f(tot, wv - 1);
     incl = __fadd_rn(woff, incl_w);
     excl = __fadd_rn(woff, excl_w);
-    if (R > 0.f || k.mode == kModeP) break;
+    if (__builtin_expect(R > 0.f || k.mode == kModeP, 1)) break;
     k.mode = kModeP;   // no rejection possible at this position: any law is optimal, use p
     fell_back = true;
   }
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(kThreadsW) void sequence_whole_kernel(const KArgs a
   } else {
     token = sample_whole<DT, XF, kVW>(rt, rd, k, a.u_res[b], a.V, sm, R, writer, trust);
   }
-  if (draw_needs_fp64(writer, trust, a.exact_draw, &sm.needs64)) {
+  if (__builtin_expect(draw_needs_fp64(writer, trust, a.exact_draw, &sm.needs64), 0)) {     // rare: keep its code off the hot path
     token = exact_draw<kThreadsW>(job, a.u_res[b], R, smx);
     writer = threadIdx.x == 0;
   }

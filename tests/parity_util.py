@@ -161,7 +161,7 @@ def compare_verify(O, w, omega, gpu, ref=None, resample_mode=0, has_bonus=True, 
         # token differs (or tau took the exempt branch): check against the oracle's law of that row
         xo, R, g = _oracle_row_law(O, w, b, tg, om_b[min(tg, L - 1)], resample_mode)
         mass_close(gpu["resid_mass"][b], R, exact_R())
-        if xg != xo and R < R_FLOOR:
+        if xg != xo and min(R, exact_R()) < R_FLOOR:      # (R is 1 where the oracle fell back to p)
             p, _ = _oracle_rows(O, w, b, tg)
             assert 0 <= xg < w.V and p[xg] > 0, "seq %d: gpu token %d has no probability" % (b, xg)
             stats["token_exempt"] += 1

@@ -226,6 +226,27 @@ def _tokens_match_or_sit_on_a_boundary(tok, ot, g, R, u):
     return n
 
 
+@pytest.mark.parametrize("V", [2, 64, 16384, 40000])
+def test_draft_equal_to_target_up_to_a_shift(P, oracle, V):
+    """Draft logits = target logits - 1/2: the two softmaxes are the same distribution, but the kernels
+    form them against different reference exponents, so [p - q]_+ comes out as rounding residue instead
+    of zero.  Rejected at once (omega = 0), the vanilla law has no mass: the call must fall back to p like
+    the oracle -- same token, mass 1 -- and not draw from the residue."""
+    B, L = 8, 2
+    w = make_workload(5, device="cuda", B=B, L=L, V=V)
+    g = torch.Generator(device="cuda").manual_seed(V)
+    t = (torch.randint(-64, 65, (B, L + 1, V), generator=g, device="cuda").float() / 8).to(torch.bfloat16)
+    w.target = t
+    w.draft = (t[:, :L].float() - 0.5).to(torch.bfloat16)
+    assert torch.equal(w.draft.float() + 0.5, t[:, :L].float())          # the shift is exact in bf16
+    om = np.zeros(L, np.float32)
+    for mode in (1, 0):
+        gpu = _run(P, oracle, w, om, resample_mode=mode)
+        ref = compare_verify(oracle, w, om, gpu, resample_mode=mode)
+        assert ref["token_exempt"] == 0 and (gpu["accept_len"] == 0).all()
+        np.testing.assert_allclose(gpu["resid_mass"], 1.0, rtol=1e-5)
+
+
 def test_resample_where_the_law_has_no_mass(P, oracle):
     """p and q that coincide (here: both one-hot on the same token after top-1 truncation, from
     different logits) leave [p - q]_+ without mass: any law is optimal there, the oracle falls

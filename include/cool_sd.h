@@ -30,9 +30,10 @@
  *   - The workspace holds only intermediate results of one call (chunk statistics, masses);
  *     nothing persists between calls and it needs no initialisation.  Calls that share a
  *     workspace must be ordered on one stream.
- *   - No kernel uses fences or waits on another workgroup, and the only global atomics are
- *     integer counts whose sums do not depend on the order (top-k on rows beyond 65536 logits);
- *     for given inputs the outputs are bit-identical from run to run.
+ *   - No kernel spins or waits on another workgroup.  The only global atomics are integer counts
+ *     whose sums do not depend on the order (top-k on rows beyond 65536 logits) and a per-sequence
+ *     ticket that decides which workgroup finishes a sequence, not what it computes; for given
+ *     inputs the outputs are bit-identical from run to run.
  */
 #ifndef COOL_SD_H
 #define COOL_SD_H
